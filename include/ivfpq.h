@@ -1,0 +1,159 @@
+/*
+ * ivfpq.h -- C ABI of the MI355X (gfx950) IVFPQ search library.
+ *
+ * The library implements the search phase of IVFPQ as described in
+ * arXiv 2301.06672, Sec. I-C (second enumeration) and Sec. I-D, with the
+ * "norm2 fragment lookup table" held in LDS as fp32, IEEE half or the paper's
+ * sign-less 8-bit float e5m3 (Sec. II).  All compute of the search runs in
+ * hand-written HIP kernels; this header is the only interface.
+ *
+ * Conventions
+ *  - Every function returns an ivfpq_status (0 = OK, negative = error); nothing
+ *    throws across the ABI.  ivfpq_last_error() gives a text for the last
+ *    non-OK return on the calling thread.
+ *  - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *    memory of the current device.  The caller owns every buffer it passes; the
+ *    library never allocates or frees device memory (the entry points whose
+ *    comment says so excepted: none at present).
+ *  - Row-major everywhere.  Distances are squared L2 (Sec. I-B).
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *    Search calls only enqueue work; they do not synchronise.
+ */
+#ifndef IVFPQ_H
+#define IVFPQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ivfpq_index ivfpq_index_t; /* opaque; created by build/import, destroyed by ivfpq_free */
+
+/* Storage type of the lookup-table entries F(y_v) in LDS (Sec. I-D, Sec. II). */
+typedef enum {
+    IVFPQ_LUT_FP32 = 0,     /* IEEE binary32 */
+    IVFPQ_LUT_FP16 = 1,     /* IEEE binary16, round-to-nearest-even, saturating at 65504 */
+    IVFPQ_LUT_FP8_E5M3 = 2  /* 5 exponent + 3 mantissa bits, no sign, bias 15, all codes normal:
+                               value(b) = (1 + (b&7)/8) * 2^((b>>3) - 15); FP32 -> code: nearest, ties up,
+                               clamped to [0x00, 0xFF]; code -> FP32 bits: (b << 20) + 0x38000000 */
+} ivfpq_lut_dtype_t;
+
+typedef enum {
+    IVFPQ_OK = 0,
+    IVFPQ_EINVAL = -1,       /* null pointer, bad shape or parameter */
+    IVFPQ_ENOSPACE = -2,     /* a caller buffer is smaller than the matching *_bytes() query says */
+    IVFPQ_EHIP = -3,         /* a HIP runtime call failed (text in ivfpq_last_error) */
+    IVFPQ_EUNSUPPORTED = -4, /* shape outside what the kernels handle (e.g. table does not fit LDS) */
+    IVFPQ_ESTATE = -5        /* index not uploaded, or uploaded to another device */
+} ivfpq_status;
+
+enum { IVFPQ_MAX_K = 1024, IVFPQ_MAX_PROBES = 1024 };
+
+/* ---- index construction (Sec. I-C, first enumeration; host side, not timed) ---- */
+
+/* Builds an index on the host CPU: (1) Lloyd k-means with n_lists clusters (kmeans_iters
+ * iterations, start rows drawn from `seed`), (2) residuals to the own centroid, (3) product
+ * quantisation of the residuals: pq_dim contiguous sub-vectors of d/pq_dim components, one
+ * codebook of 2^pq_bits entries per sub-space, (4) the saved lists, codes and codebook.
+ * data: host [n][d] fp32.  Requires d % pq_dim == 0, pq_bits in {4, 8},
+ * (pq_dim*pq_bits/8) % 4 == 0, 1 <= n_lists <= n.  *out receives the new handle. */
+int ivfpq_build_host(const float* data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim,
+                     int32_t pq_bits, int32_t kmeans_iters, uint64_t seed, ivfpq_index_t** out);
+
+/* Imports the logical saved index (Sec. I-C build step 4).  All host pointers; the library copies.
+ *   centroids    [n_lists][d] f32
+ *   codebooks    [pq_dim][2^pq_bits][d/pq_dim] f32
+ *   list_offsets [n_lists+1] i64, non-decreasing, [0] = 0, [n_lists] = n
+ *   codes        [n][pq_dim*pq_bits/8] u8 in list order; pq_bits = 8: byte j = code of sub-space j;
+ *                pq_bits = 4: byte j holds sub-space 2j in its low and 2j+1 in its high nibble
+ *   ids          [n] i64 in list order (the caller's labels; returned by search) */
+int ivfpq_index_from_arrays(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,
+                            const float* centroids, const float* codebooks, const int64_t* list_offsets,
+                            const uint8_t* codes, const int64_t* ids, ivfpq_index_t** out);
+
+/* Shape of an index; any out pointer may be NULL. */
+int ivfpq_index_info(const ivfpq_index_t* index, int64_t* n, int32_t* d, int32_t* n_lists,
+                     int32_t* pq_dim, int32_t* pq_bits);
+
+/* Copies the logical arrays (same layout as ivfpq_index_from_arrays) into caller host buffers of
+ * the sizes ivfpq_index_info implies; any pointer may be NULL to skip that array. */
+int ivfpq_index_export(const ivfpq_index_t* index, float* centroids, float* codebooks,
+                       int64_t* list_offsets, uint8_t* codes, int64_t* ids);
+
+void ivfpq_free(ivfpq_index_t* index);
+
+/* ---- device residency ---- */
+
+/* Bytes of device memory the uploaded index needs (lists are padded to 64 vectors and the codes
+ * re-laid out for coalesced wave64 loads; see ivfpq_upload). */
+size_t ivfpq_device_bytes(const ivfpq_index_t* index);
+
+/* Writes the device image of the index into d_buf (device, >= ivfpq_device_bytes, 256-byte aligned)
+ * on the current device and remembers the pointer.  Synchronous.  d_buf must stay alive and
+ * unmodified while the handle is used for searches. */
+int ivfpq_upload(ivfpq_index_t* index, void* d_buf, size_t bytes, void* hip_stream);
+
+/* Bytes of device scratch one search call needs for these parameters (probe lists, coarse
+ * distances, per-candidate distances R).  Large batches are processed in query tiles so that
+ * the figure stays bounded. */
+size_t ivfpq_search_workspace_bytes(const ivfpq_index_t* index, int64_t nq, int32_t n_probes,
+                                    int32_t k, int32_t lut_dtype);
+
+/* ---- search (Sec. I-C, second enumeration, steps 1-5) ---- */
+
+/* For each of nq queries: picks the n_probes clusters with the nearest centroids (step 1), and for
+ * each picked cluster forms the query residual (step 2), builds the lookup table F in LDS in
+ * lut_dtype (step 3), accumulates R = sum_j F(y_j) (Eq. 1) over every coded vector of the cluster
+ * (step 4); then keeps the k smallest R over all picked clusters (step 5).
+ *   d_queries [nq][d] f32 (device)          d_ids [nq][k] i64 (device, out)
+ *   d_dists   [nq][k] f32 (device, out): R of the returned vectors, ascending; ties ordered by id.
+ * Rows with fewer than k candidates are padded with id -1, distance +inf.
+ * 1 <= n_probes <= min(n_lists, IVFPQ_MAX_PROBES), 1 <= k <= IVFPQ_MAX_K.
+ * d_workspace: device scratch of >= ivfpq_search_workspace_bytes(...), 256-byte aligned; calls that
+ * may overlap in time need distinct workspaces. */
+int ivfpq_search(const ivfpq_index_t* index, const float* d_queries, int64_t nq, int32_t n_probes,
+                 int32_t k, int32_t lut_dtype, int64_t* d_ids, float* d_dists,
+                 void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Step 1 alone: d_probes [nq][n_probes] u32 (device, out), nearest first, ties to the lower
+ * cluster index; d_probe_dists [nq][n_probes] f32 (device, out, may be NULL). */
+int ivfpq_select_probes(const ivfpq_index_t* index, const float* d_queries, int64_t nq,
+                        int32_t n_probes, uint32_t* d_probes, float* d_probe_dists,
+                        void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Steps 2-5 on caller-chosen clusters: d_probes [nq][n_probes] u32 (device, in), every entry
+ * < n_lists; a cluster listed twice for one query is scanned twice. */
+int ivfpq_search_with_probes(const ivfpq_index_t* index, const float* d_queries, int64_t nq,
+                             const uint32_t* d_probes, int32_t n_probes, int32_t k, int32_t lut_dtype,
+                             int64_t* d_ids, float* d_dists,
+                             void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Steps 2-3 alone, for inspection: builds the table of one (query, cluster) pair exactly as the
+ * search kernel stages it in LDS and copies the raw bytes out.
+ * d_query [d] f32 (device); d_lut_out (device) [pq_dim][2^pq_bits] entries of lut_dtype,
+ * i.e. pq_dim * 2^pq_bits * {4, 2, 1} bytes. */
+int ivfpq_dump_lut(const ivfpq_index_t* index, const float* d_query, uint32_t list_id,
+                   int32_t lut_dtype, void* d_lut_out, void* hip_stream);
+
+/* Step 4 alone, for inspection: R of every coded vector of one cluster for one query, in list
+ * order.  d_R_out (device) [list length] f32. */
+int ivfpq_scan_list(const ivfpq_index_t* index, const float* d_query, uint32_t list_id,
+                    int32_t lut_dtype, float* d_R_out, void* hip_stream);
+
+/* ---- measurement aid ---- */
+
+/* When enabled, search calls record HIP events around their stages on the stream they run on.
+ * After the stream has been synchronised, ivfpq_stage_times_ms reports the last call's
+ * milliseconds: ms[0] = probe selection (step 1), ms[1] = table build + scan kernel (steps 2-4),
+ * ms[2] = top-k (step 5), ms[3] = whole call; summed over query tiles. */
+int ivfpq_set_stage_timing(ivfpq_index_t* index, int32_t enabled);
+int ivfpq_stage_times_ms(ivfpq_index_t* index, float ms[4]);
+
+const char* ivfpq_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IVFPQ_H */

@@ -1,0 +1,250 @@
+"""ctypes binding of libivfpq.so: argument marshalling only.
+
+Function names mirror the C ABI in include/ivfpq.h.  PyTorch is used for device memory
+(`torch.empty(..., device="cuda")`) and for the current HIP stream -- nothing is computed here.
+There is no CPU fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+import torch  # imported before the library so that both share one HIP runtime
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libivfpq.so")
+
+LUT_FP32, LUT_FP16, LUT_FP8_E5M3 = 0, 1, 2
+LUT_NAMES = {LUT_FP32: "fp32", LUT_FP16: "fp16", LUT_FP8_E5M3: "e5m3"}
+LUT_BYTES = {LUT_FP32: 4, LUT_FP16: 2, LUT_FP8_E5M3: 1}
+MAX_K = 1024
+MAX_PROBES = 1024
+
+OK, EINVAL, ENOSPACE, EHIP, EUNSUPPORTED, ESTATE = 0, -1, -2, -3, -4, -5
+
+# every symbol include/ivfpq.h declares
+EXPORTS = (
+    "ivfpq_build_host", "ivfpq_index_from_arrays", "ivfpq_index_info", "ivfpq_index_export", "ivfpq_free",
+    "ivfpq_device_bytes", "ivfpq_upload", "ivfpq_search_workspace_bytes", "ivfpq_search",
+    "ivfpq_select_probes", "ivfpq_search_with_probes", "ivfpq_dump_lut", "ivfpq_scan_list",
+    "ivfpq_set_stage_timing", "ivfpq_stage_times_ms", "ivfpq_last_error",
+)
+
+
+class IvfpqError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"ivfpq status {status}: {message}")
+        self.status = status
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libivfpq.so (built by `python -m paper_2301_06672_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2301_06672_amd.build` "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        _declare(L)
+        _lib = L
+    return _lib
+
+
+def _declare(L):
+    c = ctypes
+    vp, i64, i32, u32, u64, sz = c.c_void_p, c.c_int64, c.c_int32, c.c_uint32, c.c_uint64, c.c_size_t
+    pp = c.POINTER(c.c_void_p)
+    L.ivfpq_build_host.argtypes = [vp, i64, i32, i32, i32, i32, i32, u64, pp]
+    L.ivfpq_index_from_arrays.argtypes = [i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, pp]
+    L.ivfpq_index_info.argtypes = [vp, c.POINTER(i64), c.POINTER(i32), c.POINTER(i32), c.POINTER(i32), c.POINTER(i32)]
+    L.ivfpq_index_export.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.ivfpq_free.argtypes = [vp]
+    L.ivfpq_free.restype = None
+    L.ivfpq_device_bytes.argtypes = [vp]
+    L.ivfpq_device_bytes.restype = sz
+    L.ivfpq_upload.argtypes = [vp, vp, sz, vp]
+    L.ivfpq_search_workspace_bytes.argtypes = [vp, i64, i32, i32, i32]
+    L.ivfpq_search_workspace_bytes.restype = sz
+    L.ivfpq_search.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, vp, sz, vp]
+    L.ivfpq_select_probes.argtypes = [vp, vp, i64, i32, vp, vp, vp, sz, vp]
+    L.ivfpq_search_with_probes.argtypes = [vp, vp, i64, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    L.ivfpq_dump_lut.argtypes = [vp, vp, u32, i32, vp, vp]
+    L.ivfpq_scan_list.argtypes = [vp, vp, u32, i32, vp, vp]
+    L.ivfpq_set_stage_timing.argtypes = [vp, i32]
+    L.ivfpq_stage_times_ms.argtypes = [vp, c.POINTER(c.c_float * 4)]
+    L.ivfpq_last_error.restype = c.c_char_p
+    for name in EXPORTS:
+        fn = getattr(L, name)
+        if fn.restype is c.c_int:      # default: status code
+            fn.restype = c.c_int
+
+
+def _check(status: int):
+    if status != OK:
+        raise IvfpqError(status, lib().ivfpq_last_error().decode("utf-8", "replace"))
+
+
+def _np(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hp(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dp(t: Optional[torch.Tensor]):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_f32(x) -> torch.Tensor:
+    if isinstance(x, torch.Tensor):
+        assert x.is_cuda and x.dtype == torch.float32
+        return x.contiguous()
+    return torch.from_numpy(_np(x, np.float32)).cuda()
+
+
+class Index:
+    """Owns one ivfpq_index_t handle plus the torch tensors that back its device image and scratch."""
+
+    def __init__(self, handle: ctypes.c_void_p):
+        self._h = handle
+        self._image: Optional[torch.Tensor] = None
+        self._ws: Optional[torch.Tensor] = None
+        n, d, nl, s, p = ctypes.c_int64(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+        _check(lib().ivfpq_index_info(self._h, n, d, nl, s, p))
+        self.n, self.d, self.n_lists, self.pq_dim, self.pq_bits = n.value, d.value, nl.value, s.value, p.value
+
+    # ---- construction
+    @staticmethod
+    def ivfpq_build_host(data, n_lists: int, pq_dim: int, pq_bits: int, kmeans_iters: int = 10, seed: int = 0) -> "Index":
+        data = _np(data, np.float32)
+        h = ctypes.c_void_p()
+        _check(lib().ivfpq_build_host(_hp(data), data.shape[0], data.shape[1], n_lists, pq_dim, pq_bits,
+                                      kmeans_iters, seed, ctypes.byref(h)))
+        return Index(h)
+
+    @staticmethod
+    def ivfpq_index_from_arrays(d: int, n_lists: int, pq_dim: int, pq_bits: int, centroids, codebooks,
+                                list_offsets, codes, ids) -> "Index":
+        centroids, codebooks = _np(centroids, np.float32), _np(codebooks, np.float32)
+        list_offsets, codes, ids = _np(list_offsets, np.int64), _np(codes, np.uint8), _np(ids, np.int64)
+        ksub, m, cb = 1 << pq_bits, d // max(pq_dim, 1), pq_dim * pq_bits // 8
+        n = int(ids.shape[0])
+        assert centroids.size == n_lists * d and codebooks.size == pq_dim * ksub * m
+        assert list_offsets.size == n_lists + 1 and codes.size == n * cb
+        h = ctypes.c_void_p()
+        _check(lib().ivfpq_index_from_arrays(n, d, n_lists, pq_dim, pq_bits, _hp(centroids), _hp(codebooks),
+                                             _hp(list_offsets), _hp(codes), _hp(ids), ctypes.byref(h)))
+        return Index(h)
+
+    def ivfpq_index_export(self):
+        ksub, m, cb = 1 << self.pq_bits, self.d // self.pq_dim, self.pq_dim * self.pq_bits // 8
+        centroids = np.empty((self.n_lists, self.d), np.float32)
+        codebooks = np.empty((self.pq_dim, ksub, m), np.float32)
+        list_offsets = np.empty(self.n_lists + 1, np.int64)
+        codes = np.empty((self.n, cb), np.uint8)
+        ids = np.empty(self.n, np.int64)
+        _check(lib().ivfpq_index_export(self._h, _hp(centroids), _hp(codebooks), _hp(list_offsets), _hp(codes), _hp(ids)))
+        return centroids, codebooks, list_offsets, codes, ids
+
+    def ivfpq_free(self):
+        if self._h:
+            lib().ivfpq_free(self._h)
+            self._h = None
+            self._image = None
+            self._ws = None
+
+    def __del__(self):
+        try:
+            self.ivfpq_free()
+        except Exception:
+            pass
+
+    # ---- device residency
+    def ivfpq_device_bytes(self) -> int:
+        return int(lib().ivfpq_device_bytes(self._h))
+
+    def ivfpq_upload(self) -> "Index":
+        nbytes = self.ivfpq_device_bytes()
+        self._image = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        _check(lib().ivfpq_upload(self._h, _dp(self._image), nbytes, _stream()))
+        return self
+
+    def ivfpq_search_workspace_bytes(self, nq: int, n_probes: int, k: int, lut_dtype: int) -> int:
+        return int(lib().ivfpq_search_workspace_bytes(self._h, nq, n_probes, k, lut_dtype))
+
+    def _workspace(self, nq, n_probes, k, lut_dtype) -> torch.Tensor:
+        need = self.ivfpq_search_workspace_bytes(nq, n_probes, k, lut_dtype)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = None
+            self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        return self._ws
+
+    # ---- search
+    def ivfpq_search(self, queries, n_probes: int, k: int, lut_dtype: int = LUT_FP8_E5M3, out=None):
+        q = _dev_f32(queries)
+        nq = q.shape[0]
+        ids, dists = out if out is not None else (
+            torch.empty((nq, k), dtype=torch.int64, device="cuda"),
+            torch.empty((nq, k), dtype=torch.float32, device="cuda"))
+        ws = self._workspace(nq, n_probes, k, lut_dtype)
+        _check(lib().ivfpq_search(self._h, _dp(q), nq, n_probes, k, lut_dtype, _dp(ids), _dp(dists),
+                                  _dp(ws), ws.numel(), _stream()))
+        return ids, dists
+
+    def ivfpq_select_probes(self, queries, n_probes: int):
+        q = _dev_f32(queries)
+        nq = q.shape[0]
+        probes = torch.empty((nq, n_probes), dtype=torch.int32, device="cuda")   # u32 payload
+        pd = torch.empty((nq, n_probes), dtype=torch.float32, device="cuda")
+        ws = self._workspace(nq, n_probes, 1, LUT_FP32)
+        _check(lib().ivfpq_select_probes(self._h, _dp(q), nq, n_probes, _dp(probes), _dp(pd), _dp(ws),
+                                         ws.numel(), _stream()))
+        return probes, pd
+
+    def ivfpq_search_with_probes(self, queries, probes, k: int, lut_dtype: int = LUT_FP8_E5M3):
+        q = _dev_f32(queries)
+        nq = q.shape[0]
+        if not isinstance(probes, torch.Tensor):
+            probes = torch.from_numpy(_np(probes, np.uint32).view(np.int32)).cuda()
+        probes = probes.contiguous()
+        assert probes.is_cuda and probes.dtype == torch.int32 and probes.shape[0] == nq
+        n_probes = probes.shape[1]
+        ids = torch.empty((nq, k), dtype=torch.int64, device="cuda")
+        dists = torch.empty((nq, k), dtype=torch.float32, device="cuda")
+        ws = self._workspace(nq, n_probes, k, lut_dtype)
+        _check(lib().ivfpq_search_with_probes(self._h, _dp(q), nq, _dp(probes), n_probes, k, lut_dtype,
+                                              _dp(ids), _dp(dists), _dp(ws), ws.numel(), _stream()))
+        return ids, dists
+
+    def ivfpq_dump_lut(self, query, list_id: int, lut_dtype: int) -> torch.Tensor:
+        q = _dev_f32(query).reshape(-1)
+        nbytes = self.pq_dim * (1 << self.pq_bits) * LUT_BYTES[lut_dtype]
+        out = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        _check(lib().ivfpq_dump_lut(self._h, _dp(q), list_id, lut_dtype, _dp(out), _stream()))
+        return out
+
+    def ivfpq_scan_list(self, query, list_id: int, lut_dtype: int, list_len: int) -> torch.Tensor:
+        q = _dev_f32(query).reshape(-1)
+        out = torch.empty(max(list_len, 1), dtype=torch.float32, device="cuda")
+        _check(lib().ivfpq_scan_list(self._h, _dp(q), list_id, lut_dtype, _dp(out), _stream()))
+        return out[:list_len]
+
+    # ---- measurement aid
+    def ivfpq_set_stage_timing(self, enabled: bool):
+        _check(lib().ivfpq_set_stage_timing(self._h, int(enabled)))
+
+    def ivfpq_stage_times_ms(self):
+        ms = (ctypes.c_float * 4)()
+        _check(lib().ivfpq_stage_times_ms(self._h, ctypes.byref(ms)))
+        return {"probe_select": ms[0], "scan": ms[1], "topk": ms[2], "total": ms[3]}

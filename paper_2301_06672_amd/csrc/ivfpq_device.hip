@@ -1,0 +1,1060 @@
+// Device half of libivfpq: upload of the index image and the HIP kernels of the IVFPQ search phase
+// (arXiv 2301.06672, Sec. I-C second enumeration, Sec. I-D, Sec. II) for gfx950 (MI355X, wave64).
+//
+// Kernels, in the order one search call runs them:
+//   coarse_dist_kernel   step 1a: |q - c_l|^2 for a tile of queries x all clusters (fp32, direct form)
+//   select_probes_kernel step 1b: the n_probes nearest clusters per query (exact radix select),
+//                        plus the per-query offsets of each probed cluster in the R scratch
+//   scan_kernel          steps 2-4: one workgroup per (query, probed cluster): query residual, lookup
+//                        table F built in LDS as fp32 / half / e5m3, then every wave streams 64-vector
+//                        groups of PQ codes from HBM and accumulates R = sum_j F(y_j) (Eq. 1)
+//   topk_kernel          step 5: the k smallest R over all probed clusters of a query, ordered by
+//                        (R, id), and the map from (cluster, position) to the caller's ids
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <type_traits>
+
+#include "ivfpq_internal.hpp"
+
+using namespace ivfpq;
+
+#define HIP_TRY(expr)                                                                               \
+    do {                                                                                            \
+        hipError_t e_ = (expr);                                                                     \
+        if (e_ != hipSuccess)                                                                       \
+            return fail(IVFPQ_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr uint32_t kPadKey = 0xFFFFFFFFu;      // R of a padding lane: sorts after every real distance
+constexpr size_t kLdsBytes = 160 * 1024;       // LDS of one gfx950 compute unit
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+
+// ================================================================================================
+// Step 1a: coarse distances.  Tile of 64 queries x 64 clusters per 256-thread workgroup, 4x4 outputs
+// per thread, operands staged through LDS in slices of 16 components.  The distance is accumulated
+// in the direct form sum_t (q_t - c_t)^2 so that its rounding error stays relative to the distance
+// itself (the expanded form |q|^2 - 2 q.c + |c|^2 cancels badly for far-from-origin data).
+// ================================================================================================
+constexpr int CT = 64;   // tile edge
+constexpr int CK = 16;   // components per LDS slice
+
+__global__ void __launch_bounds__(256)
+coarse_dist_kernel(const float* __restrict__ queries, const float* __restrict__ centroids,
+                   int nq, int n_lists, int d, float* __restrict__ D) {
+    __shared__ float qs[CK][CT + 4];
+    __shared__ float cs[CK][CT + 4];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int q0 = blockIdx.y * CT, l0 = blockIdx.x * CT;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+    const int lr = tid >> 2;          // row of the tile this thread loads
+    const int lk = (tid & 3) * 4;     // first of its 4 components
+    for (int k0 = 0; k0 < d; k0 += CK) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int t = k0 + lk + u;
+            int qi = q0 + lr, li = l0 + lr;
+            qs[lk + u][lr] = (qi < nq && t < d) ? queries[(size_t)qi * d + t] : 0.f;
+            cs[lk + u][lr] = (li < n_lists && t < d) ? centroids[(size_t)li * d + t] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < CK; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = qs[kk][ty * 4 + i]; b[i] = cs[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float diff = a[i] - b[j];
+                    acc[i][j] = __builtin_fmaf(diff, diff, acc[i][j]);
+                }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int qi = q0 + ty * 4 + i;
+        if (qi >= nq) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int li = l0 + tx * 4 + j;
+            if (li < n_lists) D[(size_t)qi * n_lists + li] = acc[i][j];
+        }
+    }
+}
+
+// ================================================================================================
+// Exact selection of the k smallest of n keyed elements by one workgroup.
+// Keys are the bit patterns of non-negative floats (order-preserving as unsigned integers); equal
+// keys are ordered by a signed 64-bit tie key, then by position.  MSB-first radix select with 8-bit
+// digits finds the k-th smallest key; everything below it and the needed share of the ties is
+// collected into LDS records and sorted there (bitonic).
+// ================================================================================================
+constexpr int SEL_THREADS = 256;
+constexpr int SEL_CAP = 2048;      // record capacity; k <= IVFPQ_MAX_K = 1024 always fits
+
+struct SelectShared {
+    uint32_t hist[256];
+    uint32_t rec_key[SEL_CAP];
+    uint32_t rec_pos[SEL_CAP];
+    long long rec_tie[SEL_CAP];
+    uint32_t digit, need, count;   // broadcast slots of the digit search
+    uint32_t n_rec, n_eq;
+};
+
+__device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        uint32_t o = __shfl_up(v, off, kWave);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+// hist holds digit counts; finds the digit that contains the `need`-th smallest element
+// (1-based).  Result in s.digit (the digit), s.need (rank inside that digit), s.count (its count).
+// Called by all threads; contains barriers.
+__device__ inline void find_digit(SelectShared& s, uint32_t need) {
+    __syncthreads();
+    if (threadIdx.x < kWave) {
+        const int t = threadIdx.x;
+        uint32_t c0 = s.hist[4 * t], c1 = s.hist[4 * t + 1], c2 = s.hist[4 * t + 2], c3 = s.hist[4 * t + 3];
+        uint32_t sum = c0 + c1 + c2 + c3;
+        uint32_t incl = wave_inclusive_scan(sum);
+        uint32_t excl = incl - sum;
+        if (excl < need && need <= incl) {
+            uint32_t r = need - excl, dsel = 0, cnt = c0;
+            if (r > c0) { r -= c0; dsel = 1; cnt = c1;
+                if (r > c1) { r -= c1; dsel = 2; cnt = c2;
+                    if (r > c2) { r -= c2; dsel = 3; cnt = c3; } } }
+            s.digit = 4 * t + dsel;
+            s.need = r;
+            s.count = cnt;
+        }
+    }
+    __syncthreads();
+}
+
+__device__ inline bool rec_less(uint32_t ka, long long ta, uint32_t pa, uint32_t kb, long long tb, uint32_t pb) {
+    if (ka != kb) return ka < kb;
+    if (ta != tb) return ta < tb;
+    return pa < pb;
+}
+
+// sorts records [0, np2) ascending by (key, tie, pos); np2 is a power of two <= SEL_CAP
+__device__ inline void sort_records(SelectShared& s, int np2) {
+    for (int size = 2; size <= np2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int t = threadIdx.x; t < (np2 >> 1); t += blockDim.x) {
+                int lo = ((t / stride) * stride * 2) + (t % stride);
+                int hi = lo + stride;
+                bool up = ((lo & size) == 0);
+                uint32_t ka = s.rec_key[lo], kb = s.rec_key[hi];
+                long long ta = s.rec_tie[lo], tb = s.rec_tie[hi];
+                uint32_t pa = s.rec_pos[lo], pb = s.rec_pos[hi];
+                bool b_lt_a = rec_less(kb, tb, pb, ka, ta, pa);
+                if (b_lt_a == up) {
+                    s.rec_key[lo] = kb; s.rec_key[hi] = ka;
+                    s.rec_tie[lo] = tb; s.rec_tie[hi] = ta;
+                    s.rec_pos[lo] = pb; s.rec_pos[hi] = pa;
+                }
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// KeyFn(i) -> uint32 key of element i; TieFn(i) -> long long tie key of element i.
+// On return records [0, min(k, n)) hold the selected elements in ascending (key, tie, pos) order.
+// Returns min(k, n).  Must be called by every thread of the workgroup.
+template <class KeyFn, class TieFn>
+__device__ int block_select_smallest(SelectShared& s, uint32_t n, uint32_t k, KeyFn key_of, TieFn tie_of) {
+    const uint32_t kk = k < n ? k : n;
+    if (kk == 0) return 0;
+    const int tid = threadIdx.x, nth = blockDim.x;
+
+    // ---- the kk-th smallest key T, by four 8-bit digits from the top
+    uint32_t prefix = 0, need = kk, n_eq = 0;
+    for (int pass = 3; pass >= 0; --pass) {
+        const int shift = pass * 8;
+        __syncthreads();
+        for (int b = tid; b < 256; b += nth) s.hist[b] = 0;
+        __syncthreads();
+        for (uint32_t i = tid; i < n; i += nth) {
+            uint32_t key = key_of(i);
+            bool in = (pass == 3) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
+            if (in) atomicAdd(&s.hist[(key >> shift) & 255u], 1u);
+        }
+        find_digit(s, need);
+        prefix |= s.digit << shift;
+        need = s.need;
+        n_eq = s.count;
+    }
+    const uint32_t T = prefix;
+    const uint32_t n_less = kk - need;     // elements strictly below T: all selected
+
+    // ---- collect
+    __syncthreads();
+    if (tid == 0) { s.n_rec = 0; s.n_eq = 0; }
+    __syncthreads();
+    const bool all_fit = (n_less + n_eq) <= (uint32_t)SEL_CAP;
+    if (all_fit) {
+        // everything <= T goes into the records; the sort decides which ties stay
+        for (uint32_t i = tid; i < n; i += nth) {
+            uint32_t key = key_of(i);
+            if (key <= T) {
+                uint32_t slot = atomicAdd(&s.n_rec, 1u);
+                s.rec_key[slot] = key; s.rec_pos[slot] = i; s.rec_tie[slot] = tie_of(i);
+            }
+        }
+    } else {
+        // too many elements equal to T: pick the `need` smallest tie keys among them with a second,
+        // 64-bit radix select (tie keys mapped to unsigned order by flipping the sign bit)
+        unsigned long long uprefix = 0;
+        uint32_t uneed = need;
+        for (int pass = 7; pass >= 0; --pass) {
+            const int shift = pass * 8;
+            __syncthreads();
+            for (int b = tid; b < 256; b += nth) s.hist[b] = 0;
+            __syncthreads();
+            for (uint32_t i = tid; i < n; i += nth) {
+                if (key_of(i) != T) continue;
+                unsigned long long u = (unsigned long long)tie_of(i) ^ 0x8000000000000000ull;
+                bool in = (pass == 7) || ((u >> (shift + 8)) == (uprefix >> (shift + 8)));
+                if (in) atomicAdd(&s.hist[(uint32_t)(u >> shift) & 255u], 1u);
+            }
+            find_digit(s, uneed);
+            uprefix |= (unsigned long long)s.digit << shift;
+            uneed = s.need;
+        }
+        // uprefix = the need-th smallest tie key; uneed = how many copies of it to take
+        __syncthreads();
+        for (uint32_t i = tid; i < n; i += nth) {
+            uint32_t key = key_of(i);
+            if (key > T) continue;
+            bool take = key < T;
+            long long tie = tie_of(i);
+            if (!take) {
+                unsigned long long u = (unsigned long long)tie ^ 0x8000000000000000ull;
+                if (u < uprefix) take = true;
+                else if (u == uprefix) take = atomicAdd(&s.n_eq, 1u) < uneed;
+            }
+            if (take) {
+                uint32_t slot = atomicAdd(&s.n_rec, 1u);
+                s.rec_key[slot] = key; s.rec_pos[slot] = i; s.rec_tie[slot] = tie;
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t n_rec = s.n_rec;
+    int np2 = 1;
+    while ((uint32_t)np2 < n_rec) np2 <<= 1;
+    for (int i = n_rec + tid; i < np2; i += nth) {
+        s.rec_key[i] = 0xFFFFFFFFu; s.rec_pos[i] = 0xFFFFFFFFu; s.rec_tie[i] = 0x7FFFFFFFFFFFFFFFll;
+    }
+    sort_records(s, np2);
+    return (int)kk;
+}
+
+// ================================================================================================
+// Step 1b: probe selection for one query per workgroup, from the coarse distance row.
+// Also lays out the query's slice of the R scratch: roff[p] = first slot of probe p, roff[n_probes]
+// = padded candidate count (every cluster padded to a multiple of 64 vectors).
+// ================================================================================================
+__global__ void __launch_bounds__(SEL_THREADS)
+select_probes_kernel(const float* __restrict__ D, int n_lists, int n_probes,
+                     const uint32_t* __restrict__ list_sizes,
+                     uint32_t* __restrict__ probes, float* __restrict__ probe_dists,
+                     uint32_t* __restrict__ roff) {
+    __shared__ SelectShared s;
+    const int q = blockIdx.x;
+    const float* row = D + (size_t)q * n_lists;
+    auto key_of = [&](uint32_t i) { return __float_as_uint(row[i]); };
+    auto tie_of = [&](uint32_t i) { return (long long)i; };
+    int got = block_select_smallest(s, (uint32_t)n_lists, (uint32_t)n_probes, key_of, tie_of);
+    for (int p = threadIdx.x; p < got; p += blockDim.x) {
+        probes[(size_t)q * n_probes + p] = s.rec_pos[p];
+        if (probe_dists) probe_dists[(size_t)q * n_probes + p] = __uint_as_float(s.rec_key[p]);
+    }
+    if (roff && threadIdx.x == 0) {
+        uint32_t at = 0;
+        for (int p = 0; p < got; ++p) {
+            roff[(size_t)q * (n_probes + 1) + p] = at;
+            at += (list_sizes[s.rec_pos[p]] + 63u) & ~63u;
+        }
+        roff[(size_t)q * (n_probes + 1) + got] = at;
+    }
+}
+
+// Same layout step for caller-given probes.
+__global__ void __launch_bounds__(256)
+layout_probes_kernel(const uint32_t* __restrict__ probes_in, int nq, int n_probes, int n_lists,
+                     const uint32_t* __restrict__ list_sizes,
+                     uint32_t* __restrict__ probes, uint32_t* __restrict__ roff) {
+    int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= nq) return;
+    uint32_t at = 0;
+    for (int p = 0; p < n_probes; ++p) {
+        uint32_t l = probes_in[(size_t)q * n_probes + p];
+        probes[(size_t)q * n_probes + p] = l;
+        roff[(size_t)q * (n_probes + 1) + p] = at;
+        if (l < (uint32_t)n_lists) at += (list_sizes[l] + 63u) & ~63u;   // an out-of-range entry is skipped
+    }
+    roff[(size_t)q * (n_probes + 1) + n_probes] = at;
+}
+
+// ================================================================================================
+// Steps 2-4: residual, lookup table in LDS, code scan.
+// ================================================================================================
+template <int LUT> struct LutTraits;
+template <> struct LutTraits<IVFPQ_LUT_FP32> { static constexpr int bytes = 4; };
+template <> struct LutTraits<IVFPQ_LUT_FP16> { static constexpr int bytes = 2; };
+template <> struct LutTraits<IVFPQ_LUT_FP8_E5M3> { static constexpr int bytes = 1; };
+
+// FP32 -> e5m3 (Sec. II): clamp the bit pattern, as a signed integer, to the codes' range, subtract
+// the exponent-bias difference (112 << 23) less half an 8-bit ulp (so that the shift rounds to
+// nearest, ties up), shift the 8 surviving bits down.
+__device__ inline uint32_t e5m3_from_f32(float x) {
+    int b = __float_as_int(x);
+    b = min(max(b, 0x38000000), 0x47F00000);
+    return (uint32_t)(b - 0x37F80000) >> 20;
+}
+// e5m3 -> FP32 (Sec. II): shift the code into the exponent/mantissa field, add the bias difference.
+__device__ inline float e5m3_to_f32(uint32_t b) { return __uint_as_float((b << 20) + 0x38000000u); }
+
+// IEEE half, round to nearest even, saturating at the largest finite half.
+__device__ inline uint32_t half_bits_from_f32(float x) {
+    float c = x > 65504.0f ? 65504.0f : x;
+    return (uint32_t)__half_as_ushort(__float2half_rn(c));
+}
+
+// One table entry: sum over the sub-vector, left to right, of (cb - rq)^2 with one rounding per
+// step (subtract, then fused multiply-add into the running sum).
+template <int M>
+__device__ inline float lut_entry(const float* cbv, const float* rq) {
+    float acc = 0.f;
+#pragma unroll
+    for (int t = 0; t < M; ++t) {
+        float diff = cbv[t] - rq[t];
+        acc = __builtin_fmaf(diff, diff, acc);
+    }
+    return acc;
+}
+
+template <int LUT>
+__device__ inline void store4(unsigned char* lut, int e, const float f[4]) {
+    if constexpr (LUT == IVFPQ_LUT_FP32) {
+        *reinterpret_cast<float4*>(lut + (size_t)e * 4) = make_float4(f[0], f[1], f[2], f[3]);
+    } else if constexpr (LUT == IVFPQ_LUT_FP16) {
+        uint2 v;
+        v.x = half_bits_from_f32(f[0]) | (half_bits_from_f32(f[1]) << 16);
+        v.y = half_bits_from_f32(f[2]) | (half_bits_from_f32(f[3]) << 16);
+        *reinterpret_cast<uint2*>(lut + (size_t)e * 2) = v;
+    } else {
+        uint32_t v = e5m3_from_f32(f[0]) | (e5m3_from_f32(f[1]) << 8) | (e5m3_from_f32(f[2]) << 16) |
+                     (e5m3_from_f32(f[3]) << 24);
+        *reinterpret_cast<uint32_t*>(lut + e) = v;
+    }
+}
+
+// Builds F[pq_dim][ksub] in LDS.  Every thread handles 4 consecutive entries of one sub-space per
+// step (ksub is 16 or 256, so 4 consecutive entries never straddle sub-spaces).
+// codebooks: global [pq_dim][ksub][M]; rq: LDS [pq_dim*M].
+template <int LUT, int M>
+__device__ inline void build_lut(const float* __restrict__ codebooks, const float* rq, int n_entries,
+                                 int bits, int m_runtime, unsigned char* lut) {
+    for (int e = threadIdx.x * 4; e < n_entries; e += blockDim.x * 4) {
+        const int j = e >> bits;
+        float f[4];
+        if constexpr (M > 0) {
+            float r[M];
+#pragma unroll
+            for (int t = 0; t < M; ++t) r[t] = rq[j * M + t];
+            float cbv[4 * M];
+            const float4* src = reinterpret_cast<const float4*>(codebooks + (size_t)e * M);
+#pragma unroll
+            for (int v = 0; v < M; ++v) {
+                float4 x = src[v];
+                cbv[4 * v] = x.x; cbv[4 * v + 1] = x.y; cbv[4 * v + 2] = x.z; cbv[4 * v + 3] = x.w;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) f[u] = lut_entry<M>(cbv + u * M, r);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float* cbv = codebooks + (size_t)(e + u) * m_runtime;
+                float acc = 0.f;
+                for (int t = 0; t < m_runtime; ++t) {
+                    float diff = cbv[t] - rq[j * m_runtime + t];
+                    acc = __builtin_fmaf(diff, diff, acc);
+                }
+                f[u] = acc;
+            }
+        }
+        store4<LUT>(lut, e, f);
+    }
+}
+
+template <int LUT>
+__device__ inline void build_lut_any_m(const float* __restrict__ codebooks, const float* rq, int n_entries,
+                                       int bits, int m, unsigned char* lut) {
+    switch (m) {
+        case 1: build_lut<LUT, 1>(codebooks, rq, n_entries, bits, m, lut); break;
+        case 2: build_lut<LUT, 2>(codebooks, rq, n_entries, bits, m, lut); break;
+        case 4: build_lut<LUT, 4>(codebooks, rq, n_entries, bits, m, lut); break;
+        default: build_lut<LUT, 0>(codebooks, rq, n_entries, bits, m, lut); break;
+    }
+}
+
+template <int LUT>
+__device__ inline float lut_get(const unsigned char* lut, uint32_t idx) {
+    if constexpr (LUT == IVFPQ_LUT_FP32) return reinterpret_cast<const float*>(lut)[idx];
+    else if constexpr (LUT == IVFPQ_LUT_FP16) return __half2float(reinterpret_cast<const __half*>(lut)[idx]);
+    else return e5m3_to_f32(lut[idx]);
+}
+
+// adds the table entries selected by the 4 code bytes of `w` (sub-spaces row0.. in ascending order)
+template <int LUT, int BITS>
+__device__ inline float add_word(float acc, const unsigned char* lut, uint32_t w, int row0) {
+    if constexpr (BITS == 8) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            uint32_t code = (w >> (8 * b)) & 255u;
+            acc += lut_get<LUT>(lut, (uint32_t)(row0 + b) * 256u + code);
+        }
+    } else {
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            uint32_t code = (w >> (4 * b)) & 15u;
+            acc += lut_get<LUT>(lut, (uint32_t)(row0 + b) * 16u + code);
+        }
+    }
+    return acc;
+}
+
+struct ScanArgs {
+    const float* queries;         // [nq][d] (tile base)
+    const float* centroids;
+    const float* codebooks;
+    const uint32_t* list_sizes;
+    const int64_t* group_offsets;
+    const uint8_t* codes;
+    const uint32_t* probes;       // [nq][n_probes]; unused in single-list mode
+    const uint32_t* roff;         // [nq][n_probes+1]
+    float* R;                     // [nq][stride]
+    size_t stride;
+    int n_probes;
+    int n_lists;
+    int d, pq_dim, m, bits;
+    int n_chunks;                 // chunks per vector (code_bytes / CW)
+    int single_list;              // >= 0: scan this cluster for query 0, R written from offset 0
+};
+
+// Code layout of one cluster (written by ivfpq_upload): vectors in groups of 64 (the last one
+// zero-padded); inside a group, chunk c of all 64 vectors is contiguous:
+//   byte address = ((group * n_chunks + c) * 64 + lane) * CW
+// so one wave-wide load of chunk c reads 64*CW contiguous bytes.
+template <int LUT, int BITS, int CW, int NCH>
+__global__ void __launch_bounds__(1024)
+scan_kernel(ScanArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int ksub = 1 << BITS;
+    const int n_entries = a.pq_dim * ksub;
+    unsigned char* lut = smem;
+    float* rq = reinterpret_cast<float*>(smem + (((size_t)n_entries * LutTraits<LUT>::bytes + 15) & ~(size_t)15));
+
+    int q, l;
+    float* Rout;
+    if (a.single_list >= 0) {
+        q = 0; l = a.single_list; Rout = a.R;
+    } else {
+        q = blockIdx.x / a.n_probes;
+        const int slot = blockIdx.x - q * a.n_probes;
+        l = (int)a.probes[(size_t)q * a.n_probes + slot];
+        Rout = a.R + (size_t)q * a.stride + a.roff[(size_t)q * (a.n_probes + 1) + slot];
+    }
+    if ((uint32_t)l >= (uint32_t)a.n_lists) return;   // caller-given probe out of range: nothing to scan
+    const uint32_t len = a.list_sizes[l];
+    if (len == 0) return;
+    const int n_groups = (int)((len + 63u) >> 6);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const int nch = NCH > 0 ? NCH : a.n_chunks;
+    const uint8_t* codes_l = a.codes + (size_t)a.group_offsets[l] * 64 * ((size_t)nch * CW);
+
+    using chunk_t = typename std::conditional<CW == 16, uint4, uint32_t>::type;
+    const chunk_t* cbase = reinterpret_cast<const chunk_t*>(codes_l);
+
+    // issue the loads of this wave's first group before the table is built: HBM latency overlaps it
+    constexpr int NBUF = NCH > 0 ? NCH : 1;
+    chunk_t cur[NBUF];
+    int g = wave;
+    if constexpr (NCH > 0) {
+        if (g < n_groups) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) cur[c] = cbase[((size_t)g * NCH + c) * 64 + lane];
+        }
+    }
+
+    // step 2: residual of the query against this cluster's centroid
+    for (int t = threadIdx.x; t < a.d; t += blockDim.x)
+        rq[t] = a.queries[(size_t)q * a.d + t] - a.centroids[(size_t)l * a.d + t];
+    __syncthreads();
+    // step 3: the table
+    build_lut_any_m<LUT>(a.codebooks, rq, n_entries, BITS, a.m, lut);
+    __syncthreads();
+
+    // step 4: Eq. (1), one lane per coded vector, sub-spaces in ascending order
+    constexpr int ROWS_PER_WORD = BITS == 8 ? 4 : 8;
+    while (g < n_groups) {
+        float acc = 0.f;
+        const int gn = g + n_waves;
+        if constexpr (NCH > 0) {
+            chunk_t nxt[NBUF];
+            if (gn < n_groups) {
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) nxt[c] = cbase[((size_t)gn * NCH + c) * 64 + lane];
+            }
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                if constexpr (CW == 16) {
+                    const uint32_t w[4] = {cur[c].x, cur[c].y, cur[c].z, cur[c].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc = add_word<LUT, BITS>(acc, lut, w[i], (c * 4 + i) * ROWS_PER_WORD);
+                } else {
+                    acc = add_word<LUT, BITS>(acc, lut, cur[c], c * ROWS_PER_WORD);
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) cur[c] = nxt[c];
+        } else {
+            for (int c = 0; c < nch; ++c) {
+                uint32_t w = reinterpret_cast<const uint32_t*>(codes_l)[((size_t)g * nch + c) * 64 + lane];
+                acc = add_word<LUT, BITS>(acc, lut, w, c * ROWS_PER_WORD);
+            }
+        }
+        const uint32_t i = (uint32_t)g * 64u + lane;
+        if (i < len) Rout[i] = acc;
+        else if (a.single_list < 0) Rout[i] = __uint_as_float(kPadKey);   // padding slot of the R scratch
+        g = gn;
+    }
+}
+
+// Steps 2-3 only: the table of one pair, copied out of LDS byte for byte.
+template <int LUT>
+__global__ void __launch_bounds__(256)
+dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centroid,
+                const float* __restrict__ codebooks, int d, int pq_dim, int m, int bits,
+                unsigned char* __restrict__ out) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int n_entries = pq_dim << bits;
+    const size_t lut_bytes = (size_t)n_entries * LutTraits<LUT>::bytes;
+    unsigned char* lut = smem;
+    float* rq = reinterpret_cast<float*>(smem + ((lut_bytes + 15) & ~(size_t)15));
+    for (int t = threadIdx.x; t < d; t += blockDim.x) rq[t] = query[t] - centroid[t];
+    __syncthreads();
+    build_lut_any_m<LUT>(codebooks, rq, n_entries, bits, m, lut);
+    __syncthreads();
+    for (size_t i = threadIdx.x; i < lut_bytes / 4; i += blockDim.x)
+        reinterpret_cast<uint32_t*>(out)[i] = reinterpret_cast<const uint32_t*>(lut)[i];
+}
+
+// ================================================================================================
+// Step 5: per query, the k smallest R over all probed clusters, ordered by (R, id).
+// ================================================================================================
+__global__ void __launch_bounds__(SEL_THREADS)
+topk_kernel(const float* __restrict__ R, size_t stride, const uint32_t* __restrict__ roff,
+            const uint32_t* __restrict__ probes, int n_probes, int k,
+            const int64_t* __restrict__ list_offsets, const int64_t* __restrict__ ids,
+            int64_t* __restrict__ out_ids, float* __restrict__ out_dists) {
+    __shared__ SelectShared s;
+    __shared__ uint32_t s_roff[IVFPQ_MAX_PROBES + 1];
+    __shared__ uint32_t s_probe[IVFPQ_MAX_PROBES];
+    const int q = blockIdx.x;
+    for (int p = threadIdx.x; p <= n_probes; p += blockDim.x) s_roff[p] = roff[(size_t)q * (n_probes + 1) + p];
+    for (int p = threadIdx.x; p < n_probes; p += blockDim.x) s_probe[p] = probes[(size_t)q * n_probes + p];
+    __syncthreads();
+    const uint32_t n = s_roff[n_probes];
+    const uint32_t* row = reinterpret_cast<const uint32_t*>(R + (size_t)q * stride);
+    auto key_of = [&](uint32_t i) { return row[i]; };
+    auto tie_of = [&](uint32_t i) -> long long {
+        if (row[i] == kPadKey) return 0x7FFFFFFFFFFFFFFFll;
+        int lo = 0, hi = n_probes;            // largest slot with s_roff[slot] <= i
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if (s_roff[mid] <= i) lo = mid; else hi = mid;
+        }
+        return (long long)ids[list_offsets[s_probe[lo]] + (int64_t)(i - s_roff[lo])];
+    };
+    const int got = block_select_smallest(s, n, (uint32_t)k, key_of, tie_of);
+    for (int j = threadIdx.x; j < k; j += blockDim.x) {
+        int64_t id = -1;
+        float dist = __uint_as_float(0x7F800000u);
+        if (j < got && s.rec_key[j] != kPadKey) { id = (int64_t)s.rec_tie[j]; dist = __uint_as_float(s.rec_key[j]); }
+        out_ids[(size_t)q * k + j] = id;
+        out_dists[(size_t)q * k + j] = dist;
+    }
+}
+
+// ================================================================================================
+// Host side
+// ================================================================================================
+struct ImageLayout {
+    size_t centroids, codebooks, list_offsets, list_sizes, group_offsets, codes, ids, total;
+};
+
+int chunk_width(const ivfpq_index* idx) {
+    int cb = idx->code_bytes();
+    return (cb % 16 == 0 && cb / 16 <= 4) ? 16 : 4;
+}
+
+ImageLayout image_layout(const ivfpq_index* idx) {
+    ImageLayout L{};
+    size_t at = 0;
+    auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
+    L.centroids = take(idx->centroids.size() * sizeof(float));
+    L.codebooks = take(idx->codebooks.size() * sizeof(float));
+    L.list_offsets = take(((size_t)idx->n_lists + 1) * sizeof(int64_t));
+    L.list_sizes = take((size_t)idx->n_lists * sizeof(uint32_t));
+    L.group_offsets = take(((size_t)idx->n_lists + 1) * sizeof(int64_t));
+    L.codes = take((size_t)idx->total_groups * 64 * idx->code_bytes());
+    L.ids = take((size_t)idx->n * sizeof(int64_t));
+    L.total = at == 0 ? kAlign : at;
+    return L;
+}
+
+struct Plan {
+    int64_t tile;           // queries per tile
+    size_t stride;          // R slots per query
+    size_t probes, probe_d, roff, D, R, total;
+};
+
+constexpr size_t kScratchTarget = (size_t)1 << 30;   // aim for about 1 GiB of R + D per tile
+
+// given_probes: the caller chooses the clusters and may name one several times, so the bound on a
+// query's candidates is n_probes times the largest cluster rather than the n_probes largest ones
+int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_probes, Plan* plan) {
+    const bool need_D = !given_probes;
+    int64_t stride = given_probes
+        ? (int64_t)n_probes * (idx->sorted_padded_sizes.empty() ? 0 : idx->sorted_padded_sizes[0])
+        : idx->max_padded_candidates(n_probes);
+    if (stride >= ((int64_t)1 << 31))
+        return fail(IVFPQ_EUNSUPPORTED, "a query may see %lld candidates (limit 2^31)", (long long)stride);
+    if (stride < 64) stride = 64;
+    size_t per_query = (size_t)stride * 4 + (need_D ? (size_t)idx->n_lists * 4 : 0);
+    int64_t tile = (int64_t)(kScratchTarget / per_query);
+    tile = std::max<int64_t>(1, std::min<int64_t>(tile, std::max<int64_t>(nq, 1)));
+    plan->tile = tile;
+    plan->stride = (size_t)stride;
+    size_t at = 0;
+    auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
+    plan->probes = take((size_t)tile * n_probes * 4);
+    plan->probe_d = take((size_t)tile * n_probes * 4);
+    plan->roff = take((size_t)tile * (n_probes + 1) * 4);
+    plan->D = take(need_D ? (size_t)tile * idx->n_lists * 4 : 0);
+    plan->R = take((size_t)tile * stride * 4);
+    plan->total = at;
+    return IVFPQ_OK;
+}
+
+int check_search_args(const ivfpq_index* idx, const void* q, int64_t nq, int32_t n_probes, int32_t k,
+                      int32_t lut_dtype, bool need_k) {
+    if (!idx) return fail(IVFPQ_EINVAL, "null index");
+    if (nq < 0) return fail(IVFPQ_EINVAL, "nq=%lld", (long long)nq);
+    if (nq > 0 && !q) return fail(IVFPQ_EINVAL, "null queries");
+    if (n_probes < 1 || n_probes > idx->n_lists || n_probes > IVFPQ_MAX_PROBES)
+        return fail(IVFPQ_EINVAL, "n_probes=%d outside [1, min(n_lists=%d, %d)]", n_probes, idx->n_lists, IVFPQ_MAX_PROBES);
+    if (need_k && (k < 1 || k > IVFPQ_MAX_K)) return fail(IVFPQ_EINVAL, "k=%d outside [1, %d]", k, IVFPQ_MAX_K);
+    if (lut_dtype < 0 || lut_dtype > 2) return fail(IVFPQ_EINVAL, "unknown lut_dtype %d", lut_dtype);
+    return IVFPQ_OK;
+}
+
+size_t lut_elem_bytes(int lut_dtype) { return lut_dtype == IVFPQ_LUT_FP32 ? 4 : (lut_dtype == IVFPQ_LUT_FP16 ? 2 : 1); }
+
+size_t scan_lds_bytes(const ivfpq_index* idx, int lut_dtype) {
+    size_t lut = (size_t)idx->pq_dim * idx->ksub() * lut_elem_bytes(lut_dtype);
+    return ((lut + 15) & ~(size_t)15) + (size_t)idx->d * 4;
+}
+
+int check_device(const ivfpq_index* idx) {
+    if (!idx->dev.valid) return fail(IVFPQ_ESTATE, "index has no device image: call ivfpq_upload first");
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != idx->dev.device)
+        return fail(IVFPQ_ESTATE, "index was uploaded to device %d, current device is %d", idx->dev.device, dev);
+    return IVFPQ_OK;
+}
+
+int scan_threads(const ivfpq_index* idx, int lut_dtype) {
+    if (const char* env = std::getenv("IVFPQ_SCAN_THREADS")) {
+        int v = std::atoi(env);
+        if (v == 64 || v == 128 || v == 256 || v == 512 || v == 1024) return v;
+    }
+    size_t lds = scan_lds_bytes(idx, lut_dtype);
+    if (lds <= 20 * 1024) return 256;
+    if (lds <= 40 * 1024) return 512;
+    return 1024;
+}
+
+template <int LUT, int BITS>
+int launch_scan_bits(const ScanArgs& a, int cw, int nch, dim3 grid, int threads, size_t lds, hipStream_t st) {
+    auto go = [&](auto kernel) -> int {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, st, a);
+        HIP_TRY(hipGetLastError());
+        return IVFPQ_OK;
+    };
+    if (cw == 16) {
+        switch (nch) {
+            case 1: return go(scan_kernel<LUT, BITS, 16, 1>);
+            case 2: return go(scan_kernel<LUT, BITS, 16, 2>);
+            case 3: return go(scan_kernel<LUT, BITS, 16, 3>);
+            case 4: return go(scan_kernel<LUT, BITS, 16, 4>);
+            default: break;
+        }
+        return fail(IVFPQ_EUNSUPPORTED, "internal: no scan kernel for %d chunks of 16 bytes", nch);
+    }
+    return go(scan_kernel<LUT, BITS, 4, 0>);
+}
+
+int launch_scan(const ivfpq_index* idx, ScanArgs a, int lut_dtype, dim3 grid, hipStream_t st) {
+    const size_t lds = scan_lds_bytes(idx, lut_dtype);
+    if (lds > kLdsBytes)
+        return fail(IVFPQ_EUNSUPPORTED, "lookup table + residual need %zu bytes of LDS (limit %zu)", lds, kLdsBytes);
+    const int cw = chunk_width(idx);
+    const int nch = idx->code_bytes() / cw;
+    a.n_chunks = nch;
+    const int threads = scan_threads(idx, lut_dtype);
+    const bool b8 = idx->pq_bits == 8;
+    switch (lut_dtype) {
+        case IVFPQ_LUT_FP32:
+            return b8 ? launch_scan_bits<IVFPQ_LUT_FP32, 8>(a, cw, nch, grid, threads, lds, st)
+                      : launch_scan_bits<IVFPQ_LUT_FP32, 4>(a, cw, nch, grid, threads, lds, st);
+        case IVFPQ_LUT_FP16:
+            return b8 ? launch_scan_bits<IVFPQ_LUT_FP16, 8>(a, cw, nch, grid, threads, lds, st)
+                      : launch_scan_bits<IVFPQ_LUT_FP16, 4>(a, cw, nch, grid, threads, lds, st);
+        default:
+            return b8 ? launch_scan_bits<IVFPQ_LUT_FP8_E5M3, 8>(a, cw, nch, grid, threads, lds, st)
+                      : launch_scan_bits<IVFPQ_LUT_FP8_E5M3, 4>(a, cw, nch, grid, threads, lds, st);
+    }
+}
+
+ScanArgs base_scan_args(const ivfpq_index* idx) {
+    ScanArgs a{};
+    a.centroids = idx->dev.centroids;
+    a.codebooks = idx->dev.codebooks;
+    a.list_sizes = idx->dev.list_sizes;
+    a.group_offsets = idx->dev.group_offsets;
+    a.codes = idx->dev.codes;
+    a.d = idx->d; a.pq_dim = idx->pq_dim; a.m = idx->m(); a.bits = idx->pq_bits;
+    a.n_lists = idx->n_lists;
+    a.single_list = -1;
+    return a;
+}
+
+// ---- stage timing ----
+int timing_mark(ivfpq_index* idx, hipStream_t st, void** out) {
+    if (idx->events_used == idx->event_pool.size()) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        idx->event_pool.push_back((void*)e);
+    }
+    hipEvent_t e = (hipEvent_t)idx->event_pool[idx->events_used++];
+    HIP_TRY(hipEventRecord(e, st));
+    *out = (void*)e;
+    return IVFPQ_OK;
+}
+
+struct StageTimer {
+    ivfpq_index* idx; hipStream_t st; int stage; void* a = nullptr; bool on;
+    StageTimer(ivfpq_index* i, hipStream_t s, int stage_) : idx(i), st(s), stage(stage_), on(i->timing) {}
+    int begin() { return on ? timing_mark(idx, st, &a) : IVFPQ_OK; }
+    int end() {
+        if (!on) return IVFPQ_OK;
+        void* b = nullptr;
+        if (int s = timing_mark(idx, st, &b)) return s;
+        idx->spans.push_back({a, b, stage});
+        return IVFPQ_OK;
+    }
+};
+
+int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint32_t* d_probes_in,
+                int32_t n_probes, int32_t k, int32_t lut_dtype, int64_t* d_ids, float* d_dists,
+                void* d_ws, size_t ws_bytes, void* hip_stream) {
+    if (int s = check_search_args(idx, d_queries, nq, n_probes, k, lut_dtype, true)) return s;
+    if (nq > 0 && (!d_ids || !d_dists)) return fail(IVFPQ_EINVAL, "null output pointer");
+    if (int s = check_device(idx)) return s;
+    if (nq == 0) return IVFPQ_OK;
+    Plan plan;
+    if (int s = make_plan(idx, nq, n_probes, d_probes_in != nullptr, &plan)) return s;
+    if (!d_ws || ws_bytes < plan.total)
+        return fail(IVFPQ_ENOSPACE, "workspace of %zu bytes given, %zu needed", ws_bytes, plan.total);
+    if (scan_lds_bytes(idx, lut_dtype) > kLdsBytes)
+        return fail(IVFPQ_EUNSUPPORTED, "lookup table + residual need %zu bytes of LDS (limit %zu)",
+                    scan_lds_bytes(idx, lut_dtype), kLdsBytes);
+    hipStream_t st = (hipStream_t)hip_stream;
+    unsigned char* ws = (unsigned char*)d_ws;
+    uint32_t* w_probes = (uint32_t*)(ws + plan.probes);
+    float* w_probe_d = (float*)(ws + plan.probe_d);
+    uint32_t* w_roff = (uint32_t*)(ws + plan.roff);
+    float* w_D = (float*)(ws + plan.D);
+    float* w_R = (float*)(ws + plan.R);
+
+    if (idx->timing) { idx->events_used = 0; idx->spans.clear(); idx->stage_valid = true; }
+    StageTimer whole(idx, st, 3);
+    if (int s = whole.begin()) return s;
+    for (int64_t q0 = 0; q0 < nq; q0 += plan.tile) {
+        const int tq = (int)std::min<int64_t>(plan.tile, nq - q0);
+        const float* qt = d_queries + (size_t)q0 * idx->d;
+        // step 1
+        StageTimer t0(idx, st, 0);
+        if (int s = t0.begin()) return s;
+        if (!d_probes_in) {
+            dim3 grid((idx->n_lists + CT - 1) / CT, (tq + CT - 1) / CT);
+            hipLaunchKernelGGL(coarse_dist_kernel, grid, dim3(256), 0, st, qt, idx->dev.centroids, tq,
+                               idx->n_lists, idx->d, w_D);
+            HIP_TRY(hipGetLastError());
+            hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_D, idx->n_lists,
+                               n_probes, idx->dev.list_sizes, w_probes, w_probe_d, w_roff);
+            HIP_TRY(hipGetLastError());
+        } else {
+            hipLaunchKernelGGL(layout_probes_kernel, dim3((tq + 255) / 256), dim3(256), 0, st,
+                               d_probes_in + (size_t)q0 * n_probes, tq, n_probes, idx->n_lists, idx->dev.list_sizes,
+                               w_probes, w_roff);
+            HIP_TRY(hipGetLastError());
+        }
+        if (int s = t0.end()) return s;
+        // steps 2-4
+        StageTimer t1(idx, st, 1);
+        if (int s = t1.begin()) return s;
+        ScanArgs a = base_scan_args(idx);
+        a.queries = qt; a.probes = w_probes; a.roff = w_roff; a.R = w_R; a.stride = plan.stride;
+        a.n_probes = n_probes;
+        if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)((size_t)tq * n_probes)), st)) return s;
+        if (int s = t1.end()) return s;
+        // step 5
+        StageTimer t2(idx, st, 2);
+        if (int s = t2.begin()) return s;
+        hipLaunchKernelGGL(topk_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_R, plan.stride, w_roff, w_probes,
+                           n_probes, k, idx->dev.list_offsets, idx->dev.ids, d_ids + (size_t)q0 * k,
+                           d_dists + (size_t)q0 * k);
+        HIP_TRY(hipGetLastError());
+        if (int s = t2.end()) return s;
+    }
+    if (int s = whole.end()) return s;
+    return IVFPQ_OK;
+}
+
+}  // namespace
+
+namespace ivfpq {
+void release_device_state(ivfpq_index* idx) {
+    for (void* e : idx->event_pool) (void)hipEventDestroy((hipEvent_t)e);
+    idx->event_pool.clear();
+}
+}  // namespace ivfpq
+
+extern "C" {
+
+size_t ivfpq_device_bytes(const ivfpq_index_t* index) {
+    if (!index) { set_error("ivfpq_device_bytes: null index"); return 0; }
+    return image_layout(index).total;
+}
+
+int ivfpq_upload(ivfpq_index_t* idx, void* d_buf, size_t bytes, void* hip_stream) {
+    if (!idx || !d_buf) return fail(IVFPQ_EINVAL, "ivfpq_upload: null pointer");
+    const ImageLayout L = image_layout(idx);
+    if (bytes < L.total) return fail(IVFPQ_ENOSPACE, "device buffer of %zu bytes given, %zu needed", bytes, L.total);
+    if (((uintptr_t)d_buf % kAlign) != 0) return fail(IVFPQ_EINVAL, "device buffer must be %zu-byte aligned", kAlign);
+    hipStream_t st = (hipStream_t)hip_stream;
+    unsigned char* base = (unsigned char*)d_buf;
+    const int cb = idx->code_bytes(), cw = chunk_width(idx), nch = cb / cw;
+
+    std::vector<uint32_t> sizes((size_t)idx->n_lists);
+    std::vector<int64_t> goff((size_t)idx->n_lists + 1, 0);
+    for (int l = 0; l < idx->n_lists; ++l) {
+        int64_t len = idx->list_offsets[l + 1] - idx->list_offsets[l];
+        sizes[l] = (uint32_t)len;
+        goff[l + 1] = goff[l] + (len + 63) / 64;
+    }
+    // interleave the codes, one cluster at a time, through a bounded staging buffer
+    HIP_TRY(hipMemcpyAsync(base + L.centroids, idx->centroids.data(), idx->centroids.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(base + L.codebooks, idx->codebooks.data(), idx->codebooks.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(base + L.list_offsets, idx->list_offsets.data(), idx->list_offsets.size() * 8, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(base + L.list_sizes, sizes.data(), sizes.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(base + L.group_offsets, goff.data(), goff.size() * 8, hipMemcpyHostToDevice, st));
+    if (idx->n > 0)
+        HIP_TRY(hipMemcpyAsync(base + L.ids, idx->ids.data(), idx->ids.size() * 8, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+
+    const size_t group_bytes = (size_t)64 * cb;
+    const size_t stage_groups = std::max<size_t>(1, ((size_t)256 << 20) / group_bytes);
+    std::vector<uint8_t> stage;
+    int64_t g_done = 0;
+    while (g_done < idx->total_groups) {
+        const int64_t g_end = std::min<int64_t>(idx->total_groups, g_done + (int64_t)stage_groups);
+        stage.assign((size_t)(g_end - g_done) * group_bytes, 0);
+        // clusters overlapping [g_done, g_end)
+        int l_first = (int)(std::upper_bound(goff.begin(), goff.end(), g_done) - goff.begin()) - 1;
+        for (int l = l_first; l < idx->n_lists; ++l) {
+            if (goff[l] >= g_end) continue;
+            const int64_t lo = idx->list_offsets[l], len = idx->list_offsets[l + 1] - lo;
+            for (int64_t g = std::max(goff[l], g_done); g < std::min(goff[l + 1], g_end); ++g) {
+                uint8_t* dst = stage.data() + (size_t)(g - g_done) * group_bytes;
+                const int64_t first = (g - goff[l]) * 64;
+                for (int v = 0; v < 64 && first + v < len; ++v) {
+                    const uint8_t* src = &idx->codes[(size_t)(lo + first + v) * cb];
+                    for (int c = 0; c < nch; ++c)
+                        std::memcpy(dst + ((size_t)c * 64 + v) * cw, src + (size_t)c * cw, (size_t)cw);
+                }
+            }
+        }
+        HIP_TRY(hipMemcpy(base + L.codes + (size_t)g_done * group_bytes, stage.data(), stage.size(), hipMemcpyHostToDevice));
+        g_done = g_end;
+    }
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    idx->dev.valid = true;
+    idx->dev.device = dev;
+    idx->dev.centroids = (const float*)(base + L.centroids);
+    idx->dev.codebooks = (const float*)(base + L.codebooks);
+    idx->dev.list_offsets = (const int64_t*)(base + L.list_offsets);
+    idx->dev.list_sizes = (const uint32_t*)(base + L.list_sizes);
+    idx->dev.group_offsets = (const int64_t*)(base + L.group_offsets);
+    idx->dev.codes = (const uint8_t*)(base + L.codes);
+    idx->dev.ids = (const int64_t*)(base + L.ids);
+    return IVFPQ_OK;
+}
+
+size_t ivfpq_search_workspace_bytes(const ivfpq_index_t* index, int64_t nq, int32_t n_probes, int32_t k,
+                                    int32_t lut_dtype) {
+    (void)k; (void)lut_dtype;
+    if (!index || n_probes < 1 || nq < 0) { set_error("ivfpq_search_workspace_bytes: bad arguments"); return 0; }
+    Plan own, given;   // large enough for ivfpq_search and for ivfpq_search_with_probes
+    if (make_plan(index, nq, n_probes, false, &own) != IVFPQ_OK) return 0;
+    if (make_plan(index, nq, n_probes, true, &given) != IVFPQ_OK) return 0;
+    return std::max(own.total, given.total);
+}
+
+int ivfpq_search(const ivfpq_index_t* index, const float* d_queries, int64_t nq, int32_t n_probes, int32_t k,
+                 int32_t lut_dtype, int64_t* d_ids, float* d_dists, void* d_workspace, size_t workspace_bytes,
+                 void* hip_stream) {
+    return search_impl(const_cast<ivfpq_index_t*>(index), d_queries, nq, nullptr, n_probes, k, lut_dtype, d_ids,
+                       d_dists, d_workspace, workspace_bytes, hip_stream);
+}
+
+int ivfpq_search_with_probes(const ivfpq_index_t* index, const float* d_queries, int64_t nq,
+                             const uint32_t* d_probes, int32_t n_probes, int32_t k, int32_t lut_dtype,
+                             int64_t* d_ids, float* d_dists, void* d_workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+    if (nq > 0 && !d_probes) return fail(IVFPQ_EINVAL, "ivfpq_search_with_probes: null probes");
+    return search_impl(const_cast<ivfpq_index_t*>(index), d_queries, nq, d_probes, n_probes, k, lut_dtype, d_ids,
+                       d_dists, d_workspace, workspace_bytes, hip_stream);
+}
+
+int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_t nq, int32_t n_probes,
+                        uint32_t* d_probes, float* d_probe_dists, void* d_workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+    if (int s = check_search_args(idx, d_queries, nq, n_probes, 1, 0, false)) return s;
+    if (nq > 0 && !d_probes) return fail(IVFPQ_EINVAL, "ivfpq_select_probes: null output");
+    if (int s = check_device(idx)) return s;
+    if (nq == 0) return IVFPQ_OK;
+    Plan plan;
+    if (int s = make_plan(idx, nq, n_probes, false, &plan)) return s;
+    if (!d_workspace || workspace_bytes < plan.total)
+        return fail(IVFPQ_ENOSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, plan.total);
+    hipStream_t st = (hipStream_t)hip_stream;
+    float* w_D = (float*)((unsigned char*)d_workspace + plan.D);
+    for (int64_t q0 = 0; q0 < nq; q0 += plan.tile) {
+        const int tq = (int)std::min<int64_t>(plan.tile, nq - q0);
+        dim3 grid((idx->n_lists + CT - 1) / CT, (tq + CT - 1) / CT);
+        hipLaunchKernelGGL(coarse_dist_kernel, grid, dim3(256), 0, st, d_queries + (size_t)q0 * idx->d,
+                           idx->dev.centroids, tq, idx->n_lists, idx->d, w_D);
+        HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_D, idx->n_lists, n_probes,
+                           idx->dev.list_sizes, d_probes + (size_t)q0 * n_probes,
+                           d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr);
+        HIP_TRY(hipGetLastError());
+    }
+    return IVFPQ_OK;
+}
+
+int ivfpq_dump_lut(const ivfpq_index_t* idx, const float* d_query, uint32_t list_id, int32_t lut_dtype,
+                   void* d_lut_out, void* hip_stream) {
+    if (!idx || !d_query || !d_lut_out) return fail(IVFPQ_EINVAL, "ivfpq_dump_lut: null pointer");
+    if (lut_dtype < 0 || lut_dtype > 2) return fail(IVFPQ_EINVAL, "unknown lut_dtype %d", lut_dtype);
+    if (list_id >= (uint32_t)idx->n_lists) return fail(IVFPQ_EINVAL, "list_id %u >= n_lists %d", list_id, idx->n_lists);
+    if (int s = check_device(idx)) return s;
+    const size_t lds = scan_lds_bytes(idx, lut_dtype);
+    if (lds > kLdsBytes) return fail(IVFPQ_EUNSUPPORTED, "lookup table needs %zu bytes of LDS (limit %zu)", lds, kLdsBytes);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const float* centroid = idx->dev.centroids + (size_t)list_id * idx->d;
+    auto go = [&](auto kernel) -> int {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(kernel, dim3(1), dim3(256), lds, st, d_query, centroid, idx->dev.codebooks, idx->d,
+                           idx->pq_dim, idx->m(), idx->pq_bits, (unsigned char*)d_lut_out);
+        HIP_TRY(hipGetLastError());
+        return IVFPQ_OK;
+    };
+    switch (lut_dtype) {
+        case IVFPQ_LUT_FP32: return go(dump_lut_kernel<IVFPQ_LUT_FP32>);
+        case IVFPQ_LUT_FP16: return go(dump_lut_kernel<IVFPQ_LUT_FP16>);
+        default: return go(dump_lut_kernel<IVFPQ_LUT_FP8_E5M3>);
+    }
+}
+
+int ivfpq_scan_list(const ivfpq_index_t* idx, const float* d_query, uint32_t list_id, int32_t lut_dtype,
+                    float* d_R_out, void* hip_stream) {
+    if (!idx || !d_query) return fail(IVFPQ_EINVAL, "ivfpq_scan_list: null pointer");
+    if (lut_dtype < 0 || lut_dtype > 2) return fail(IVFPQ_EINVAL, "unknown lut_dtype %d", lut_dtype);
+    if (list_id >= (uint32_t)idx->n_lists) return fail(IVFPQ_EINVAL, "list_id %u >= n_lists %d", list_id, idx->n_lists);
+    if (int s = check_device(idx)) return s;
+    if (idx->list_offsets[list_id + 1] == idx->list_offsets[list_id]) return IVFPQ_OK;
+    if (!d_R_out) return fail(IVFPQ_EINVAL, "ivfpq_scan_list: null output");
+    ScanArgs a = base_scan_args(idx);
+    a.queries = d_query; a.R = d_R_out; a.single_list = (int)list_id; a.n_probes = 1;
+    return launch_scan(idx, a, lut_dtype, dim3(1), (hipStream_t)hip_stream);
+}
+
+int ivfpq_set_stage_timing(ivfpq_index_t* index, int32_t enabled) {
+    if (!index) return fail(IVFPQ_EINVAL, "null index");
+    index->timing = enabled != 0;
+    index->stage_valid = false;
+    return IVFPQ_OK;
+}
+
+int ivfpq_stage_times_ms(ivfpq_index_t* index, float ms[4]) {
+    if (!index || !ms) return fail(IVFPQ_EINVAL, "null pointer");
+    if (!index->timing || !index->stage_valid) return fail(IVFPQ_ESTATE, "no timed search call recorded");
+    for (int i = 0; i < 4; ++i) ms[i] = 0.f;
+    for (const auto& sp : index->spans) {
+        float t = 0.f;
+        HIP_TRY(hipEventElapsedTime(&t, (hipEvent_t)sp.a, (hipEvent_t)sp.b));
+        ms[sp.stage] += t;
+    }
+    return IVFPQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,82 @@
+// Internal definitions shared by the host-side and device-side halves of libivfpq.
+#pragma once
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "../../include/ivfpq.h"
+
+namespace ivfpq {
+
+// Device image of an index.  All pointers point into the single buffer the caller handed to
+// ivfpq_upload; the library owns none of them.
+struct DeviceImage {
+    bool valid = false;
+    int device = -1;
+    const float* centroids = nullptr;      // [n_lists][d]
+    const float* codebooks = nullptr;      // [pq_dim][ksub][m]
+    const int64_t* list_offsets = nullptr; // [n_lists+1], unpadded vector offsets (into ids)
+    const uint32_t* list_sizes = nullptr;  // [n_lists]
+    const int64_t* group_offsets = nullptr;// [n_lists+1], offsets in 64-vector groups (into codes)
+    const uint8_t* codes = nullptr;        // interleaved, see ivfpq_upload
+    const int64_t* ids = nullptr;          // [n] list order
+};
+
+}  // namespace ivfpq
+
+struct ivfpq_index {
+    int64_t n = 0;
+    int32_t d = 0, n_lists = 0, pq_dim = 0, pq_bits = 0;
+    std::vector<float> centroids;       // [n_lists][d]
+    std::vector<float> codebooks;       // [pq_dim][2^pq_bits][d/pq_dim]
+    std::vector<int64_t> list_offsets;  // [n_lists+1]
+    std::vector<uint8_t> codes;         // [n][code_bytes], list order
+    std::vector<int64_t> ids;           // [n], list order
+
+    // derived at import
+    int64_t total_groups = 0;           // sum over lists of ceil(len/64)
+    int64_t max_candidates = 0;         // filled per (n_probes) query: see max_padded_candidates()
+    std::vector<uint32_t> sorted_padded_sizes;  // padded list lengths, descending
+
+    ivfpq::DeviceImage dev;
+
+    // stage timing (hipEvent_t kept as void* so this header stays free of HIP types)
+    bool timing = false;
+    void* ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    float stage_ms[4] = {0, 0, 0, 0};
+    bool stage_valid = false;
+    struct Span { void* a; void* b; int stage; };
+    std::vector<void*> event_pool;
+    std::vector<Span> spans;
+    size_t events_used = 0;
+
+    int32_t ksub() const { return 1 << pq_bits; }
+    int32_t m() const { return d / pq_dim; }
+    int32_t code_bytes() const { return pq_dim * pq_bits / 8; }
+    // upper bound of (padded) candidates one query can see with n_probes probes
+    int64_t max_padded_candidates(int32_t n_probes) const {
+        int64_t s = 0;
+        for (int32_t i = 0; i < n_probes && i < (int32_t)sorted_padded_sizes.size(); ++i)
+            s += sorted_padded_sizes[i];
+        return s;
+    }
+};
+
+namespace ivfpq {
+
+void set_error(const char* fmt, ...);
+int fail(int status, const char* fmt, ...);
+
+// validates shape parameters common to build and import; returns IVFPQ_OK or sets the error
+int check_shape(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits);
+
+// fills the derived fields after the logical arrays are in place
+void finish_import(ivfpq_index* idx);
+
+// called by ivfpq_free before the handle goes away (destroys HIP events); defined in the device half
+void release_device_state(ivfpq_index* idx);
+
+}  // namespace ivfpq

@@ -1,0 +1,296 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, on the same seeded
+inputs, through the C ABI (ctypes binding).  Every test here needs an MI355X.
+
+Bars (stated here, used below):
+  * table entries for half and e5m3: the stored bytes are identical to the oracle's;
+    the fp32 table too (same fp32 operation order on both sides);
+  * accumulated distances R: within 1e-5 relative (fp32 adds of <= 64 non-negative terms in the
+    same order; the tolerance leaves room for a different summation order);
+  * top-k ids: equal except inside ties within that tolerance; padding identical;
+  * probe lists: same clusters rank by rank, swaps only between clusters whose float64
+    distances agree to 1e-5 relative.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from util_parity import (RTOL, assert_probes_match, assert_topk_matches, oracle_tiny_index, random_pair,
+                         to_library)
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [oracle.LUT_FP32, oracle.LUT_FP16, oracle.LUT_E5M3]
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2301_06672_amd as pkg
+    pkg.lib()
+    assert torch.cuda.is_available()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def tiny(P):
+    w, data, oidx = oracle_tiny_index()
+    return w, data, oidx, to_library(P, oidx)
+
+
+def _step(msg):
+    print(f"[parity] {msg}", flush=True)
+
+
+# ---------------------------------------------------------------- table entries (search steps 2-3)
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_lut_bytes_identical_tiny(P, tiny, dtype):
+    w, data, oidx, gidx = tiny
+    q = si.queries(w, 16)
+    for qi in range(0, 16, 3):
+        for l in (0, 7, 63):
+            _step(f"dump_lut dtype={dtype} q={qi} list={l}")
+            got = gidx.ivfpq_dump_lut(q[qi], l, dtype).cpu().numpy()
+            want, _ = oracle.lut_store(oracle.lut_f32(oidx, q[qi], l), dtype)
+            np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("d,pq_dim,pq_bits", [(32, 32, 8), (32, 16, 8), (32, 8, 8), (48, 16, 8), (24, 8, 4),
+                                              (128, 64, 8), (96, 48, 8), (128, 64, 4), (128, 32, 8)])
+def test_lut_bytes_identical_shapes_and_ranges(P, d, pq_dim, pq_bits):
+    # sub-vector lengths 1, 2, 4 (templated) and 3 (generic); value scales that reach below the
+    # smallest e5m3 value, into the half subnormals, and above the largest half / e5m3 value
+    for scale in (1e-3, 1.0, 300.0):
+        oidx, gidx = random_pair(P, 300, d, 3, pq_dim, pq_bits, salt=100 + d + pq_dim, scale=scale)
+        q = (scale * np.random.default_rng(d).standard_normal(d)).astype(np.float32)
+        for dtype in DTYPES:
+            _step(f"dump_lut d={d} s={pq_dim} p={pq_bits} scale={scale} dtype={dtype}")
+            got = gidx.ivfpq_dump_lut(q, 1, dtype).cpu().numpy()
+            F = oracle.lut_f32(oidx, q, 1)
+            want, _ = oracle.lut_store(F, dtype)
+            np.testing.assert_array_equal(got, want)
+        if scale == 300.0:
+            assert F.max() > 122880.0      # the saturating end was exercised
+        if scale == 1e-3:
+            assert F.min() < 2.0 ** -15     # and the flooring end
+
+
+# ---------------------------------------------------------------- Eq. (1) over one cluster (step 4)
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_scan_list_R_tiny(P, tiny, dtype):
+    w, data, oidx, gidx = tiny
+    q = si.queries(w, 4)
+    sizes = np.diff(oidx.list_offsets)
+    for l in (int(np.argmax(sizes)), int(np.argmin(sizes)), 5):
+        _step(f"scan_list dtype={dtype} list={l} len={sizes[l]}")
+        _, dec = oracle.lut_store(oracle.lut_f32(oidx, q[1], l), dtype)
+        want, _ = oracle.scan_list(oidx, dec, l)
+        got = gidx.ivfpq_scan_list(q[1], l, dtype, int(sizes[l])).cpu().numpy()
+        np.testing.assert_allclose(got, want, rtol=RTOL, atol=0)
+
+
+@pytest.mark.parametrize("d,pq_dim,pq_bits", [(128, 64, 8), (96, 48, 8), (128, 64, 4), (128, 32, 8), (32, 16, 8),
+                                              (24, 24, 8), (24, 8, 4), (160, 80, 8)])
+def test_scan_list_R_code_widths(P, d, pq_dim, pq_bits):
+    # 64/48/32/16-byte codes (16-byte chunk kernels) and 24/4/80-byte codes (generic 4-byte path);
+    # list lengths that span several 64-vector groups with a ragged tail
+    oidx, gidx = random_pair(P, 1500, d, 4, pq_dim, pq_bits, salt=200 + d + pq_bits)
+    q = np.random.default_rng(pq_dim).standard_normal(d).astype(np.float32)
+    sizes = np.diff(oidx.list_offsets)
+    for dtype in DTYPES:
+        for l in range(4):
+            _step(f"scan_list d={d} s={pq_dim} p={pq_bits} dtype={dtype} list={l} len={sizes[l]}")
+            _, dec = oracle.lut_store(oracle.lut_f32(oidx, q, l), dtype)
+            want, _ = oracle.scan_list(oidx, dec, l)
+            got = gidx.ivfpq_scan_list(q, l, dtype, int(sizes[l])).cpu().numpy()
+            np.testing.assert_allclose(got, want, rtol=RTOL, atol=0)
+
+
+# ---------------------------------------------------------------- probe selection (step 1)
+
+@pytest.mark.parametrize("n_probes", [1, 8, 64])
+def test_select_probes_tiny(P, tiny, n_probes):
+    w, data, oidx, gidx = tiny
+    q = si.queries(w, 300)
+    _step(f"select_probes P={n_probes}")
+    probes, pd = gidx.ivfpq_select_probes(q, n_probes)
+    probes = probes.cpu().numpy().view(np.uint32)
+    assert_probes_match(probes, oidx.centroids, q, n_probes)
+    want, want_d = oracle.select_probes(oidx, q, n_probes)
+    np.testing.assert_allclose(pd.cpu().numpy(), want_d, rtol=RTOL)
+    assert (probes == want).mean() > 0.999
+
+
+def test_select_probes_many_lists_and_exact_ties(P):
+    # 3000 clusters (does not fit one pass of anything), 96 dims, duplicated centroids -> exact ties
+    arrays = list(si.random_index_arrays(64, 96, 3000, 48, 8, salt=300))
+    arrays[0][100:110] = arrays[0][50]          # ten copies of centroid 50
+    oidx = oracle.make_index(96, 3000, 48, 8, *arrays)
+    gidx = to_library(P, oidx)
+    rng = np.random.default_rng(300)
+    q = rng.standard_normal((40, 96)).astype(np.float32)
+    q[:5] = arrays[0][50] + 0.01 * rng.standard_normal((5, 96)).astype(np.float32)
+    for n_probes in (5, 200, 1000):
+        _step(f"select_probes L=3000 P={n_probes}")
+        probes, _ = gidx.ivfpq_select_probes(q, n_probes)
+        probes = probes.cpu().numpy().view(np.uint32)
+        assert_probes_match(probes, oidx.centroids, q, n_probes)
+    # the tie group must come out in ascending cluster index
+    probes, _ = gidx.ivfpq_select_probes(q[:5], 11)
+    for row in probes.cpu().numpy().view(np.uint32):
+        np.testing.assert_array_equal(row, [50] + list(range(100, 110)))
+
+
+# ---------------------------------------------------------------- whole search (steps 1-5)
+
+def _search_both(gidx, oidx, q, n_probes, k, dtype):
+    """GPU search; the oracle is run on the GPU's probe lists so that a near-tie in step 1 does not
+    turn into a different (and equally valid) candidate set downstream."""
+    ids_g, d_g = gidx.ivfpq_search(q, n_probes, k, dtype)
+    probes, _ = gidx.ivfpq_select_probes(q, n_probes)
+    probes = probes.cpu().numpy().view(np.uint32)
+    ids_o, d_o = oracle.search(oidx, q, n_probes, k, dtype, probes=probes)
+    return ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_search_tiny_config(P, tiny, dtype):
+    w, data, oidx, gidx = tiny
+    q = si.queries(w)                            # all 1,000 queries of the configuration
+    _step(f"search tiny dtype={dtype}")
+    ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, w.n_probes, w.k, dtype)
+    swapped = assert_topk_matches(ids_g, d_g, ids_o, d_o, context=f"tiny dtype={dtype}")
+    assert swapped <= 0.01 * ids_o.size
+    # and against the oracle's own probe selection: same answer for (nearly) every query
+    ids_oo, _ = oracle.search(oidx, q, w.n_probes, w.k, dtype)
+    assert (ids_oo == ids_g).all(axis=1).mean() > 0.99
+    gt, _ = oracle.exact_knn(data, q[:200], w.k)
+    assert abs(oracle.recall(ids_g[:200], gt) - oracle.recall(ids_oo[:200], gt)) < 1e-3
+
+
+@pytest.mark.parametrize("n_probes,k", [(1, 1), (3, 100), (64, 10), (8, 1024)])
+def test_search_tiny_probe_and_k_range(P, tiny, n_probes, k):
+    w, data, oidx, gidx = tiny
+    q = si.queries(w, 64)
+    for dtype in (oracle.LUT_FP32, oracle.LUT_E5M3):
+        _step(f"search tiny P={n_probes} k={k} dtype={dtype}")
+        ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, n_probes, k, dtype)
+        assert_topk_matches(ids_g, d_g, ids_o, d_o, context=f"P={n_probes} k={k} dtype={dtype}")
+
+
+@pytest.mark.parametrize("d,pq_dim,pq_bits", [(128, 64, 8), (96, 48, 8), (128, 64, 4), (128, 32, 8), (24, 8, 4)])
+def test_search_random_index_ragged_and_empty_lists(P, d, pq_dim, pq_bits):
+    oidx, gidx = random_pair(P, 5000, d, 37, pq_dim, pq_bits, salt=400 + d + pq_bits, empty_lists=(0, 5, 36))
+    q = np.random.default_rng(400).standard_normal((50, d)).astype(np.float32)
+    for dtype in DTYPES:
+        for n_probes, k in ((4, 10), (37, 100)):
+            _step(f"search random d={d} s={pq_dim} p={pq_bits} dtype={dtype} P={n_probes} k={k}")
+            ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, n_probes, k, dtype)
+            assert_topk_matches(ids_g, d_g, ids_o, d_o, context=f"d={d} p={pq_bits} dtype={dtype}")
+
+
+def test_search_fewer_candidates_than_k_pads(P):
+    oidx, gidx = random_pair(P, 70, 32, 9, 16, 8, salt=500, empty_lists=(1, 2))
+    q = np.random.default_rng(500).standard_normal((8, 32)).astype(np.float32)
+    probes = np.tile(np.array([[1, 2, 3]], dtype=np.uint32), (8, 1))      # two empty clusters and a small one
+    ids_g, d_g = gidx.ivfpq_search_with_probes(q, probes, 50, oracle.LUT_FP16)
+    ids_o, d_o = oracle.search(oidx, q, 3, 50, oracle.LUT_FP16, probes=probes)
+    assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context="padding")
+    assert (ids_o == -1).any()
+    probes = np.tile(np.array([[1, 2]], dtype=np.uint32), (8, 1))         # nothing to scan at all
+    ids_g, d_g = gidx.ivfpq_search_with_probes(q, probes, 5, oracle.LUT_FP32)
+    assert (ids_g.cpu().numpy() == -1).all() and np.isinf(d_g.cpu().numpy()).all()
+
+
+def test_search_massive_ties_order_by_id(P):
+    # 6000 identical codes in one cluster: every R is equal, the answer is the k smallest ids
+    # (more ties than the selection's LDS record capacity -> the 64-bit tie-key path)
+    cent, cb, offs, codes, ids = si.random_index_arrays(6400, 32, 2, 16, 8, salt=600)
+    codes[:] = codes[0]
+    oidx = oracle.make_index(32, 2, 16, 8, cent, cb, offs, codes, ids)
+    gidx = to_library(P, oidx)
+    q = np.random.default_rng(600).standard_normal((3, 32)).astype(np.float32)
+    for k in (1, 10, 1000):
+        for n_probes in (1, 2):
+            _step(f"massive ties k={k} P={n_probes}")
+            ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, n_probes, k, oracle.LUT_E5M3)
+            np.testing.assert_array_equal(ids_g, ids_o)
+            np.testing.assert_array_equal(d_g, d_o)
+
+
+def test_search_cluster_listed_twice_is_scanned_twice(P, tiny):
+    w, data, oidx, gidx = tiny
+    q = si.queries(w, 10)
+    probes = np.tile(np.array([[4, 4, 9]], dtype=np.uint32), (10, 1))
+    ids_g, d_g = gidx.ivfpq_search_with_probes(q, probes, 20, oracle.LUT_FP32)
+    ids_o, d_o = oracle.search(oidx, q, 3, 20, oracle.LUT_FP32, probes=probes)
+    assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context="dup cluster")
+
+
+def test_empty_inputs(P, tiny):
+    w, data, oidx, gidx = tiny
+    ids, d = gidx.ivfpq_search(np.zeros((0, w.d), np.float32), 4, 10, oracle.LUT_E5M3)
+    assert ids.shape == (0, 10) and d.shape == (0, 10)
+    # an index with no vectors at all
+    cent, cb, offs, codes, ids0 = si.random_index_arrays(0, 32, 4, 16, 8, salt=700)
+    oidx0 = oracle.make_index(32, 4, 16, 8, cent, cb, offs, codes, ids0)
+    g0 = to_library(P, oidx0)
+    q = np.ones((3, 32), np.float32)
+    ids, d = g0.ivfpq_search(q, 2, 5, oracle.LUT_FP32)
+    assert (ids.cpu().numpy() == -1).all() and np.isinf(d.cpu().numpy()).all()
+
+
+def test_error_paths(P, tiny):
+    w, data, oidx, gidx = tiny
+    q = torch.from_numpy(si.queries(w, 4)).cuda()
+    with pytest.raises(P.IvfpqError) as e:
+        gidx.ivfpq_search(q, 0, 10, 0)
+    assert e.value.status == P.EINVAL
+    with pytest.raises(P.IvfpqError) as e:
+        gidx.ivfpq_search(q, w.n_lists + 1, 10, 0)
+    assert e.value.status == P.EINVAL
+    with pytest.raises(P.IvfpqError) as e:
+        gidx.ivfpq_search(q, 4, P.MAX_K + 1, 0)
+    assert e.value.status == P.EINVAL
+    with pytest.raises(P.IvfpqError) as e:
+        gidx.ivfpq_search(q, 4, 10, 7)
+    assert e.value.status == P.EINVAL
+    # a workspace that is too small is refused before anything is launched
+    import ctypes
+    ids = torch.empty((4, 10), dtype=torch.int64, device="cuda")
+    d = torch.empty((4, 10), dtype=torch.float32, device="cuda")
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    st = P.lib().ivfpq_search(gidx._h, ctypes.c_void_p(q.data_ptr()), 4, 4, 10, 0, ctypes.c_void_p(ids.data_ptr()),
+                              ctypes.c_void_p(d.data_ptr()), ctypes.c_void_p(ws.data_ptr()), 256, None)
+    assert st == P.ENOSPACE
+    # no device image yet
+    fresh = P.Index.ivfpq_index_from_arrays(oidx.d, oidx.n_lists, oidx.pq_dim, oidx.pq_bits, oidx.centroids,
+                                            oidx.codebooks, oidx.list_offsets, oidx.codes, oidx.ids)
+    with pytest.raises(P.IvfpqError) as e:
+        fresh.ivfpq_search(q, 4, 10, 0)
+    assert e.value.status == P.ESTATE
+
+
+def test_stage_timing_reports(P, tiny):
+    w, data, oidx, gidx = tiny
+    q = torch.from_numpy(si.queries(w, 256)).cuda()
+    gidx.ivfpq_set_stage_timing(True)
+    gidx.ivfpq_search(q, 8, 10, oracle.LUT_E5M3)
+    torch.cuda.synchronize()
+    ms = gidx.ivfpq_stage_times_ms()
+    gidx.ivfpq_set_stage_timing(False)
+    assert ms["total"] > 0 and ms["scan"] > 0
+    assert ms["probe_select"] + ms["scan"] + ms["topk"] <= ms["total"] * 1.05 + 0.05
+
+
+def test_library_builder_index_searches_like_oracle_builder(P, tiny):
+    # the two builders run different k-means code: compare them by recall only
+    w, data, oidx, _ = tiny
+    g = P.Index.ivfpq_build_host(data, w.n_lists, w.pq_dim, w.pq_bits, w.kmeans_iters, seed=3).ivfpq_upload()
+    q = si.queries(w, 300)
+    gt, _ = oracle.exact_knn(data, q, w.k)
+    ids_lib, _ = g.ivfpq_search(q, w.n_probes, w.k, oracle.LUT_FP32)
+    ids_orc, _ = oracle.search(oidx, q, w.n_probes, w.k, oracle.LUT_FP32)
+    assert abs(oracle.recall(ids_lib.cpu().numpy(), gt) - oracle.recall(ids_orc, gt)) < 0.06
