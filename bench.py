@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the IVFPQ search path on one MI355X.
+
+A "step" is one pass of the whole hot path -- probe selection, lookup-table build, PQ-code scan,
+top-k -- over one batch of synthetic queries that already sits in HBM.  The workload is the
+d=128 integer-valued million-vector configuration (1,024 clusters, 64-byte PQ codes, 20 probes,
+k=10, 10,000 queries) the headline metric is quoted on; inputs are seeded and synthetic.
+
+Prints ONE JSON line: queries/s of the headline table dtype, with
+  roofline     -- the code-scan kernel's algorithmic PQ-code bytes per second against HBM peak,
+                  timed live with HIP events on the stream the kernel runs on;
+  cpu_baseline -- the CPU oracle timed on a bounded sample of the same queries and index.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth, GB/s
+
+# HBM traffic of the scan kernel per step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/scan_kernel_<workload>_pmc.txt), in bytes; None where no counter run is recorded.
+MEASURED_TRAFFIC = {}
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def exact_topk_gpu(data_np, queries_t, k, chunk=200_000):
+    """Harness-side ground truth: exact k nearest by float64 distances, chunked over the data."""
+    import torch
+    q = queries_t.double()
+    qn = (q * q).sum(1, keepdim=True)
+    best_d = torch.full((q.shape[0], k), float("inf"), dtype=torch.float64, device="cuda")
+    best_i = torch.full((q.shape[0], k), -1, dtype=torch.int64, device="cuda")
+    for lo in range(0, data_np.shape[0], chunk):
+        x = torch.from_numpy(data_np[lo:lo + chunk]).cuda().double()
+        d2 = qn + (x * x).sum(1)[None, :] - 2.0 * (q @ x.T)
+        dd, ii = torch.topk(d2, min(k, x.shape[0]), dim=1, largest=False)
+        cat_d = torch.cat([best_d, dd], 1)
+        cat_i = torch.cat([best_i, ii + lo], 1)
+        dd, sel = torch.topk(cat_d, k, dim=1, largest=False)
+        best_d, best_i = dd, torch.gather(cat_i, 1, sel)
+    return best_i, best_d
+
+
+def tie_aware_recall(found_ids_t, data_np, queries_t, gt_d, k):
+    """|V & V_GT| / |V_GT| where a returned vector counts if its true distance does not exceed the
+    true k-th distance (integer-valued data have exact distance ties)."""
+    import torch
+    ids = found_ids_t.cpu().numpy()
+    q = queries_t.double()
+    hits = 0
+    thr = gt_d[:, k - 1] * (1 + 1e-12)
+    import numpy as np
+    safe = np.where(ids >= 0, ids, 0)
+    x = torch.from_numpy(data_np[safe.reshape(-1)]).cuda().double().reshape(ids.shape[0], ids.shape[1], -1)
+    d2 = ((x - q[:, None, :]) ** 2).sum(-1)
+    ok = (d2 <= thr[:, None]) & torch.from_numpy(ids >= 0).cuda()
+    hits = int(ok.sum().item())
+    return hits / float(ids.shape[0] * k)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="intgrid_1m")
+    ap.add_argument("--lut", default="e5m3", choices=["fp32", "fp16", "e5m3"])
+    ap.add_argument("--kmeans-iters", type=int, default=6, help="Lloyd iterations of the (untimed) index build")
+    ap.add_argument("--n-probes", type=int, default=None)
+    ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--recall-queries", type=int, default=1000)
+    ap.add_argument("--cpu-queries", type=int, default=2000)
+    ap.add_argument("--only-headline", action="store_true", help="skip the other table dtypes (for profiling runs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; the path shards by query across GPUs with no "
+              "communication (see DESIGN.md), and no multi-GPU figure is produced.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    import paper_2301_06672_amd as pkg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the search path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    pkg.lib()
+    torch.cuda.set_device(0)
+    w = si.WORKLOADS[args.workload]
+    n_probes = args.n_probes or w.n_probes
+    k = args.k or w.k
+    lut_ids = {"fp32": pkg.LUT_FP32, "fp16": pkg.LUT_FP16, "e5m3": pkg.LUT_FP8_E5M3}
+
+    t0 = time.time()
+    data = si.dataset(w)
+    queries_np = si.queries(w)
+    log(f"generated {w.name}: data {data.shape}, queries {queries_np.shape} in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    idx = pkg.Index.ivfpq_build_host(data, w.n_lists, w.pq_dim, w.pq_bits, args.kmeans_iters, seed=1)
+    log(f"ivfpq_build_host ({args.kmeans_iters} Lloyd iterations) {time.time() - t0:.1f}s")
+    idx.ivfpq_upload()
+    cent, cb, offs, codes, ids_arr = idx.ivfpq_index_export()
+    sizes = np.diff(offs)
+
+    q = torch.from_numpy(queries_np).cuda()
+    nq = q.shape[0]
+    out = (torch.empty((nq, k), dtype=torch.int64, device="cuda"),
+           torch.empty((nq, k), dtype=torch.float32, device="cuda"))
+
+    # exact algorithmic bytes of the scan: every probed cluster's packed codes, once per (query, probe)
+    probes, _ = idx.ivfpq_select_probes(q, n_probes)
+    probes_np = probes.cpu().numpy().view(np.uint32)
+    scanned_vectors = int(sizes[probes_np].sum())
+    code_bytes = scanned_vectors * w.code_bytes
+
+    # ground truth for recall on a query subset (harness work, outside the timed region)
+    nr = min(args.recall_queries, nq)
+    gt_i, gt_d = exact_topk_gpu(data, q[:nr], k)
+
+    def run(lut_name, steps, warmup):
+        lut = lut_ids[lut_name]
+        for _ in range(warmup):
+            idx.ivfpq_search(q, n_probes, k, lut, out=out)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(steps):
+            idx.ivfpq_search(q, n_probes, k, lut, out=out)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        # stage times of one more (untimed) step, from HIP events on the search stream
+        idx.ivfpq_set_stage_timing(True)
+        reps = 3
+        acc = {"probe_select": 0.0, "scan": 0.0, "topk": 0.0, "total": 0.0}
+        for _ in range(reps):
+            idx.ivfpq_search(q, n_probes, k, lut, out=out)
+            torch.cuda.synchronize()
+            for name, v in idx.ivfpq_stage_times_ms().items():
+                acc[name] += v / reps
+        idx.ivfpq_set_stage_timing(False)
+        rec = tie_aware_recall(out[0][:nr], data, q[:nr], gt_d, k)
+        return {"qps": nq * steps / dt, "ms_per_step": 1e3 * dt / steps, "recall": rec, "stage_ms": acc}
+
+    results = {}
+    order = [args.lut] if args.only_headline else ["fp32", "fp16", "e5m3"]
+    for name in order:
+        steps = args.steps if name == args.lut else max(3, args.steps // 2)
+        results[name] = run(name, steps, args.warmup)
+        r = results[name]
+        log(f"lut={name}: {r['qps']:.0f} q/s, {r['ms_per_step']:.3f} ms/step, recall@{k}={r['recall']:.4f}, "
+            f"stages {r['stage_ms']}")
+    head = results[args.lut]
+
+    ws_bytes = idx.ivfpq_search_workspace_bytes(nq, n_probes, k, lut_ids[args.lut])
+    scan_ms = head["stage_ms"]["scan"]
+    achieved = code_bytes / (scan_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": "scan_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": MEASURED_TRAFFIC.get((w.name, args.lut)),
+        "algorithmic_bytes_per_step": code_bytes, "scanned_vectors_per_step": scanned_vectors,
+        "scan_ms_per_step": round(scan_ms, 4),
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oidx = oracle.make_index(w.d, w.n_lists, w.pq_dim, w.pq_bits, cent, cb, offs, codes, ids_arr)
+        nc = min(args.cpu_queries, nq)
+        t = time.perf_counter()
+        oracle.search(oidx, queries_np[:nc], n_probes, k, lut_ids[args.lut])
+        dt = time.perf_counter() - t
+        cpu = {"value": round(nc / dt, 1), "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"first {nc} of the {nq} queries, same index, lut={args.lut}, {dt:.1f}s wall, one pass"}
+        log(f"cpu oracle: {cpu}")
+
+    line = {
+        "metric": f"queries/sec at recall@{k} ({args.lut} LUT)",
+        "value": round(head["qps"], 1), "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(head["ms_per_step"], 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={w.n} d={w.d} nq={nq} n_lists={w.n_lists} pq_dim={w.pq_dim} "
+                               f"pq_bits={w.pq_bits} n_probes={n_probes} k={k}",
+                   "lut_dtype": args.lut, "kmeans_iters": args.kmeans_iters,
+                   "workspace_bytes": ws_bytes, "recall_queries": nr},
+        "recall_at_k": round(head["recall"], 4),
+        "by_lut": {n: {"qps": round(r["qps"], 1), "recall": round(r["recall"], 4),
+                       "stage_ms": {a: round(b, 4) for a, b in r["stage_ms"].items()}} for n, r in results.items()},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
