@@ -182,6 +182,52 @@ __device__ inline void sort_records(SelectShared& s, int np2) {
     __syncthreads();
 }
 
+// One histogram increment per active lane, with the increments of a wave folded into a single
+// LDS atomic when all its active lanes hit the same bin (the usual case for the leading digit of
+// distances of similar magnitude, where per-lane atomics on one address would serialise).
+__device__ inline void hist_add(uint32_t* hist, uint32_t digit, bool active) {
+    const unsigned long long act = __ballot(active);
+    if (act == 0) return;
+    const int first = __ffsll((long long)act) - 1;
+    const uint32_t d0 = (uint32_t)__shfl((int)digit, first, kWave);
+    const unsigned long long same = __ballot(active && digit == d0);
+    if (same == act) {
+        if ((int)(threadIdx.x & (kWave - 1)) == first) atomicAdd(&hist[d0], (uint32_t)__popcll(act));
+    } else if (active) {
+        atomicAdd(&hist[digit], 1u);
+    }
+}
+
+// The kk-th smallest (1-based, 1 <= kk <= n) of n keys, by four 8-bit digits from the top.
+// *rank_in_ties = how many elements equal to the result rank at or below kk (1..*n_ties),
+// *n_ties = number of elements equal to the result.  Called by every thread of the workgroup.
+template <class KeyFn>
+__device__ uint32_t block_kth_key(SelectShared& s, uint32_t n, uint32_t kk, KeyFn key_of,
+                                  uint32_t* rank_in_ties, uint32_t* n_ties) {
+    const int tid = threadIdx.x, nth = blockDim.x;
+    uint32_t prefix = 0, need = kk, n_eq = 0;
+    for (int pass = 3; pass >= 0; --pass) {
+        const int shift = pass * 8;
+        __syncthreads();
+        for (int b = tid; b < 256; b += nth) s.hist[b] = 0;
+        __syncthreads();
+        for (uint32_t base = 0; base < n; base += nth) {
+            const uint32_t i = base + tid;
+            const bool valid = i < n;
+            const uint32_t key = valid ? key_of(i) : 0u;
+            const bool in = valid && ((pass == 3) || ((key >> (shift + 8)) == (prefix >> (shift + 8))));
+            hist_add(s.hist, (key >> shift) & 255u, in);
+        }
+        find_digit(s, need);
+        prefix |= s.digit << shift;
+        need = s.need;
+        n_eq = s.count;
+    }
+    *rank_in_ties = need;
+    *n_ties = n_eq;
+    return prefix;
+}
+
 // KeyFn(i) -> uint32 key of element i; TieFn(i) -> long long tie key of element i.
 // On return records [0, min(k, n)) hold the selected elements in ascending (key, tie, pos) order.
 // Returns min(k, n).  Must be called by every thread of the workgroup.
@@ -191,24 +237,8 @@ __device__ int block_select_smallest(SelectShared& s, uint32_t n, uint32_t k, Ke
     if (kk == 0) return 0;
     const int tid = threadIdx.x, nth = blockDim.x;
 
-    // ---- the kk-th smallest key T, by four 8-bit digits from the top
-    uint32_t prefix = 0, need = kk, n_eq = 0;
-    for (int pass = 3; pass >= 0; --pass) {
-        const int shift = pass * 8;
-        __syncthreads();
-        for (int b = tid; b < 256; b += nth) s.hist[b] = 0;
-        __syncthreads();
-        for (uint32_t i = tid; i < n; i += nth) {
-            uint32_t key = key_of(i);
-            bool in = (pass == 3) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
-            if (in) atomicAdd(&s.hist[(key >> shift) & 255u], 1u);
-        }
-        find_digit(s, need);
-        prefix |= s.digit << shift;
-        need = s.need;
-        n_eq = s.count;
-    }
-    const uint32_t T = prefix;
+    uint32_t need = 0, n_eq = 0;
+    const uint32_t T = block_kth_key(s, n, kk, key_of, &need, &n_eq);
     const uint32_t n_less = kk - need;     // elements strictly below T: all selected
 
     // ---- collect
@@ -235,11 +265,15 @@ __device__ int block_select_smallest(SelectShared& s, uint32_t n, uint32_t k, Ke
             __syncthreads();
             for (int b = tid; b < 256; b += nth) s.hist[b] = 0;
             __syncthreads();
-            for (uint32_t i = tid; i < n; i += nth) {
-                if (key_of(i) != T) continue;
-                unsigned long long u = (unsigned long long)tie_of(i) ^ 0x8000000000000000ull;
-                bool in = (pass == 7) || ((u >> (shift + 8)) == (uprefix >> (shift + 8)));
-                if (in) atomicAdd(&s.hist[(uint32_t)(u >> shift) & 255u], 1u);
+            for (uint32_t base = 0; base < n; base += nth) {
+                const uint32_t i = base + tid;
+                bool in = i < n && key_of(i) == T;
+                unsigned long long u = 0;
+                if (in) {
+                    u = (unsigned long long)tie_of(i) ^ 0x8000000000000000ull;
+                    in = (pass == 7) || ((u >> (shift + 8)) == (uprefix >> (shift + 8)));
+                }
+                hist_add(s.hist, (uint32_t)(u >> shift) & 255u, in);
             }
             find_digit(s, uneed);
             uprefix |= (unsigned long long)s.digit << shift;
@@ -581,33 +615,87 @@ dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centr
 
 // ================================================================================================
 // Step 5: per query, the k smallest R over all probed clusters, ordered by (R, id).
+// The query's candidates (tens of thousands) are cut down in one streaming pass: the k-th smallest
+// R among the first CAND_CAP candidates -- they come from the nearest cluster(s), so the bound is
+// tight -- is an upper bound of the k-th smallest overall; only candidates not above it are
+// compacted into LDS, and the exact selection runs on that small set.  If the compacted set
+// overflows LDS the kernel falls back to exact selection over the whole row in global memory.
 // ================================================================================================
+constexpr int CAND_CAP = 2048;
+
+struct TopkShared {
+    SelectShared sel;
+    uint32_t cand_key[CAND_CAP];
+    uint32_t cand_pos[CAND_CAP];
+    uint32_t n_cand;
+    uint32_t roff[IVFPQ_MAX_PROBES + 1];
+    uint32_t probe[IVFPQ_MAX_PROBES];
+};
+
 __global__ void __launch_bounds__(SEL_THREADS)
 topk_kernel(const float* __restrict__ R, size_t stride, const uint32_t* __restrict__ roff,
             const uint32_t* __restrict__ probes, int n_probes, int k,
             const int64_t* __restrict__ list_offsets, const int64_t* __restrict__ ids,
             int64_t* __restrict__ out_ids, float* __restrict__ out_dists) {
-    __shared__ SelectShared s;
-    __shared__ uint32_t s_roff[IVFPQ_MAX_PROBES + 1];
-    __shared__ uint32_t s_probe[IVFPQ_MAX_PROBES];
+    __shared__ TopkShared t;
+    SelectShared& s = t.sel;
     const int q = blockIdx.x;
-    for (int p = threadIdx.x; p <= n_probes; p += blockDim.x) s_roff[p] = roff[(size_t)q * (n_probes + 1) + p];
-    for (int p = threadIdx.x; p < n_probes; p += blockDim.x) s_probe[p] = probes[(size_t)q * n_probes + p];
+    const int tid = threadIdx.x, nth = blockDim.x;
+    for (int p = tid; p <= n_probes; p += nth) t.roff[p] = roff[(size_t)q * (n_probes + 1) + p];
+    for (int p = tid; p < n_probes; p += nth) t.probe[p] = probes[(size_t)q * n_probes + p];
+    if (tid == 0) t.n_cand = 0;
     __syncthreads();
-    const uint32_t n = s_roff[n_probes];
+    const uint32_t n = t.roff[n_probes];      // padded candidate count: a multiple of 64
     const uint32_t* row = reinterpret_cast<const uint32_t*>(R + (size_t)q * stride);
-    auto key_of = [&](uint32_t i) { return row[i]; };
-    auto tie_of = [&](uint32_t i) -> long long {
-        if (row[i] == kPadKey) return 0x7FFFFFFFFFFFFFFFll;
-        int lo = 0, hi = n_probes;            // largest slot with s_roff[slot] <= i
+
+    // caller's id of the candidate at slot `i` of the row
+    auto id_of = [&](uint32_t i) -> long long {
+        int lo = 0, hi = n_probes;            // largest probe slot with roff[slot] <= i
         while (hi - lo > 1) {
             int mid = (lo + hi) >> 1;
-            if (s_roff[mid] <= i) lo = mid; else hi = mid;
+            if (t.roff[mid] <= i) lo = mid; else hi = mid;
         }
-        return (long long)ids[list_offsets[s_probe[lo]] + (int64_t)(i - s_roff[lo])];
+        return (long long)ids[list_offsets[t.probe[lo]] + (int64_t)(i - t.roff[lo])];
     };
-    const int got = block_select_smallest(s, n, (uint32_t)k, key_of, tie_of);
-    for (int j = threadIdx.x; j < k; j += blockDim.x) {
+
+    bool compact = true;
+    uint32_t n_cand = n;
+    if (n > (uint32_t)CAND_CAP) {
+        for (int i = tid; i < CAND_CAP; i += nth) t.cand_key[i] = row[i];
+        uint32_t r0, r1;
+        const uint32_t bound = block_kth_key(s, (uint32_t)CAND_CAP, (uint32_t)k, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1);
+        __syncthreads();
+        const uint4* row4 = reinterpret_cast<const uint4*>(row);
+        for (uint32_t i4 = tid; i4 < n / 4; i4 += nth) {
+            const uint4 v = row4[i4];
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (w[u] <= bound) {
+                    uint32_t slot = atomicAdd(&t.n_cand, 1u);
+                    if (slot < (uint32_t)CAND_CAP) { t.cand_key[slot] = w[u]; t.cand_pos[slot] = i4 * 4 + u; }
+                }
+            }
+        }
+        __syncthreads();
+        n_cand = t.n_cand;
+        compact = n_cand <= (uint32_t)CAND_CAP;
+    } else {
+        for (uint32_t i = tid; i < n; i += nth) { t.cand_key[i] = row[i]; t.cand_pos[i] = i; }
+        __syncthreads();
+    }
+
+    int got;
+    if (compact) {
+        got = block_select_smallest(s, n_cand, (uint32_t)k,
+            [&](uint32_t i) { return t.cand_key[i]; },
+            [&](uint32_t i) -> long long { return t.cand_key[i] == kPadKey ? 0x7FFFFFFFFFFFFFFFll : id_of(t.cand_pos[i]); });
+    } else {
+        got = block_select_smallest(s, n, (uint32_t)k,
+            [&](uint32_t i) { return row[i]; },
+            [&](uint32_t i) -> long long { return row[i] == kPadKey ? 0x7FFFFFFFFFFFFFFFll : id_of(i); });
+    }
+    for (int j = tid; j < k; j += nth) {
         int64_t id = -1;
         float dist = __uint_as_float(0x7F800000u);
         if (j < got && s.rec_key[j] != kPadKey) { id = (int64_t)s.rec_tie[j]; dist = __uint_as_float(s.rec_key[j]); }
