@@ -79,6 +79,11 @@ def main():
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--recall-queries", type=int, default=1000)
     ap.add_argument("--cpu-queries", type=int, default=2000)
+    ap.add_argument("--builder", default="auto", choices=["auto", "host", "torch"],
+                    help="index construction (untimed): ivfpq_build_host on the CPU, or torch matmuls on the GPU + import")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="only run a plain elementwise copy (read BYTES, write BYTES) three times and exit: "
+                         "reference for scaling the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--only-headline", action="store_true", help="skip the other table dtypes (for profiling runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -97,6 +102,15 @@ def main():
         sys.exit(2)
     pkg.lib()
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = args.copy_calibration // 4
+        x = torch.ones(n, dtype=torch.float32, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(3):
+            torch.mul(x, 2.0, out=y)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n * 4, "bytes_written": n * 4, "launches": 3}))
+        return
     w = si.WORKLOADS[args.workload]
     n_probes = args.n_probes or w.n_probes
     k = args.k or w.k
@@ -107,8 +121,16 @@ def main():
     queries_np = si.queries(w)
     log(f"generated {w.name}: data {data.shape}, queries {queries_np.shape} in {time.time() - t0:.1f}s")
     t0 = time.time()
-    idx = pkg.Index.ivfpq_build_host(data, w.n_lists, w.pq_dim, w.pq_bits, args.kmeans_iters, seed=1)
-    log(f"ivfpq_build_host ({args.kmeans_iters} Lloyd iterations) {time.time() - t0:.1f}s")
+    builder = args.builder if args.builder != "auto" else ("host" if w.n <= 2_000_000 else "torch")
+    if builder == "host":
+        idx = pkg.Index.ivfpq_build_host(data, w.n_lists, w.pq_dim, w.pq_bits, args.kmeans_iters, seed=1)
+    else:
+        from paper_2301_06672_amd.torch_builder import build_index_arrays
+        arrays = build_index_arrays(data, w.n_lists, w.pq_dim, w.pq_bits, args.kmeans_iters, seed=1)
+        idx = pkg.Index.ivfpq_index_from_arrays(w.d, w.n_lists, w.pq_dim, w.pq_bits, *arrays)
+        del arrays
+        torch.cuda.empty_cache()
+    log(f"index build ({builder}, {args.kmeans_iters} Lloyd iterations) {time.time() - t0:.1f}s")
     idx.ivfpq_upload()
     cent, cb, offs, codes, ids_arr = idx.ivfpq_index_export()
     sizes = np.diff(offs)
@@ -193,7 +215,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.n} d={w.d} nq={nq} n_lists={w.n_lists} pq_dim={w.pq_dim} "
                                f"pq_bits={w.pq_bits} n_probes={n_probes} k={k}",
-                   "lut_dtype": args.lut, "kmeans_iters": args.kmeans_iters,
+                   "lut_dtype": args.lut, "kmeans_iters": args.kmeans_iters, "builder": builder,
                    "workspace_bytes": ws_bytes, "recall_queries": nr},
         "recall_at_k": round(head["recall"], 4),
         "by_lut": {n: {"qps": round(r["qps"], 1), "recall": round(r["recall"], 4),

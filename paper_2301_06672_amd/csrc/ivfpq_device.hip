@@ -17,6 +17,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
+#include <utility>
 
 #include "ivfpq_internal.hpp"
 
@@ -447,14 +448,56 @@ __device__ inline void build_lut(const float* __restrict__ codebooks, const floa
     }
 }
 
-template <int LUT>
-__device__ inline void build_lut_any_m(const float* __restrict__ codebooks, const float* rq, int n_entries,
-                                       int bits, int m, unsigned char* lut) {
+// 8-bit codes: a table row has 256 entries = 4 per lane of a wave, so every wave builds whole rows
+// (row index wave-uniform: residual components are read once per row, addresses advance by a
+// constant stride).
+template <int LUT, int M>
+__device__ inline void build_lut_rows256(const float* __restrict__ codebooks, const float* rq, int pq_dim,
+                                         unsigned char* lut) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = blockDim.x >> 6;
+    const float* src = codebooks + ((size_t)wave * 256 + lane * 4) * M;
+    const size_t src_step = (size_t)n_waves * 256 * M;
+    int e = wave * 256 + lane * 4;
+    const int e_step = n_waves * 256;
+#pragma unroll 2
+    for (int j = wave; j < pq_dim; j += n_waves) {
+        float r[M];
+#pragma unroll
+        for (int t = 0; t < M; ++t) r[t] = rq[j * M + t];
+        float cbv[4 * M];
+#pragma unroll
+        for (int v = 0; v < M; ++v) {
+            float4 x = reinterpret_cast<const float4*>(src)[v];
+            cbv[4 * v] = x.x; cbv[4 * v + 1] = x.y; cbv[4 * v + 2] = x.z; cbv[4 * v + 3] = x.w;
+        }
+        float f[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) f[u] = lut_entry<M>(cbv + u * M, r);
+        store4<LUT>(lut, e, f);
+        src += src_step;
+        e += e_step;
+    }
+}
+
+template <int LUT, int BITS>
+__device__ inline void build_lut_any_m(const float* __restrict__ codebooks, const float* rq, int pq_dim,
+                                       int m, unsigned char* lut) {
+    const int n_entries = pq_dim << BITS;
+    if constexpr (BITS == 8) {
+        switch (m) {
+            case 1: build_lut_rows256<LUT, 1>(codebooks, rq, pq_dim, lut); return;
+            case 2: build_lut_rows256<LUT, 2>(codebooks, rq, pq_dim, lut); return;
+            case 4: build_lut_rows256<LUT, 4>(codebooks, rq, pq_dim, lut); return;
+            default: break;
+        }
+    }
     switch (m) {
-        case 1: build_lut<LUT, 1>(codebooks, rq, n_entries, bits, m, lut); break;
-        case 2: build_lut<LUT, 2>(codebooks, rq, n_entries, bits, m, lut); break;
-        case 4: build_lut<LUT, 4>(codebooks, rq, n_entries, bits, m, lut); break;
-        default: build_lut<LUT, 0>(codebooks, rq, n_entries, bits, m, lut); break;
+        case 1: build_lut<LUT, 1>(codebooks, rq, n_entries, BITS, m, lut); break;
+        case 2: build_lut<LUT, 2>(codebooks, rq, n_entries, BITS, m, lut); break;
+        case 4: build_lut<LUT, 4>(codebooks, rq, n_entries, BITS, m, lut); break;
+        default: build_lut<LUT, 0>(codebooks, rq, n_entries, BITS, m, lut); break;
     }
 }
 
@@ -538,15 +581,40 @@ scan_kernel(ScanArgs a) {
     using chunk_t = typename std::conditional<CW == 16, uint4, uint32_t>::type;
     const chunk_t* cbase = reinterpret_cast<const chunk_t*>(codes_l);
 
-    // issue the loads of this wave's first group before the table is built: HBM latency overlaps it
     constexpr int NBUF = NCH > 0 ? NCH : 1;
-    chunk_t cur[NBUF];
+    constexpr int ROWS_PER_WORD = BITS == 8 ? 4 : 8;
+
+    auto load_group = [&](chunk_t (&buf)[NBUF], int g) {
+#pragma unroll
+        for (int c = 0; c < NBUF; ++c) buf[c] = cbase[((size_t)g * NBUF + c) * 64 + lane];
+    };
+    // Eq. (1) for the vector this lane holds in buf: sub-spaces in ascending order
+    auto accumulate = [&](const chunk_t (&buf)[NBUF]) -> float {
+        float acc = 0.f;
+#pragma unroll
+        for (int c = 0; c < NBUF; ++c) {
+            if constexpr (CW == 16) {
+                const uint32_t w[4] = {buf[c].x, buf[c].y, buf[c].z, buf[c].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    acc = add_word<LUT, BITS>(acc, lut, w[i], (c * 4 + i) * ROWS_PER_WORD);
+            } else {
+                acc = add_word<LUT, BITS>(acc, lut, buf[c], c * ROWS_PER_WORD);
+            }
+        }
+        return acc;
+    };
+    auto store_R = [&](int g, float acc) {
+        const uint32_t i = (uint32_t)g * 64u + lane;
+        if (i < len) Rout[i] = acc;
+        else if (a.single_list < 0) Rout[i] = __uint_as_float(kPadKey);   // padding slot of the R scratch
+    };
+
+    // issue the loads of this wave's first group before the table is built: HBM latency overlaps it
+    chunk_t buf_a[NBUF], buf_b[NBUF];
     int g = wave;
     if constexpr (NCH > 0) {
-        if (g < n_groups) {
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) cur[c] = cbase[((size_t)g * NCH + c) * 64 + lane];
-        }
+        if (g < n_groups) load_group(buf_a, g);
     }
 
     // step 2: residual of the query against this cluster's centroid
@@ -554,43 +622,30 @@ scan_kernel(ScanArgs a) {
         rq[t] = a.queries[(size_t)q * a.d + t] - a.centroids[(size_t)l * a.d + t];
     __syncthreads();
     // step 3: the table
-    build_lut_any_m<LUT>(a.codebooks, rq, n_entries, BITS, a.m, lut);
+    build_lut_any_m<LUT, BITS>(a.codebooks, rq, a.pq_dim, a.m, lut);
     __syncthreads();
 
-    // step 4: Eq. (1), one lane per coded vector, sub-spaces in ascending order
-    constexpr int ROWS_PER_WORD = BITS == 8 ? 4 : 8;
-    while (g < n_groups) {
-        float acc = 0.f;
-        const int gn = g + n_waves;
-        if constexpr (NCH > 0) {
-            chunk_t nxt[NBUF];
-            if (gn < n_groups) {
-#pragma unroll
-                for (int c = 0; c < NCH; ++c) nxt[c] = cbase[((size_t)gn * NCH + c) * 64 + lane];
-            }
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                if constexpr (CW == 16) {
-                    const uint32_t w[4] = {cur[c].x, cur[c].y, cur[c].z, cur[c].w};
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        acc = add_word<LUT, BITS>(acc, lut, w[i], (c * 4 + i) * ROWS_PER_WORD);
-                } else {
-                    acc = add_word<LUT, BITS>(acc, lut, cur[c], c * ROWS_PER_WORD);
-                }
-            }
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) cur[c] = nxt[c];
-        } else {
+    // step 4: Eq. (1), one lane per coded vector; the next group is loaded into the other register
+    // buffer while the current one is looked up
+    if constexpr (NCH > 0) {
+        while (g < n_groups) {
+            int gn = g + n_waves;
+            if (gn < n_groups) load_group(buf_b, gn);
+            store_R(g, accumulate(buf_a));
+            if (gn >= n_groups) break;
+            g = gn + n_waves;
+            if (g < n_groups) load_group(buf_a, g);
+            store_R(gn, accumulate(buf_b));
+        }
+    } else {
+        for (; g < n_groups; g += n_waves) {
+            float acc = 0.f;
             for (int c = 0; c < nch; ++c) {
                 uint32_t w = reinterpret_cast<const uint32_t*>(codes_l)[((size_t)g * nch + c) * 64 + lane];
                 acc = add_word<LUT, BITS>(acc, lut, w, c * ROWS_PER_WORD);
             }
+            store_R(g, acc);
         }
-        const uint32_t i = (uint32_t)g * 64u + lane;
-        if (i < len) Rout[i] = acc;
-        else if (a.single_list < 0) Rout[i] = __uint_as_float(kPadKey);   // padding slot of the R scratch
-        g = gn;
     }
 }
 
@@ -607,7 +662,8 @@ dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centr
     float* rq = reinterpret_cast<float*>(smem + ((lut_bytes + 15) & ~(size_t)15));
     for (int t = threadIdx.x; t < d; t += blockDim.x) rq[t] = query[t] - centroid[t];
     __syncthreads();
-    build_lut_any_m<LUT>(codebooks, rq, n_entries, bits, m, lut);
+    if (bits == 8) build_lut_any_m<LUT, 8>(codebooks, rq, pq_dim, m, lut);
+    else build_lut_any_m<LUT, 4>(codebooks, rq, pq_dim, m, lut);
     __syncthreads();
     for (size_t i = threadIdx.x; i < lut_bytes / 4; i += blockDim.x)
         reinterpret_cast<uint32_t*>(out)[i] = reinterpret_cast<const uint32_t*>(lut)[i];
