@@ -40,48 +40,77 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 
 // ================================================================================================
-// Step 1a: coarse distances.  Tile of 64 queries x 64 clusters per 256-thread workgroup, 4x4 outputs
-// per thread, operands staged through LDS in slices of 16 components.  The distance is accumulated
-// in the direct form sum_t (q_t - c_t)^2 so that its rounding error stays relative to the distance
-// itself (the expanded form |q|^2 - 2 q.c + |c|^2 cancels badly for far-from-origin data).
+// Step 1a: coarse distances.  Tile of 128 queries x 128 clusters per 256-thread workgroup, 8x8
+// outputs per thread (two 4-wide strips per axis, so that LDS reads are 16-byte and conflict-free),
+// operands staged through LDS in slices of 16 components.  The distance is accumulated in the
+// direct form sum_t (q_t - c_t)^2, components in ascending order, so that its rounding error stays
+// relative to the distance itself (the expanded form |q|^2 - 2 q.c + |c|^2 cancels badly for
+// far-from-origin data and would not keep the probe lists within 1e-5 of exact).
 // ================================================================================================
-constexpr int CT = 64;   // tile edge
 constexpr int CK = 16;   // components per LDS slice
 
+// STRIPS = 1: 64 x 64 tile, 4x4 outputs per thread (more workgroups, for small problems);
+// STRIPS = 2: 128 x 128 tile, 8x8 outputs per thread (twice the arithmetic per LDS byte).
+template <int STRIPS>
 __global__ void __launch_bounds__(256)
 coarse_dist_kernel(const float* __restrict__ queries, const float* __restrict__ centroids,
                    int nq, int n_lists, int d, float* __restrict__ D) {
-    __shared__ float qs[CK][CT + 4];
-    __shared__ float cs[CK][CT + 4];
+    constexpr int CT = 64 * STRIPS;      // tile edge
+    constexpr int RT = 4 * STRIPS;       // outputs per thread and axis; also components a thread loads per row
+    __shared__ __align__(16) float qs[CK][CT + 4];
+    __shared__ __align__(16) float cs[CK][CT + 4];
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int q0 = blockIdx.y * CT, l0 = blockIdx.x * CT;
-    float acc[4][4];
+    float acc[RT][RT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+        for (int j = 0; j < RT; ++j) acc[i][j] = 0.f;
 
-    const int lr = tid >> 2;          // row of the tile this thread loads
-    const int lk = (tid & 3) * 4;     // first of its 4 components
+    constexpr int TPR = CK / RT;              // threads per tile row when loading
+    const int lr = tid / TPR;                 // row of the tile this thread loads
+    const int lk = (tid % TPR) * RT;          // first of its RT components
+    const bool vec_ok = (d & 3) == 0;
     for (int k0 = 0; k0 < d; k0 += CK) {
+        {
+            const int qi = q0 + lr, li = l0 + lr;
+            float qv[RT], cv[RT];
+            if (vec_ok && k0 + lk + RT <= d) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int t = k0 + lk + u;
-            int qi = q0 + lr, li = l0 + lr;
-            qs[lk + u][lr] = (qi < nq && t < d) ? queries[(size_t)qi * d + t] : 0.f;
-            cs[lk + u][lr] = (li < n_lists && t < d) ? centroids[(size_t)li * d + t] : 0.f;
+                for (int v = 0; v < STRIPS; ++v) {
+                    float4 x = make_float4(0.f, 0.f, 0.f, 0.f), y = x;
+                    if (qi < nq) x = reinterpret_cast<const float4*>(queries + (size_t)qi * d + k0 + lk)[v];
+                    if (li < n_lists) y = reinterpret_cast<const float4*>(centroids + (size_t)li * d + k0 + lk)[v];
+                    qv[4 * v] = x.x; qv[4 * v + 1] = x.y; qv[4 * v + 2] = x.z; qv[4 * v + 3] = x.w;
+                    cv[4 * v] = y.x; cv[4 * v + 1] = y.y; cv[4 * v + 2] = y.z; cv[4 * v + 3] = y.w;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < RT; ++u) {
+                    const int t = k0 + lk + u;
+                    qv[u] = (qi < nq && t < d) ? queries[(size_t)qi * d + t] : 0.f;
+                    cv[u] = (li < n_lists && t < d) ? centroids[(size_t)li * d + t] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < RT; ++u) { qs[lk + u][lr] = qv[u]; cs[lk + u][lr] = cv[u]; }
         }
         __syncthreads();
 #pragma unroll
         for (int kk = 0; kk < CK; ++kk) {
-            float a[4], b[4];
+            float a[RT], b[RT];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { a[i] = qs[kk][ty * 4 + i]; b[i] = cs[kk][tx * 4 + i]; }
+            for (int v = 0; v < STRIPS; ++v) {
+                const float4 x = *reinterpret_cast<const float4*>(&qs[kk][64 * v + ty * 4]);
+                const float4 y = *reinterpret_cast<const float4*>(&cs[kk][64 * v + tx * 4]);
+                a[4 * v] = x.x; a[4 * v + 1] = x.y; a[4 * v + 2] = x.z; a[4 * v + 3] = x.w;
+                b[4 * v] = y.x; b[4 * v + 1] = y.y; b[4 * v + 2] = y.z; b[4 * v + 3] = y.w;
+            }
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < RT; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < RT; ++j) {
                     float diff = a[i] - b[j];
                     acc[i][j] = __builtin_fmaf(diff, diff, acc[i][j]);
                 }
@@ -89,15 +118,37 @@ coarse_dist_kernel(const float* __restrict__ queries, const float* __restrict__ 
         __syncthreads();
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int qi = q0 + ty * 4 + i;
+    for (int i = 0; i < RT; ++i) {
+        const int qi = q0 + 64 * (i / 4) + ty * 4 + (i % 4);
         if (qi >= nq) continue;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int li = l0 + tx * 4 + j;
-            if (li < n_lists) D[(size_t)qi * n_lists + li] = acc[i][j];
+        for (int h = 0; h < STRIPS; ++h) {
+            const int lbase = l0 + h * 64 + tx * 4;
+            float* dst = D + (size_t)qi * n_lists + lbase;
+            if ((n_lists & 3) == 0 && lbase + 4 <= n_lists) {
+                *reinterpret_cast<float4*>(dst) = make_float4(acc[i][h * 4], acc[i][h * 4 + 1], acc[i][h * 4 + 2], acc[i][h * 4 + 3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (lbase + j < n_lists) dst[j] = acc[i][h * 4 + j];
+            }
         }
     }
+}
+
+// picks the tile size so that the grid still covers the chip
+int launch_coarse(const float* q, const float* centroids, int nq, int n_lists, int d, float* D, hipStream_t st) {
+    const long big_blocks = (long)((n_lists + 127) / 128) * ((nq + 127) / 128);
+    if (big_blocks >= 1024) {
+        dim3 grid((n_lists + 127) / 128, (nq + 127) / 128);
+        hipLaunchKernelGGL(coarse_dist_kernel<2>, grid, dim3(256), 0, st, q, centroids, nq, n_lists, d, D);
+    } else {
+        dim3 grid((n_lists + 63) / 64, (nq + 63) / 64);
+        hipLaunchKernelGGL(coarse_dist_kernel<1>, grid, dim3(256), 0, st, q, centroids, nq, n_lists, d, D);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(IVFPQ_EHIP, "coarse_dist_kernel launch failed: %s", hipGetErrorString(e));
+    return IVFPQ_OK;
 }
 
 // ================================================================================================
@@ -108,7 +159,7 @@ coarse_dist_kernel(const float* __restrict__ queries, const float* __restrict__ 
 // collected into LDS records and sorted there (bitonic).
 // ================================================================================================
 constexpr int SEL_THREADS = 256;
-constexpr int SEL_CAP = 2048;      // record capacity; k <= IVFPQ_MAX_K = 1024 always fits
+constexpr int SEL_CAP = 1024;      // record capacity = IVFPQ_MAX_K: the selected elements always fit
 
 struct SelectShared {
     uint32_t hist[256];
@@ -309,6 +360,78 @@ __device__ int block_select_smallest(SelectShared& s, uint32_t n, uint32_t k, Ke
     return (int)kk;
 }
 
+// ------------------------------------------------------------------------------------------------
+// The k smallest of a long row of keys in global memory (tens of thousands per query).
+// The k-th smallest key among the first CAND_CAP elements is an upper bound of the k-th smallest
+// of the whole row, so one streaming pass that keeps only keys not above that bound compacts the
+// row into LDS (typically a few times k elements); the exact selection then runs on that small
+// set.  If the compacted set overflows LDS the routine falls back to exact selection over the
+// whole row in global memory.  tie_of_pos(pos, key) gives the tie key of the element at row
+// position pos.  On return records [0, got) hold key, tie and row position in ascending
+// (key, tie) order.
+// ------------------------------------------------------------------------------------------------
+constexpr int CAND_CAP = 2048;
+
+struct RowSelectShared {
+    SelectShared sel;
+    uint32_t cand_key[CAND_CAP];
+    uint32_t cand_pos[CAND_CAP];
+    uint32_t n_cand;
+};
+
+template <class TieFn>
+__device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
+                                TieFn tie_of_pos) {
+    SelectShared& s = t.sel;
+    const int tid = threadIdx.x, nth = blockDim.x;
+    __syncthreads();
+    if (tid == 0) t.n_cand = 0;
+    __syncthreads();
+    bool compact = true;
+    uint32_t n_cand = n;
+    if (n > (uint32_t)CAND_CAP) {
+        for (int i = tid; i < CAND_CAP; i += nth) t.cand_key[i] = row[i];
+        uint32_t r0, r1;
+        const uint32_t kk = k < (uint32_t)CAND_CAP ? k : (uint32_t)CAND_CAP;
+        const uint32_t bound = block_kth_key(s, (uint32_t)CAND_CAP, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1);
+        __syncthreads();
+        auto keep = [&](uint32_t key, uint32_t pos) {
+            if (key <= bound) {
+                uint32_t slot = atomicAdd(&t.n_cand, 1u);
+                if (slot < (uint32_t)CAND_CAP) { t.cand_key[slot] = key; t.cand_pos[slot] = pos; }
+            }
+        };
+        if ((n & 3u) == 0 && (reinterpret_cast<uintptr_t>(row) & 15u) == 0) {
+            const uint4* row4 = reinterpret_cast<const uint4*>(row);
+            for (uint32_t i4 = tid; i4 < n / 4; i4 += nth) {
+                const uint4 v = row4[i4];
+                keep(v.x, i4 * 4); keep(v.y, i4 * 4 + 1); keep(v.z, i4 * 4 + 2); keep(v.w, i4 * 4 + 3);
+            }
+        } else {
+            for (uint32_t i = tid; i < n; i += nth) keep(row[i], i);
+        }
+        __syncthreads();
+        n_cand = t.n_cand;
+        compact = n_cand <= (uint32_t)CAND_CAP;
+    } else {
+        for (uint32_t i = tid; i < n; i += nth) { t.cand_key[i] = row[i]; t.cand_pos[i] = i; }
+        __syncthreads();
+    }
+    int got;
+    if (compact) {
+        got = block_select_smallest(s, n_cand, k,
+            [&](uint32_t i) { return t.cand_key[i]; },
+            [&](uint32_t i) -> long long { return tie_of_pos(t.cand_pos[i], t.cand_key[i]); });
+        for (int j = tid; j < got; j += nth) s.rec_pos[j] = t.cand_pos[s.rec_pos[j]];   // back to row positions
+        __syncthreads();
+    } else {
+        got = block_select_smallest(s, n, k,
+            [&](uint32_t i) { return row[i]; },
+            [&](uint32_t i) -> long long { return tie_of_pos(i, row[i]); });
+    }
+    return got;
+}
+
 // ================================================================================================
 // Step 1b: probe selection for one query per workgroup, from the coarse distance row.
 // Also lays out the query's slice of the R scratch: roff[p] = first slot of probe p, roff[n_probes]
@@ -319,12 +442,12 @@ select_probes_kernel(const float* __restrict__ D, int n_lists, int n_probes,
                      const uint32_t* __restrict__ list_sizes,
                      uint32_t* __restrict__ probes, float* __restrict__ probe_dists,
                      uint32_t* __restrict__ roff) {
-    __shared__ SelectShared s;
+    __shared__ RowSelectShared t;
+    SelectShared& s = t.sel;
     const int q = blockIdx.x;
-    const float* row = D + (size_t)q * n_lists;
-    auto key_of = [&](uint32_t i) { return __float_as_uint(row[i]); };
-    auto tie_of = [&](uint32_t i) { return (long long)i; };
-    int got = block_select_smallest(s, (uint32_t)n_lists, (uint32_t)n_probes, key_of, tie_of);
+    const uint32_t* row = reinterpret_cast<const uint32_t*>(D + (size_t)q * n_lists);   // distances >= +0
+    int got = block_select_row(t, row, (uint32_t)n_lists, (uint32_t)n_probes,
+                               [](uint32_t pos, uint32_t) { return (long long)pos; });
     for (int p = threadIdx.x; p < got; p += blockDim.x) {
         probes[(size_t)q * n_probes + p] = s.rec_pos[p];
         if (probe_dists) probe_dists[(size_t)q * n_probes + p] = __uint_as_float(s.rec_key[p]);
@@ -670,87 +793,34 @@ dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centr
 }
 
 // ================================================================================================
-// Step 5: per query, the k smallest R over all probed clusters, ordered by (R, id).
-// The query's candidates (tens of thousands) are cut down in one streaming pass: the k-th smallest
-// R among the first CAND_CAP candidates -- they come from the nearest cluster(s), so the bound is
-// tight -- is an upper bound of the k-th smallest overall; only candidates not above it are
-// compacted into LDS, and the exact selection runs on that small set.  If the compacted set
-// overflows LDS the kernel falls back to exact selection over the whole row in global memory.
+// Step 5: per query, the k smallest R over all probed clusters, ordered by (R, id), by one exact
+// row selection over the query's slice of the R scratch; (cluster, position) -> the caller's id.
 // ================================================================================================
-constexpr int CAND_CAP = 2048;
-
-struct TopkShared {
-    SelectShared sel;
-    uint32_t cand_key[CAND_CAP];
-    uint32_t cand_pos[CAND_CAP];
-    uint32_t n_cand;
-    uint32_t roff[IVFPQ_MAX_PROBES + 1];
-    uint32_t probe[IVFPQ_MAX_PROBES];
-};
-
 __global__ void __launch_bounds__(SEL_THREADS)
 topk_kernel(const float* __restrict__ R, size_t stride, const uint32_t* __restrict__ roff,
             const uint32_t* __restrict__ probes, int n_probes, int k,
             const int64_t* __restrict__ list_offsets, const int64_t* __restrict__ ids,
             int64_t* __restrict__ out_ids, float* __restrict__ out_dists) {
-    __shared__ TopkShared t;
+    __shared__ RowSelectShared t;
     SelectShared& s = t.sel;
     const int q = blockIdx.x;
     const int tid = threadIdx.x, nth = blockDim.x;
-    for (int p = tid; p <= n_probes; p += nth) t.roff[p] = roff[(size_t)q * (n_probes + 1) + p];
-    for (int p = tid; p < n_probes; p += nth) t.probe[p] = probes[(size_t)q * n_probes + p];
-    if (tid == 0) t.n_cand = 0;
-    __syncthreads();
-    const uint32_t n = t.roff[n_probes];      // padded candidate count: a multiple of 64
+    const uint32_t* s_roff = roff + (size_t)q * (n_probes + 1);     // read through the vector cache:
+    const uint32_t* s_probe = probes + (size_t)q * n_probes;        // only the few survivors look them up
+    const uint32_t n = s_roff[n_probes];      // padded candidate count: a multiple of 64
     const uint32_t* row = reinterpret_cast<const uint32_t*>(R + (size_t)q * stride);
 
-    // caller's id of the candidate at slot `i` of the row
-    auto id_of = [&](uint32_t i) -> long long {
+    // tie key = the caller's id of the candidate at slot `i` of the row (padding slots sort last)
+    auto id_of = [&](uint32_t i, uint32_t key) -> long long {
+        if (key == kPadKey) return 0x7FFFFFFFFFFFFFFFll;
         int lo = 0, hi = n_probes;            // largest probe slot with roff[slot] <= i
         while (hi - lo > 1) {
             int mid = (lo + hi) >> 1;
-            if (t.roff[mid] <= i) lo = mid; else hi = mid;
+            if (s_roff[mid] <= i) lo = mid; else hi = mid;
         }
-        return (long long)ids[list_offsets[t.probe[lo]] + (int64_t)(i - t.roff[lo])];
+        return (long long)ids[list_offsets[s_probe[lo]] + (int64_t)(i - s_roff[lo])];
     };
-
-    bool compact = true;
-    uint32_t n_cand = n;
-    if (n > (uint32_t)CAND_CAP) {
-        for (int i = tid; i < CAND_CAP; i += nth) t.cand_key[i] = row[i];
-        uint32_t r0, r1;
-        const uint32_t bound = block_kth_key(s, (uint32_t)CAND_CAP, (uint32_t)k, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1);
-        __syncthreads();
-        const uint4* row4 = reinterpret_cast<const uint4*>(row);
-        for (uint32_t i4 = tid; i4 < n / 4; i4 += nth) {
-            const uint4 v = row4[i4];
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (w[u] <= bound) {
-                    uint32_t slot = atomicAdd(&t.n_cand, 1u);
-                    if (slot < (uint32_t)CAND_CAP) { t.cand_key[slot] = w[u]; t.cand_pos[slot] = i4 * 4 + u; }
-                }
-            }
-        }
-        __syncthreads();
-        n_cand = t.n_cand;
-        compact = n_cand <= (uint32_t)CAND_CAP;
-    } else {
-        for (uint32_t i = tid; i < n; i += nth) { t.cand_key[i] = row[i]; t.cand_pos[i] = i; }
-        __syncthreads();
-    }
-
-    int got;
-    if (compact) {
-        got = block_select_smallest(s, n_cand, (uint32_t)k,
-            [&](uint32_t i) { return t.cand_key[i]; },
-            [&](uint32_t i) -> long long { return t.cand_key[i] == kPadKey ? 0x7FFFFFFFFFFFFFFFll : id_of(t.cand_pos[i]); });
-    } else {
-        got = block_select_smallest(s, n, (uint32_t)k,
-            [&](uint32_t i) { return row[i]; },
-            [&](uint32_t i) -> long long { return row[i] == kPadKey ? 0x7FFFFFFFFFFFFFFFll : id_of(i); });
-    }
+    const int got = block_select_row(t, row, n, (uint32_t)k, id_of);
     for (int j = tid; j < k; j += nth) {
         int64_t id = -1;
         float dist = __uint_as_float(0x7F800000u);
@@ -975,10 +1045,7 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         StageTimer t0(idx, st, 0);
         if (int s = t0.begin()) return s;
         if (!d_probes_in) {
-            dim3 grid((idx->n_lists + CT - 1) / CT, (tq + CT - 1) / CT);
-            hipLaunchKernelGGL(coarse_dist_kernel, grid, dim3(256), 0, st, qt, idx->dev.centroids, tq,
-                               idx->n_lists, idx->d, w_D);
-            HIP_TRY(hipGetLastError());
+            if (int s = launch_coarse(qt, idx->dev.centroids, tq, idx->n_lists, idx->d, w_D, st)) return s;
             hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_D, idx->n_lists,
                                n_probes, idx->dev.list_sizes, w_probes, w_probe_d, w_roff);
             HIP_TRY(hipGetLastError());
@@ -1132,10 +1199,8 @@ int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_
     float* w_D = (float*)((unsigned char*)d_workspace + plan.D);
     for (int64_t q0 = 0; q0 < nq; q0 += plan.tile) {
         const int tq = (int)std::min<int64_t>(plan.tile, nq - q0);
-        dim3 grid((idx->n_lists + CT - 1) / CT, (tq + CT - 1) / CT);
-        hipLaunchKernelGGL(coarse_dist_kernel, grid, dim3(256), 0, st, d_queries + (size_t)q0 * idx->d,
-                           idx->dev.centroids, tq, idx->n_lists, idx->d, w_D);
-        HIP_TRY(hipGetLastError());
+        if (int s = launch_coarse(d_queries + (size_t)q0 * idx->d, idx->dev.centroids, tq, idx->n_lists, idx->d, w_D, st))
+            return s;
         hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_D, idx->n_lists, n_probes,
                            idx->dev.list_sizes, d_probes + (size_t)q0 * n_probes,
                            d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr);
