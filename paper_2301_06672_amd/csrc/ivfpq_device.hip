@@ -370,7 +370,7 @@ __device__ int block_select_smallest(SelectShared& s, uint32_t n, uint32_t k, Ke
 // position pos.  On return records [0, got) hold key, tie and row position in ascending
 // (key, tie) order.
 // ------------------------------------------------------------------------------------------------
-constexpr int CAND_CAP = 2048;
+constexpr int CAND_CAP = 1024;   // >= IVFPQ_MAX_K
 
 struct RowSelectShared {
     SelectShared sel;
