@@ -435,13 +435,15 @@ __device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__
 // ================================================================================================
 // Step 1b: probe selection for one query per workgroup, from the coarse distance row.
 // Also lays out the query's slice of the R scratch: roff[p] = first slot of probe p, roff[n_probes]
-// = padded candidate count (every cluster padded to a multiple of 64 vectors).
+// = padded candidate count (every cluster padded to a multiple of 64 vectors), and writes one
+// descriptor per (query, probe) pair -- {cluster, length, first 64-vector group, R offset} -- so
+// that a scan workgroup starts from a single 16-byte load.
 // ================================================================================================
 __global__ void __launch_bounds__(SEL_THREADS)
 select_probes_kernel(const float* __restrict__ D, int n_lists, int n_probes,
-                     const uint32_t* __restrict__ list_sizes,
+                     const uint32_t* __restrict__ list_sizes, const int64_t* __restrict__ group_offsets,
                      uint32_t* __restrict__ probes, float* __restrict__ probe_dists,
-                     uint32_t* __restrict__ roff) {
+                     uint32_t* __restrict__ roff, uint4* __restrict__ pairs) {
     __shared__ RowSelectShared t;
     SelectShared& s = t.sel;
     const int q = blockIdx.x;
@@ -455,8 +457,10 @@ select_probes_kernel(const float* __restrict__ D, int n_lists, int n_probes,
     if (roff && threadIdx.x == 0) {
         uint32_t at = 0;
         for (int p = 0; p < got; ++p) {
+            const uint32_t l = s.rec_pos[p], len = list_sizes[l];
             roff[(size_t)q * (n_probes + 1) + p] = at;
-            at += (list_sizes[s.rec_pos[p]] + 63u) & ~63u;
+            pairs[(size_t)q * n_probes + p] = make_uint4(l, len, (uint32_t)group_offsets[l], at);
+            at += (len + 63u) & ~63u;
         }
         roff[(size_t)q * (n_probes + 1) + got] = at;
     }
@@ -465,16 +469,19 @@ select_probes_kernel(const float* __restrict__ D, int n_lists, int n_probes,
 // Same layout step for caller-given probes.
 __global__ void __launch_bounds__(256)
 layout_probes_kernel(const uint32_t* __restrict__ probes_in, int nq, int n_probes, int n_lists,
-                     const uint32_t* __restrict__ list_sizes,
-                     uint32_t* __restrict__ probes, uint32_t* __restrict__ roff) {
+                     const uint32_t* __restrict__ list_sizes, const int64_t* __restrict__ group_offsets,
+                     uint32_t* __restrict__ probes, uint32_t* __restrict__ roff, uint4* __restrict__ pairs) {
     int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nq) return;
     uint32_t at = 0;
     for (int p = 0; p < n_probes; ++p) {
         uint32_t l = probes_in[(size_t)q * n_probes + p];
+        const bool ok = l < (uint32_t)n_lists;                 // an out-of-range entry is skipped
+        const uint32_t len = ok ? list_sizes[l] : 0u;
         probes[(size_t)q * n_probes + p] = l;
         roff[(size_t)q * (n_probes + 1) + p] = at;
-        if (l < (uint32_t)n_lists) at += (list_sizes[l] + 63u) & ~63u;   // an out-of-range entry is skipped
+        pairs[(size_t)q * n_probes + p] = make_uint4(l, len, ok ? (uint32_t)group_offsets[l] : 0u, at);
+        at += (len + 63u) & ~63u;
     }
     roff[(size_t)q * (n_probes + 1) + n_probes] = at;
 }
@@ -657,8 +664,7 @@ struct ScanArgs {
     const uint32_t* list_sizes;
     const int64_t* group_offsets;
     const uint8_t* codes;
-    const uint32_t* probes;       // [nq][n_probes]; unused in single-list mode
-    const uint32_t* roff;         // [nq][n_probes+1]
+    const uint4* pairs;           // [nq][n_probes] {cluster, length, first group, R offset}; unused in single-list mode
     float* R;                     // [nq][stride]
     size_t stride;
     int n_probes;
@@ -682,24 +688,25 @@ scan_kernel(ScanArgs a) {
     float* rq = reinterpret_cast<float*>(smem + (((size_t)n_entries * LutTraits<LUT>::bytes + 15) & ~(size_t)15));
 
     int q, l;
+    uint32_t len, first_group;
     float* Rout;
     if (a.single_list >= 0) {
         q = 0; l = a.single_list; Rout = a.R;
+        len = a.list_sizes[l];
+        first_group = (uint32_t)a.group_offsets[l];
     } else {
         q = blockIdx.x / a.n_probes;
-        const int slot = blockIdx.x - q * a.n_probes;
-        l = (int)a.probes[(size_t)q * a.n_probes + slot];
-        Rout = a.R + (size_t)q * a.stride + a.roff[(size_t)q * (a.n_probes + 1) + slot];
+        const uint4 pair = a.pairs[blockIdx.x];
+        l = (int)pair.x; len = pair.y; first_group = pair.z;
+        Rout = a.R + (size_t)q * a.stride + pair.w;
     }
-    if ((uint32_t)l >= (uint32_t)a.n_lists) return;   // caller-given probe out of range: nothing to scan
-    const uint32_t len = a.list_sizes[l];
-    if (len == 0) return;
+    if (len == 0) return;     // empty cluster (or a caller-given probe that was out of range)
     const int n_groups = (int)((len + 63u) >> 6);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int n_waves = blockDim.x >> 6;
     const int nch = NCH > 0 ? NCH : a.n_chunks;
-    const uint8_t* codes_l = a.codes + (size_t)a.group_offsets[l] * 64 * ((size_t)nch * CW);
+    const uint8_t* codes_l = a.codes + (size_t)first_group * 64 * ((size_t)nch * CW);
 
     using chunk_t = typename std::conditional<CW == 16, uint4, uint32_t>::type;
     const chunk_t* cbase = reinterpret_cast<const chunk_t*>(codes_l);
@@ -860,7 +867,7 @@ ImageLayout image_layout(const ivfpq_index* idx) {
 struct Plan {
     int64_t tile;           // queries per tile
     size_t stride;          // R slots per query
-    size_t probes, probe_d, roff, D, R, total;
+    size_t probes, probe_d, roff, pairs, D, R, total;
 };
 
 constexpr size_t kScratchTarget = (size_t)1 << 30;   // aim for about 1 GiB of R + D per tile
@@ -885,6 +892,7 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     plan->probes = take((size_t)tile * n_probes * 4);
     plan->probe_d = take((size_t)tile * n_probes * 4);
     plan->roff = take((size_t)tile * (n_probes + 1) * 4);
+    plan->pairs = take((size_t)tile * n_probes * 16);
     plan->D = take(need_D ? (size_t)tile * idx->n_lists * 4 : 0);
     plan->R = take((size_t)tile * stride * 4);
     plan->total = at;
@@ -1032,6 +1040,7 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
     uint32_t* w_probes = (uint32_t*)(ws + plan.probes);
     float* w_probe_d = (float*)(ws + plan.probe_d);
     uint32_t* w_roff = (uint32_t*)(ws + plan.roff);
+    uint4* w_pairs = (uint4*)(ws + plan.pairs);
     float* w_D = (float*)(ws + plan.D);
     float* w_R = (float*)(ws + plan.R);
 
@@ -1047,12 +1056,12 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         if (!d_probes_in) {
             if (int s = launch_coarse(qt, idx->dev.centroids, tq, idx->n_lists, idx->d, w_D, st)) return s;
             hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_D, idx->n_lists,
-                               n_probes, idx->dev.list_sizes, w_probes, w_probe_d, w_roff);
+                               n_probes, idx->dev.list_sizes, idx->dev.group_offsets, w_probes, w_probe_d, w_roff, w_pairs);
             HIP_TRY(hipGetLastError());
         } else {
             hipLaunchKernelGGL(layout_probes_kernel, dim3((tq + 255) / 256), dim3(256), 0, st,
                                d_probes_in + (size_t)q0 * n_probes, tq, n_probes, idx->n_lists, idx->dev.list_sizes,
-                               w_probes, w_roff);
+                               idx->dev.group_offsets, w_probes, w_roff, w_pairs);
             HIP_TRY(hipGetLastError());
         }
         if (int s = t0.end()) return s;
@@ -1060,7 +1069,7 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         StageTimer t1(idx, st, 1);
         if (int s = t1.begin()) return s;
         ScanArgs a = base_scan_args(idx);
-        a.queries = qt; a.probes = w_probes; a.roff = w_roff; a.R = w_R; a.stride = plan.stride;
+        a.queries = qt; a.pairs = w_pairs; a.R = w_R; a.stride = plan.stride;
         a.n_probes = n_probes;
         if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)((size_t)tq * n_probes)), st)) return s;
         if (int s = t1.end()) return s;
@@ -1098,6 +1107,8 @@ int ivfpq_upload(ivfpq_index_t* idx, void* d_buf, size_t bytes, void* hip_stream
     const ImageLayout L = image_layout(idx);
     if (bytes < L.total) return fail(IVFPQ_ENOSPACE, "device buffer of %zu bytes given, %zu needed", bytes, L.total);
     if (((uintptr_t)d_buf % kAlign) != 0) return fail(IVFPQ_EINVAL, "device buffer must be %zu-byte aligned", kAlign);
+    if (idx->total_groups >= ((int64_t)1 << 32))
+        return fail(IVFPQ_EUNSUPPORTED, "%lld 64-vector groups (limit 2^32)", (long long)idx->total_groups);
     hipStream_t st = (hipStream_t)hip_stream;
     unsigned char* base = (unsigned char*)d_buf;
     const int cb = idx->code_bytes(), cw = chunk_width(idx), nch = cb / cw;
@@ -1202,8 +1213,9 @@ int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_
         if (int s = launch_coarse(d_queries + (size_t)q0 * idx->d, idx->dev.centroids, tq, idx->n_lists, idx->d, w_D, st))
             return s;
         hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_D, idx->n_lists, n_probes,
-                           idx->dev.list_sizes, d_probes + (size_t)q0 * n_probes,
-                           d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr);
+                           idx->dev.list_sizes, idx->dev.group_offsets, d_probes + (size_t)q0 * n_probes,
+                           d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr,
+                           (uint4*)nullptr);
         HIP_TRY(hipGetLastError());
     }
     return IVFPQ_OK;
