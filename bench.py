@@ -23,9 +23,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth, GB/s
 
-# HBM traffic of the scan kernel per step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/scan_kernel_<workload>_pmc.txt), in bytes; None where no counter run is recorded.
-MEASURED_TRAFFIC = {}
+# Memory-side traffic of the scan kernel per step (all launches of one step), in bytes, from two
+# rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads
+# for a plain 1 GiB copy (FETCH_SIZE reads half the true KiB on this chip, WRITE_SIZE the true
+# figure): profiles/scan_kernel_<workload>_e5m3_hbm_traffic.txt.  None where no run is recorded.
+MEASURED_TRAFFIC = {
+    ("intgrid_1m", "e5m3"): 21.211e9,     # 19.251 GB fetched + 1.960 GB written (algorithmic: 30.98 GB of codes)
+    ("unitnorm_10m", "e5m3"): 10.360e9,   # 9.567 GB fetched + 0.793 GB written (algorithmic: 9.24 GB of codes)
+}
 
 
 def log(msg):
@@ -192,6 +197,8 @@ def main():
         "traffic": MEASURED_TRAFFIC.get((w.name, args.lut)),
         "algorithmic_bytes_per_step": code_bytes, "scanned_vectors_per_step": scanned_vectors,
         "scan_ms_per_step": round(scan_ms, 4),
+        "note": "achieved, traffic and the byte counts are per step = all scan_kernel launches of one step "
+                "(one launch per query tile); the ratio equals bytes per launch / average launch time",
     }
 
     cpu = None
