@@ -37,7 +37,7 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def exact_topk_gpu(data_np, queries_t, k, chunk=200_000):
+def exact_topk_gpu(data_np, queries_t, k, chunk=1_000_000):
     """Harness-side ground truth: exact k nearest by float64 distances, chunked over the data."""
     import torch
     q = queries_t.double()

@@ -63,8 +63,13 @@ def build_index_arrays(data: np.ndarray, n_lists: int, pq_dim: int, pq_bits: int
     counts = torch.bincount(labels, minlength=n_lists)
     offsets = torch.zeros(n_lists + 1, dtype=torch.int64, device=dev)
     offsets[1:] = torch.cumsum(counts, 0)
-    residual = x[order] - centroids[labels[order]]
+    # residuals in list order, in place and in slices (the 10^8-vector sets leave no room for copies)
+    residual = x[order]
     del x
+    lab_sorted = labels[order]
+    for lo in range(0, n, 1 << 22):
+        residual[lo:lo + (1 << 22)] -= centroids[lab_sorted[lo:lo + (1 << 22)]]
+    del lab_sorted
     codebooks = torch.empty((pq_dim, ksub, m), dtype=torch.float32, device=dev)
     sub_codes = torch.empty((n, pq_dim), dtype=torch.uint8, device=dev)
     train_rows = _stride_rows(n, 262144, dev)
