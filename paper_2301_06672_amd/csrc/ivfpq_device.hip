@@ -379,42 +379,57 @@ struct RowSelectShared {
     uint32_t n_cand;
 };
 
-template <class TieFn>
+// pos_of(i): logical position of row element i (what the records report and what tie_of_pos
+// takes); have_bound/bound: an upper bound of the k-th smallest key that the caller already knows
+// (it must be the key of at least k elements' worth of the row, i.e. at least k elements are <= it).
+template <class PosFn, class TieFn>
 __device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
-                                TieFn tie_of_pos) {
+                                bool have_bound, uint32_t bound, PosFn pos_of, TieFn tie_of_pos) {
     SelectShared& s = t.sel;
     const int tid = threadIdx.x, nth = blockDim.x;
-    __syncthreads();
-    if (tid == 0) t.n_cand = 0;
-    __syncthreads();
+    const uint32_t kk = k < (uint32_t)CAND_CAP ? k : (uint32_t)CAND_CAP;
     bool compact = true;
     uint32_t n_cand = n;
+    __syncthreads();
     if (n > (uint32_t)CAND_CAP) {
-        for (int i = tid; i < CAND_CAP; i += nth) t.cand_key[i] = row[i];
         uint32_t r0, r1;
-        const uint32_t kk = k < (uint32_t)CAND_CAP ? k : (uint32_t)CAND_CAP;
-        const uint32_t bound = block_kth_key(s, (uint32_t)CAND_CAP, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1);
-        __syncthreads();
-        auto keep = [&](uint32_t key, uint32_t pos) {
-            if (key <= bound) {
-                uint32_t slot = atomicAdd(&t.n_cand, 1u);
-                if (slot < (uint32_t)CAND_CAP) { t.cand_key[slot] = key; t.cand_pos[slot] = pos; }
-            }
-        };
-        if ((n & 3u) == 0 && (reinterpret_cast<uintptr_t>(row) & 15u) == 0) {
-            const uint4* row4 = reinterpret_cast<const uint4*>(row);
-            for (uint32_t i4 = tid; i4 < n / 4; i4 += nth) {
-                const uint4 v = row4[i4];
-                keep(v.x, i4 * 4); keep(v.y, i4 * 4 + 1); keep(v.z, i4 * 4 + 2); keep(v.w, i4 * 4 + 3);
-            }
-        } else {
-            for (uint32_t i = tid; i < n; i += nth) keep(row[i], i);
+        if (!have_bound) {
+            for (int i = tid; i < CAND_CAP; i += nth) t.cand_key[i] = row[i];
+            bound = block_kth_key(s, (uint32_t)CAND_CAP, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1);
         }
-        __syncthreads();
-        n_cand = t.n_cand;
-        compact = n_cand <= (uint32_t)CAND_CAP;
+        const bool vec = (n & 3u) == 0 && (reinterpret_cast<uintptr_t>(row) & 15u) == 0;
+        compact = false;
+        // Each pass keeps the elements not above the bound.  If they overflow the LDS buffer, the
+        // k-th smallest of the ones that were kept is a tighter valid bound (they are all members
+        // of the row): the survivor count shrinks by about CAND_CAP / k per pass.
+        for (int pass = 0; pass < 8; ++pass) {
+            __syncthreads();
+            if (tid == 0) t.n_cand = 0;
+            __syncthreads();
+            auto keep = [&](uint32_t key, uint32_t i) {
+                if (key <= bound) {
+                    uint32_t slot = atomicAdd(&t.n_cand, 1u);
+                    if (slot < (uint32_t)CAND_CAP) { t.cand_key[slot] = key; t.cand_pos[slot] = pos_of(i); }
+                }
+            };
+            if (vec) {
+                const uint4* row4 = reinterpret_cast<const uint4*>(row);
+                for (uint32_t i4 = tid; i4 < n / 4; i4 += nth) {
+                    const uint4 v = row4[i4];
+                    keep(v.x, i4 * 4); keep(v.y, i4 * 4 + 1); keep(v.z, i4 * 4 + 2); keep(v.w, i4 * 4 + 3);
+                }
+            } else {
+                for (uint32_t i = tid; i < n; i += nth) keep(row[i], i);
+            }
+            __syncthreads();
+            n_cand = t.n_cand;
+            if (n_cand <= (uint32_t)CAND_CAP) { compact = true; break; }
+            const uint32_t tighter = block_kth_key(s, (uint32_t)CAND_CAP, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1);
+            if (tighter >= bound) break;      // a plateau of equal keys: no progress possible this way
+            bound = tighter;
+        }
     } else {
-        for (uint32_t i = tid; i < n; i += nth) { t.cand_key[i] = row[i]; t.cand_pos[i] = i; }
+        for (uint32_t i = tid; i < n; i += nth) { t.cand_key[i] = row[i]; t.cand_pos[i] = pos_of(i); }
         __syncthreads();
     }
     int got;
@@ -422,13 +437,14 @@ __device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__
         got = block_select_smallest(s, n_cand, k,
             [&](uint32_t i) { return t.cand_key[i]; },
             [&](uint32_t i) -> long long { return tie_of_pos(t.cand_pos[i], t.cand_key[i]); });
-        for (int j = tid; j < got; j += nth) s.rec_pos[j] = t.cand_pos[s.rec_pos[j]];   // back to row positions
-        __syncthreads();
+        for (int j = tid; j < got; j += nth) s.rec_pos[j] = t.cand_pos[s.rec_pos[j]];   // back to logical positions
     } else {
         got = block_select_smallest(s, n, k,
             [&](uint32_t i) { return row[i]; },
-            [&](uint32_t i) -> long long { return tie_of_pos(i, row[i]); });
+            [&](uint32_t i) -> long long { return tie_of_pos(pos_of(i), row[i]); });
+        for (int j = tid; j < got; j += nth) s.rec_pos[j] = pos_of(s.rec_pos[j]);
     }
+    __syncthreads();
     return got;
 }
 
@@ -448,7 +464,8 @@ select_probes_kernel(const float* __restrict__ D, int n_lists, int n_probes,
     SelectShared& s = t.sel;
     const int q = blockIdx.x;
     const uint32_t* row = reinterpret_cast<const uint32_t*>(D + (size_t)q * n_lists);   // distances >= +0
-    int got = block_select_row(t, row, (uint32_t)n_lists, (uint32_t)n_probes,
+    int got = block_select_row(t, row, (uint32_t)n_lists, (uint32_t)n_probes, false, 0u,
+                               [](uint32_t i) { return i; },
                                [](uint32_t pos, uint32_t) { return (long long)pos; });
     for (int p = threadIdx.x; p < got; p += blockDim.x) {
         probes[(size_t)q * n_probes + p] = s.rec_pos[p];
@@ -657,6 +674,8 @@ __device__ inline float add_word(float acc, const unsigned char* lut, uint32_t w
     return acc;
 }
 
+constexpr int kStageCap = 128;   // survivors a wave stages in LDS before it appends them (8 bytes each)
+
 struct ScanArgs {
     const float* queries;         // [nq][d] (tile base)
     const float* centroids;
@@ -665,6 +684,11 @@ struct ScanArgs {
     const int64_t* group_offsets;
     const uint8_t* codes;
     const uint4* pairs;           // [nq][n_probes] {cluster, length, first group, R offset}; unused in single-list mode
+    const uint32_t* bounds;       // [nq] per-query upper bound of the k-th smallest R (filtered mode)
+    uint32_t* counts;             // [nq] survivors appended so far (filtered mode)
+    uint32_t* Rpos;               // [nq][stride] row position of each appended survivor (filtered mode)
+    int mode;                     // 1: nearest probe of every query, every R written in place;
+                                  // 2: the other probes, only R <= bound appended behind the nearest probe's segment
     float* R;                     // [nq][stride]
     size_t stride;
     int n_probes;
@@ -688,19 +712,39 @@ scan_kernel(ScanArgs a) {
     float* rq = reinterpret_cast<float*>(smem + (((size_t)n_entries * LutTraits<LUT>::bytes + 15) & ~(size_t)15));
 
     int q, l;
-    uint32_t len, first_group;
+    uint32_t len, first_group, row_pos0 = 0;
     float* Rout;
     if (a.single_list >= 0) {
         q = 0; l = a.single_list; Rout = a.R;
         len = a.list_sizes[l];
         first_group = (uint32_t)a.group_offsets[l];
     } else {
-        q = blockIdx.x / a.n_probes;
-        const uint4 pair = a.pairs[blockIdx.x];
+        size_t pair_idx;
+        if (a.mode == 1) {
+            q = blockIdx.x;
+            pair_idx = (size_t)q * a.n_probes;
+        } else {
+            q = blockIdx.x / (a.n_probes - 1);
+            pair_idx = (size_t)q * a.n_probes + 1 + (blockIdx.x - q * (a.n_probes - 1));
+        }
+        const uint4 pair = a.pairs[pair_idx];
         l = (int)pair.x; len = pair.y; first_group = pair.z;
         Rout = a.R + (size_t)q * a.stride + pair.w;
+        row_pos0 = pair.w;
     }
     if (len == 0) return;     // empty cluster (or a caller-given probe that was out of range)
+    const bool filtered = a.single_list < 0 && a.mode == 2;
+    uint32_t bound = 0, seg0 = 0;
+    if (filtered) {
+        bound = a.bounds[q];
+        seg0 = a.pairs[(size_t)q * a.n_probes + 1].w;     // padded length of the nearest probe's segment
+    }
+    // filtered mode: every wave stages its survivors in a private LDS buffer and appends them to the
+    // query's row with one global atomic per flush (the counter of a query is shared by all the
+    // workgroups of that query: one atomic per 64-vector group would serialise on it)
+    uint2* stage = reinterpret_cast<uint2*>(reinterpret_cast<unsigned char*>(rq) + (((size_t)a.d * 4 + 15) & ~(size_t)15))
+                   + (size_t)(threadIdx.x >> 6) * kStageCap;
+    uint32_t staged = 0;       // wave-uniform
     const int n_groups = (int)((len + 63u) >> 6);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
@@ -734,10 +778,35 @@ scan_kernel(ScanArgs a) {
         }
         return acc;
     };
+    auto flush_stage = [&]() {
+        if (staged == 0) return;
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&a.counts[q], staged);
+        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+        uint32_t* dst_key = reinterpret_cast<uint32_t*>(a.R) + (size_t)q * a.stride + seg0 + base;
+        uint32_t* dst_pos = a.Rpos + (size_t)q * a.stride + seg0 + base;
+        for (uint32_t j = lane; j < staged; j += kWave) {
+            const uint2 e = stage[j];
+            dst_key[j] = e.x;
+            dst_pos[j] = e.y;
+        }
+        staged = 0;
+    };
     auto store_R = [&](int g, float acc) {
         const uint32_t i = (uint32_t)g * 64u + lane;
-        if (i < len) Rout[i] = acc;
-        else if (a.single_list < 0) Rout[i] = __uint_as_float(kPadKey);   // padding slot of the R scratch
+        if (!filtered) {
+            if (i < len) Rout[i] = acc;
+            else if (a.single_list < 0) Rout[i] = __uint_as_float(kPadKey);   // padding slot of the R scratch
+        } else {
+            // keep only what can still be among the k best
+            const bool keep = i < len && __float_as_uint(acc) <= bound;
+            const unsigned long long m = __ballot(keep);
+            if (m != 0) {
+                if (staged + 64u > (uint32_t)kStageCap) flush_stage();
+                if (keep) stage[staged + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = make_uint2(__float_as_uint(acc), row_pos0 + i);
+                staged += (uint32_t)__popcll(m);
+            }
+        }
     };
 
     // issue the loads of this wave's first group before the table is built: HBM latency overlaps it
@@ -777,6 +846,7 @@ scan_kernel(ScanArgs a) {
             store_R(g, acc);
         }
     }
+    if (filtered) flush_stage();
 }
 
 // Steps 2-3 only: the table of one pair, copied out of LDS byte for byte.
@@ -800,12 +870,44 @@ dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centr
 }
 
 // ================================================================================================
+// Between the two scan launches: per query, an upper bound of the k-th smallest R, taken from the
+// nearest probed cluster (whose R values are all in place): its k-th smallest R.  With fewer than
+// k vectors there the bound admits everything.  Also clears the query's survivor counter.
+// ================================================================================================
+constexpr uint32_t kAdmitAll = 0xFFFFFFFEu;   // every real R is below this, the padding key is above
+
+__global__ void __launch_bounds__(SEL_THREADS)
+bound_kernel(const float* __restrict__ R, size_t stride, const uint4* __restrict__ pairs, int n_probes, int k,
+             uint32_t* __restrict__ bounds, uint32_t* __restrict__ counts) {
+    __shared__ SelectShared s;
+    __shared__ uint32_t keys[CAND_CAP];
+    const int q = blockIdx.x;
+    const int tid = threadIdx.x, nth = blockDim.x;
+    const uint32_t seg0 = n_probes > 1 ? pairs[(size_t)q * n_probes + 1].w : 0u;
+    const uint32_t len0 = pairs[(size_t)q * n_probes].y;       // real values in the segment (the rest is padding)
+    const uint32_t* row = reinterpret_cast<const uint32_t*>(R + (size_t)q * stride);
+    uint32_t bound = kAdmitAll;
+    if (len0 >= (uint32_t)k && seg0 >= len0) {
+        uint32_t r0, r1;
+        if (seg0 <= (uint32_t)CAND_CAP) {
+            for (uint32_t i = tid; i < seg0; i += nth) keys[i] = row[i];
+            bound = block_kth_key(s, seg0, (uint32_t)k, [&](uint32_t i) { return keys[i]; }, &r0, &r1);
+        } else {
+            bound = block_kth_key(s, seg0, (uint32_t)k, [&](uint32_t i) { return row[i]; }, &r0, &r1);
+        }
+    }
+    if (tid == 0) { bounds[q] = bound; counts[q] = 0; }
+}
+
+// ================================================================================================
 // Step 5: per query, the k smallest R over all probed clusters, ordered by (R, id), by one exact
-// row selection over the query's slice of the R scratch; (cluster, position) -> the caller's id.
+// selection over the query's R row -- the nearest probe's segment followed by the survivors the
+// filtered scan appended -- and the map from (cluster, position) to the caller's id.
 // ================================================================================================
 __global__ void __launch_bounds__(SEL_THREADS)
-topk_kernel(const float* __restrict__ R, size_t stride, const uint32_t* __restrict__ roff,
-            const uint32_t* __restrict__ probes, int n_probes, int k,
+topk_kernel(const float* __restrict__ R, const uint32_t* __restrict__ Rpos, size_t stride,
+            const uint32_t* __restrict__ roff, const uint32_t* __restrict__ probes,
+            const uint32_t* __restrict__ bounds, const uint32_t* __restrict__ counts, int n_probes, int k,
             const int64_t* __restrict__ list_offsets, const int64_t* __restrict__ ids,
             int64_t* __restrict__ out_ids, float* __restrict__ out_dists) {
     __shared__ RowSelectShared t;
@@ -814,20 +916,25 @@ topk_kernel(const float* __restrict__ R, size_t stride, const uint32_t* __restri
     const int tid = threadIdx.x, nth = blockDim.x;
     const uint32_t* s_roff = roff + (size_t)q * (n_probes + 1);     // read through the vector cache:
     const uint32_t* s_probe = probes + (size_t)q * n_probes;        // only the few survivors look them up
-    const uint32_t n = s_roff[n_probes];      // padded candidate count: a multiple of 64
+    const uint32_t seg0 = s_roff[1];          // padded length of the nearest probe's segment (a multiple of 64)
+    const uint32_t n = seg0 + (n_probes > 1 ? counts[q] : 0u);
     const uint32_t* row = reinterpret_cast<const uint32_t*>(R + (size_t)q * stride);
+    const uint32_t* row_pos = Rpos + (size_t)q * stride;
 
-    // tie key = the caller's id of the candidate at slot `i` of the row (padding slots sort last)
-    auto id_of = [&](uint32_t i, uint32_t key) -> long long {
+    // position of row element i in the unfiltered layout (probe segments back to back)
+    auto pos_of = [&](uint32_t i) { return i < seg0 ? i : row_pos[i]; };
+    // tie key = the caller's id of the candidate at that position (padding slots sort last)
+    auto id_of = [&](uint32_t pos, uint32_t key) -> long long {
         if (key == kPadKey) return 0x7FFFFFFFFFFFFFFFll;
-        int lo = 0, hi = n_probes;            // largest probe slot with roff[slot] <= i
+        int lo = 0, hi = n_probes;            // largest probe slot with roff[slot] <= pos
         while (hi - lo > 1) {
             int mid = (lo + hi) >> 1;
-            if (s_roff[mid] <= i) lo = mid; else hi = mid;
+            if (s_roff[mid] <= pos) lo = mid; else hi = mid;
         }
-        return (long long)ids[list_offsets[s_probe[lo]] + (int64_t)(i - s_roff[lo])];
+        return (long long)ids[list_offsets[s_probe[lo]] + (int64_t)(pos - s_roff[lo])];
     };
-    const int got = block_select_row(t, row, n, (uint32_t)k, id_of);
+    const bool have_bound = n_probes > 1;
+    const int got = block_select_row(t, row, n, (uint32_t)k, have_bound, have_bound ? bounds[q] : 0u, pos_of, id_of);
     for (int j = tid; j < k; j += nth) {
         int64_t id = -1;
         float dist = __uint_as_float(0x7F800000u);
@@ -867,10 +974,10 @@ ImageLayout image_layout(const ivfpq_index* idx) {
 struct Plan {
     int64_t tile;           // queries per tile
     size_t stride;          // R slots per query
-    size_t probes, probe_d, roff, pairs, D, R, total;
+    size_t probes, probe_d, roff, pairs, bounds, counts, D, R, Rpos, total;
 };
 
-constexpr size_t kScratchTarget = (size_t)1 << 30;   // aim for about 1 GiB of R + D per tile
+constexpr size_t kScratchTarget = (size_t)2 << 30;   // aim for about 2 GiB of scratch (R, positions, D) per tile
 
 // given_probes: the caller chooses the clusters and may name one several times, so the bound on a
 // query's candidates is n_probes times the largest cluster rather than the n_probes largest ones
@@ -882,7 +989,7 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     if (stride >= ((int64_t)1 << 31))
         return fail(IVFPQ_EUNSUPPORTED, "a query may see %lld candidates (limit 2^31)", (long long)stride);
     if (stride < 64) stride = 64;
-    size_t per_query = (size_t)stride * 4 + (need_D ? (size_t)idx->n_lists * 4 : 0);
+    size_t per_query = (size_t)stride * 8 + (need_D ? (size_t)idx->n_lists * 4 : 0);
     int64_t tile = (int64_t)(kScratchTarget / per_query);
     tile = std::max<int64_t>(1, std::min<int64_t>(tile, std::max<int64_t>(nq, 1)));
     plan->tile = tile;
@@ -893,8 +1000,11 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     plan->probe_d = take((size_t)tile * n_probes * 4);
     plan->roff = take((size_t)tile * (n_probes + 1) * 4);
     plan->pairs = take((size_t)tile * n_probes * 16);
+    plan->bounds = take((size_t)tile * 4);
+    plan->counts = take((size_t)tile * 4);
     plan->D = take(need_D ? (size_t)tile * idx->n_lists * 4 : 0);
     plan->R = take((size_t)tile * stride * 4);
+    plan->Rpos = take((size_t)tile * stride * 4);
     plan->total = at;
     return IVFPQ_OK;
 }
@@ -915,7 +1025,11 @@ size_t lut_elem_bytes(int lut_dtype) { return lut_dtype == IVFPQ_LUT_FP32 ? 4 : 
 
 size_t scan_lds_bytes(const ivfpq_index* idx, int lut_dtype) {
     size_t lut = (size_t)idx->pq_dim * idx->ksub() * lut_elem_bytes(lut_dtype);
-    return ((lut + 15) & ~(size_t)15) + (size_t)idx->d * 4;
+    return ((lut + 15) & ~(size_t)15) + (((size_t)idx->d * 4 + 15) & ~(size_t)15);
+}
+// plus the per-wave survivor staging of the filtered scan
+size_t scan_lds_bytes_staged(const ivfpq_index* idx, int lut_dtype, int threads) {
+    return scan_lds_bytes(idx, lut_dtype) + (size_t)(threads / 64) * kStageCap * 8;
 }
 
 int check_device(const ivfpq_index* idx) {
@@ -932,10 +1046,13 @@ int scan_threads(const ivfpq_index* idx, int lut_dtype) {
         int v = std::atoi(env);
         if (v == 64 || v == 128 || v == 256 || v == 512 || v == 1024) return v;
     }
+    // measured on MI355X: small tables want many 4-wave workgroups per CU; large tables want the
+    // largest workgroup of which two still fit the CU's LDS (table + residual + survivor staging)
     size_t lds = scan_lds_bytes(idx, lut_dtype);
     if (lds <= 20 * 1024) return 256;
     if (lds <= 40 * 1024) return 512;
-    return 1024;
+    if (2 * (lds + (size_t)16 * kStageCap * 8) <= kLdsBytes) return 1024;
+    return 512;
 }
 
 template <int LUT, int BITS>
@@ -961,13 +1078,13 @@ int launch_scan_bits(const ScanArgs& a, int cw, int nch, dim3 grid, int threads,
 }
 
 int launch_scan(const ivfpq_index* idx, ScanArgs a, int lut_dtype, dim3 grid, hipStream_t st) {
-    const size_t lds = scan_lds_bytes(idx, lut_dtype);
+    const int threads = scan_threads(idx, lut_dtype);
+    const size_t lds = scan_lds_bytes_staged(idx, lut_dtype, threads);
     if (lds > kLdsBytes)
-        return fail(IVFPQ_EUNSUPPORTED, "lookup table + residual need %zu bytes of LDS (limit %zu)", lds, kLdsBytes);
+        return fail(IVFPQ_EUNSUPPORTED, "lookup table + residual + staging need %zu bytes of LDS (limit %zu)", lds, kLdsBytes);
     const int cw = chunk_width(idx);
     const int nch = idx->code_bytes() / cw;
     a.n_chunks = nch;
-    const int threads = scan_threads(idx, lut_dtype);
     const bool b8 = idx->pq_bits == 8;
     switch (lut_dtype) {
         case IVFPQ_LUT_FP32:
@@ -1032,15 +1149,18 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
     if (int s = make_plan(idx, nq, n_probes, d_probes_in != nullptr, &plan)) return s;
     if (!d_ws || ws_bytes < plan.total)
         return fail(IVFPQ_ENOSPACE, "workspace of %zu bytes given, %zu needed", ws_bytes, plan.total);
-    if (scan_lds_bytes(idx, lut_dtype) > kLdsBytes)
-        return fail(IVFPQ_EUNSUPPORTED, "lookup table + residual need %zu bytes of LDS (limit %zu)",
-                    scan_lds_bytes(idx, lut_dtype), kLdsBytes);
+    if (scan_lds_bytes_staged(idx, lut_dtype, scan_threads(idx, lut_dtype)) > kLdsBytes)
+        return fail(IVFPQ_EUNSUPPORTED, "lookup table + residual + staging need %zu bytes of LDS (limit %zu)",
+                    scan_lds_bytes_staged(idx, lut_dtype, scan_threads(idx, lut_dtype)), kLdsBytes);
     hipStream_t st = (hipStream_t)hip_stream;
     unsigned char* ws = (unsigned char*)d_ws;
     uint32_t* w_probes = (uint32_t*)(ws + plan.probes);
     float* w_probe_d = (float*)(ws + plan.probe_d);
     uint32_t* w_roff = (uint32_t*)(ws + plan.roff);
     uint4* w_pairs = (uint4*)(ws + plan.pairs);
+    uint32_t* w_bounds = (uint32_t*)(ws + plan.bounds);
+    uint32_t* w_counts = (uint32_t*)(ws + plan.counts);
+    uint32_t* w_Rpos = (uint32_t*)(ws + plan.Rpos);
     float* w_D = (float*)(ws + plan.D);
     float* w_R = (float*)(ws + plan.R);
 
@@ -1068,16 +1188,25 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         // steps 2-4
         StageTimer t1(idx, st, 1);
         if (int s = t1.begin()) return s;
+        // nearest probe of every query first: its R values give the bound that filters the rest
         ScanArgs a = base_scan_args(idx);
         a.queries = qt; a.pairs = w_pairs; a.R = w_R; a.stride = plan.stride;
-        a.n_probes = n_probes;
-        if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)((size_t)tq * n_probes)), st)) return s;
+        a.n_probes = n_probes; a.bounds = w_bounds; a.counts = w_counts; a.Rpos = w_Rpos;
+        a.mode = 1;
+        if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)tq), st)) return s;
+        if (n_probes > 1) {
+            hipLaunchKernelGGL(bound_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_R, plan.stride, w_pairs, n_probes, k,
+                               w_bounds, w_counts);
+            HIP_TRY(hipGetLastError());
+            a.mode = 2;
+            if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)((size_t)tq * (n_probes - 1))), st)) return s;
+        }
         if (int s = t1.end()) return s;
         // step 5
         StageTimer t2(idx, st, 2);
         if (int s = t2.begin()) return s;
-        hipLaunchKernelGGL(topk_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_R, plan.stride, w_roff, w_probes,
-                           n_probes, k, idx->dev.list_offsets, idx->dev.ids, d_ids + (size_t)q0 * k,
+        hipLaunchKernelGGL(topk_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_R, w_Rpos, plan.stride, w_roff, w_probes,
+                           w_bounds, w_counts, n_probes, k, idx->dev.list_offsets, idx->dev.ids, d_ids + (size_t)q0 * k,
                            d_dists + (size_t)q0 * k);
         HIP_TRY(hipGetLastError());
         if (int s = t2.end()) return s;
