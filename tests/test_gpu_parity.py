@@ -220,6 +220,24 @@ def test_search_massive_ties_order_by_id(P):
             np.testing.assert_array_equal(d_g, d_o)
 
 
+def test_search_small_nearest_cluster_admits_everything(P):
+    # the nearest probe holds fewer than k vectors, so its R values give no bound: every vector of
+    # the large second cluster survives the filter (each wave appends several staged batches)
+    n, d = 3300, 32
+    cent, cb, _, codes, ids = si.random_index_arrays(n, d, 3, 16, 8, salt=800)
+    offs = np.array([0, 40, 3240, 3300], dtype=np.int64)
+    oidx = oracle.make_index(d, 3, 16, 8, cent, cb, offs, codes, ids)
+    gidx = to_library(P, oidx)
+    q = np.random.default_rng(800).standard_normal((6, d)).astype(np.float32)
+    for probes_row, k in (([0, 1], 100), ([0, 1, 2], 1000), ([2, 1], 64), ([1, 0], 10)):
+        probes = np.tile(np.array([probes_row], dtype=np.uint32), (6, 1))
+        for dtype in (oracle.LUT_FP32, oracle.LUT_E5M3):
+            _step(f"small nearest cluster probes={probes_row} k={k} dtype={dtype}")
+            ids_g, d_g = gidx.ivfpq_search_with_probes(q, probes, k, dtype)
+            ids_o, d_o = oracle.search(oidx, q, len(probes_row), k, dtype, probes=probes)
+            assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"probes={probes_row} k={k}")
+
+
 def test_search_cluster_listed_twice_is_scanned_twice(P, tiny):
     w, data, oidx, gidx = tiny
     q = si.queries(w, 10)
