@@ -40,114 +40,126 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 
 // ================================================================================================
-// Step 1a: coarse distances.  Tile of 128 queries x 128 clusters per 256-thread workgroup, 8x8
-// outputs per thread (two 4-wide strips per axis, so that LDS reads are 16-byte and conflict-free),
-// operands staged through LDS in slices of 16 components.  The distance is accumulated in the
-// direct form sum_t (q_t - c_t)^2, components in ascending order, so that its rounding error stays
-// relative to the distance itself (the expanded form |q|^2 - 2 q.c + |c|^2 cancels badly for
-// far-from-origin data and would not keep the probe lists within 1e-5 of exact).
+// Step 1a: coarse ranking values on the matrix cores.
+// For ranking the clusters of one query |q - c|^2 can be replaced by a(q, c) = |c|^2 - 2 q.c (the
+// |q|^2 term is common).  The dot products are one fp32 GEMM: v_mfma_f32_32x32x2_f32, a tile of
+// 128 queries x 128 clusters (or 64 x 64 for small problems) per 256-thread workgroup, operands
+// staged through LDS in slices of 16 components.  The expanded form cancels, so these values only
+// SHORT-LIST clusters: the selection kernel below recomputes the short-listed distances exactly
+// (direct form) and bounds the error of a() rigorously, so the probe list is the exact one.
+// Values are stored as order-preserving unsigned keys (a() can be negative).
 // ================================================================================================
 constexpr int CK = 16;   // components per LDS slice
+typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-// STRIPS = 1: 64 x 64 tile, 4x4 outputs per thread (more workgroups, for small problems);
-// STRIPS = 2: 128 x 128 tile, 8x8 outputs per thread (twice the arithmetic per LDS byte).
-template <int STRIPS>
+__device__ inline uint32_t ordered_key(float f) {          // monotone map float -> uint32
+    const uint32_t b = __float_as_uint(f);
+    return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ inline float ordered_key_value(uint32_t key) {
+    return __uint_as_float(key ^ ((key >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+}
+
+// WB = 32x32 output blocks per wave and axis; the 4 waves sit 2 x 2, so the tile edge is 64 * WB.
+template <int WB>
 __global__ void __launch_bounds__(256)
-coarse_dist_kernel(const float* __restrict__ queries, const float* __restrict__ centroids,
-                   int nq, int n_lists, int d, float* __restrict__ D) {
-    constexpr int CT = 64 * STRIPS;      // tile edge
-    constexpr int RT = 4 * STRIPS;       // outputs per thread and axis; also components a thread loads per row
-    __shared__ __align__(16) float qs[CK][CT + 4];
-    __shared__ __align__(16) float cs[CK][CT + 4];
+coarse_rank_kernel(const float* __restrict__ queries, const float* __restrict__ centroids,
+                   const float* __restrict__ centroid_norms, int nq, int n_lists, int d,
+                   uint32_t* __restrict__ A) {
+    constexpr int CT = 64 * WB;          // tile edge
+    constexpr int RT = 4 * WB;           // components a thread loads per tile row and slice
+    __shared__ float qs[CK][CT + 4];
+    __shared__ float cs[CK][CT + 4];
     const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
     const int q0 = blockIdx.y * CT, l0 = blockIdx.x * CT;
-    float acc[RT][RT];
+    floatx16 acc[WB][WB];
 #pragma unroll
-    for (int i = 0; i < RT; ++i)
+    for (int i = 0; i < WB; ++i)
 #pragma unroll
-        for (int j = 0; j < RT; ++j) acc[i][j] = 0.f;
+        for (int j = 0; j < WB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     constexpr int TPR = CK / RT;              // threads per tile row when loading
     const int lr = tid / TPR;                 // row of the tile this thread loads
     const int lk = (tid % TPR) * RT;          // first of its RT components
     const bool vec_ok = (d & 3) == 0;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int qi = q0 + lr, li = l0 + lr;
+    float qv[RT], cv[RT];
+    // global -> registers for the slice starting at component k0 (zero beyond the matrix edges)
+    auto fetch = [&](int k0) {
+        if (vec_ok && k0 + lk + RT <= d) {
+#pragma unroll
+            for (int v = 0; v < WB; ++v) {
+                float4 x = make_float4(0.f, 0.f, 0.f, 0.f), y = x;
+                if (qi < nq) x = reinterpret_cast<const float4*>(queries + (size_t)qi * d + k0 + lk)[v];
+                if (li < n_lists) y = reinterpret_cast<const float4*>(centroids + (size_t)li * d + k0 + lk)[v];
+                qv[4 * v] = x.x; qv[4 * v + 1] = x.y; qv[4 * v + 2] = x.z; qv[4 * v + 3] = x.w;
+                cv[4 * v] = y.x; cv[4 * v + 1] = y.y; cv[4 * v + 2] = y.z; cv[4 * v + 3] = y.w;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < RT; ++u) {
+                const int t = k0 + lk + u;
+                qv[u] = (qi < nq && t < d) ? queries[(size_t)qi * d + t] : 0.f;
+                cv[u] = (li < n_lists && t < d) ? centroids[(size_t)li * d + t] : 0.f;
+            }
+        }
+    };
+    fetch(0);
     for (int k0 = 0; k0 < d; k0 += CK) {
-        {
-            const int qi = q0 + lr, li = l0 + lr;
-            float qv[RT], cv[RT];
-            if (vec_ok && k0 + lk + RT <= d) {
 #pragma unroll
-                for (int v = 0; v < STRIPS; ++v) {
-                    float4 x = make_float4(0.f, 0.f, 0.f, 0.f), y = x;
-                    if (qi < nq) x = reinterpret_cast<const float4*>(queries + (size_t)qi * d + k0 + lk)[v];
-                    if (li < n_lists) y = reinterpret_cast<const float4*>(centroids + (size_t)li * d + k0 + lk)[v];
-                    qv[4 * v] = x.x; qv[4 * v + 1] = x.y; qv[4 * v + 2] = x.z; qv[4 * v + 3] = x.w;
-                    cv[4 * v] = y.x; cv[4 * v + 1] = y.y; cv[4 * v + 2] = y.z; cv[4 * v + 3] = y.w;
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < RT; ++u) {
-                    const int t = k0 + lk + u;
-                    qv[u] = (qi < nq && t < d) ? queries[(size_t)qi * d + t] : 0.f;
-                    cv[u] = (li < n_lists && t < d) ? centroids[(size_t)li * d + t] : 0.f;
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < RT; ++u) { qs[lk + u][lr] = qv[u]; cs[lk + u][lr] = cv[u]; }
-        }
+        for (int u = 0; u < RT; ++u) { qs[lk + u][lr] = qv[u]; cs[lk + u][lr] = cv[u]; }
         __syncthreads();
+        if (k0 + CK < d) fetch(k0 + CK);       // the next slice travels while this one is multiplied
+        // one MFMA consumes two components: lanes 0-31 feed component kk, lanes 32-63 component kk+1
 #pragma unroll
-        for (int kk = 0; kk < CK; ++kk) {
-            float a[RT], b[RT];
+        for (int kk = 0; kk < CK; kk += 2) {
+            float av[WB], bv[WB];
 #pragma unroll
-            for (int v = 0; v < STRIPS; ++v) {
-                const float4 x = *reinterpret_cast<const float4*>(&qs[kk][64 * v + ty * 4]);
-                const float4 y = *reinterpret_cast<const float4*>(&cs[kk][64 * v + tx * 4]);
-                a[4 * v] = x.x; a[4 * v + 1] = x.y; a[4 * v + 2] = x.z; a[4 * v + 3] = x.w;
-                b[4 * v] = y.x; b[4 * v + 1] = y.y; b[4 * v + 2] = y.z; b[4 * v + 3] = y.w;
-            }
+            for (int i = 0; i < WB; ++i) av[i] = qs[kk + half][(wr * WB + i) * 32 + l32];
 #pragma unroll
-            for (int i = 0; i < RT; ++i)
+            for (int j = 0; j < WB; ++j) bv[j] = cs[kk + half][(wc * WB + j) * 32 + l32];
 #pragma unroll
-                for (int j = 0; j < RT; ++j) {
-                    float diff = a[i] - b[j];
-                    acc[i][j] = __builtin_fmaf(diff, diff, acc[i][j]);
-                }
+            for (int i = 0; i < WB; ++i)
+#pragma unroll
+                for (int j = 0; j < WB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
         __syncthreads();
     }
+    // accumulator layout of the 32x32 block: register v of lane L holds row 8*(v/4) + 4*(L/32) + v%4, column L%32
 #pragma unroll
-    for (int i = 0; i < RT; ++i) {
-        const int qi = q0 + 64 * (i / 4) + ty * 4 + (i % 4);
-        if (qi >= nq) continue;
+    for (int i = 0; i < WB; ++i)
 #pragma unroll
-        for (int h = 0; h < STRIPS; ++h) {
-            const int lbase = l0 + h * 64 + tx * 4;
-            float* dst = D + (size_t)qi * n_lists + lbase;
-            if ((n_lists & 3) == 0 && lbase + 4 <= n_lists) {
-                *reinterpret_cast<float4*>(dst) = make_float4(acc[i][h * 4], acc[i][h * 4 + 1], acc[i][h * 4 + 2], acc[i][h * 4 + 3]);
-            } else {
+        for (int j = 0; j < WB; ++j) {
+            const int li = l0 + (wc * WB + j) * 32 + l32;
+            if (li >= n_lists) continue;
+            const float cn = centroid_norms[li];
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (lbase + j < n_lists) dst[j] = acc[i][h * 4 + j];
+            for (int v = 0; v < 16; ++v) {
+                const int qi = q0 + (wr * WB + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                if (qi < nq) A[(size_t)qi * n_lists + li] = ordered_key(__builtin_fmaf(-2.f, acc[i][j][v], cn));
             }
         }
-    }
 }
 
 // picks the tile size so that the grid still covers the chip
-int launch_coarse(const float* q, const float* centroids, int nq, int n_lists, int d, float* D, hipStream_t st) {
+int launch_coarse(const float* q, const float* centroids, const float* centroid_norms, int nq, int n_lists, int d,
+                  uint32_t* A, hipStream_t st) {
     const long big_blocks = (long)((n_lists + 127) / 128) * ((nq + 127) / 128);
     if (big_blocks >= 1024) {
         dim3 grid((n_lists + 127) / 128, (nq + 127) / 128);
-        hipLaunchKernelGGL(coarse_dist_kernel<2>, grid, dim3(256), 0, st, q, centroids, nq, n_lists, d, D);
+        hipLaunchKernelGGL(coarse_rank_kernel<2>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A);
     } else {
         dim3 grid((n_lists + 63) / 64, (nq + 63) / 64);
-        hipLaunchKernelGGL(coarse_dist_kernel<1>, grid, dim3(256), 0, st, q, centroids, nq, n_lists, d, D);
+        hipLaunchKernelGGL(coarse_rank_kernel<1>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A);
     }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(IVFPQ_EHIP, "coarse_dist_kernel launch failed: %s", hipGetErrorString(e));
+    if (e != hipSuccess) return fail(IVFPQ_EHIP, "coarse_rank_kernel launch failed: %s", hipGetErrorString(e));
     return IVFPQ_OK;
 }
 
@@ -381,10 +393,18 @@ struct RowSelectShared {
 
 // pos_of(i): logical position of row element i (what the records report and what tie_of_pos
 // takes); have_bound/bound: an upper bound of the k-th smallest key that the caller already knows
-// (it must be the key of at least k elements' worth of the row, i.e. at least k elements are <= it).
-template <class PosFn, class TieFn>
-__device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
-                                bool have_bound, uint32_t bound, PosFn pos_of, TieFn tie_of_pos) {
+// (at least k elements of the row are <= it).
+// Hooks for rows whose keys are only approximate (probe selection): widen(bound) is applied to every
+// bound before it filters (it must return a key that no element the exact selection could need
+// exceeds); refine(n_cand) runs once the candidates sit in LDS and may replace their keys by exact
+// ones; whole_row() is the fallback when compaction fails and must return the selection itself.
+struct NoWiden { __device__ uint32_t operator()(uint32_t b) const { return b; } };
+struct NoRefine { __device__ void operator()(uint32_t) const {} };
+
+template <class PosFn, class TieFn, class WidenFn, class RefineFn, class WholeRowFn>
+__device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
+                                   bool have_bound, uint32_t bound, PosFn pos_of, TieFn tie_of_pos,
+                                   WidenFn widen, RefineFn refine, WholeRowFn whole_row) {
     SelectShared& s = t.sel;
     const int tid = threadIdx.x, nth = blockDim.x;
     const uint32_t kk = k < (uint32_t)CAND_CAP ? k : (uint32_t)CAND_CAP;
@@ -397,6 +417,7 @@ __device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__
             for (int i = tid; i < CAND_CAP; i += nth) t.cand_key[i] = row[i];
             bound = block_kth_key(s, (uint32_t)CAND_CAP, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1);
         }
+        bound = widen(bound);
         const bool vec = (n & 3u) == 0 && (reinterpret_cast<uintptr_t>(row) & 15u) == 0;
         compact = false;
         // Each pass keeps the elements not above the bound.  If they overflow the LDS buffer, the
@@ -424,7 +445,7 @@ __device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__
             __syncthreads();
             n_cand = t.n_cand;
             if (n_cand <= (uint32_t)CAND_CAP) { compact = true; break; }
-            const uint32_t tighter = block_kth_key(s, (uint32_t)CAND_CAP, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1);
+            const uint32_t tighter = widen(block_kth_key(s, (uint32_t)CAND_CAP, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1));
             if (tighter >= bound) break;      // a plateau of equal keys: no progress possible this way
             bound = tighter;
         }
@@ -434,44 +455,143 @@ __device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__
     }
     int got;
     if (compact) {
+        refine(n_cand);
         got = block_select_smallest(s, n_cand, k,
             [&](uint32_t i) { return t.cand_key[i]; },
             [&](uint32_t i) -> long long { return tie_of_pos(t.cand_pos[i], t.cand_key[i]); });
         for (int j = tid; j < got; j += nth) s.rec_pos[j] = t.cand_pos[s.rec_pos[j]];   // back to logical positions
     } else {
-        got = block_select_smallest(s, n, k,
-            [&](uint32_t i) { return row[i]; },
-            [&](uint32_t i) -> long long { return tie_of_pos(pos_of(i), row[i]); });
-        for (int j = tid; j < got; j += nth) s.rec_pos[j] = pos_of(s.rec_pos[j]);
+        got = whole_row();
     }
     __syncthreads();
     return got;
 }
 
+template <class PosFn, class TieFn>
+__device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
+                                bool have_bound, uint32_t bound, PosFn pos_of, TieFn tie_of_pos) {
+    SelectShared& s = t.sel;
+    return block_select_row_ex(t, row, n, k, have_bound, bound, pos_of, tie_of_pos, NoWiden{}, NoRefine{},
+        [&]() -> int {
+            const int got = block_select_smallest(s, n, k,
+                [&](uint32_t i) { return row[i]; },
+                [&](uint32_t i) -> long long { return tie_of_pos(pos_of(i), row[i]); });
+            for (int j = threadIdx.x; j < got; j += blockDim.x) s.rec_pos[j] = pos_of(s.rec_pos[j]);
+            return got;
+        });
+}
+
 // ================================================================================================
-// Step 1b: probe selection for one query per workgroup, from the coarse distance row.
+// Step 1b: probe selection for one query per workgroup: short-list by the ranking values of step
+// 1a (with their error bound), exact distances for the short list, exact selection among those.
 // Also lays out the query's slice of the R scratch: roff[p] = first slot of probe p, roff[n_probes]
 // = padded candidate count (every cluster padded to a multiple of 64 vectors), and writes one
 // descriptor per (query, probe) pair -- {cluster, length, first 64-vector group, R offset} -- so
 // that a scan workgroup starts from a single 16-byte load.
 // ================================================================================================
 __global__ void __launch_bounds__(SEL_THREADS)
-select_probes_kernel(const float* __restrict__ D, int n_lists, int n_probes,
+select_probes_kernel(uint32_t* __restrict__ A, const float* __restrict__ queries,
+                     const float* __restrict__ centroids, float centroid_norm_max, int d,
+                     int n_lists, int n_probes,
                      const uint32_t* __restrict__ list_sizes, const int64_t* __restrict__ group_offsets,
                      uint32_t* __restrict__ probes, float* __restrict__ probe_dists,
                      uint32_t* __restrict__ roff, uint4* __restrict__ pairs) {
     __shared__ RowSelectShared t;
+    __shared__ float s_part[SEL_THREADS / kWave];
     SelectShared& s = t.sel;
     const int q = blockIdx.x;
-    const uint32_t* row = reinterpret_cast<const uint32_t*>(D + (size_t)q * n_lists);   // distances >= +0
-    int got = block_select_row(t, row, (uint32_t)n_lists, (uint32_t)n_probes, false, 0u,
-                               [](uint32_t i) { return i; },
-                               [](uint32_t pos, uint32_t) { return (long long)pos; });
-    for (int p = threadIdx.x; p < got; p += blockDim.x) {
+    const int tid = threadIdx.x, nth = blockDim.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6, n_waves = nth >> 6;
+    const float* qv = queries + (size_t)q * d;
+    uint32_t* row = A + (size_t)q * n_lists;       // ranking keys of a(q, c) = |c|^2 - 2 q.c
+
+    auto wave_sum = [&](float v) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+        return v;
+    };
+    // |q|^2, for the error bound of a()
+    float part = 0.f;
+    for (int c = tid; c < d; c += nth) part = __builtin_fmaf(qv[c], qv[c], part);
+    part = wave_sum(part);
+    if (lane == 0) s_part[wave] = part;
+    __syncthreads();
+    float qn = 0.f;
+    for (int w = 0; w < n_waves; ++w) qn += s_part[w];
+    // |a_computed - a_exact| <= delta: rounding of |c|^2 (2^-24 relative), of the d-term fp32 dot
+    // product (<= d 2^-24 |q||c| for any summation order, times 2), of the final multiply-add; taken
+    // with a factor 4 of slack: (d + 8) 2^-22 (|q|^2 + max|c|^2)
+    const float delta = (float)(d + 8) * 2.3841858e-07f * (qn + centroid_norm_max);
+    // keys up to this one can belong to a cluster whose exact rank is within the bound's rank
+    auto widen = [&](uint32_t key) {
+        const float f = ordered_key_value(key);
+        float g = f + 2.f * delta;
+        g += __builtin_fabsf(g) * 2.3841858e-07f;          // the addition above rounds: stay on the safe side
+        return (g == g) ? ordered_key(g) : 0xFFFFFFFFu;     // NaN (from infinite inputs): admit everything
+    };
+    // exact squared distance to cluster l (direct form) by a group of 8 adjacent lanes: each lane sums
+    // every 8th component, then three exchange steps; the order is fixed, so the value of a cluster
+    // does not depend on which path computes it.  Every lane of the group gets the result.
+    auto exact8 = [&](uint32_t l, bool valid) {
+        float acc = 0.f;
+        if (valid) {
+            const float* c = centroids + (size_t)l * d;
+            for (int u = tid & 7; u < d; u += 8) { const float diff = qv[u] - c[u]; acc = __builtin_fmaf(diff, diff, acc); }
+        }
+        acc += __shfl_xor(acc, 1, kWave);
+        acc += __shfl_xor(acc, 2, kWave);
+        acc += __shfl_xor(acc, 4, kWave);
+        return acc;
+    };
+    // candidates in LDS: keep those whose a() is within 2 delta of the n_probes-th smallest a() among
+    // them (every cluster of the exact answer is among these), give them their exact distance
+    auto refine = [&](uint32_t n_cand) {
+        const uint32_t kk = (uint32_t)n_probes < n_cand ? (uint32_t)n_probes : n_cand;
+        if (kk == 0) return;
+        uint32_t r0, r1;
+        const uint32_t limit = widen(block_kth_key(s, n_cand, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1));
+        __syncthreads();
+        if (tid == 0) s.n_rec = 0;
+        __syncthreads();
+        // the short list, as indices into the candidate arrays (the record array is free at this point)
+        for (uint32_t i = tid; i < n_cand; i += nth) {
+            if (t.cand_key[i] <= limit) s.rec_pos[atomicAdd(&s.n_rec, 1u)] = i;
+            else t.cand_key[i] = 0xFFFFFFFFu;
+        }
+        __syncthreads();
+        const uint32_t n_short = s.n_rec;
+        for (uint32_t base = 0; base < n_short; base += nth / 8) {
+            const uint32_t j = base + (tid >> 3);
+            const bool valid = j < n_short;
+            const uint32_t i = valid ? s.rec_pos[j] : 0u;
+            const float dist = exact8(valid ? t.cand_pos[i] : 0u, valid);
+            if (valid && (tid & 7) == 0) t.cand_key[i] = __float_as_uint(dist);
+        }
+        __syncthreads();
+    };
+    // compaction failed (a plateau of equal ranking values): exact distances of all clusters
+    auto whole_row = [&]() -> int {
+        __syncthreads();
+        for (uint32_t base = 0; base < (uint32_t)n_lists; base += nth / 8) {
+            const uint32_t l = base + (tid >> 3);
+            const bool valid = l < (uint32_t)n_lists;
+            const float dist = exact8(valid ? l : 0u, valid);
+            if (valid && (tid & 7) == 0) row[l] = __float_as_uint(dist);
+        }
+        __threadfence_block();
+        __syncthreads();
+        return block_select_smallest(s, (uint32_t)n_lists, (uint32_t)n_probes,
+            [&](uint32_t i) { return row[i]; }, [&](uint32_t i) { return (long long)i; });
+    };
+    int got = block_select_row_ex(t, row, (uint32_t)n_lists, (uint32_t)n_probes, false, 0u,
+                                  [](uint32_t i) { return i; },
+                                  [](uint32_t pos, uint32_t) { return (long long)pos; },
+                                  widen, refine, whole_row);
+    for (int p = tid; p < got; p += nth) {
         probes[(size_t)q * n_probes + p] = s.rec_pos[p];
         if (probe_dists) probe_dists[(size_t)q * n_probes + p] = __uint_as_float(s.rec_key[p]);
     }
-    if (roff && threadIdx.x == 0) {
+    if (roff && tid == 0) {
         uint32_t at = 0;
         for (int p = 0; p < got; ++p) {
             const uint32_t l = s.rec_pos[p], len = list_sizes[l];
@@ -948,7 +1068,7 @@ topk_kernel(const float* __restrict__ R, const uint32_t* __restrict__ Rpos, size
 // Host side
 // ================================================================================================
 struct ImageLayout {
-    size_t centroids, codebooks, list_offsets, list_sizes, group_offsets, codes, ids, total;
+    size_t centroids, centroid_norms, codebooks, list_offsets, list_sizes, group_offsets, codes, ids, total;
 };
 
 int chunk_width(const ivfpq_index* idx) {
@@ -961,6 +1081,7 @@ ImageLayout image_layout(const ivfpq_index* idx) {
     size_t at = 0;
     auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
     L.centroids = take(idx->centroids.size() * sizeof(float));
+    L.centroid_norms = take((size_t)idx->n_lists * sizeof(float));
     L.codebooks = take(idx->codebooks.size() * sizeof(float));
     L.list_offsets = take(((size_t)idx->n_lists + 1) * sizeof(int64_t));
     L.list_sizes = take((size_t)idx->n_lists * sizeof(uint32_t));
@@ -1174,8 +1295,9 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         StageTimer t0(idx, st, 0);
         if (int s = t0.begin()) return s;
         if (!d_probes_in) {
-            if (int s = launch_coarse(qt, idx->dev.centroids, tq, idx->n_lists, idx->d, w_D, st)) return s;
-            hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_D, idx->n_lists,
+            if (int s = launch_coarse(qt, idx->dev.centroids, idx->dev.centroid_norms, tq, idx->n_lists, idx->d, (uint32_t*)w_D, st)) return s;
+            hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, qt,
+                               idx->dev.centroids, idx->centroid_norm_max, idx->d, idx->n_lists,
                                n_probes, idx->dev.list_sizes, idx->dev.group_offsets, w_probes, w_probe_d, w_roff, w_pairs);
             HIP_TRY(hipGetLastError());
         } else {
@@ -1249,6 +1371,16 @@ int ivfpq_upload(ivfpq_index_t* idx, void* d_buf, size_t bytes, void* hip_stream
         sizes[l] = (uint32_t)len;
         goff[l + 1] = goff[l] + (len + 63) / 64;
     }
+    std::vector<float> cnorm((size_t)idx->n_lists);
+    float cn_max = 0.f;
+    for (int l = 0; l < idx->n_lists; ++l) {
+        double acc = 0.0;
+        for (int t = 0; t < idx->d; ++t) { double v = idx->centroids[(size_t)l * idx->d + t]; acc += v * v; }
+        cnorm[l] = (float)acc;
+        if (cnorm[l] > cn_max) cn_max = cnorm[l];
+    }
+    idx->centroid_norm_max = cn_max;
+    HIP_TRY(hipMemcpyAsync(base + L.centroid_norms, cnorm.data(), cnorm.size() * 4, hipMemcpyHostToDevice, st));
     // interleave the codes, one cluster at a time, through a bounded staging buffer
     HIP_TRY(hipMemcpyAsync(base + L.centroids, idx->centroids.data(), idx->centroids.size() * 4, hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(base + L.codebooks, idx->codebooks.data(), idx->codebooks.size() * 4, hipMemcpyHostToDevice, st));
@@ -1289,6 +1421,7 @@ int ivfpq_upload(ivfpq_index_t* idx, void* d_buf, size_t bytes, void* hip_stream
     idx->dev.valid = true;
     idx->dev.device = dev;
     idx->dev.centroids = (const float*)(base + L.centroids);
+    idx->dev.centroid_norms = (const float*)(base + L.centroid_norms);
     idx->dev.codebooks = (const float*)(base + L.codebooks);
     idx->dev.list_offsets = (const int64_t*)(base + L.list_offsets);
     idx->dev.list_sizes = (const uint32_t*)(base + L.list_sizes);
@@ -1339,10 +1472,12 @@ int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_
     float* w_D = (float*)((unsigned char*)d_workspace + plan.D);
     for (int64_t q0 = 0; q0 < nq; q0 += plan.tile) {
         const int tq = (int)std::min<int64_t>(plan.tile, nq - q0);
-        if (int s = launch_coarse(d_queries + (size_t)q0 * idx->d, idx->dev.centroids, tq, idx->n_lists, idx->d, w_D, st))
+        if (int s = launch_coarse(d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->dev.centroid_norms, tq,
+                                  idx->n_lists, idx->d, (uint32_t*)w_D, st))
             return s;
-        hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_D, idx->n_lists, n_probes,
-                           idx->dev.list_sizes, idx->dev.group_offsets, d_probes + (size_t)q0 * n_probes,
+        hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D,
+                           d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->centroid_norm_max, idx->d,
+                           idx->n_lists, n_probes, idx->dev.list_sizes, idx->dev.group_offsets, d_probes + (size_t)q0 * n_probes,
                            d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr,
                            (uint4*)nullptr);
         HIP_TRY(hipGetLastError());

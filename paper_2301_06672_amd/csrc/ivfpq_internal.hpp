@@ -17,6 +17,7 @@ struct DeviceImage {
     bool valid = false;
     int device = -1;
     const float* centroids = nullptr;      // [n_lists][d]
+    const float* centroid_norms = nullptr; // [n_lists] squared L2 norms
     const float* codebooks = nullptr;      // [pq_dim][ksub][m]
     const int64_t* list_offsets = nullptr; // [n_lists+1], unpadded vector offsets (into ids)
     const uint32_t* list_sizes = nullptr;  // [n_lists]
@@ -42,6 +43,7 @@ struct ivfpq_index {
     std::vector<uint32_t> sorted_padded_sizes;  // padded list lengths, descending
 
     ivfpq::DeviceImage dev;
+    float centroid_norm_max = 0.f;      // largest squared centroid norm (set by ivfpq_upload)
 
     // stage timing (hipEvent_t kept as void* so this header stays free of HIP types)
     bool timing = false;
