@@ -95,9 +95,9 @@ size_t ivfpq_device_bytes(const ivfpq_index_t* index);
  * unmodified while the handle is used for searches. */
 int ivfpq_upload(ivfpq_index_t* index, void* d_buf, size_t bytes, void* hip_stream);
 
-/* Bytes of device scratch one search call needs for these parameters (probe lists, coarse
- * distances, per-candidate distances R).  Large batches are processed in query tiles so that
- * the figure stays bounded. */
+/* Bytes of device scratch one search call needs for these parameters (probe lists, per-pair
+ * descriptors, cluster ranking values, the R rows and the positions of filtered candidates).
+ * Large batches are processed in query tiles so that the figure stays bounded (about 2 GiB). */
 size_t ivfpq_search_workspace_bytes(const ivfpq_index_t* index, int64_t nq, int32_t n_probes,
                                     int32_t k, int32_t lut_dtype);
 
@@ -146,8 +146,9 @@ int ivfpq_scan_list(const ivfpq_index_t* index, const float* d_query, uint32_t l
 
 /* When enabled, search calls record HIP events around their stages on the stream they run on.
  * After the stream has been synchronised, ivfpq_stage_times_ms reports the last call's
- * milliseconds: ms[0] = probe selection (step 1), ms[1] = table build + scan kernel (steps 2-4),
- * ms[2] = top-k (step 5), ms[3] = whole call; summed over query tiles. */
+ * milliseconds: ms[0] = probe selection (step 1: ranking GEMM + selection), ms[1] = table build +
+ * code scan (steps 2-4: the scan kernel over the nearest probe, the bound kernel, the scan kernel
+ * over the remaining probes), ms[2] = top-k (step 5), ms[3] = whole call; summed over query tiles. */
 int ivfpq_set_stage_timing(ivfpq_index_t* index, int32_t enabled);
 int ivfpq_stage_times_ms(ivfpq_index_t* index, float ms[4]);
 
