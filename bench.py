@@ -78,7 +78,10 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="intgrid_1m")
-    ap.add_argument("--lut", default="e5m3", choices=["fp32", "fp16", "e5m3"])
+    ap.add_argument("--lut", default="e5m3", choices=["fp32", "fp16", "e5m3", "e4m4"])
+    ap.add_argument("--e4m4-bias", type=int, default=None,
+                    help="exponent bias of the e4m4 table dtype (default: 1 for the integer-valued sets, 16 for the unit-norm sets)")
+    ap.add_argument("--all-luts", action="store_true", help="also time the e4m4 table")
     ap.add_argument("--kmeans-iters", type=int, default=6, help="Lloyd iterations of the (untimed) index build")
     ap.add_argument("--n-probes", type=int, default=None)
     ap.add_argument("--k", type=int, default=None)
@@ -119,7 +122,8 @@ def main():
     w = si.WORKLOADS[args.workload]
     n_probes = args.n_probes or w.n_probes
     k = args.k or w.k
-    lut_ids = {"fp32": pkg.LUT_FP32, "fp16": pkg.LUT_FP16, "e5m3": pkg.LUT_FP8_E5M3}
+    lut_ids = {"fp32": pkg.LUT_FP32, "fp16": pkg.LUT_FP16, "e5m3": pkg.LUT_FP8_E5M3, "e4m4": pkg.LUT_FP8_E4M4}
+    e4m4_bias = args.e4m4_bias if args.e4m4_bias is not None else (1 if w.kind == "intgrid" else 16)
 
     t0 = time.time()
     data = si.dataset(w)
@@ -137,6 +141,7 @@ def main():
         torch.cuda.empty_cache()
     log(f"index build ({builder}, {args.kmeans_iters} Lloyd iterations) {time.time() - t0:.1f}s")
     idx.ivfpq_upload()
+    idx.ivfpq_set_e4m4_bias(e4m4_bias)
     cent, cb, offs, codes, ids_arr = idx.ivfpq_index_export()
     sizes = np.diff(offs)
 
@@ -180,6 +185,8 @@ def main():
 
     results = {}
     order = [args.lut] if args.only_headline else ["fp32", "fp16", "e5m3"]
+    if not args.only_headline and (args.all_luts or args.lut == "e4m4"):
+        order.append("e4m4")
     for name in order:
         steps = args.steps if name == args.lut else max(3, args.steps // 2)
         results[name] = run(name, steps, args.warmup)
@@ -207,7 +214,7 @@ def main():
         oidx = oracle.make_index(w.d, w.n_lists, w.pq_dim, w.pq_bits, cent, cb, offs, codes, ids_arr)
         nc = min(args.cpu_queries, nq)
         t = time.perf_counter()
-        oracle.search(oidx, queries_np[:nc], n_probes, k, lut_ids[args.lut])
+        oracle.search(oidx, queries_np[:nc], n_probes, k, lut_ids[args.lut], e4m4_bias=e4m4_bias)
         dt = time.perf_counter() - t
         cpu = {"value": round(nc / dt, 1), "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"first {nc} of the {nq} queries, same index, lut={args.lut}, {dt:.1f}s wall, one pass"}
@@ -222,7 +229,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.n} d={w.d} nq={nq} n_lists={w.n_lists} pq_dim={w.pq_dim} "
                                f"pq_bits={w.pq_bits} n_probes={n_probes} k={k}",
-                   "lut_dtype": args.lut, "kmeans_iters": args.kmeans_iters, "builder": builder,
+                   "lut_dtype": args.lut, "e4m4_bias": e4m4_bias, "kmeans_iters": args.kmeans_iters, "builder": builder,
                    "workspace_bytes": ws_bytes, "recall_queries": nr},
         "recall_at_k": round(head["recall"], 4),
         "by_lut": {n: {"qps": round(r["qps"], 1), "recall": round(r["recall"], 4),

@@ -35,9 +35,12 @@ typedef struct ivfpq_index ivfpq_index_t; /* opaque; created by build/import, de
 typedef enum {
     IVFPQ_LUT_FP32 = 0,     /* IEEE binary32 */
     IVFPQ_LUT_FP16 = 1,     /* IEEE binary16, round-to-nearest-even, saturating at 65504 */
-    IVFPQ_LUT_FP8_E5M3 = 2  /* 5 exponent + 3 mantissa bits, no sign, bias 15, all codes normal:
+    IVFPQ_LUT_FP8_E5M3 = 2, /* 5 exponent + 3 mantissa bits, no sign, bias 15, all codes normal:
                                value(b) = (1 + (b&7)/8) * 2^((b>>3) - 15); FP32 -> code: nearest, ties up,
                                clamped to [0x00, 0xFF]; code -> FP32 bits: (b << 20) + 0x38000000 */
+    IVFPQ_LUT_FP8_E4M4 = 3  /* the paper's other split, 4 exponent + 4 mantissa bits, same rules:
+                               value(b) = (1 + (b&15)/16) * 2^((b>>4) - bias), 16 binades from 2^-bias;
+                               the bias is set per index with ivfpq_set_e4m4_bias (default 7) */
 } ivfpq_lut_dtype_t;
 
 typedef enum {
@@ -81,6 +84,11 @@ int ivfpq_index_info(const ivfpq_index_t* index, int64_t* n, int32_t* d, int32_t
  * the sizes ivfpq_index_info implies; any pointer may be NULL to skip that array. */
 int ivfpq_index_export(const ivfpq_index_t* index, float* centroids, float* codebooks,
                        int64_t* list_offsets, uint8_t* codes, int64_t* ids);
+
+/* Exponent bias of the IVFPQ_LUT_FP8_E4M4 table dtype for searches on this index (Sec. II gives the
+ * 4+4 split but not its bias): representable table values are 2^-bias .. 1.9375 * 2^(15-bias); what
+ * falls outside is clamped to the nearest end.  -100 <= bias <= 110.  Takes effect at the next call. */
+int ivfpq_set_e4m4_bias(ivfpq_index_t* index, int32_t bias);
 
 void ivfpq_free(ivfpq_index_t* index);
 

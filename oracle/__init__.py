@@ -15,8 +15,8 @@ import numpy as np
 
 from .build import build as _build, LIB_PATH, SRC as _SRC
 
-LUT_FP32, LUT_FP16, LUT_E5M3 = 0, 1, 2
-LUT_NAMES = {LUT_FP32: "fp32", LUT_FP16: "fp16", LUT_E5M3: "e5m3"}
+LUT_FP32, LUT_FP16, LUT_E5M3, LUT_E4M4 = 0, 1, 2, 3
+LUT_NAMES = {LUT_FP32: "fp32", LUT_FP16: "fp16", LUT_E5M3: "e5m3", LUT_E4M4: "e4m4"}
 
 _lib = None
 
@@ -63,10 +63,10 @@ def _declare(L):
     L.orc_fp16_decode_array.argtypes = [vp, i64, vp]
     L.orc_select_probes.argtypes = [vp, i32, i32, vp, i64, i32, vp, vp]
     L.orc_lut_f32.argtypes = [vp, vp, vp, i32, i32, i32, vp]
-    L.orc_lut_store.argtypes = [vp, i64, i32, i32, vp, vp]
+    L.orc_lut_store.argtypes = [vp, i64, i32, i32, i32, vp, vp]
     L.orc_scan_list.argtypes = [vp, i32, i32, vp, i64, vp, vp]
     L.orc_search.argtypes = [i64, i32, i32, i32, i32, vp, vp, vp, vp, vp,
-                             vp, i64, i32, i32, i32, i32, vp, vp, vp, vp]
+                             vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     L.orc_lut_elem_bytes.argtypes = [i32]
     L.orc_lut_elem_bytes.restype = i32
 
@@ -268,13 +268,13 @@ def lut_f32(index: Index, query, list_id: int) -> np.ndarray:
     return F
 
 
-def lut_store(F: np.ndarray, lut_dtype: int, truncate: bool = False):
+def lut_store(F: np.ndarray, lut_dtype: int, truncate: bool = False, e4m4_bias: int = 7):
     """-> (bytes as stored on chip, decoded fp32 values a lookup returns)."""
     F = _f32(F)
     eb = lib().orc_lut_elem_bytes(lut_dtype)
     stored = np.empty(F.size * eb, dtype=np.uint8)
     decoded = np.empty(F.shape, dtype=np.float32)
-    lib().orc_lut_store(_p(F), F.size, lut_dtype, int(truncate), _p(stored), _p(decoded))
+    lib().orc_lut_store(_p(F), F.size, lut_dtype, int(truncate), int(e4m4_bias), _p(stored), _p(decoded))
     return stored, decoded
 
 
@@ -290,7 +290,7 @@ def scan_list(index: Index, lut_decoded: np.ndarray, list_id: int):
 
 
 def search(index: Index, queries, n_probes: int, k: int, lut_dtype: int = LUT_FP32,
-           truncate: bool = False, probes=None, return_stats: bool = False):
+           truncate: bool = False, probes=None, return_stats: bool = False, e4m4_bias: int = 7):
     queries = _f32(queries)
     nq = queries.shape[0]
     out_ids = np.empty((nq, k), dtype=np.int64)
@@ -303,7 +303,7 @@ def search(index: Index, queries, n_probes: int, k: int, lut_dtype: int = LUT_FP
     lib().orc_search(index.n, index.d, index.n_lists, index.pq_dim, index.pq_bits,
                      _p(index.centroids), _p(index.codebooks), _p(index.list_offsets),
                      _p(index.codes), _p(index.ids), _p(queries), nq, n_probes, k,
-                     lut_dtype, int(truncate), _p(pr) if pr is not None else None,
+                     lut_dtype, int(truncate), int(e4m4_bias), _p(pr) if pr is not None else None,
                      _p(out_ids), _p(out_d), _p(stats))
     if return_stats:
         return out_ids, out_d, {"floored": int(stats[0]), "saturated": int(stats[1])}

@@ -332,17 +332,20 @@ void orc_lut_f32(const float* query, const float* centroid, const float* codeboo
     free(rq);
 }
 
-/* lut_dtype: 0 = fp32 (4 B little-endian), 1 = IEEE half (2 B), 2 = e5m3 (1 B).
+/* lut_dtype: 0 = fp32 (4 B little-endian), 1 = IEEE half (2 B), 2 = e5m3 (1 B), 3 = e4m4 (1 B; the
+ * 4+4 split of Sec. II with exponent bias `e4m4_bias`, which the text does not give).
  * `stored` receives the table exactly as it sits in on-chip memory;
  * `decoded` (may be NULL) receives what a lookup returns, as fp32. */
-enum { ORC_LUT_FP32 = 0, ORC_LUT_FP16 = 1, ORC_LUT_E5M3 = 2 };
+enum { ORC_LUT_FP32 = 0, ORC_LUT_FP16 = 1, ORC_LUT_E5M3 = 2, ORC_LUT_E4M4 = 3 };
 
 static int lut_elem_bytes(int lut_dtype) { return lut_dtype == 0 ? 4 : (lut_dtype == 1 ? 2 : 1); }
 
-void orc_lut_store(const float* F, int64_t n, int lut_dtype, int truncate,
+void orc_lut_store(const float* F, int64_t n, int lut_dtype, int truncate, int e4m4_bias,
                    uint8_t* stored, float* decoded) {
     double table[256];
-    fp8_table(3, 15, table);
+    const int mant_bits = lut_dtype == ORC_LUT_E4M4 ? 4 : 3;
+    const int bias = lut_dtype == ORC_LUT_E4M4 ? e4m4_bias : 15;
+    fp8_table(mant_bits, bias, table);
     for (int64_t i = 0; i < n; ++i) {
         float back;
         if (lut_dtype == ORC_LUT_FP32) {
@@ -352,7 +355,7 @@ void orc_lut_store(const float* F, int64_t n, int lut_dtype, int truncate,
             memcpy(stored + 2 * i, &h, 2); back = orc_fp16_decode(h);
         } else {
             uint8_t b = fp8_encode_with_table(F[i], table, truncate);
-            stored[i] = b; back = orc_e5m3_decode(b);
+            stored[i] = b; back = orc_fp8_decode(b, mant_bits, bias);
         }
         if (decoded) decoded[i] = back;
     }
@@ -399,13 +402,13 @@ void orc_scan_list(const float* lut_decoded, int pq_dim, int pq_bits,
 /* Step 5: gather (R, id) of all probed clusters, full sort by (R, id),   */
 /* first k; fewer than k candidates -> id -1, distance +inf.              */
 /* stats (may be NULL) [2]: number of table entries that hit the lowest / */
-/* highest code of the 8-bit format (floored / saturated), summed.        */
+/* highest code of an 8-bit format (floored / saturated), summed.        */
 /* ------------------------------------------------------------------ */
 void orc_search(int64_t n, int d, int n_lists, int pq_dim, int pq_bits,
                 const float* centroids, const float* codebooks,
                 const int64_t* list_offsets, const uint8_t* codes, const int64_t* ids,
                 const float* queries, int64_t nq, int n_probes, int k,
-                int lut_dtype, int truncate, const uint32_t* probes_in,
+                int lut_dtype, int truncate, int e4m4_bias, const uint32_t* probes_in,
                 int64_t* out_ids, float* out_d, int64_t* stats) {
     (void)n;
     int ksub = 1 << pq_bits;
@@ -432,8 +435,8 @@ void orc_search(int64_t n, int d, int n_lists, int pq_dim, int pq_bits,
                 uint32_t l = probes[p];
                 int64_t lo = list_offsets[l], len = list_offsets[l + 1] - lo;
                 orc_lut_f32(qv, centroids + (int64_t)l * d, codebooks, d, pq_dim, ksub, F);
-                orc_lut_store(F, lut_n, lut_dtype, truncate, stored, Fd);
-                if (lut_dtype == ORC_LUT_E5M3)
+                orc_lut_store(F, lut_n, lut_dtype, truncate, e4m4_bias, stored, Fd);
+                if (lut_dtype == ORC_LUT_E5M3 || lut_dtype == ORC_LUT_E4M4)
                     for (int64_t e = 0; e < lut_n; ++e) {
                         floored += stored[e] == 0x00; saturated += stored[e] == 0xFF;
                     }

@@ -1,6 +1,6 @@
 """MI355X-native IVFPQ search (arXiv 2301.06672): thin Python binding over libivfpq.so."""
 from .binding import (  # noqa: F401
     Index, IvfpqError, lib, EXPORTS, LIB_PATH,
-    LUT_FP32, LUT_FP16, LUT_FP8_E5M3, LUT_NAMES, LUT_BYTES, MAX_K, MAX_PROBES,
+    LUT_FP32, LUT_FP16, LUT_FP8_E5M3, LUT_FP8_E4M4, LUT_NAMES, LUT_BYTES, MAX_K, MAX_PROBES,
     OK, EINVAL, ENOSPACE, EHIP, EUNSUPPORTED, ESTATE,
 )

@@ -16,9 +16,9 @@ import torch  # imported before the library so that both share one HIP runtime
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("IVFPQ_LIB", os.path.join(HERE, "libivfpq.so"))   # IVFPQ_LIB: development override
 
-LUT_FP32, LUT_FP16, LUT_FP8_E5M3 = 0, 1, 2
-LUT_NAMES = {LUT_FP32: "fp32", LUT_FP16: "fp16", LUT_FP8_E5M3: "e5m3"}
-LUT_BYTES = {LUT_FP32: 4, LUT_FP16: 2, LUT_FP8_E5M3: 1}
+LUT_FP32, LUT_FP16, LUT_FP8_E5M3, LUT_FP8_E4M4 = 0, 1, 2, 3
+LUT_NAMES = {LUT_FP32: "fp32", LUT_FP16: "fp16", LUT_FP8_E5M3: "e5m3", LUT_FP8_E4M4: "e4m4"}
+LUT_BYTES = {LUT_FP32: 4, LUT_FP16: 2, LUT_FP8_E5M3: 1, LUT_FP8_E4M4: 1}
 MAX_K = 1024
 MAX_PROBES = 1024
 
@@ -27,6 +27,7 @@ OK, EINVAL, ENOSPACE, EHIP, EUNSUPPORTED, ESTATE = 0, -1, -2, -3, -4, -5
 # every symbol include/ivfpq.h declares
 EXPORTS = (
     "ivfpq_build_host", "ivfpq_index_from_arrays", "ivfpq_index_info", "ivfpq_index_export", "ivfpq_free",
+    "ivfpq_set_e4m4_bias",
     "ivfpq_device_bytes", "ivfpq_upload", "ivfpq_search_workspace_bytes", "ivfpq_search",
     "ivfpq_select_probes", "ivfpq_search_with_probes", "ivfpq_dump_lut", "ivfpq_scan_list",
     "ivfpq_set_stage_timing", "ivfpq_stage_times_ms", "ivfpq_last_error",
@@ -65,6 +66,7 @@ def _declare(L):
     L.ivfpq_index_info.argtypes = [vp, c.POINTER(i64), c.POINTER(i32), c.POINTER(i32), c.POINTER(i32), c.POINTER(i32)]
     L.ivfpq_index_export.argtypes = [vp, vp, vp, vp, vp, vp]
     L.ivfpq_free.argtypes = [vp]
+    L.ivfpq_set_e4m4_bias.argtypes = [vp, i32]
     L.ivfpq_free.restype = None
     L.ivfpq_device_bytes.argtypes = [vp]
     L.ivfpq_device_bytes.restype = sz
@@ -156,6 +158,9 @@ class Index:
         ids = np.empty(self.n, np.int64)
         _check(lib().ivfpq_index_export(self._h, _hp(centroids), _hp(codebooks), _hp(list_offsets), _hp(codes), _hp(ids)))
         return centroids, codebooks, list_offsets, codes, ids
+
+    def ivfpq_set_e4m4_bias(self, bias: int):
+        _check(lib().ivfpq_set_e4m4_bias(self._h, int(bias)))
 
     def ivfpq_free(self):
         if self._h:

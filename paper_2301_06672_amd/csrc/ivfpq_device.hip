@@ -630,6 +630,28 @@ template <int LUT> struct LutTraits;
 template <> struct LutTraits<IVFPQ_LUT_FP32> { static constexpr int bytes = 4; };
 template <> struct LutTraits<IVFPQ_LUT_FP16> { static constexpr int bytes = 2; };
 template <> struct LutTraits<IVFPQ_LUT_FP8_E5M3> { static constexpr int bytes = 1; };
+template <> struct LutTraits<IVFPQ_LUT_FP8_E4M4> { static constexpr int bytes = 1; };
+
+// Constants of the 4+4 split of the sign-less 8-bit float (Sec. II) for a caller-chosen exponent
+// bias B: value(b) = (1 + (b&15)/16) * 2^((b>>4) - B).  Same two conversions as e5m3 with a 19-bit
+// shift: code = (clamp_s32(bits, lo, hi) - sub) >> 19, bits = (code << 19) + lo, where
+// lo = (127 - B) << 23 (the smallest value), hi = lo + (255 << 19) (the largest), sub = lo less half
+// an 8-bit ulp (1 << 18) so that the shift rounds to nearest, ties up.
+struct Fp8Params { int lo, hi, sub; };
+
+__host__ __device__ inline Fp8Params e4m4_params(int bias) {
+    Fp8Params p;
+    p.lo = (127 - bias) << 23;
+    p.hi = p.lo + (255 << 19);
+    p.sub = p.lo - (1 << 18);
+    return p;
+}
+__device__ inline uint32_t e4m4_from_f32(float x, const Fp8Params p) {
+    int b = __float_as_int(x);
+    b = min(max(b, p.lo), p.hi);
+    return (uint32_t)(b - p.sub) >> 19;
+}
+__device__ inline float e4m4_to_f32(uint32_t b, const Fp8Params p) { return __uint_as_float((b << 19) + (uint32_t)p.lo); }
 
 // FP32 -> e5m3 (Sec. II): clamp the bit pattern, as a signed integer, to the codes' range, subtract
 // the exponent-bias difference (112 << 23) less half an 8-bit ulp (so that the shift rounds to
@@ -662,7 +684,7 @@ __device__ inline float lut_entry(const float* cbv, const float* rq) {
 }
 
 template <int LUT>
-__device__ inline void store4(unsigned char* lut, int e, const float f[4]) {
+__device__ inline void store4(unsigned char* lut, int e, const float f[4], const Fp8Params fp8) {
     if constexpr (LUT == IVFPQ_LUT_FP32) {
         *reinterpret_cast<float4*>(lut + (size_t)e * 4) = make_float4(f[0], f[1], f[2], f[3]);
     } else if constexpr (LUT == IVFPQ_LUT_FP16) {
@@ -670,9 +692,13 @@ __device__ inline void store4(unsigned char* lut, int e, const float f[4]) {
         v.x = half_bits_from_f32(f[0]) | (half_bits_from_f32(f[1]) << 16);
         v.y = half_bits_from_f32(f[2]) | (half_bits_from_f32(f[3]) << 16);
         *reinterpret_cast<uint2*>(lut + (size_t)e * 2) = v;
-    } else {
+    } else if constexpr (LUT == IVFPQ_LUT_FP8_E5M3) {
         uint32_t v = e5m3_from_f32(f[0]) | (e5m3_from_f32(f[1]) << 8) | (e5m3_from_f32(f[2]) << 16) |
                      (e5m3_from_f32(f[3]) << 24);
+        *reinterpret_cast<uint32_t*>(lut + e) = v;
+    } else {
+        uint32_t v = e4m4_from_f32(f[0], fp8) | (e4m4_from_f32(f[1], fp8) << 8) | (e4m4_from_f32(f[2], fp8) << 16) |
+                     (e4m4_from_f32(f[3], fp8) << 24);
         *reinterpret_cast<uint32_t*>(lut + e) = v;
     }
 }
@@ -682,7 +708,7 @@ __device__ inline void store4(unsigned char* lut, int e, const float f[4]) {
 // codebooks: global [pq_dim][ksub][M]; rq: LDS [pq_dim*M].
 template <int LUT, int M>
 __device__ inline void build_lut(const float* __restrict__ codebooks, const float* rq, int n_entries,
-                                 int bits, int m_runtime, unsigned char* lut) {
+                                 int bits, int m_runtime, unsigned char* lut, const Fp8Params fp8) {
     for (int e = threadIdx.x * 4; e < n_entries; e += blockDim.x * 4) {
         const int j = e >> bits;
         float f[4];
@@ -711,7 +737,7 @@ __device__ inline void build_lut(const float* __restrict__ codebooks, const floa
                 f[u] = acc;
             }
         }
-        store4<LUT>(lut, e, f);
+        store4<LUT>(lut, e, f, fp8);
     }
 }
 
@@ -720,7 +746,7 @@ __device__ inline void build_lut(const float* __restrict__ codebooks, const floa
 // constant stride).
 template <int LUT, int M>
 __device__ inline void build_lut_rows256(const float* __restrict__ codebooks, const float* rq, int pq_dim,
-                                         unsigned char* lut) {
+                                         unsigned char* lut, const Fp8Params fp8) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_waves = blockDim.x >> 6;
@@ -742,7 +768,7 @@ __device__ inline void build_lut_rows256(const float* __restrict__ codebooks, co
         float f[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) f[u] = lut_entry<M>(cbv + u * M, r);
-        store4<LUT>(lut, e, f);
+        store4<LUT>(lut, e, f, fp8);
         src += src_step;
         e += e_step;
     }
@@ -750,45 +776,46 @@ __device__ inline void build_lut_rows256(const float* __restrict__ codebooks, co
 
 template <int LUT, int BITS>
 __device__ inline void build_lut_any_m(const float* __restrict__ codebooks, const float* rq, int pq_dim,
-                                       int m, unsigned char* lut) {
+                                       int m, unsigned char* lut, const Fp8Params fp8) {
     const int n_entries = pq_dim << BITS;
     if constexpr (BITS == 8) {
         switch (m) {
-            case 1: build_lut_rows256<LUT, 1>(codebooks, rq, pq_dim, lut); return;
-            case 2: build_lut_rows256<LUT, 2>(codebooks, rq, pq_dim, lut); return;
-            case 4: build_lut_rows256<LUT, 4>(codebooks, rq, pq_dim, lut); return;
+            case 1: build_lut_rows256<LUT, 1>(codebooks, rq, pq_dim, lut, fp8); return;
+            case 2: build_lut_rows256<LUT, 2>(codebooks, rq, pq_dim, lut, fp8); return;
+            case 4: build_lut_rows256<LUT, 4>(codebooks, rq, pq_dim, lut, fp8); return;
             default: break;
         }
     }
     switch (m) {
-        case 1: build_lut<LUT, 1>(codebooks, rq, n_entries, BITS, m, lut); break;
-        case 2: build_lut<LUT, 2>(codebooks, rq, n_entries, BITS, m, lut); break;
-        case 4: build_lut<LUT, 4>(codebooks, rq, n_entries, BITS, m, lut); break;
-        default: build_lut<LUT, 0>(codebooks, rq, n_entries, BITS, m, lut); break;
+        case 1: build_lut<LUT, 1>(codebooks, rq, n_entries, BITS, m, lut, fp8); break;
+        case 2: build_lut<LUT, 2>(codebooks, rq, n_entries, BITS, m, lut, fp8); break;
+        case 4: build_lut<LUT, 4>(codebooks, rq, n_entries, BITS, m, lut, fp8); break;
+        default: build_lut<LUT, 0>(codebooks, rq, n_entries, BITS, m, lut, fp8); break;
     }
 }
 
 template <int LUT>
-__device__ inline float lut_get(const unsigned char* lut, uint32_t idx) {
+__device__ inline float lut_get(const unsigned char* lut, uint32_t idx, const Fp8Params fp8) {
     if constexpr (LUT == IVFPQ_LUT_FP32) return reinterpret_cast<const float*>(lut)[idx];
     else if constexpr (LUT == IVFPQ_LUT_FP16) return __half2float(reinterpret_cast<const __half*>(lut)[idx]);
-    else return e5m3_to_f32(lut[idx]);
+    else if constexpr (LUT == IVFPQ_LUT_FP8_E5M3) return e5m3_to_f32(lut[idx]);
+    else return e4m4_to_f32(lut[idx], fp8);
 }
 
 // adds the table entries selected by the 4 code bytes of `w` (sub-spaces row0.. in ascending order)
 template <int LUT, int BITS>
-__device__ inline float add_word(float acc, const unsigned char* lut, uint32_t w, int row0) {
+__device__ inline float add_word(float acc, const unsigned char* lut, uint32_t w, int row0, const Fp8Params fp8) {
     if constexpr (BITS == 8) {
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             uint32_t code = (w >> (8 * b)) & 255u;
-            acc += lut_get<LUT>(lut, (uint32_t)(row0 + b) * 256u + code);
+            acc += lut_get<LUT>(lut, (uint32_t)(row0 + b) * 256u + code, fp8);
         }
     } else {
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
             uint32_t code = (w >> (4 * b)) & 15u;
-            acc += lut_get<LUT>(lut, (uint32_t)(row0 + b) * 16u + code);
+            acc += lut_get<LUT>(lut, (uint32_t)(row0 + b) * 16u + code, fp8);
         }
     }
     return acc;
@@ -807,6 +834,7 @@ struct ScanArgs {
     const uint32_t* bounds;       // [nq] per-query upper bound of the k-th smallest R (filtered mode)
     uint32_t* counts;             // [nq] survivors appended so far (filtered mode)
     uint32_t* Rpos;               // [nq][stride] row position of each appended survivor (filtered mode)
+    Fp8Params fp8;                // constants of the e4m4 table dtype (unused by the other dtypes)
     int mode;                     // 1: nearest probe of every query, every R written in place;
                                   // 2: the other probes, only R <= bound appended behind the nearest probe's segment
     float* R;                     // [nq][stride]
@@ -891,9 +919,9 @@ scan_kernel(ScanArgs a) {
                 const uint32_t w[4] = {buf[c].x, buf[c].y, buf[c].z, buf[c].w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    acc = add_word<LUT, BITS>(acc, lut, w[i], (c * 4 + i) * ROWS_PER_WORD);
+                    acc = add_word<LUT, BITS>(acc, lut, w[i], (c * 4 + i) * ROWS_PER_WORD, a.fp8);
             } else {
-                acc = add_word<LUT, BITS>(acc, lut, buf[c], c * ROWS_PER_WORD);
+                acc = add_word<LUT, BITS>(acc, lut, buf[c], c * ROWS_PER_WORD, a.fp8);
             }
         }
         return acc;
@@ -941,7 +969,7 @@ scan_kernel(ScanArgs a) {
         rq[t] = a.queries[(size_t)q * a.d + t] - a.centroids[(size_t)l * a.d + t];
     __syncthreads();
     // step 3: the table
-    build_lut_any_m<LUT, BITS>(a.codebooks, rq, a.pq_dim, a.m, lut);
+    build_lut_any_m<LUT, BITS>(a.codebooks, rq, a.pq_dim, a.m, lut, a.fp8);
     __syncthreads();
 
     // step 4: Eq. (1), one lane per coded vector; the next group is loaded into the other register
@@ -961,7 +989,7 @@ scan_kernel(ScanArgs a) {
             float acc = 0.f;
             for (int c = 0; c < nch; ++c) {
                 uint32_t w = reinterpret_cast<const uint32_t*>(codes_l)[((size_t)g * nch + c) * 64 + lane];
-                acc = add_word<LUT, BITS>(acc, lut, w, c * ROWS_PER_WORD);
+                acc = add_word<LUT, BITS>(acc, lut, w, c * ROWS_PER_WORD, a.fp8);
             }
             store_R(g, acc);
         }
@@ -973,7 +1001,7 @@ scan_kernel(ScanArgs a) {
 template <int LUT>
 __global__ void __launch_bounds__(256)
 dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centroid,
-                const float* __restrict__ codebooks, int d, int pq_dim, int m, int bits,
+                const float* __restrict__ codebooks, int d, int pq_dim, int m, int bits, Fp8Params fp8,
                 unsigned char* __restrict__ out) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int n_entries = pq_dim << bits;
@@ -982,8 +1010,8 @@ dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centr
     float* rq = reinterpret_cast<float*>(smem + ((lut_bytes + 15) & ~(size_t)15));
     for (int t = threadIdx.x; t < d; t += blockDim.x) rq[t] = query[t] - centroid[t];
     __syncthreads();
-    if (bits == 8) build_lut_any_m<LUT, 8>(codebooks, rq, pq_dim, m, lut);
-    else build_lut_any_m<LUT, 4>(codebooks, rq, pq_dim, m, lut);
+    if (bits == 8) build_lut_any_m<LUT, 8>(codebooks, rq, pq_dim, m, lut, fp8);
+    else build_lut_any_m<LUT, 4>(codebooks, rq, pq_dim, m, lut, fp8);
     __syncthreads();
     for (size_t i = threadIdx.x; i < lut_bytes / 4; i += blockDim.x)
         reinterpret_cast<uint32_t*>(out)[i] = reinterpret_cast<const uint32_t*>(lut)[i];
@@ -1138,7 +1166,7 @@ int check_search_args(const ivfpq_index* idx, const void* q, int64_t nq, int32_t
     if (n_probes < 1 || n_probes > idx->n_lists || n_probes > IVFPQ_MAX_PROBES)
         return fail(IVFPQ_EINVAL, "n_probes=%d outside [1, min(n_lists=%d, %d)]", n_probes, idx->n_lists, IVFPQ_MAX_PROBES);
     if (need_k && (k < 1 || k > IVFPQ_MAX_K)) return fail(IVFPQ_EINVAL, "k=%d outside [1, %d]", k, IVFPQ_MAX_K);
-    if (lut_dtype < 0 || lut_dtype > 2) return fail(IVFPQ_EINVAL, "unknown lut_dtype %d", lut_dtype);
+    if (lut_dtype < 0 || lut_dtype > 3) return fail(IVFPQ_EINVAL, "unknown lut_dtype %d", lut_dtype);
     return IVFPQ_OK;
 }
 
@@ -1214,9 +1242,12 @@ int launch_scan(const ivfpq_index* idx, ScanArgs a, int lut_dtype, dim3 grid, hi
         case IVFPQ_LUT_FP16:
             return b8 ? launch_scan_bits<IVFPQ_LUT_FP16, 8>(a, cw, nch, grid, threads, lds, st)
                       : launch_scan_bits<IVFPQ_LUT_FP16, 4>(a, cw, nch, grid, threads, lds, st);
-        default:
+        case IVFPQ_LUT_FP8_E5M3:
             return b8 ? launch_scan_bits<IVFPQ_LUT_FP8_E5M3, 8>(a, cw, nch, grid, threads, lds, st)
                       : launch_scan_bits<IVFPQ_LUT_FP8_E5M3, 4>(a, cw, nch, grid, threads, lds, st);
+        default:
+            return b8 ? launch_scan_bits<IVFPQ_LUT_FP8_E4M4, 8>(a, cw, nch, grid, threads, lds, st)
+                      : launch_scan_bits<IVFPQ_LUT_FP8_E4M4, 4>(a, cw, nch, grid, threads, lds, st);
     }
 }
 
@@ -1229,6 +1260,7 @@ ScanArgs base_scan_args(const ivfpq_index* idx) {
     a.codes = idx->dev.codes;
     a.d = idx->d; a.pq_dim = idx->pq_dim; a.m = idx->m(); a.bits = idx->pq_bits;
     a.n_lists = idx->n_lists;
+    a.fp8 = e4m4_params(idx->e4m4_bias);
     a.single_list = -1;
     return a;
 }
@@ -1488,7 +1520,7 @@ int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_
 int ivfpq_dump_lut(const ivfpq_index_t* idx, const float* d_query, uint32_t list_id, int32_t lut_dtype,
                    void* d_lut_out, void* hip_stream) {
     if (!idx || !d_query || !d_lut_out) return fail(IVFPQ_EINVAL, "ivfpq_dump_lut: null pointer");
-    if (lut_dtype < 0 || lut_dtype > 2) return fail(IVFPQ_EINVAL, "unknown lut_dtype %d", lut_dtype);
+    if (lut_dtype < 0 || lut_dtype > 3) return fail(IVFPQ_EINVAL, "unknown lut_dtype %d", lut_dtype);
     if (list_id >= (uint32_t)idx->n_lists) return fail(IVFPQ_EINVAL, "list_id %u >= n_lists %d", list_id, idx->n_lists);
     if (int s = check_device(idx)) return s;
     const size_t lds = scan_lds_bytes(idx, lut_dtype);
@@ -1499,21 +1531,22 @@ int ivfpq_dump_lut(const ivfpq_index_t* idx, const float* d_query, uint32_t list
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(kernel, dim3(1), dim3(256), lds, st, d_query, centroid, idx->dev.codebooks, idx->d,
-                           idx->pq_dim, idx->m(), idx->pq_bits, (unsigned char*)d_lut_out);
+                           idx->pq_dim, idx->m(), idx->pq_bits, e4m4_params(idx->e4m4_bias), (unsigned char*)d_lut_out);
         HIP_TRY(hipGetLastError());
         return IVFPQ_OK;
     };
     switch (lut_dtype) {
         case IVFPQ_LUT_FP32: return go(dump_lut_kernel<IVFPQ_LUT_FP32>);
         case IVFPQ_LUT_FP16: return go(dump_lut_kernel<IVFPQ_LUT_FP16>);
-        default: return go(dump_lut_kernel<IVFPQ_LUT_FP8_E5M3>);
+        case IVFPQ_LUT_FP8_E5M3: return go(dump_lut_kernel<IVFPQ_LUT_FP8_E5M3>);
+        default: return go(dump_lut_kernel<IVFPQ_LUT_FP8_E4M4>);
     }
 }
 
 int ivfpq_scan_list(const ivfpq_index_t* idx, const float* d_query, uint32_t list_id, int32_t lut_dtype,
                     float* d_R_out, void* hip_stream) {
     if (!idx || !d_query) return fail(IVFPQ_EINVAL, "ivfpq_scan_list: null pointer");
-    if (lut_dtype < 0 || lut_dtype > 2) return fail(IVFPQ_EINVAL, "unknown lut_dtype %d", lut_dtype);
+    if (lut_dtype < 0 || lut_dtype > 3) return fail(IVFPQ_EINVAL, "unknown lut_dtype %d", lut_dtype);
     if (list_id >= (uint32_t)idx->n_lists) return fail(IVFPQ_EINVAL, "list_id %u >= n_lists %d", list_id, idx->n_lists);
     if (int s = check_device(idx)) return s;
     if (idx->list_offsets[list_id + 1] == idx->list_offsets[list_id]) return IVFPQ_OK;

@@ -340,6 +340,13 @@ int ivfpq_index_export(const ivfpq_index_t* index, float* centroids, float* code
     return IVFPQ_OK;
 }
 
+int ivfpq_set_e4m4_bias(ivfpq_index_t* index, int32_t bias) {
+    if (!index) return fail(IVFPQ_EINVAL, "ivfpq_set_e4m4_bias: null index");
+    if (bias < -100 || bias > 110) return fail(IVFPQ_EINVAL, "e4m4 bias %d outside [-100, 110]", bias);
+    index->e4m4_bias = bias;
+    return IVFPQ_OK;
+}
+
 void ivfpq_free(ivfpq_index_t* index) {
     if (!index) return;
     release_device_state(index);

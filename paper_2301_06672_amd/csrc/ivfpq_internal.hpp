@@ -43,6 +43,7 @@ struct ivfpq_index {
     std::vector<uint32_t> sorted_padded_sizes;  // padded list lengths, descending
 
     ivfpq::DeviceImage dev;
+    int32_t e4m4_bias = 7;              // exponent bias of the e4m4 table dtype (ivfpq_set_e4m4_bias)
     float centroid_norm_max = 0.f;      // largest squared centroid norm (set by ivfpq_upload)
 
     // stage timing (hipEvent_t kept as void* so this header stays free of HIP types)

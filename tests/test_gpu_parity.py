@@ -76,6 +76,37 @@ def test_lut_bytes_identical_shapes_and_ranges(P, d, pq_dim, pq_bits):
             assert F.min() < 2.0 ** -15     # and the flooring end
 
 
+@pytest.mark.parametrize("bias", [-2, 1, 7, 14])
+def test_e4m4_lut_bytes_and_search(P, tiny, bias):
+    # the 4+4 split with a caller-chosen exponent bias: table bytes identical, search results as the oracle's
+    w, data, oidx, gidx = tiny
+    gidx.ivfpq_set_e4m4_bias(bias)
+    q = si.queries(w, 40)
+    for l in (3, 40):
+        _step(f"e4m4 bias={bias} dump_lut list={l}")
+        got = gidx.ivfpq_dump_lut(q[2], l, P.LUT_FP8_E4M4).cpu().numpy()
+        want, _ = oracle.lut_store(oracle.lut_f32(oidx, q[2], l), oracle.LUT_E4M4, e4m4_bias=bias)
+        np.testing.assert_array_equal(got, want)
+    ids_g, d_g = gidx.ivfpq_search(q, w.n_probes, w.k, P.LUT_FP8_E4M4)
+    probes, _ = gidx.ivfpq_select_probes(q, w.n_probes)
+    ids_o, d_o = oracle.search(oidx, q, w.n_probes, w.k, oracle.LUT_E4M4, probes=probes.cpu().numpy().view(np.uint32),
+                               e4m4_bias=bias)
+    assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"e4m4 bias={bias}")
+    gidx.ivfpq_set_e4m4_bias(7)
+
+
+def test_e4m4_other_shapes(P):
+    for d, pq_dim, pq_bits in ((128, 64, 4), (128, 32, 8), (24, 8, 4)):
+        oidx, gidx = random_pair(P, 2000, d, 5, pq_dim, pq_bits, salt=900 + d + pq_bits)
+        gidx.ivfpq_set_e4m4_bias(5)
+        q = np.random.default_rng(900).standard_normal((20, d)).astype(np.float32)
+        _step(f"e4m4 d={d} s={pq_dim} p={pq_bits}")
+        ids_g, d_g = gidx.ivfpq_search(q, 3, 20, P.LUT_FP8_E4M4)
+        probes, _ = gidx.ivfpq_select_probes(q, 3)
+        ids_o, d_o = oracle.search(oidx, q, 3, 20, oracle.LUT_E4M4, probes=probes.cpu().numpy().view(np.uint32), e4m4_bias=5)
+        assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"e4m4 d={d} p={pq_bits}")
+
+
 # ---------------------------------------------------------------- Eq. (1) over one cluster (step 4)
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -274,6 +305,9 @@ def test_error_paths(P, tiny):
     assert e.value.status == P.EINVAL
     with pytest.raises(P.IvfpqError) as e:
         gidx.ivfpq_search(q, 4, 10, 7)
+    assert e.value.status == P.EINVAL
+    with pytest.raises(P.IvfpqError) as e:
+        gidx.ivfpq_set_e4m4_bias(500)
     assert e.value.status == P.EINVAL
     # a workspace that is too small is refused before anything is launched
     import ctypes

@@ -143,6 +143,28 @@ def test_e4m4_general_format_round_trip():
         np.testing.assert_array_equal(bits.view(np.float32), dec)
 
 
+def test_e4m4_hand_values_and_bit_formula():
+    # bias 7: 1.0 = 2^0 has exponent field 7; one mantissa step is 1/16
+    enc = lambda x, bias=7: int(oracle.fp8_encode(np.float32(x), 4, bias)[0])
+    dec = lambda b, bias=7: float(oracle.fp8_decode(np.uint8(b), 4, bias)[0])
+    assert enc(1.0) == 0x70 and dec(0x70) == 1.0
+    assert enc(1.0625) == 0x71 and enc(1.03125) == 0x71 and enc(1.03124) == 0x70      # tie goes up
+    assert dec(0x00) == 2.0 ** -7 and enc(0.0) == 0x00 and enc(1e-9) == 0x00
+    assert dec(0xFF) == 1.9375 * 2.0 ** 8 and enc(1000.0) == 0xFF and enc(np.inf) == 0xFF
+    assert enc(3.0) == 0x88 and dec(0x88) == 3.0                                        # 1.5 * 2^1
+    assert enc(100.0, bias=1) == enc(100.0 / 64.0, bias=7)                              # a bias shift is a power-of-two scale
+    x = _random_floats(300_000, 6)
+    for bias in (-3, 1, 7, 12):
+        lo = (127 - bias) << 23
+        i = np.clip(x.view(np.int32).astype(np.int64), lo, lo + (255 << 19))
+        want = ((i - (lo - (1 << 18))) >> 19).astype(np.uint8)
+        np.testing.assert_array_equal(oracle.fp8_encode(x, 4, bias), want)
+        F = np.abs(x[:4096]).reshape(16, 256)
+        st, back = oracle.lut_store(F, oracle.LUT_E4M4, e4m4_bias=bias)
+        np.testing.assert_array_equal(st, oracle.fp8_encode(F.ravel(), 4, bias))
+        np.testing.assert_array_equal(back.ravel(), oracle.fp8_decode(st, 4, bias))
+
+
 def test_fp16_encode_matches_numpy():
     rng = np.random.default_rng(4)
     x = np.concatenate([
