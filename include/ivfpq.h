@@ -3,8 +3,8 @@
  *
  * The library implements the search phase of IVFPQ as described in
  * arXiv 2301.06672, Sec. I-C (second enumeration) and Sec. I-D, with the
- * "norm2 fragment lookup table" held in LDS as fp32, IEEE half or the paper's
- * sign-less 8-bit float e5m3 (Sec. II).  All compute of the search runs in
+ * "norm2 fragment lookup table" held in LDS as fp32, IEEE half or one of the
+ * paper's sign-less 8-bit floats, e5m3 and e4m4 (Sec. II).  All compute of the search runs in
  * hand-written HIP kernels; this header is the only interface.
  *
  * Conventions
@@ -141,7 +141,7 @@ int ivfpq_search_with_probes(const ivfpq_index_t* index, const float* d_queries,
 /* Steps 2-3 alone, for inspection: builds the table of one (query, cluster) pair exactly as the
  * search kernel stages it in LDS and copies the raw bytes out.
  * d_query [d] f32 (device); d_lut_out (device) [pq_dim][2^pq_bits] entries of lut_dtype,
- * i.e. pq_dim * 2^pq_bits * {4, 2, 1} bytes. */
+ * i.e. pq_dim * 2^pq_bits * {4, 2, 1, 1} bytes for the four dtypes. */
 int ivfpq_dump_lut(const ivfpq_index_t* index, const float* d_query, uint32_t list_id,
                    int32_t lut_dtype, void* d_lut_out, void* hip_stream);
 

@@ -14,7 +14,7 @@ import numpy as np
 import torch  # imported before the library so that both share one HIP runtime
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("IVFPQ_LIB", os.path.join(HERE, "libivfpq.so"))   # IVFPQ_LIB: development override
+LIB_PATH = os.path.join(HERE, "libivfpq.so")
 
 LUT_FP32, LUT_FP16, LUT_FP8_E5M3, LUT_FP8_E4M4 = 0, 1, 2, 3
 LUT_NAMES = {LUT_FP32: "fp32", LUT_FP16: "fp16", LUT_FP8_E5M3: "e5m3", LUT_FP8_E4M4: "e4m4"}

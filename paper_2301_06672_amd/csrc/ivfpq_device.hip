@@ -1,13 +1,18 @@
 // Device half of libivfpq: upload of the index image and the HIP kernels of the IVFPQ search phase
 // (arXiv 2301.06672, Sec. I-C second enumeration, Sec. I-D, Sec. II) for gfx950 (MI355X, wave64).
 //
-// Kernels, in the order one search call runs them:
-//   coarse_dist_kernel   step 1a: |q - c_l|^2 for a tile of queries x all clusters (fp32, direct form)
-//   select_probes_kernel step 1b: the n_probes nearest clusters per query (exact radix select),
-//                        plus the per-query offsets of each probed cluster in the R scratch
-//   scan_kernel          steps 2-4: one workgroup per (query, probed cluster): query residual, lookup
-//                        table F built in LDS as fp32 / half / e5m3, then every wave streams 64-vector
+// Kernels, in the order one search call runs them (per tile of queries):
+//   coarse_rank_kernel   step 1a: ranking values |c|^2 - 2 q.c of every (query, cluster) pair on the
+//                        matrix cores (fp32 MFMA)
+//   select_probes_kernel step 1b: short list by ranking value with a rigorous error bound, exact
+//                        direct-form distances for the short list, exact selection of the n_probes
+//                        nearest clusters; per-pair descriptors and R offsets
+//   scan_kernel (mode 1) steps 2-4 for the nearest probe of every query: query residual, lookup table F
+//                        built in LDS as fp32 / half / e5m3 / e4m4, then every wave streams 64-vector
 //                        groups of PQ codes from HBM and accumulates R = sum_j F(y_j) (Eq. 1)
+//   bound_kernel         the k-th smallest R of that nearest cluster: an upper bound of the final
+//                        k-th distance of the query
+//   scan_kernel (mode 2) steps 2-4 for the other probes; only R values under the bound are kept
 //   topk_kernel          step 5: the k smallest R over all probed clusters of a query, ordered by
 //                        (R, id), and the map from (cluster, position) to the caller's ids
 #include <hip/hip_runtime.h>

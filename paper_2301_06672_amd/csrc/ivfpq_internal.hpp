@@ -39,7 +39,6 @@ struct ivfpq_index {
 
     // derived at import
     int64_t total_groups = 0;           // sum over lists of ceil(len/64)
-    int64_t max_candidates = 0;         // filled per (n_probes) query: see max_padded_candidates()
     std::vector<uint32_t> sorted_padded_sizes;  // padded list lengths, descending
 
     ivfpq::DeviceImage dev;
@@ -48,8 +47,6 @@ struct ivfpq_index {
 
     // stage timing (hipEvent_t kept as void* so this header stays free of HIP types)
     bool timing = false;
-    void* ev[4] = {nullptr, nullptr, nullptr, nullptr};
-    float stage_ms[4] = {0, 0, 0, 0};
     bool stage_valid = false;
     struct Span { void* a; void* b; int stage; };
     std::vector<void*> event_pool;
