@@ -63,10 +63,13 @@ def _declare(L):
     L.orc_fp16_decode_array.argtypes = [vp, i64, vp]
     L.orc_select_probes.argtypes = [vp, i32, i32, vp, i64, i32, vp, vp]
     L.orc_lut_f32.argtypes = [vp, vp, vp, i32, i32, i32, vp]
-    L.orc_lut_store.argtypes = [vp, i64, i32, i32, i32, vp, vp]
+    L.orc_lut_store.argtypes = [vp, i64, i32, i32, i32, i32, i32, i32, vp, vp]
+    L.orc_lut_store.restype = i32
+    L.orc_fp8_table_bias.argtypes = [vp, i64, i32, i32, i32]
+    L.orc_fp8_table_bias.restype = i32
     L.orc_scan_list.argtypes = [vp, i32, i32, vp, i64, vp, vp]
     L.orc_search.argtypes = [i64, i32, i32, i32, i32, vp, vp, vp, vp, vp,
-                             vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+                             vp, i64, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     L.orc_lut_elem_bytes.argtypes = [i32]
     L.orc_lut_elem_bytes.restype = i32
 
@@ -268,13 +271,39 @@ def lut_f32(index: Index, query, list_id: int) -> np.ndarray:
     return F
 
 
-def lut_store(F: np.ndarray, lut_dtype: int, truncate: bool = False, e4m4_bias: int = 7):
-    """-> (bytes as stored on chip, decoded fp32 values a lookup returns)."""
+# Range of the exponent bias of the two 8-bit formats (every code stays a finite, normal FP32 number)
+FP8_BIAS_RANGE = {2: (-96, 110), 3: (-100, 110)}
+FP8_DEFAULT_BIAS = {2: 15, 3: 7}
+
+
+def _fp8_bias(lut_dtype: int, bias, e4m4_bias: int) -> int:
+    if bias is not None:
+        return int(bias)
+    return int(e4m4_bias) if lut_dtype == LUT_E4M4 else FP8_DEFAULT_BIAS.get(lut_dtype, 0)
+
+
+def fp8_table_bias(F: np.ndarray, lut_dtype: int) -> int:
+    """Exponent bias that puts the binade of the table's largest entry on the format's top binade."""
+    F = _f32(F)
+    lo, hi = FP8_BIAS_RANGE[lut_dtype]
+    return int(lib().orc_fp8_table_bias(_p(F), F.size, 5 if lut_dtype == LUT_E5M3 else 4, lo, hi))
+
+
+def lut_store(F: np.ndarray, lut_dtype: int, truncate: bool = False, e4m4_bias: int = 7, bias=None,
+              per_table: bool = False, return_bias: bool = False):
+    """-> (bytes as stored on chip, decoded fp32 values a lookup returns).
+
+    bias: exponent bias of the 8-bit format in use (default 15 for e5m3, e4m4_bias for e4m4);
+    per_table: choose the bias from the table's largest entry instead (power-of-two table scaling)."""
     F = _f32(F)
     eb = lib().orc_lut_elem_bytes(lut_dtype)
     stored = np.empty(F.size * eb, dtype=np.uint8)
     decoded = np.empty(F.shape, dtype=np.float32)
-    lib().orc_lut_store(_p(F), F.size, lut_dtype, int(truncate), int(e4m4_bias), _p(stored), _p(decoded))
+    lo, hi = FP8_BIAS_RANGE.get(lut_dtype, (0, 0))
+    used = lib().orc_lut_store(_p(F), F.size, lut_dtype, int(truncate), _fp8_bias(lut_dtype, bias, e4m4_bias),
+                               int(per_table), lo, hi, _p(stored), _p(decoded))
+    if return_bias:
+        return stored, decoded, int(used)
     return stored, decoded
 
 
@@ -290,7 +319,8 @@ def scan_list(index: Index, lut_decoded: np.ndarray, list_id: int):
 
 
 def search(index: Index, queries, n_probes: int, k: int, lut_dtype: int = LUT_FP32,
-           truncate: bool = False, probes=None, return_stats: bool = False, e4m4_bias: int = 7):
+           truncate: bool = False, probes=None, return_stats: bool = False, e4m4_bias: int = 7, bias=None,
+           per_table: bool = False):
     queries = _f32(queries)
     nq = queries.shape[0]
     out_ids = np.empty((nq, k), dtype=np.int64)
@@ -303,7 +333,8 @@ def search(index: Index, queries, n_probes: int, k: int, lut_dtype: int = LUT_FP
     lib().orc_search(index.n, index.d, index.n_lists, index.pq_dim, index.pq_bits,
                      _p(index.centroids), _p(index.codebooks), _p(index.list_offsets),
                      _p(index.codes), _p(index.ids), _p(queries), nq, n_probes, k,
-                     lut_dtype, int(truncate), int(e4m4_bias), _p(pr) if pr is not None else None,
+                     lut_dtype, int(truncate), _fp8_bias(lut_dtype, bias, e4m4_bias), int(per_table),
+                     *FP8_BIAS_RANGE.get(lut_dtype, (0, 0)), _p(pr) if pr is not None else None,
                      _p(out_ids), _p(out_d), _p(stats))
     if return_stats:
         return out_ids, out_d, {"floored": int(stats[0]), "saturated": int(stats[1])}

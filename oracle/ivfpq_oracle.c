@@ -332,19 +332,43 @@ void orc_lut_f32(const float* query, const float* centroid, const float* codeboo
     free(rq);
 }
 
+/* Power-of-two scaling of a table stored in an 8-bit format (a reading that goes beyond Sec. II,
+ * which fixes one bias per format): multiplying every entry by 2^s before the encode and dividing
+ * by 2^s after the decode is the same as moving the format's exponent bias by s, so the scale is
+ * expressed as a per-table bias.  It is chosen so that the binade of the table's largest entry is
+ * the format's top binade: with e = floor(log2(max F)) and E = 2^exp_bits - 1 (the largest exponent
+ * field), bias = E - e.  Entries below the FP32 normal range count as 2^-127 (e = -127; so does an
+ * all-zero table), +Inf as 2^128; the result is clamped to [bias_min, bias_max]. */
+int orc_fp8_table_bias(const float* F, int64_t n, int exp_bits, int bias_min, int bias_max) {
+    double mx = 0.0;
+    for (int64_t i = 0; i < n; ++i)
+        if (!isnan(F[i]) && (double)F[i] > mx) mx = (double)F[i];
+    int e;
+    if (isinf(mx)) e = 128;
+    else if (mx < ldexp(1.0, -126)) e = -127;
+    else { (void)frexp(mx, &e); e -= 1; }       /* frexp: mx = f * 2^e with f in [0.5, 1) */
+    int bias = ((1 << exp_bits) - 1) - e;
+    if (bias < bias_min) bias = bias_min;
+    if (bias > bias_max) bias = bias_max;
+    return bias;
+}
+
 /* lut_dtype: 0 = fp32 (4 B little-endian), 1 = IEEE half (2 B), 2 = e5m3 (1 B), 3 = e4m4 (1 B; the
- * 4+4 split of Sec. II with exponent bias `e4m4_bias`, which the text does not give).
+ * 4+4 split of Sec. II).  For the two 8-bit formats `bias` is the exponent bias (15 is the reading
+ * taken for e5m3; the text gives none for e4m4) and `truncate` the rounding; per_table != 0 replaces
+ * `bias` by orc_fp8_table_bias of this table, clamped to [bias_min, bias_max].
  * `stored` receives the table exactly as it sits in on-chip memory;
- * `decoded` (may be NULL) receives what a lookup returns, as fp32. */
+ * `decoded` (may be NULL) receives what a lookup returns, as fp32.  Returns the bias used. */
 enum { ORC_LUT_FP32 = 0, ORC_LUT_FP16 = 1, ORC_LUT_E5M3 = 2, ORC_LUT_E4M4 = 3 };
 
 static int lut_elem_bytes(int lut_dtype) { return lut_dtype == 0 ? 4 : (lut_dtype == 1 ? 2 : 1); }
 
-void orc_lut_store(const float* F, int64_t n, int lut_dtype, int truncate, int e4m4_bias,
-                   uint8_t* stored, float* decoded) {
+int orc_lut_store(const float* F, int64_t n, int lut_dtype, int truncate, int bias, int per_table,
+                  int bias_min, int bias_max, uint8_t* stored, float* decoded) {
     double table[256];
     const int mant_bits = lut_dtype == ORC_LUT_E4M4 ? 4 : 3;
-    const int bias = lut_dtype == ORC_LUT_E4M4 ? e4m4_bias : 15;
+    if ((lut_dtype == ORC_LUT_E5M3 || lut_dtype == ORC_LUT_E4M4) && per_table)
+        bias = orc_fp8_table_bias(F, n, 8 - mant_bits, bias_min, bias_max);
     fp8_table(mant_bits, bias, table);
     for (int64_t i = 0; i < n; ++i) {
         float back;
@@ -359,6 +383,7 @@ void orc_lut_store(const float* F, int64_t n, int lut_dtype, int truncate, int e
         }
         if (decoded) decoded[i] = back;
     }
+    return bias;
 }
 
 /* PQ code of sub-space j of one stored vector.  pq_bits = 8: byte j.
@@ -408,7 +433,8 @@ void orc_search(int64_t n, int d, int n_lists, int pq_dim, int pq_bits,
                 const float* centroids, const float* codebooks,
                 const int64_t* list_offsets, const uint8_t* codes, const int64_t* ids,
                 const float* queries, int64_t nq, int n_probes, int k,
-                int lut_dtype, int truncate, int e4m4_bias, const uint32_t* probes_in,
+                int lut_dtype, int truncate, int bias, int per_table, int bias_min, int bias_max,
+                const uint32_t* probes_in,
                 int64_t* out_ids, float* out_d, int64_t* stats) {
     (void)n;
     int ksub = 1 << pq_bits;
@@ -435,7 +461,7 @@ void orc_search(int64_t n, int d, int n_lists, int pq_dim, int pq_bits,
                 uint32_t l = probes[p];
                 int64_t lo = list_offsets[l], len = list_offsets[l + 1] - lo;
                 orc_lut_f32(qv, centroids + (int64_t)l * d, codebooks, d, pq_dim, ksub, F);
-                orc_lut_store(F, lut_n, lut_dtype, truncate, e4m4_bias, stored, Fd);
+                (void)orc_lut_store(F, lut_n, lut_dtype, truncate, bias, per_table, bias_min, bias_max, stored, Fd);
                 if (lut_dtype == ORC_LUT_E5M3 || lut_dtype == ORC_LUT_E4M4)
                     for (int64_t e = 0; e < lut_n; ++e) {
                         floored += stored[e] == 0x00; saturated += stored[e] == 0xFF;

@@ -205,3 +205,78 @@ def test_lut_store_decoded_matches_formats():
     st, dec = oracle.lut_store(F, oracle.LUT_E5M3)
     np.testing.assert_array_equal(st, _encode_bits(F.ravel(), False))
     np.testing.assert_array_equal(dec.ravel(), oracle.e5m3_decode(st))
+
+
+# ------------------------------------------------------------------ general bias, truncation, per-table bias
+
+@pytest.mark.parametrize("mant_bits,default_bias", [(3, 15), (4, 7)])
+def test_fp8_bias_shift_is_a_power_of_two_scale(mant_bits, default_bias):
+    # moving the bias by s multiplies every representable value by 2^-s: encode(x, B) = encode(x * 2^(B-B0), B0)
+    rng = np.random.default_rng(7)
+    x = np.exp(rng.uniform(np.log(1e-3), np.log(1e3), size=50_000)).astype(np.float32)
+    b = np.arange(256, dtype=np.uint8)
+    for bias in (default_bias - 9, default_bias - 1, default_bias + 4, default_bias + 20):
+        s = bias - default_bias
+        scaled = (x.astype(np.float64) * 2.0 ** s).astype(np.float32)
+        assert np.all(scaled.astype(np.float64) == x.astype(np.float64) * 2.0 ** s)       # exact in fp32
+        for trunc in (False, True):
+            np.testing.assert_array_equal(oracle.fp8_encode(x, mant_bits, bias, trunc),
+                                          oracle.fp8_encode(scaled, mant_bits, default_bias, trunc))
+        np.testing.assert_array_equal(oracle.fp8_decode(b, mant_bits, bias).astype(np.float64) * 2.0 ** s,
+                                      oracle.fp8_decode(b, mant_bits, default_bias).astype(np.float64))
+
+
+@pytest.mark.parametrize("trunc", [False, True])
+def test_e5m3_general_bias_bit_formula(trunc):
+    x = _random_floats(300_000, 8)
+    for bias in (-96, 0, 15, 31, 110):
+        lo = (127 - bias) << 23
+        i = np.clip(x.view(np.int32).astype(np.int64), lo, lo + (255 << 20))
+        want = ((i - (lo if trunc else lo - (1 << 19))) >> 20).astype(np.uint8)
+        np.testing.assert_array_equal(oracle.fp8_encode(x, 3, bias, trunc), want)
+        dec = ((np.arange(256, dtype=np.int64) << 20) + lo).astype(np.uint32).view(np.float32)
+        np.testing.assert_array_equal(oracle.fp8_decode(np.arange(256, dtype=np.uint8), 3, bias), dec)
+        assert np.all(np.isfinite(dec)) and np.all(dec >= np.float32(2.0 ** -126))          # finite, normal
+
+
+def test_table_bias_hand_values():
+    tb = lambda vals, dt: oracle.fp8_table_bias(np.array(vals, dtype=np.float32), dt)
+    E5, E4 = oracle.LUT_E5M3, oracle.LUT_E4M4
+    assert tb([0.25, 1.0, 0.5], E5) == 31 and tb([0.25, 1.0, 0.5], E4) == 15      # [1, 2) is the top binade
+    assert tb([1.9999], E5) == 31 and tb([2.0], E5) == 30 and tb([2.0], E4) == 14
+    assert tb([0.75, 0.1], E5) == 32 and tb([0.75], E4) == 16
+    assert tb([100.0, 3.0], E5) == 25 and tb([100.0], E4) == 9                    # 2^6 <= 100 < 2^7
+    assert tb([65536.0], E5) == 15                                                # the fixed format's own top binade
+    assert tb([0.0, 0.0], E5) == 110 and tb([1e-45], E4) == 110                   # nothing above 2^-126: clamped
+    assert tb([np.inf], E5) == -96 and tb([np.inf], E4) == -100
+    assert tb([3e38], E5) == 31 - 127 and tb([3e38], E4) == -100
+
+
+@pytest.mark.parametrize("dt,mant_bits,top_low", [(oracle.LUT_E5M3, 3, 0xF8), (oracle.LUT_E4M4, 4, 0xF0)])
+def test_table_bias_brute_force_and_scale_invariance(dt, mant_bits, top_low):
+    rng = np.random.default_rng(9)
+    lo_b, hi_b = oracle.FP8_BIAS_RANGE[dt]
+    for trial in range(40):
+        scale = 2.0 ** rng.integers(-60, 60)
+        F = (np.exp(rng.uniform(np.log(1e-4), np.log(1.0), size=(8, 256))) * scale).astype(np.float32)
+        B = oracle.fp8_table_bias(F, dt)
+        # the smallest bias (largest values) whose top binade still starts at or below the largest entry
+        ok = [b for b in range(lo_b, hi_b + 1) if oracle.lib().orc_fp8_value(top_low, mant_bits, b) <= float(F.max())]
+        assert B == min(ok)
+        for trunc in (False, True):
+            st, dec, used = oracle.lut_store(F, dt, truncate=trunc, per_table=True, return_bias=True)
+            assert used == B
+            st_fixed, dec_fixed = oracle.lut_store(F, dt, truncate=trunc, bias=B)
+            np.testing.assert_array_equal(st, st_fixed)
+            np.testing.assert_array_equal(dec, dec_fixed)
+            assert st.max() >= top_low                                              # the largest entry sits in the top binade
+            # scaling the table by a power of two changes the bias, not the stored bytes
+            st2, dec2, used2 = oracle.lut_store((F.astype(np.float64) * 2.0 ** -7).astype(np.float32), dt,
+                                                truncate=trunc, per_table=True, return_bias=True)
+            assert used2 == B + 7
+            np.testing.assert_array_equal(st2, st)
+            np.testing.assert_array_equal(dec2.astype(np.float64) * 2.0 ** 7, dec.astype(np.float64))
+        st, dec = oracle.lut_store(F, dt, per_table=True)
+        rel = np.abs(dec.astype(np.float64) - F) / F
+        in_range = F >= dec.min()
+        assert rel[in_range].max() <= 1.0 / (2 ** (mant_bits + 1)) + 1e-12          # half a step; the clamp at the top included

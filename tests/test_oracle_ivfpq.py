@@ -314,3 +314,25 @@ def test_tiny_workload_recall_band():
     assert abs(oracle.recall(ids8, gt) - rec[8]) < 0.03
     assert oracle.recall(ids8t, gt) <= oracle.recall(ids8, gt) + 0.02
     assert stats["saturated"] == 0
+
+
+@pytest.mark.parametrize("dt", [oracle.LUT_E5M3, oracle.LUT_E4M4])
+def test_per_table_bias_makes_search_invariant_to_power_of_two_scaling(dt):
+    # every step of the path is exact under a power-of-two scale of the inputs; a per-table bias makes
+    # the 8-bit table follow the scale, so ids are unchanged and R scales by the square
+    import dataclasses
+    w, data, idx = _tiny_index(n=4000, n_lists=16, iters=5)
+    q = si.queries(w, 40)
+    s = np.float32(2.0 ** -9)
+    idx_s = dataclasses.replace(idx, centroids=idx.centroids * s, codebooks=idx.codebooks * s)
+    for trunc in (False, True):
+        ids_a, d_a = oracle.search(idx, q, 6, 10, dt, truncate=trunc, per_table=True)
+        ids_b, d_b = oracle.search(idx_s, q * s, 6, 10, dt, truncate=trunc, per_table=True)
+        np.testing.assert_array_equal(ids_a, ids_b)
+        np.testing.assert_array_equal(d_a.astype(np.float64) * float(s) ** 2, d_b.astype(np.float64))
+    # with the fixed bias the scaled tables fall under the smallest code and the results change
+    _, _, st_a = oracle.search(idx, q, 6, 10, dt, return_stats=True)
+    ids_c, _, st_c = oracle.search(idx_s, q * s, 6, 10, dt, return_stats=True)
+    assert st_c["floored"] > st_a["floored"]
+    _, _, st_p = oracle.search(idx_s, q * s, 6, 10, dt, per_table=True, return_stats=True)
+    assert st_p["floored"] < st_c["floored"]
