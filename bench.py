@@ -82,6 +82,9 @@ def main():
     ap.add_argument("--e4m4-bias", type=int, default=None,
                     help="exponent bias of the e4m4 table dtype (default: 1 for the integer-valued sets, 16 for the unit-norm sets)")
     ap.add_argument("--all-luts", action="store_true", help="also time the e4m4 table")
+    ap.add_argument("--fp8-variants", action="store_true",
+                    help="also time the 8-bit tables with a truncating encode and with a per-table exponent bias "
+                         "(reported under by_lut as e5m3+trunc, e5m3+pertable, e4m4+pertable)")
     ap.add_argument("--kmeans-iters", type=int, default=6, help="Lloyd iterations of the (untimed) index build")
     ap.add_argument("--n-probes", type=int, default=None)
     ap.add_argument("--k", type=int, default=None)
@@ -161,7 +164,12 @@ def main():
     gt_i, gt_d = exact_topk_gpu(data, q[:nr], k)
 
     def run(lut_name, steps, warmup):
-        lut = lut_ids[lut_name]
+        base, _, variant = lut_name.partition("+")
+        lut = lut_ids[base]
+        if base in ("e5m3", "e4m4"):
+            idx.ivfpq_set_fp8_encoding(lut, 15 if base == "e5m3" else e4m4_bias,
+                                       pkg.ROUND_TRUNCATE if variant == "trunc" else pkg.ROUND_NEAREST,
+                                       variant == "pertable")
         for _ in range(warmup):
             idx.ivfpq_search(q, n_probes, k, lut, out=out)
         torch.cuda.synchronize()
@@ -187,6 +195,8 @@ def main():
     order = [args.lut] if args.only_headline else ["fp32", "fp16", "e5m3"]
     if not args.only_headline and (args.all_luts or args.lut == "e4m4"):
         order.append("e4m4")
+    if args.fp8_variants and not args.only_headline:
+        order += ["e5m3+trunc", "e5m3+pertable", "e4m4+pertable"]
     for name in order:
         steps = args.steps if name == args.lut else max(3, args.steps // 2)
         results[name] = run(name, steps, args.warmup)

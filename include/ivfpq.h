@@ -43,6 +43,13 @@ typedef enum {
                                the bias is set per index with ivfpq_set_e4m4_bias (default 7) */
 } ivfpq_lut_dtype_t;
 
+/* Rounding of the FP32 -> 8-bit encode (Sec. II: "shift the bit string and adjust the exponent bias";
+ * whether the shift rounds is left open by the text). */
+typedef enum {
+    IVFPQ_ROUND_NEAREST = 0, /* nearest representable value, ties to the larger one (the default) */
+    IVFPQ_ROUND_TRUNCATE = 1 /* the largest representable value not above the input: a bare shift */
+} ivfpq_fp8_rounding_t;
+
 typedef enum {
     IVFPQ_OK = 0,
     IVFPQ_EINVAL = -1,       /* null pointer, bad shape or parameter */
@@ -85,7 +92,21 @@ int ivfpq_index_info(const ivfpq_index_t* index, int64_t* n, int32_t* d, int32_t
 int ivfpq_index_export(const ivfpq_index_t* index, float* centroids, float* codebooks,
                        int64_t* list_offsets, uint8_t* codes, int64_t* ids);
 
-/* Exponent bias of the IVFPQ_LUT_FP8_E4M4 table dtype for searches on this index (Sec. II gives the
+/* Encoding of one of the two 8-bit table dtypes (lut_dtype = IVFPQ_LUT_FP8_E5M3 or _E4M4) for searches
+ * on this index; takes effect at the next call.  Defaults: bias 15 (e5m3) / 7 (e4m4), nearest, fixed.
+ *   bias            exponent bias B of the format: value(b) = (1 + mant/2^M) * 2^(exp - B).  Moving the
+ *                   bias by s is a scale of the table by 2^s before the encode and 2^-s after the
+ *                   decode; returned distances are always in the data's own units.
+ *                   -96 <= B <= 110 (e5m3), -100 <= B <= 110 (e4m4): every code a normal FP32 number.
+ *   rounding        an ivfpq_fp8_rounding_t
+ *   per_table_bias  0: `bias` for every table.  1: per (query, cluster) table, the bias that puts the
+ *                   binade of the table's largest entry on the format's top binade (with e the FP32
+ *                   exponent of that entry, B = 31 - e for e5m3, 15 - e for e4m4, clamped to the range
+ *                   above); `bias` is ignored.  Costs a second pass over the table's entries. */
+int ivfpq_set_fp8_encoding(ivfpq_index_t* index, int32_t lut_dtype, int32_t bias, int32_t rounding,
+                           int32_t per_table_bias);
+
+/* Shorthand: sets only the exponent bias of the IVFPQ_LUT_FP8_E4M4 table dtype for searches on this index (Sec. II gives the
  * 4+4 split but not its bias): representable table values are 2^-bias .. 1.9375 * 2^(15-bias); what
  * falls outside is clamped to the nearest end.  -100 <= bias <= 110.  Takes effect at the next call. */
 int ivfpq_set_e4m4_bias(ivfpq_index_t* index, int32_t bias);

@@ -2,5 +2,6 @@
 from .binding import (  # noqa: F401
     Index, IvfpqError, lib, EXPORTS, LIB_PATH,
     LUT_FP32, LUT_FP16, LUT_FP8_E5M3, LUT_FP8_E4M4, LUT_NAMES, LUT_BYTES, MAX_K, MAX_PROBES,
+    ROUND_NEAREST, ROUND_TRUNCATE,
     OK, EINVAL, ENOSPACE, EHIP, EUNSUPPORTED, ESTATE,
 )

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(HERE, "libivfpq.so")
 LUT_FP32, LUT_FP16, LUT_FP8_E5M3, LUT_FP8_E4M4 = 0, 1, 2, 3
 LUT_NAMES = {LUT_FP32: "fp32", LUT_FP16: "fp16", LUT_FP8_E5M3: "e5m3", LUT_FP8_E4M4: "e4m4"}
 LUT_BYTES = {LUT_FP32: 4, LUT_FP16: 2, LUT_FP8_E5M3: 1, LUT_FP8_E4M4: 1}
+ROUND_NEAREST, ROUND_TRUNCATE = 0, 1
 MAX_K = 1024
 MAX_PROBES = 1024
 
@@ -27,7 +28,7 @@ OK, EINVAL, ENOSPACE, EHIP, EUNSUPPORTED, ESTATE = 0, -1, -2, -3, -4, -5
 # every symbol include/ivfpq.h declares
 EXPORTS = (
     "ivfpq_build_host", "ivfpq_index_from_arrays", "ivfpq_index_info", "ivfpq_index_export", "ivfpq_free",
-    "ivfpq_set_e4m4_bias",
+    "ivfpq_set_e4m4_bias", "ivfpq_set_fp8_encoding",
     "ivfpq_device_bytes", "ivfpq_upload", "ivfpq_search_workspace_bytes", "ivfpq_search",
     "ivfpq_select_probes", "ivfpq_search_with_probes", "ivfpq_dump_lut", "ivfpq_scan_list",
     "ivfpq_set_stage_timing", "ivfpq_stage_times_ms", "ivfpq_last_error",
@@ -67,6 +68,7 @@ def _declare(L):
     L.ivfpq_index_export.argtypes = [vp, vp, vp, vp, vp, vp]
     L.ivfpq_free.argtypes = [vp]
     L.ivfpq_set_e4m4_bias.argtypes = [vp, i32]
+    L.ivfpq_set_fp8_encoding.argtypes = [vp, i32, i32, i32, i32]
     L.ivfpq_free.restype = None
     L.ivfpq_device_bytes.argtypes = [vp]
     L.ivfpq_device_bytes.restype = sz
@@ -158,6 +160,9 @@ class Index:
         ids = np.empty(self.n, np.int64)
         _check(lib().ivfpq_index_export(self._h, _hp(centroids), _hp(codebooks), _hp(list_offsets), _hp(codes), _hp(ids)))
         return centroids, codebooks, list_offsets, codes, ids
+
+    def ivfpq_set_fp8_encoding(self, lut_dtype: int, bias: int, rounding: int = ROUND_NEAREST, per_table_bias: bool = False):
+        _check(lib().ivfpq_set_fp8_encoding(self._h, int(lut_dtype), int(bias), int(rounding), int(per_table_bias)))
 
     def ivfpq_set_e4m4_bias(self, bias: int):
         _check(lib().ivfpq_set_e4m4_bias(self._h, int(bias)))

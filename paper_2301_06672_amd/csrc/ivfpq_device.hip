@@ -631,43 +631,47 @@ layout_probes_kernel(const uint32_t* __restrict__ probes_in, int nq, int n_probe
 // ================================================================================================
 // Steps 2-4: residual, lookup table in LDS, code scan.
 // ================================================================================================
-template <int LUT> struct LutTraits;
+template <int LUT> struct LutTraits;     // bytes: size of one table entry
 template <> struct LutTraits<IVFPQ_LUT_FP32> { static constexpr int bytes = 4; };
 template <> struct LutTraits<IVFPQ_LUT_FP16> { static constexpr int bytes = 2; };
 template <> struct LutTraits<IVFPQ_LUT_FP8_E5M3> { static constexpr int bytes = 1; };
 template <> struct LutTraits<IVFPQ_LUT_FP8_E4M4> { static constexpr int bytes = 1; };
+// The two 8-bit formats.  shift: how far a code is shifted to line up with the FP32 exponent/mantissa
+// field (23 less the mantissa bits); top_exp: the largest exponent field; bias_min/bias_max: range of
+// the exponent bias for which every code is a finite normal FP32 number.
+template <int LUT> struct Fp8Format {     // e5m3
+    static constexpr int shift = 20, top_exp = 31, bias_min = -96, bias_max = 110;
+};
+template <> struct Fp8Format<IVFPQ_LUT_FP8_E4M4> {
+    static constexpr int shift = 19, top_exp = 15, bias_min = -100, bias_max = 110;
+};
+template <int LUT> constexpr bool kIsFp8 = LUT == IVFPQ_LUT_FP8_E5M3 || LUT == IVFPQ_LUT_FP8_E4M4;
 
-// Constants of the 4+4 split of the sign-less 8-bit float (Sec. II) for a caller-chosen exponent
-// bias B: value(b) = (1 + (b&15)/16) * 2^((b>>4) - B).  Same two conversions as e5m3 with a 19-bit
-// shift: code = (clamp_s32(bits, lo, hi) - sub) >> 19, bits = (code << 19) + lo, where
-// lo = (127 - B) << 23 (the smallest value), hi = lo + (255 << 19) (the largest), sub = lo less half
-// an 8-bit ulp (1 << 18) so that the shift rounds to nearest, ties up.
+// Constants of a sign-less 8-bit float (Sec. II) with M mantissa bits (shift = 23 - M) and exponent
+// bias B: value(b) = (1 + mant/2^M) * 2^(exp - B).  Both conversions are a shift plus a bias
+// adjustment on the FP32 bit pattern:
+//   code = (clamp_s32(bits, lo, hi) - sub) >> shift        bits = (code << shift) + lo
+// lo = (127 - B) << 23 is the smallest value, hi = lo + (255 << shift) the largest; sub = lo less half
+// an 8-bit ulp, so that the shift rounds to nearest with ties up, or lo itself to truncate.  The clamp
+// acts on the pattern as a signed integer: zero and negatives give code 0, +Inf code 255.
+// e5m3 with B = 15: lo = 0x38000000, hi = 0x47F00000, sub = 0x37F80000.
 struct Fp8Params { int lo, hi, sub; };
 
-__host__ __device__ inline Fp8Params e4m4_params(int bias) {
+__host__ __device__ inline Fp8Params fp8_params(int shift, int bias, int truncate) {
     Fp8Params p;
     p.lo = (127 - bias) << 23;
-    p.hi = p.lo + (255 << 19);
-    p.sub = p.lo - (1 << 18);
+    p.hi = p.lo + (255 << shift);
+    p.sub = truncate ? p.lo : p.lo - (1 << (shift - 1));
     return p;
 }
-__device__ inline uint32_t e4m4_from_f32(float x, const Fp8Params p) {
+template <int SHIFT>
+__device__ inline uint32_t fp8_from_f32(float x, const Fp8Params p) {
     int b = __float_as_int(x);
     b = min(max(b, p.lo), p.hi);
-    return (uint32_t)(b - p.sub) >> 19;
+    return (uint32_t)(b - p.sub) >> SHIFT;
 }
-__device__ inline float e4m4_to_f32(uint32_t b, const Fp8Params p) { return __uint_as_float((b << 19) + (uint32_t)p.lo); }
-
-// FP32 -> e5m3 (Sec. II): clamp the bit pattern, as a signed integer, to the codes' range, subtract
-// the exponent-bias difference (112 << 23) less half an 8-bit ulp (so that the shift rounds to
-// nearest, ties up), shift the 8 surviving bits down.
-__device__ inline uint32_t e5m3_from_f32(float x) {
-    int b = __float_as_int(x);
-    b = min(max(b, 0x38000000), 0x47F00000);
-    return (uint32_t)(b - 0x37F80000) >> 20;
-}
-// e5m3 -> FP32 (Sec. II): shift the code into the exponent/mantissa field, add the bias difference.
-__device__ inline float e5m3_to_f32(uint32_t b) { return __uint_as_float((b << 20) + 0x38000000u); }
+template <int SHIFT>
+__device__ inline float fp8_to_f32(uint32_t b, const Fp8Params p) { return __uint_as_float((b << SHIFT) + (uint32_t)p.lo); }
 
 // IEEE half, round to nearest even, saturating at the largest finite half.
 __device__ inline uint32_t half_bits_from_f32(float x) {
@@ -697,23 +701,20 @@ __device__ inline void store4(unsigned char* lut, int e, const float f[4], const
         v.x = half_bits_from_f32(f[0]) | (half_bits_from_f32(f[1]) << 16);
         v.y = half_bits_from_f32(f[2]) | (half_bits_from_f32(f[3]) << 16);
         *reinterpret_cast<uint2*>(lut + (size_t)e * 2) = v;
-    } else if constexpr (LUT == IVFPQ_LUT_FP8_E5M3) {
-        uint32_t v = e5m3_from_f32(f[0]) | (e5m3_from_f32(f[1]) << 8) | (e5m3_from_f32(f[2]) << 16) |
-                     (e5m3_from_f32(f[3]) << 24);
-        *reinterpret_cast<uint32_t*>(lut + e) = v;
     } else {
-        uint32_t v = e4m4_from_f32(f[0], fp8) | (e4m4_from_f32(f[1], fp8) << 8) | (e4m4_from_f32(f[2], fp8) << 16) |
-                     (e4m4_from_f32(f[3], fp8) << 24);
+        constexpr int SH = Fp8Format<LUT>::shift;
+        uint32_t v = fp8_from_f32<SH>(f[0], fp8) | (fp8_from_f32<SH>(f[1], fp8) << 8) |
+                     (fp8_from_f32<SH>(f[2], fp8) << 16) | (fp8_from_f32<SH>(f[3], fp8) << 24);
         *reinterpret_cast<uint32_t*>(lut + e) = v;
     }
 }
 
-// Builds F[pq_dim][ksub] in LDS.  Every thread handles 4 consecutive entries of one sub-space per
-// step (ksub is 16 or 256, so 4 consecutive entries never straddle sub-spaces).
-// codebooks: global [pq_dim][ksub][M]; rq: LDS [pq_dim*M].
-template <int LUT, int M>
-__device__ inline void build_lut(const float* __restrict__ codebooks, const float* rq, int n_entries,
-                                 int bits, int m_runtime, unsigned char* lut, const Fp8Params fp8) {
+// Visits every entry of F[pq_dim][ksub], 4 consecutive entries of one sub-space per call of
+// sink(first entry index, values) (ksub is 16 or 256, so 4 consecutive entries never straddle
+// sub-spaces).  codebooks: global [pq_dim][ksub][M]; rq: LDS [pq_dim*M].
+template <int M, class Sink>
+__device__ __forceinline__ void visit_lut(const float* __restrict__ codebooks, const float* rq, int n_entries,
+                                 int bits, int m_runtime, Sink sink) {
     for (int e = threadIdx.x * 4; e < n_entries; e += blockDim.x * 4) {
         const int j = e >> bits;
         float f[4];
@@ -742,16 +743,15 @@ __device__ inline void build_lut(const float* __restrict__ codebooks, const floa
                 f[u] = acc;
             }
         }
-        store4<LUT>(lut, e, f, fp8);
+        sink(e, f);
     }
 }
 
-// 8-bit codes: a table row has 256 entries = 4 per lane of a wave, so every wave builds whole rows
+// 8-bit codes: a table row has 256 entries = 4 per lane of a wave, so every wave visits whole rows
 // (row index wave-uniform: residual components are read once per row, addresses advance by a
 // constant stride).
-template <int LUT, int M>
-__device__ inline void build_lut_rows256(const float* __restrict__ codebooks, const float* rq, int pq_dim,
-                                         unsigned char* lut, const Fp8Params fp8) {
+template <int M, class Sink>
+__device__ __forceinline__ void visit_lut_rows256(const float* __restrict__ codebooks, const float* rq, int pq_dim, Sink sink) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_waves = blockDim.x >> 6;
@@ -773,38 +773,76 @@ __device__ inline void build_lut_rows256(const float* __restrict__ codebooks, co
         float f[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) f[u] = lut_entry<M>(cbv + u * M, r);
-        store4<LUT>(lut, e, f, fp8);
+        sink(e, f);
         src += src_step;
         e += e_step;
     }
 }
 
-template <int LUT, int BITS>
-__device__ inline void build_lut_any_m(const float* __restrict__ codebooks, const float* rq, int pq_dim,
-                                       int m, unsigned char* lut, const Fp8Params fp8) {
+template <int BITS, class Sink>
+__device__ __forceinline__ void visit_lut_any_m(const float* __restrict__ codebooks, const float* rq, int pq_dim, int m, Sink sink) {
     const int n_entries = pq_dim << BITS;
     if constexpr (BITS == 8) {
         switch (m) {
-            case 1: build_lut_rows256<LUT, 1>(codebooks, rq, pq_dim, lut, fp8); return;
-            case 2: build_lut_rows256<LUT, 2>(codebooks, rq, pq_dim, lut, fp8); return;
-            case 4: build_lut_rows256<LUT, 4>(codebooks, rq, pq_dim, lut, fp8); return;
+            case 1: visit_lut_rows256<1>(codebooks, rq, pq_dim, sink); return;
+            case 2: visit_lut_rows256<2>(codebooks, rq, pq_dim, sink); return;
+            case 4: visit_lut_rows256<4>(codebooks, rq, pq_dim, sink); return;
             default: break;
         }
     }
     switch (m) {
-        case 1: build_lut<LUT, 1>(codebooks, rq, n_entries, BITS, m, lut, fp8); break;
-        case 2: build_lut<LUT, 2>(codebooks, rq, n_entries, BITS, m, lut, fp8); break;
-        case 4: build_lut<LUT, 4>(codebooks, rq, n_entries, BITS, m, lut, fp8); break;
-        default: build_lut<LUT, 0>(codebooks, rq, n_entries, BITS, m, lut, fp8); break;
+        case 1: visit_lut<1>(codebooks, rq, n_entries, BITS, m, sink); break;
+        case 2: visit_lut<2>(codebooks, rq, n_entries, BITS, m, sink); break;
+        case 4: visit_lut<4>(codebooks, rq, n_entries, BITS, m, sink); break;
+        default: visit_lut<0>(codebooks, rq, n_entries, BITS, m, sink); break;
     }
+}
+
+// Encoding of an 8-bit table as the caller configured it: fixed constants, or a bias chosen per table.
+struct Fp8Mode {
+    Fp8Params fixed;     // constants for the configured bias and rounding
+    int truncate;        // rounding of the encode: 0 nearest (ties up), 1 truncate
+    int per_table;       // 1: the bias follows the largest entry of each table
+};
+
+// Step 3: builds F[pq_dim][ksub] in LDS in the table's dtype; rq must be complete (barrier passed).
+// Ends with a barrier.  Returns the constants the 8-bit lookups decode with (workgroup-uniform).
+// Per-table bias (a power-of-two scale of the table, expressed as a shift of the format's exponent
+// bias): a first pass over the entries finds the largest one; with e its FP32 exponent, the bias is
+// top_exp - e, so that the entry's binade becomes the format's top binade; a second pass encodes.
+template <int LUT, int BITS>
+__device__ __forceinline__ Fp8Params stage_table(const float* __restrict__ codebooks, const float* rq, int pq_dim, int m,
+                                        unsigned char* lut, uint32_t* max_slot, const Fp8Mode mode) {
+    Fp8Params fp8 = mode.fixed;
+    if constexpr (kIsFp8<LUT>) {
+        if (mode.per_table) {
+            if (threadIdx.x == 0) *max_slot = 0u;
+            __syncthreads();
+            float mx = 0.f;                       // entries are sums of squares: never negative
+            visit_lut_any_m<BITS>(codebooks, rq, pq_dim, m, [&](int, const float (&f)[4]) {
+                mx = fmaxf(fmaxf(mx, f[0]), fmaxf(f[1], fmaxf(f[2], f[3])));
+            });
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+            if ((threadIdx.x & (kWave - 1)) == 0) atomicMax(max_slot, __float_as_uint(mx));
+            __syncthreads();
+            const int e = (int)(*max_slot >> 23) - 127;
+            int bias = Fp8Format<LUT>::top_exp - e;
+            bias = min(max(bias, Fp8Format<LUT>::bias_min), Fp8Format<LUT>::bias_max);
+            bias = __builtin_amdgcn_readfirstlane(bias);
+            fp8 = fp8_params(Fp8Format<LUT>::shift, bias, mode.truncate);
+        }
+    }
+    visit_lut_any_m<BITS>(codebooks, rq, pq_dim, m, [&](int e, const float (&f)[4]) { store4<LUT>(lut, e, f, fp8); });
+    __syncthreads();
+    return fp8;
 }
 
 template <int LUT>
 __device__ inline float lut_get(const unsigned char* lut, uint32_t idx, const Fp8Params fp8) {
     if constexpr (LUT == IVFPQ_LUT_FP32) return reinterpret_cast<const float*>(lut)[idx];
     else if constexpr (LUT == IVFPQ_LUT_FP16) return __half2float(reinterpret_cast<const __half*>(lut)[idx]);
-    else if constexpr (LUT == IVFPQ_LUT_FP8_E5M3) return e5m3_to_f32(lut[idx]);
-    else return e4m4_to_f32(lut[idx], fp8);
+    else return fp8_to_f32<Fp8Format<LUT>::shift>(lut[idx], fp8);
 }
 
 // adds the table entries selected by the 4 code bytes of `w` (sub-spaces row0.. in ascending order)
@@ -839,7 +877,7 @@ struct ScanArgs {
     const uint32_t* bounds;       // [nq] per-query upper bound of the k-th smallest R (filtered mode)
     uint32_t* counts;             // [nq] survivors appended so far (filtered mode)
     uint32_t* Rpos;               // [nq][stride] row position of each appended survivor (filtered mode)
-    Fp8Params fp8;                // constants of the e4m4 table dtype (unused by the other dtypes)
+    Fp8Mode fp8;                  // encoding of the 8-bit table dtypes (unused by the other two)
     int mode;                     // 1: nearest probe of every query, every R written in place;
                                   // 2: the other probes, only R <= bound appended behind the nearest probe's segment
     float* R;                     // [nq][stride]
@@ -861,8 +899,12 @@ scan_kernel(ScanArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int ksub = 1 << BITS;
     const int n_entries = a.pq_dim * ksub;
+    // LDS: table | residual (d floats) | 16 bytes (largest entry, per-table bias) | survivor staging
     unsigned char* lut = smem;
     float* rq = reinterpret_cast<float*>(smem + (((size_t)n_entries * LutTraits<LUT>::bytes + 15) & ~(size_t)15));
+    unsigned char* after_rq = reinterpret_cast<unsigned char*>(rq) + (((size_t)a.d * 4 + 15) & ~(size_t)15);
+    uint32_t* max_slot = reinterpret_cast<uint32_t*>(after_rq);
+    Fp8Params fp8 = a.fp8.fixed;
 
     int q, l;
     uint32_t len, first_group, row_pos0 = 0;
@@ -895,8 +937,7 @@ scan_kernel(ScanArgs a) {
     // filtered mode: every wave stages its survivors in a private LDS buffer and appends them to the
     // query's row with one global atomic per flush (the counter of a query is shared by all the
     // workgroups of that query: one atomic per 64-vector group would serialise on it)
-    uint2* stage = reinterpret_cast<uint2*>(reinterpret_cast<unsigned char*>(rq) + (((size_t)a.d * 4 + 15) & ~(size_t)15))
-                   + (size_t)(threadIdx.x >> 6) * kStageCap;
+    uint2* stage = reinterpret_cast<uint2*>(after_rq + 16) + (size_t)(threadIdx.x >> 6) * kStageCap;
     uint32_t staged = 0;       // wave-uniform
     const int n_groups = (int)((len + 63u) >> 6);
     const int lane = threadIdx.x & (kWave - 1);
@@ -924,9 +965,9 @@ scan_kernel(ScanArgs a) {
                 const uint32_t w[4] = {buf[c].x, buf[c].y, buf[c].z, buf[c].w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    acc = add_word<LUT, BITS>(acc, lut, w[i], (c * 4 + i) * ROWS_PER_WORD, a.fp8);
+                    acc = add_word<LUT, BITS>(acc, lut, w[i], (c * 4 + i) * ROWS_PER_WORD, fp8);
             } else {
-                acc = add_word<LUT, BITS>(acc, lut, buf[c], c * ROWS_PER_WORD, a.fp8);
+                acc = add_word<LUT, BITS>(acc, lut, buf[c], c * ROWS_PER_WORD, fp8);
             }
         }
         return acc;
@@ -974,8 +1015,7 @@ scan_kernel(ScanArgs a) {
         rq[t] = a.queries[(size_t)q * a.d + t] - a.centroids[(size_t)l * a.d + t];
     __syncthreads();
     // step 3: the table
-    build_lut_any_m<LUT, BITS>(a.codebooks, rq, a.pq_dim, a.m, lut, a.fp8);
-    __syncthreads();
+    fp8 = stage_table<LUT, BITS>(a.codebooks, rq, a.pq_dim, a.m, lut, max_slot, a.fp8);
 
     // step 4: Eq. (1), one lane per coded vector; the next group is loaded into the other register
     // buffer while the current one is looked up
@@ -994,7 +1034,7 @@ scan_kernel(ScanArgs a) {
             float acc = 0.f;
             for (int c = 0; c < nch; ++c) {
                 uint32_t w = reinterpret_cast<const uint32_t*>(codes_l)[((size_t)g * nch + c) * 64 + lane];
-                acc = add_word<LUT, BITS>(acc, lut, w, c * ROWS_PER_WORD, a.fp8);
+                acc = add_word<LUT, BITS>(acc, lut, w, c * ROWS_PER_WORD, fp8);
             }
             store_R(g, acc);
         }
@@ -1006,18 +1046,18 @@ scan_kernel(ScanArgs a) {
 template <int LUT>
 __global__ void __launch_bounds__(256)
 dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centroid,
-                const float* __restrict__ codebooks, int d, int pq_dim, int m, int bits, Fp8Params fp8,
+                const float* __restrict__ codebooks, int d, int pq_dim, int m, int bits, Fp8Mode fp8,
                 unsigned char* __restrict__ out) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int n_entries = pq_dim << bits;
     const size_t lut_bytes = (size_t)n_entries * LutTraits<LUT>::bytes;
     unsigned char* lut = smem;
     float* rq = reinterpret_cast<float*>(smem + ((lut_bytes + 15) & ~(size_t)15));
+    uint32_t* max_slot = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(rq) + (((size_t)d * 4 + 15) & ~(size_t)15));
     for (int t = threadIdx.x; t < d; t += blockDim.x) rq[t] = query[t] - centroid[t];
     __syncthreads();
-    if (bits == 8) build_lut_any_m<LUT, 8>(codebooks, rq, pq_dim, m, lut, fp8);
-    else build_lut_any_m<LUT, 4>(codebooks, rq, pq_dim, m, lut, fp8);
-    __syncthreads();
+    if (bits == 8) (void)stage_table<LUT, 8>(codebooks, rq, pq_dim, m, lut, max_slot, fp8);
+    else (void)stage_table<LUT, 4>(codebooks, rq, pq_dim, m, lut, max_slot, fp8);
     for (size_t i = threadIdx.x; i < lut_bytes / 4; i += blockDim.x)
         reinterpret_cast<uint32_t*>(out)[i] = reinterpret_cast<const uint32_t*>(lut)[i];
 }
@@ -1179,7 +1219,7 @@ size_t lut_elem_bytes(int lut_dtype) { return lut_dtype == IVFPQ_LUT_FP32 ? 4 : 
 
 size_t scan_lds_bytes(const ivfpq_index* idx, int lut_dtype) {
     size_t lut = (size_t)idx->pq_dim * idx->ksub() * lut_elem_bytes(lut_dtype);
-    return ((lut + 15) & ~(size_t)15) + (((size_t)idx->d * 4 + 15) & ~(size_t)15);
+    return ((lut + 15) & ~(size_t)15) + (((size_t)idx->d * 4 + 15) & ~(size_t)15) + 16;
 }
 // plus the per-wave survivor staging of the filtered scan
 size_t scan_lds_bytes_staged(const ivfpq_index* idx, int lut_dtype, int threads) {
@@ -1256,7 +1296,19 @@ int launch_scan(const ivfpq_index* idx, ScanArgs a, int lut_dtype, dim3 grid, hi
     }
 }
 
-ScanArgs base_scan_args(const ivfpq_index* idx) {
+Fp8Mode fp8_mode(const ivfpq_index* idx, int lut_dtype) {
+    Fp8Mode m{};
+    if (lut_dtype == IVFPQ_LUT_FP8_E5M3 || lut_dtype == IVFPQ_LUT_FP8_E4M4) {
+        const ivfpq::Fp8Options& o = idx->fp8_opt[lut_dtype - IVFPQ_LUT_FP8_E5M3];
+        m.fixed = fp8_params(lut_dtype == IVFPQ_LUT_FP8_E5M3 ? Fp8Format<IVFPQ_LUT_FP8_E5M3>::shift : Fp8Format<IVFPQ_LUT_FP8_E4M4>::shift,
+                             o.bias, o.truncate);
+        m.truncate = o.truncate;
+        m.per_table = o.per_table;
+    }
+    return m;
+}
+
+ScanArgs base_scan_args(const ivfpq_index* idx, int lut_dtype) {
     ScanArgs a{};
     a.centroids = idx->dev.centroids;
     a.codebooks = idx->dev.codebooks;
@@ -1265,7 +1317,7 @@ ScanArgs base_scan_args(const ivfpq_index* idx) {
     a.codes = idx->dev.codes;
     a.d = idx->d; a.pq_dim = idx->pq_dim; a.m = idx->m(); a.bits = idx->pq_bits;
     a.n_lists = idx->n_lists;
-    a.fp8 = e4m4_params(idx->e4m4_bias);
+    a.fp8 = fp8_mode(idx, lut_dtype);
     a.single_list = -1;
     return a;
 }
@@ -1348,7 +1400,7 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         StageTimer t1(idx, st, 1);
         if (int s = t1.begin()) return s;
         // nearest probe of every query first: its R values give the bound that filters the rest
-        ScanArgs a = base_scan_args(idx);
+        ScanArgs a = base_scan_args(idx, lut_dtype);
         a.queries = qt; a.pairs = w_pairs; a.R = w_R; a.stride = plan.stride;
         a.n_probes = n_probes; a.bounds = w_bounds; a.counts = w_counts; a.Rpos = w_Rpos;
         a.mode = 1;
@@ -1536,7 +1588,7 @@ int ivfpq_dump_lut(const ivfpq_index_t* idx, const float* d_query, uint32_t list
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(kernel, dim3(1), dim3(256), lds, st, d_query, centroid, idx->dev.codebooks, idx->d,
-                           idx->pq_dim, idx->m(), idx->pq_bits, e4m4_params(idx->e4m4_bias), (unsigned char*)d_lut_out);
+                           idx->pq_dim, idx->m(), idx->pq_bits, fp8_mode(idx, lut_dtype), (unsigned char*)d_lut_out);
         HIP_TRY(hipGetLastError());
         return IVFPQ_OK;
     };
@@ -1556,7 +1608,7 @@ int ivfpq_scan_list(const ivfpq_index_t* idx, const float* d_query, uint32_t lis
     if (int s = check_device(idx)) return s;
     if (idx->list_offsets[list_id + 1] == idx->list_offsets[list_id]) return IVFPQ_OK;
     if (!d_R_out) return fail(IVFPQ_EINVAL, "ivfpq_scan_list: null output");
-    ScanArgs a = base_scan_args(idx);
+    ScanArgs a = base_scan_args(idx, lut_dtype);
     a.queries = d_query; a.R = d_R_out; a.single_list = (int)list_id; a.n_probes = 1;
     return launch_scan(idx, a, lut_dtype, dim3(1), (hipStream_t)hip_stream);
 }

@@ -340,11 +340,26 @@ int ivfpq_index_export(const ivfpq_index_t* index, float* centroids, float* code
     return IVFPQ_OK;
 }
 
+int ivfpq_set_fp8_encoding(ivfpq_index_t* index, int32_t lut_dtype, int32_t bias, int32_t rounding,
+                           int32_t per_table_bias) {
+    if (!index) return fail(IVFPQ_EINVAL, "ivfpq_set_fp8_encoding: null index");
+    if (lut_dtype != IVFPQ_LUT_FP8_E5M3 && lut_dtype != IVFPQ_LUT_FP8_E4M4)
+        return fail(IVFPQ_EINVAL, "lut_dtype %d is not an 8-bit table dtype", lut_dtype);
+    // every code must stay a finite, normal FP32 number: 1 <= 127 - bias and 127 - bias + (top exponent) <= 254
+    const int lo = lut_dtype == IVFPQ_LUT_FP8_E5M3 ? -96 : -100, hi = 110;
+    if (bias < lo || bias > hi)
+        return fail(IVFPQ_EINVAL, "%s bias %d outside [%d, %d]", lut_dtype == IVFPQ_LUT_FP8_E5M3 ? "e5m3" : "e4m4", bias, lo, hi);
+    if (rounding != IVFPQ_ROUND_NEAREST && rounding != IVFPQ_ROUND_TRUNCATE)
+        return fail(IVFPQ_EINVAL, "unknown rounding %d", rounding);
+    if (per_table_bias != 0 && per_table_bias != 1) return fail(IVFPQ_EINVAL, "per_table_bias=%d (0 or 1)", per_table_bias);
+    index->fp8_opt[lut_dtype - IVFPQ_LUT_FP8_E5M3] = {bias, rounding, per_table_bias};
+    return IVFPQ_OK;
+}
+
 int ivfpq_set_e4m4_bias(ivfpq_index_t* index, int32_t bias) {
     if (!index) return fail(IVFPQ_EINVAL, "ivfpq_set_e4m4_bias: null index");
-    if (bias < -100 || bias > 110) return fail(IVFPQ_EINVAL, "e4m4 bias %d outside [-100, 110]", bias);
-    index->e4m4_bias = bias;
-    return IVFPQ_OK;
+    const ivfpq::Fp8Options& o = index->fp8_opt[1];
+    return ivfpq_set_fp8_encoding(index, IVFPQ_LUT_FP8_E4M4, bias, o.truncate, o.per_table);
 }
 
 void ivfpq_free(ivfpq_index_t* index) {

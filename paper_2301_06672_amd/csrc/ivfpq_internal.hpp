@@ -11,6 +11,13 @@
 
 namespace ivfpq {
 
+// Encoding options of one 8-bit table dtype (ivfpq_set_fp8_encoding).
+struct Fp8Options {
+    int32_t bias;        // exponent bias of the format
+    int32_t truncate;    // 0: round to nearest, ties up; 1: truncate
+    int32_t per_table;   // 1: the bias is chosen per (query, cluster) table from its largest entry
+};
+
 // Device image of an index.  All pointers point into the single buffer the caller handed to
 // ivfpq_upload; the library owns none of them.
 struct DeviceImage {
@@ -42,7 +49,7 @@ struct ivfpq_index {
     std::vector<uint32_t> sorted_padded_sizes;  // padded list lengths, descending
 
     ivfpq::DeviceImage dev;
-    int32_t e4m4_bias = 7;              // exponent bias of the e4m4 table dtype (ivfpq_set_e4m4_bias)
+    ivfpq::Fp8Options fp8_opt[2] = {{15, 0, 0}, {7, 0, 0}};   // e5m3, e4m4 (ivfpq_set_fp8_encoding)
     float centroid_norm_max = 0.f;      // largest squared centroid norm (set by ivfpq_upload)
 
     // stage timing (hipEvent_t kept as void* so this header stays free of HIP types)

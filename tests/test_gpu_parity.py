@@ -107,6 +107,69 @@ def test_e4m4_other_shapes(P):
         assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"e4m4 d={d} p={pq_bits}")
 
 
+FP8 = {oracle.LUT_E5M3: "e5m3", oracle.LUT_E4M4: "e4m4"}
+
+
+def _reset_fp8(P, gidx):
+    gidx.ivfpq_set_fp8_encoding(P.LUT_FP8_E5M3, 15)
+    gidx.ivfpq_set_fp8_encoding(P.LUT_FP8_E4M4, 7)
+
+
+@pytest.mark.parametrize("dtype", list(FP8))
+@pytest.mark.parametrize("bias,trunc,per_table", [(15, True, False), (22, False, False), (3, True, False),
+                                                  (0, False, True), (0, True, True)])
+def test_fp8_encoding_options_lut_bytes_and_search(P, tiny, dtype, bias, trunc, per_table):
+    # general exponent bias, truncating encode and per-table bias of both 8-bit formats: the table
+    # bytes are identical to the oracle's and the search returns what the oracle returns
+    w, data, oidx, gidx = tiny
+    gidx.ivfpq_set_fp8_encoding(dtype, bias, P.ROUND_TRUNCATE if trunc else P.ROUND_NEAREST, per_table)
+    try:
+        q = si.queries(w, 40)
+        kw = dict(truncate=trunc, bias=bias, per_table=per_table)
+        for qi, l in ((2, 3), (5, 40), (11, 63)):
+            _step(f"{FP8[dtype]} {kw} dump_lut q={qi} list={l}")
+            got = gidx.ivfpq_dump_lut(q[qi], l, dtype).cpu().numpy()
+            want, _ = oracle.lut_store(oracle.lut_f32(oidx, q[qi], l), dtype, **kw)
+            np.testing.assert_array_equal(got, want)
+        _step(f"{FP8[dtype]} {kw} search")
+        ids_g, d_g = gidx.ivfpq_search(q, w.n_probes, w.k, dtype)
+        probes, _ = gidx.ivfpq_select_probes(q, w.n_probes)
+        ids_o, d_o = oracle.search(oidx, q, w.n_probes, w.k, dtype, probes=probes.cpu().numpy().view(np.uint32), **kw)
+        assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"{FP8[dtype]} {kw}")
+    finally:
+        _reset_fp8(P, gidx)
+
+
+@pytest.mark.parametrize("d,pq_dim,pq_bits", [(32, 32, 8), (48, 16, 8), (24, 8, 4), (128, 64, 4), (96, 48, 8)])
+def test_per_table_bias_shapes_and_ranges(P, d, pq_dim, pq_bits):
+    # every table-building code path (sub-vector lengths 1, 2, 3, 4; 4- and 8-bit codes) at value scales
+    # from far below to far above the fixed formats' ranges; with a per-table bias the bytes follow the scale
+    ref = {}
+    for scale in (2.0 ** -30, 1.0, 2.0 ** 20):
+        oidx = oracle.make_index(d, 3, pq_dim, pq_bits, *si.random_index_arrays(300, d, 3, pq_dim, pq_bits, salt=100 + d + pq_dim))
+        s = np.float32(scale)
+        oidx_s = oracle.make_index(d, 3, pq_dim, pq_bits, oidx.centroids * s, oidx.codebooks * s, oidx.list_offsets,
+                                   oidx.codes, oidx.ids)
+        gidx = to_library(P, oidx_s)
+        q = (np.random.default_rng(d).standard_normal(d)).astype(np.float32) * s
+        F = oracle.lut_f32(oidx_s, q, 1)
+        for dtype in FP8:
+            for trunc in (False, True):
+                gidx.ivfpq_set_fp8_encoding(dtype, 0, int(trunc), True)
+                _step(f"per-table d={d} s={pq_dim} p={pq_bits} scale={scale} {FP8[dtype]} trunc={trunc}")
+                got = gidx.ivfpq_dump_lut(q, 1, dtype).cpu().numpy()
+                want, _ = oracle.lut_store(F, dtype, truncate=trunc, per_table=True)
+                np.testing.assert_array_equal(got, want)
+                key = (dtype, trunc)
+                if key in ref:
+                    np.testing.assert_array_equal(got, ref[key])     # scale invariance, on the GPU side too
+                ref[key] = got
+                R_g = gidx.ivfpq_scan_list(q, 1, dtype, int(oidx.list_offsets[2] - oidx.list_offsets[1])).cpu().numpy()
+                _, dec = oracle.lut_store(F, dtype, truncate=trunc, per_table=True)
+                R_o, _ = oracle.scan_list(oidx_s, dec, 1)
+                np.testing.assert_allclose(R_g, R_o, rtol=RTOL, atol=0)
+
+
 # ---------------------------------------------------------------- Eq. (1) over one cluster (step 4)
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -309,6 +372,11 @@ def test_error_paths(P, tiny):
     with pytest.raises(P.IvfpqError) as e:
         gidx.ivfpq_set_e4m4_bias(500)
     assert e.value.status == P.EINVAL
+    for bad in ((P.LUT_FP16, 15, 0, 0), (P.LUT_FP8_E5M3, -97, 0, 0), (P.LUT_FP8_E5M3, 111, 0, 0),
+                (P.LUT_FP8_E4M4, 7, 2, 0), (P.LUT_FP8_E4M4, 7, 0, 3)):
+        with pytest.raises(P.IvfpqError) as e:
+            gidx.ivfpq_set_fp8_encoding(*bad)
+        assert e.value.status == P.EINVAL
     # a workspace that is too small is refused before anything is launched
     import ctypes
     ids = torch.empty((4, 10), dtype=torch.int64, device="cuda")

@@ -85,6 +85,19 @@ def test_bad_list_offsets_rejected(P):
         P.Index.ivfpq_index_from_arrays(8, 3, 4, 8, cent, cb, bad, codes, ids)
 
 
+def test_fp8_encoding_setter_validates(P):
+    idx = P.Index.ivfpq_index_from_arrays(32, 9, 16, 4, *si.random_index_arrays(100, 32, 9, 16, 4, salt=2))
+    idx.ivfpq_set_fp8_encoding(P.LUT_FP8_E5M3, -96, P.ROUND_TRUNCATE, True)
+    idx.ivfpq_set_fp8_encoding(P.LUT_FP8_E4M4, 110)
+    idx.ivfpq_set_e4m4_bias(-100)
+    for bad, needle in (((P.LUT_FP32, 15, 0, 0), "8-bit"), ((P.LUT_FP8_E5M3, -97, 0, 0), "outside"),
+                        ((P.LUT_FP8_E4M4, 111, 0, 0), "outside"), ((P.LUT_FP8_E4M4, 7, 2, 0), "rounding"),
+                        ((P.LUT_FP8_E5M3, 15, 0, 2), "per_table")):
+        with pytest.raises(P.IvfpqError) as e:
+            idx.ivfpq_set_fp8_encoding(*bad)
+        assert e.value.status == P.EINVAL and needle in str(e.value)
+
+
 def test_search_without_device_image_is_a_state_error(P):
     arrays = si.random_index_arrays(100, 8, 3, 4, 8, salt=3)
     idx = P.Index.ivfpq_index_from_arrays(8, 3, 4, 8, *arrays)
