@@ -72,6 +72,36 @@ enum { IVFPQ_MAX_K = 1024, IVFPQ_MAX_PROBES = 1024 };
 int ivfpq_build_host(const float* data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim,
                      int32_t pq_bits, int32_t kmeans_iters, uint64_t seed, ivfpq_index_t** out);
 
+/* The same four build steps on the GPU (current device).  d_data: device [n][d] fp32, n < 2^31.
+ * Every decision (nearest cluster centre, nearest codeword) is the arg-min of float64 squared
+ * distances, ties to the lower index; every centre is the float64 mean of its members summed in
+ * ascending row order, rounded to fp32 once; an empty cluster keeps its centre.
+ * The random draws are inputs (host arrays; each may be NULL, then it is drawn from `seed` as
+ * ivfpq_build_host does):
+ *   coarse_train_rows [n_coarse_train]  rows of d_data the cluster k-means trains on
+ *                                       (NULL: <= 256 rows per list at a fixed stride)
+ *   coarse_init_rows  [n_lists]         positions in that training set whose rows start the k-means
+ *   pq_train_rows     [n_pq_train]      rows of d_data whose residuals train the codebooks
+ *                                       (NULL: <= 262144 rows at a fixed stride); n_pq_train * pq_dim < 2^32
+ *   pq_init_rows      [pq_dim][2^pq_bits]  positions in that training set, per sub-space
+ * d_workspace: device scratch of >= ivfpq_build_device_workspace_bytes(...) (pass the two counts, or 0
+ * for the defaults), 256-byte aligned.  Synchronises the stream before it returns; the resulting handle
+ * holds the logical arrays on the host, as after ivfpq_build_host (call ivfpq_upload next). */
+size_t ivfpq_build_device_workspace_bytes(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,
+                                          int64_t n_coarse_train, int64_t n_pq_train);
+int ivfpq_build_device(const float* d_data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,
+                       int32_t kmeans_iters, const int64_t* coarse_train_rows, int64_t n_coarse_train,
+                       const int64_t* coarse_init_rows, const int64_t* pq_train_rows, int64_t n_pq_train,
+                       const int64_t* pq_init_rows, uint64_t seed, void* d_workspace, size_t workspace_bytes,
+                       void* hip_stream, ivfpq_index_t** out);
+
+/* Build step 1's assignment alone, for inspection: d_labels[i] (device, int32) = the centre nearest to
+ * row i of d_rows (device [n_rows][d]) among d_centres (device [n_centres][d]), decided as above.
+ * d_workspace >= ivfpq_assign_device_workspace_bytes(n_rows, n_centres).  Asynchronous. */
+size_t ivfpq_assign_device_workspace_bytes(int64_t n_rows, int32_t n_centres);
+int ivfpq_assign_device(const float* d_rows, int64_t n_rows, int32_t d, const float* d_centres, int32_t n_centres,
+                        int32_t* d_labels, void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Imports the logical saved index (Sec. I-C build step 4).  All host pointers; the library copies.
  *   centroids    [n_lists][d] f32
  *   codebooks    [pq_dim][2^pq_bits][d/pq_dim] f32

@@ -27,7 +27,8 @@ OK, EINVAL, ENOSPACE, EHIP, EUNSUPPORTED, ESTATE = 0, -1, -2, -3, -4, -5
 
 # every symbol include/ivfpq.h declares
 EXPORTS = (
-    "ivfpq_build_host", "ivfpq_index_from_arrays", "ivfpq_index_info", "ivfpq_index_export", "ivfpq_free",
+    "ivfpq_build_host", "ivfpq_build_device", "ivfpq_build_device_workspace_bytes", "ivfpq_assign_device",
+    "ivfpq_assign_device_workspace_bytes", "ivfpq_index_from_arrays", "ivfpq_index_info", "ivfpq_index_export", "ivfpq_free",
     "ivfpq_set_e4m4_bias", "ivfpq_set_fp8_encoding",
     "ivfpq_device_bytes", "ivfpq_upload", "ivfpq_search_workspace_bytes", "ivfpq_search",
     "ivfpq_select_probes", "ivfpq_search_with_probes", "ivfpq_dump_lut", "ivfpq_scan_list",
@@ -63,6 +64,12 @@ def _declare(L):
     vp, i64, i32, u32, u64, sz = c.c_void_p, c.c_int64, c.c_int32, c.c_uint32, c.c_uint64, c.c_size_t
     pp = c.POINTER(c.c_void_p)
     L.ivfpq_build_host.argtypes = [vp, i64, i32, i32, i32, i32, i32, u64, pp]
+    L.ivfpq_build_device_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i64, i64]
+    L.ivfpq_build_device_workspace_bytes.restype = sz
+    L.ivfpq_build_device.argtypes = [vp, i64, i32, i32, i32, i32, i32, vp, i64, vp, vp, i64, vp, u64, vp, sz, vp, pp]
+    L.ivfpq_assign_device_workspace_bytes.argtypes = [i64, i32]
+    L.ivfpq_assign_device_workspace_bytes.restype = sz
+    L.ivfpq_assign_device.argtypes = [vp, i64, i32, vp, i32, vp, vp, sz, vp]
     L.ivfpq_index_from_arrays.argtypes = [i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, pp]
     L.ivfpq_index_info.argtypes = [vp, c.POINTER(i64), c.POINTER(i32), c.POINTER(i32), c.POINTER(i32), c.POINTER(i32)]
     L.ivfpq_index_export.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -117,6 +124,19 @@ def _dev_f32(x) -> torch.Tensor:
     return torch.from_numpy(_np(x, np.float32)).cuda()
 
 
+def ivfpq_assign_device(rows, centres) -> torch.Tensor:
+    """-> int32 CUDA tensor: the nearest centre of every row (k-means assignment step)."""
+    x, c = _dev_f32(rows), _dev_f32(centres)
+    assert x.shape[1] == c.shape[1]
+    need = lib().ivfpq_assign_device_workspace_bytes(int(x.shape[0]), int(c.shape[0]))
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    labels = torch.empty(int(x.shape[0]), dtype=torch.int32, device="cuda")
+    _check(lib().ivfpq_assign_device(_dp(x), int(x.shape[0]), int(x.shape[1]), _dp(c), int(c.shape[0]), _dp(labels),
+                                     _dp(ws), need, _stream()))
+    torch.cuda.current_stream().synchronize()
+    return labels
+
+
 class Index:
     """Owns one ivfpq_index_t handle plus the torch tensors that back its device image and scratch."""
 
@@ -135,6 +155,32 @@ class Index:
         h = ctypes.c_void_p()
         _check(lib().ivfpq_build_host(_hp(data), data.shape[0], data.shape[1], n_lists, pq_dim, pq_bits,
                                       kmeans_iters, seed, ctypes.byref(h)))
+        return Index(h)
+
+    @staticmethod
+    def ivfpq_build_device(data, n_lists: int, pq_dim: int, pq_bits: int, kmeans_iters: int = 10, seed: int = 0,
+                           coarse_train_rows=None, coarse_init_rows=None, pq_train_rows=None,
+                           pq_init_rows=None) -> "Index":
+        """data: a CUDA tensor or a numpy array (copied to the device) [n][d] fp32."""
+        x = _dev_f32(data)
+        n, d = int(x.shape[0]), int(x.shape[1])
+        opt = lambda a: None if a is None else _np(a, np.int64)
+        ctr, cir, ptr, pir = opt(coarse_train_rows), opt(coarse_init_rows), opt(pq_train_rows), opt(pq_init_rows)
+        n_ct = 0 if ctr is None else int(ctr.size)
+        n_pt = 0 if ptr is None else int(ptr.size)
+        if cir is not None:
+            assert cir.size == n_lists
+        if pir is not None:
+            assert pir.size == pq_dim * (1 << pq_bits)
+        need = lib().ivfpq_build_device_workspace_bytes(n, d, n_lists, pq_dim, pq_bits, n_ct, n_pt)
+        if need == 0:
+            raise IvfpqError(EINVAL, lib().ivfpq_last_error().decode("utf-8", "replace"))
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        h = ctypes.c_void_p()
+        hp = lambda a: None if a is None else _hp(a)
+        _check(lib().ivfpq_build_device(_dp(x), n, d, n_lists, pq_dim, pq_bits, kmeans_iters, hp(ctr), n_ct, hp(cir),
+                                        hp(ptr), n_pt, hp(pir), seed, _dp(ws), need, _stream(), ctypes.byref(h)))
+        del ws
         return Index(h)
 
     @staticmethod

@@ -34,10 +34,13 @@ def build(verbose: bool = False, extra_hip_flags=()) -> str:
     obj_dir = os.path.join(HERE, "_build")
     os.makedirs(obj_dir, exist_ok=True)
     host_o = os.path.join(obj_dir, "ivfpq_host.o")
-    dev_o = os.path.join(obj_dir, "ivfpq_device.o")
     _run(["g++", *HOST_FLAGS, "-c", os.path.join(CSRC, "ivfpq_host.cpp"), "-o", host_o], verbose)
-    _run([HIPCC, *HIP_FLAGS, *extra_hip_flags, "-c", os.path.join(CSRC, "ivfpq_device.hip"), "-o", dev_o], verbose)
-    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-o", LIB_PATH, host_o, dev_o, "-lgomp"], verbose)
+    dev_objs = []
+    for name in ("ivfpq_device", "ivfpq_build"):       # search kernels; index construction kernels
+        obj = os.path.join(obj_dir, name + ".o")
+        _run([HIPCC, *HIP_FLAGS, *extra_hip_flags, "-c", os.path.join(CSRC, name + ".hip"), "-o", obj], verbose)
+        dev_objs.append(obj)
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-o", LIB_PATH, host_o, *dev_objs, "-lgomp"], verbose)
     return LIB_PATH
 
 

@@ -58,23 +58,41 @@ void finish_import(ivfpq_index* idx) {
     std::sort(idx->sorted_padded_sizes.begin(), idx->sorted_padded_sizes.end(), std::greater<uint32_t>());
 }
 
+// Seeded row draws shared by the host and the device builder.
+// `k` start rows out of `n`: distinct when n >= k, cycling otherwise
+std::vector<int64_t> draw_rows(SplitMix64& rng, int64_t n, int k) {
+    std::vector<int64_t> rows;
+    rows.reserve(k);
+    if (n >= k) {
+        std::unordered_set<int64_t> seen;
+        while ((int)rows.size() < k) {
+            int64_t r = (int64_t)rng.below((uint64_t)n);
+            if (seen.insert(r).second) rows.push_back(r);
+        }
+        std::sort(rows.begin(), rows.end());
+    } else {
+        for (int c = 0; c < k; ++c) rows.push_back(n > 0 ? c % n : 0);
+    }
+    return rows;
+}
+
+std::vector<int64_t> stride_rows(int64_t n, int64_t limit) {
+    std::vector<int64_t> rows;
+    if (n <= limit) {
+        rows.resize(n);
+        std::iota(rows.begin(), rows.end(), (int64_t)0);
+    } else {
+        rows.resize(limit);
+        for (int64_t i = 0; i < limit; ++i) rows[i] = (int64_t)(((__int128)i * n) / limit);
+    }
+    return rows;
+}
+
 // ------------------------------------------------------------------------------------------------
 // k-means used by the builder.  fp32, distance ranking by |c|^2 - 2 x.c (the |x|^2 term does not
 // change the arg-min); ties go to the lower centre index.
 // ------------------------------------------------------------------------------------------------
 namespace {
-
-struct SplitMix64 {
-    uint64_t s;
-    explicit SplitMix64(uint64_t seed) : s(seed) {}
-    uint64_t next() {
-        uint64_t z = (s += 0x9E3779B97F4A7C15ull);
-        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-        return z ^ (z >> 31);
-    }
-    uint64_t below(uint64_t bound) { return next() % bound; }
-};
 
 // labels[i] = nearest centre of row i.  x: [n][dim], centres: [k][dim].
 void assign_rows(const float* x, int64_t n, int dim, const float* centres, int k, int32_t* labels) {
@@ -163,35 +181,6 @@ void lloyd(const float* x, int64_t n, int dim, int k, int iters, float* centres)
             }
         }
     }
-}
-
-// `k` start rows out of `n`: distinct when n >= k, cycling otherwise
-std::vector<int64_t> draw_rows(SplitMix64& rng, int64_t n, int k) {
-    std::vector<int64_t> rows;
-    rows.reserve(k);
-    if (n >= k) {
-        std::unordered_set<int64_t> seen;
-        while ((int)rows.size() < k) {
-            int64_t r = (int64_t)rng.below((uint64_t)n);
-            if (seen.insert(r).second) rows.push_back(r);
-        }
-        std::sort(rows.begin(), rows.end());
-    } else {
-        for (int c = 0; c < k; ++c) rows.push_back(n > 0 ? c % n : 0);
-    }
-    return rows;
-}
-
-std::vector<int64_t> stride_rows(int64_t n, int64_t limit) {
-    std::vector<int64_t> rows;
-    if (n <= limit) {
-        rows.resize(n);
-        std::iota(rows.begin(), rows.end(), (int64_t)0);
-    } else {
-        rows.resize(limit);
-        for (int64_t i = 0; i < limit; ++i) rows[i] = (int64_t)(((__int128)i * n) / limit);
-    }
-    return rows;
 }
 
 }  // namespace

@@ -83,6 +83,24 @@ int check_shape(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t p
 // fills the derived fields after the logical arrays are in place
 void finish_import(ivfpq_index* idx);
 
+// SplitMix64: the generator behind every seeded draw of the builders
+struct SplitMix64 {
+    uint64_t s;
+    explicit SplitMix64(uint64_t seed) : s(seed) {}
+    uint64_t next() {
+        uint64_t z = (s += 0x9E3779B97F4A7C15ull);
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    }
+    uint64_t below(uint64_t bound) { return next() % bound; }
+};
+
+// `k` start rows out of `n` (ascending): distinct when n >= k, cycling otherwise
+std::vector<int64_t> draw_rows(SplitMix64& rng, int64_t n, int k);
+// at most `limit` rows of [0, n) at a fixed stride (all rows when n <= limit)
+std::vector<int64_t> stride_rows(int64_t n, int64_t limit);
+
 // called by ivfpq_free before the handle goes away (destroys HIP events); defined in the device half
 void release_device_state(ivfpq_index* idx);
 

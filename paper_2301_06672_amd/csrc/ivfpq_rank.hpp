@@ -1,0 +1,151 @@
+// Device code shared by the search kernels and the index builder: HIP error macro, small constants,
+// order-preserving float keys and the fp32 MFMA ranking GEMM |c|^2 - 2 x.c.
+// Included by .hip translation units only; everything has internal linkage.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "ivfpq_internal.hpp"
+
+#define HIP_TRY(expr)                                                                               \
+    do {                                                                                            \
+        hipError_t e_ = (expr);                                                                     \
+        if (e_ != hipSuccess)                                                                       \
+            return ivfpq::fail(IVFPQ_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+namespace {
+
+using ivfpq::fail;
+
+constexpr int kWave = 64;
+constexpr size_t kLdsBytes = 160 * 1024;       // LDS of one gfx950 compute unit
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+
+// ================================================================================================
+// Step 1a: coarse ranking values on the matrix cores.
+// For ranking the clusters of one query |q - c|^2 can be replaced by a(q, c) = |c|^2 - 2 q.c (the
+// |q|^2 term is common).  The dot products are one fp32 GEMM: v_mfma_f32_32x32x2_f32, a tile of
+// 128 queries x 128 clusters (or 64 x 64 for small problems) per 256-thread workgroup, operands
+// staged through LDS in slices of 16 components.  The expanded form cancels, so these values only
+// SHORT-LIST clusters: the selection kernel below recomputes the short-listed distances exactly
+// (direct form) and bounds the error of a() rigorously, so the probe list is the exact one.
+// Values are stored as order-preserving unsigned keys (a() can be negative).
+// ================================================================================================
+constexpr int CK = 16;   // components per LDS slice
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__device__ inline uint32_t ordered_key(float f) {          // monotone map float -> uint32
+    const uint32_t b = __float_as_uint(f);
+    return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ inline float ordered_key_value(uint32_t key) {
+    return __uint_as_float(key ^ ((key >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+}
+
+// WB = 32x32 output blocks per wave and axis; the 4 waves sit 2 x 2, so the tile edge is 64 * WB.
+template <int WB>
+__global__ void __launch_bounds__(256)
+coarse_rank_kernel(const float* __restrict__ queries, const float* __restrict__ centroids,
+                   const float* __restrict__ centroid_norms, int nq, int n_lists, int d,
+                   uint32_t* __restrict__ A) {
+    constexpr int CT = 64 * WB;          // tile edge
+    constexpr int RT = 4 * WB;           // components a thread loads per tile row and slice
+    __shared__ float qs[CK][CT + 4];
+    __shared__ float cs[CK][CT + 4];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int q0 = blockIdx.y * CT, l0 = blockIdx.x * CT;
+    floatx16 acc[WB][WB];
+#pragma unroll
+    for (int i = 0; i < WB; ++i)
+#pragma unroll
+        for (int j = 0; j < WB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    constexpr int TPR = CK / RT;              // threads per tile row when loading
+    const int lr = tid / TPR;                 // row of the tile this thread loads
+    const int lk = (tid % TPR) * RT;          // first of its RT components
+    const bool vec_ok = (d & 3) == 0;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int qi = q0 + lr, li = l0 + lr;
+    float qv[RT], cv[RT];
+    // global -> registers for the slice starting at component k0 (zero beyond the matrix edges)
+    auto fetch = [&](int k0) {
+        if (vec_ok && k0 + lk + RT <= d) {
+#pragma unroll
+            for (int v = 0; v < WB; ++v) {
+                float4 x = make_float4(0.f, 0.f, 0.f, 0.f), y = x;
+                if (qi < nq) x = reinterpret_cast<const float4*>(queries + (size_t)qi * d + k0 + lk)[v];
+                if (li < n_lists) y = reinterpret_cast<const float4*>(centroids + (size_t)li * d + k0 + lk)[v];
+                qv[4 * v] = x.x; qv[4 * v + 1] = x.y; qv[4 * v + 2] = x.z; qv[4 * v + 3] = x.w;
+                cv[4 * v] = y.x; cv[4 * v + 1] = y.y; cv[4 * v + 2] = y.z; cv[4 * v + 3] = y.w;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < RT; ++u) {
+                const int t = k0 + lk + u;
+                qv[u] = (qi < nq && t < d) ? queries[(size_t)qi * d + t] : 0.f;
+                cv[u] = (li < n_lists && t < d) ? centroids[(size_t)li * d + t] : 0.f;
+            }
+        }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < d; k0 += CK) {
+#pragma unroll
+        for (int u = 0; u < RT; ++u) { qs[lk + u][lr] = qv[u]; cs[lk + u][lr] = cv[u]; }
+        __syncthreads();
+        if (k0 + CK < d) fetch(k0 + CK);       // the next slice travels while this one is multiplied
+        // one MFMA consumes two components: lanes 0-31 feed component kk, lanes 32-63 component kk+1
+#pragma unroll
+        for (int kk = 0; kk < CK; kk += 2) {
+            float av[WB], bv[WB];
+#pragma unroll
+            for (int i = 0; i < WB; ++i) av[i] = qs[kk + half][(wr * WB + i) * 32 + l32];
+#pragma unroll
+            for (int j = 0; j < WB; ++j) bv[j] = cs[kk + half][(wc * WB + j) * 32 + l32];
+#pragma unroll
+            for (int i = 0; i < WB; ++i)
+#pragma unroll
+                for (int j = 0; j < WB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // accumulator layout of the 32x32 block: register v of lane L holds row 8*(v/4) + 4*(L/32) + v%4, column L%32
+#pragma unroll
+    for (int i = 0; i < WB; ++i)
+#pragma unroll
+        for (int j = 0; j < WB; ++j) {
+            const int li = l0 + (wc * WB + j) * 32 + l32;
+            if (li >= n_lists) continue;
+            const float cn = centroid_norms[li];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int qi = q0 + (wr * WB + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                if (qi < nq) A[(size_t)qi * n_lists + li] = ordered_key(__builtin_fmaf(-2.f, acc[i][j][v], cn));
+            }
+        }
+}
+
+// picks the tile size so that the grid still covers the chip
+int launch_coarse(const float* q, const float* centroids, const float* centroid_norms, int nq, int n_lists, int d,
+                  uint32_t* A, hipStream_t st) {
+    const long big_blocks = (long)((n_lists + 127) / 128) * ((nq + 127) / 128);
+    if (big_blocks >= 1024) {
+        dim3 grid((n_lists + 127) / 128, (nq + 127) / 128);
+        hipLaunchKernelGGL(coarse_rank_kernel<2>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A);
+    } else {
+        dim3 grid((n_lists + 63) / 64, (nq + 63) / 64);
+        hipLaunchKernelGGL(coarse_rank_kernel<1>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(IVFPQ_EHIP, "coarse_rank_kernel launch failed: %s", hipGetErrorString(e));
+    return IVFPQ_OK;
+}
+
+}  // namespace

@@ -1,0 +1,134 @@
+"""GPU parity of the index construction (Sec. I-C, first enumeration) against the oracle's builder.
+
+Both sides take every decision as the arg-min of float64 squared distances (ties to the lower index)
+and form every centre as the float64 mean of its members in ascending row order, so with the same
+training rows and the same k-means start rows the saved index must be IDENTICAL: centroids and
+codebooks bit for bit, list offsets, ids and packed codes byte for byte.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2301_06672_amd as pkg
+    pkg.lib()
+    assert torch.cuda.is_available()
+    return pkg
+
+
+def _step(msg):
+    print(f"[build] {msg}", flush=True)
+
+
+def _data(n, d, seed, offset=0.0, kind="gauss"):
+    rng = np.random.default_rng(seed)
+    if kind == "intgrid":           # integer-valued components: plenty of exactly equal distances
+        return rng.integers(0, 6, size=(n, d)).astype(np.float32)
+    centres = rng.standard_normal((12, d)) * 2.0
+    x = centres[rng.integers(0, 12, size=n)] + 0.7 * rng.standard_normal((n, d))
+    return (x + offset).astype(np.float32)
+
+
+# ---------------------------------------------------------------- the assignment step alone
+
+@pytest.mark.parametrize("n,d,k,offset,kind", [(5000, 48, 300, 0.0, "gauss"), (3000, 32, 64, 500.0, "gauss"),
+                                               (4000, 16, 200, 0.0, "intgrid"), (1000, 7, 3, 0.0, "gauss"),
+                                               (700, 128, 1, 0.0, "gauss")])
+def test_assign_device_equals_oracle(P, n, d, k, offset, kind):
+    # offset 500: norms dwarf the distances, so many rows go through the exact float64 path;
+    # intgrid: exactly tied distances, decided by the lower index
+    x = _data(n, d, 11 + n, offset, kind)
+    rng = np.random.default_rng(5 + k)
+    c = x[np.sort(rng.choice(n, size=k, replace=False))].copy()
+    if k >= 8:
+        c[5] = c[2]                  # a duplicated centre: the lower index must win
+        c[7] = x[0]
+    _step(f"assign n={n} d={d} k={k} offset={offset} {kind}")
+    got = P.ivfpq_assign_device(x, c).cpu().numpy()
+    want, _ = oracle.assign(x, c)
+    np.testing.assert_array_equal(got, want)
+    if k >= 8:
+        assert not np.any(got == 5)
+
+
+# ---------------------------------------------------------------- the whole build
+
+def _rows(n, n_lists, pq_dim, pq_bits, n_ct, n_pt, salt):
+    ct = si.stride_sample(n, n_ct)
+    pt = si.stride_sample(n, n_pt)
+    ci = si.kmeans_init_rows(si.STREAM_COARSE_INIT, 0, len(ct), n_lists, salt)
+    pi = np.stack([si.kmeans_init_rows(si.STREAM_PQ_INIT, j, len(pt), 1 << pq_bits, salt) for j in range(pq_dim)])
+    return ct, ci, pt, pi
+
+
+def _assert_same_index(gidx, oidx):
+    cent, cb, offs, codes, ids = gidx.ivfpq_index_export()
+    np.testing.assert_array_equal(offs, oidx.list_offsets)
+    np.testing.assert_array_equal(ids, oidx.ids)
+    np.testing.assert_array_equal(cent.view(np.uint32), oidx.centroids.view(np.uint32))
+    np.testing.assert_array_equal(cb.view(np.uint32).reshape(-1), oidx.codebooks.view(np.uint32).reshape(-1))
+    np.testing.assert_array_equal(codes.reshape(oidx.codes.shape), oidx.codes)
+
+
+@pytest.mark.parametrize("n,d,n_lists,pq_dim,pq_bits,iters,n_ct,n_pt,kind", [
+    (10_000, 32, 64, 16, 8, 4, 5_000, 4_000, "gauss"),      # m = 2
+    (6_000, 24, 20, 8, 4, 3, 6_000, 6_000, "gauss"),        # 4-bit codes, m = 3, all rows train
+    (6_000, 64, 16, 8, 8, 3, 3_000, 2_500, "gauss"),        # m = 8: the generic sub-vector path
+    (20_000, 16, 2, 16, 8, 2, 20_000, 3_000, "gauss"),      # two huge lists: groups longer than one LDS sort
+    (5_000, 32, 40, 32, 8, 3, 2_500, 2_000, "intgrid"),     # m = 1, tied distances everywhere
+    (3_000, 32, 48, 16, 8, 0, 1_000, 1_000, "gauss"),       # no Lloyd iteration: the start rows are the centres
+])
+def test_build_device_is_identical_to_oracle_build(P, n, d, n_lists, pq_dim, pq_bits, iters, n_ct, n_pt, kind):
+    x = _data(n, d, 100 + n + d, 0.0, kind)
+    ct, ci, pt, pi = _rows(n, n_lists, pq_dim, pq_bits, n_ct, n_pt, salt=n + d)
+    _step(f"build n={n} d={d} lists={n_lists} s={pq_dim} p={pq_bits} iters={iters} {kind}")
+    gidx = P.Index.ivfpq_build_device(x, n_lists, pq_dim, pq_bits, iters, coarse_train_rows=ct, coarse_init_rows=ci,
+                                      pq_train_rows=pt, pq_init_rows=pi)
+    oidx = oracle.build_index(x, n_lists, pq_dim, pq_bits, iters, ci, pi, coarse_train_rows=ct, pq_train_rows=pt)
+    _assert_same_index(gidx, oidx)
+
+
+def test_build_device_default_draws_and_search(P):
+    # rows drawn from the seed inside the library: a valid index that searches as well as the host-built one
+    w = si.WORKLOADS["tiny"]
+    data, q = si.dataset(w), si.queries(w, 200)
+    _step("build_device (seeded draws) + search")
+    g = P.Index.ivfpq_build_device(data, w.n_lists, w.pq_dim, w.pq_bits, 6, seed=3)
+    g2 = P.Index.ivfpq_build_device(torch.from_numpy(data).cuda(), w.n_lists, w.pq_dim, w.pq_bits, 6, seed=3)
+    for a, b in zip(g.ivfpq_index_export(), g2.ivfpq_index_export()):
+        np.testing.assert_array_equal(a, b)                                   # deterministic
+    cent, cb, offs, codes, ids = g.ivfpq_index_export()
+    assert offs[0] == 0 and offs[-1] == w.n and np.all(np.diff(offs) >= 0)
+    assert np.array_equal(np.sort(ids), np.arange(w.n))
+    labels, _ = oracle.assign(data, cent)
+    for l in range(w.n_lists):
+        seg = ids[offs[l]:offs[l + 1]]
+        assert np.all(np.diff(seg) > 0) and np.all(labels[seg] == l)
+    gt, _ = oracle.exact_knn(data, q, w.k)
+    h = P.Index.ivfpq_build_host(data, w.n_lists, w.pq_dim, w.pq_bits, 6, seed=3)
+    rec = {}
+    for name, idx in (("device", g), ("host", h)):
+        idx.ivfpq_upload()
+        found, _ = idx.ivfpq_search(q, w.n_probes, w.k, P.LUT_FP32)
+        rec[name] = oracle.recall(found.cpu().numpy(), gt)
+    _step(f"recall {rec}")
+    assert abs(rec["device"] - rec["host"]) < 0.05 and rec["device"] > 0.5
+
+
+def test_build_device_rejects_bad_arguments(P):
+    x = torch.zeros((100, 16), device="cuda")
+    for kw, status in ((dict(coarse_init_rows=np.full(4, 100)), P.EINVAL),
+                       (dict(pq_train_rows=np.array([0, 5, 100])), P.EINVAL),
+                       (dict(coarse_train_rows=np.array([-1, 2, 3, 4])), P.EINVAL)):
+        with pytest.raises(P.IvfpqError) as e:
+            P.Index.ivfpq_build_device(x, 4, 4, 8, 1, **kw)
+        assert e.value.status == status
+    with pytest.raises(P.IvfpqError):
+        P.Index.ivfpq_build_device(x, 200, 4, 8, 1)          # more lists than rows
