@@ -90,8 +90,8 @@ def main():
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--recall-queries", type=int, default=1000)
     ap.add_argument("--cpu-queries", type=int, default=2000)
-    ap.add_argument("--builder", default="auto", choices=["auto", "host", "torch"],
-                    help="index construction (untimed): ivfpq_build_host on the CPU, or torch matmuls on the GPU + import")
+    ap.add_argument("--builder", default="device", choices=["device", "host"],
+                    help="index construction (untimed): ivfpq_build_device (HIP kernels) or ivfpq_build_host (CPU)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="only run a plain elementwise copy (read BYTES, write BYTES) three times and exit: "
                          "reference for scaling the FETCH_SIZE / WRITE_SIZE counters")
@@ -133,14 +133,16 @@ def main():
     queries_np = si.queries(w)
     log(f"generated {w.name}: data {data.shape}, queries {queries_np.shape} in {time.time() - t0:.1f}s")
     t0 = time.time()
-    builder = args.builder if args.builder != "auto" else ("host" if w.n <= 2_000_000 else "torch")
+    builder = args.builder
     if builder == "host":
         idx = pkg.Index.ivfpq_build_host(data, w.n_lists, w.pq_dim, w.pq_bits, args.kmeans_iters, seed=1)
     else:
-        from paper_2301_06672_amd.torch_builder import build_index_arrays
-        arrays = build_index_arrays(data, w.n_lists, w.pq_dim, w.pq_bits, args.kmeans_iters, seed=1)
-        idx = pkg.Index.ivfpq_index_from_arrays(w.d, w.n_lists, w.pq_dim, w.pq_bits, *arrays)
-        del arrays
+        x_dev = torch.from_numpy(data).cuda()
+        torch.cuda.synchronize()
+        t1 = time.time()
+        idx = pkg.Index.ivfpq_build_device(x_dev, w.n_lists, w.pq_dim, w.pq_bits, args.kmeans_iters, seed=1)
+        log(f"ivfpq_build_device alone (data resident): {time.time() - t1:.2f}s")
+        del x_dev
         torch.cuda.empty_cache()
     log(f"index build ({builder}, {args.kmeans_iters} Lloyd iterations) {time.time() - t0:.1f}s")
     idx.ivfpq_upload()

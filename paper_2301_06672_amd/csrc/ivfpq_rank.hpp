@@ -25,13 +25,13 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 
 // ================================================================================================
-// Step 1a: coarse ranking values on the matrix cores.
+// Ranking values on the matrix cores (search step 1a; the assignment step of the index build).
 // For ranking the clusters of one query |q - c|^2 can be replaced by a(q, c) = |c|^2 - 2 q.c (the
 // |q|^2 term is common).  The dot products are one fp32 GEMM: v_mfma_f32_32x32x2_f32, a tile of
 // 128 queries x 128 clusters (or 64 x 64 for small problems) per 256-thread workgroup, operands
 // staged through LDS in slices of 16 components.  The expanded form cancels, so these values only
-// SHORT-LIST clusters: the selection kernel below recomputes the short-listed distances exactly
-// (direct form) and bounds the error of a() rigorously, so the probe list is the exact one.
+// SHORT-LIST clusters: the kernels that consume them bound the error of a() rigorously and recompute
+// the distances of everything inside that bound in direct form, so their decisions are exact.
 // Values are stored as order-preserving unsigned keys (a() can be negative).
 // ================================================================================================
 constexpr int CK = 16;   // components per LDS slice

@@ -24,13 +24,41 @@ def _build(P, w, builder):
     if builder == "host":
         idx = P.Index.ivfpq_build_host(data, w.n_lists, w.pq_dim, w.pq_bits, 4, seed=1)
     else:
-        from paper_2301_06672_amd.torch_builder import build_index_arrays
-        idx = P.Index.ivfpq_index_from_arrays(w.d, w.n_lists, w.pq_dim, w.pq_bits,
-                                              *build_index_arrays(data, w.n_lists, w.pq_dim, w.pq_bits, 4, seed=1))
+        idx = P.Index.ivfpq_build_device(data, w.n_lists, w.pq_dim, w.pq_bits, 4, seed=1)
         torch.cuda.empty_cache()
     idx.ivfpq_upload()
     oidx = oracle.make_index(w.d, w.n_lists, w.pq_dim, w.pq_bits, *idx.ivfpq_index_export())
+    if builder == "device":
+        _check_built_index(data, oidx)
     return data, idx, oidx
+
+
+def _check_built_index(data, oidx, n_sample=300):
+    """Properties of a device-built index that hold at any size: the lists partition the rows with
+    ascending ids inside a list; on sampled rows the list is the float64-nearest centroid and every
+    PQ code the float64-nearest codeword of the fp32 residual (ties to the lower index)."""
+    n = data.shape[0]
+    offs, ids = oidx.list_offsets, oidx.ids
+    assert offs[0] == 0 and offs[-1] == n and np.all(np.diff(offs) >= 0)
+    seen = np.zeros(n, dtype=bool)
+    seen[ids] = True
+    assert seen.all()
+    inner = np.ones(n, dtype=bool)
+    inner[offs[1:-1][offs[1:-1] < n]] = False            # first position of every later list
+    inner[0] = False
+    assert np.all(np.diff(ids)[inner[1:]] > 0)
+    rng = np.random.default_rng(99)
+    pos = np.sort(rng.choice(n, n_sample, replace=False))
+    rows = ids[pos]
+    lists = np.searchsorted(offs, pos, side="right") - 1
+    want, _ = oracle.assign(data[rows], oidx.centroids)
+    np.testing.assert_array_equal(lists, want)
+    resid = data[rows] - oidx.centroids[lists]
+    sub = oracle.unpack_codes(oidx.codes[pos], oidx.pq_bits)
+    m = oidx.m
+    for j in range(oidx.pq_dim):
+        code, _ = oracle.assign(np.ascontiguousarray(resid[:, j * m:(j + 1) * m]), oidx.codebooks[j])
+        np.testing.assert_array_equal(sub[:, j], code)
 
 
 def _exact_topk(data, q, k):
@@ -110,7 +138,7 @@ def P():
 
 
 def test_intgrid_1m_full_batch(P):
-    _check_workload(P, "intgrid_1m", "host", [20])
+    _check_workload(P, "intgrid_1m", "device", [20])
 
 
 def test_unitnorm_1m_probe_sweep(P):
@@ -118,4 +146,4 @@ def test_unitnorm_1m_probe_sweep(P):
 
 
 def test_unitnorm_10m_full_batch(P):
-    _check_workload(P, "unitnorm_10m", "torch", [20], n_sample=100)
+    _check_workload(P, "unitnorm_10m", "device", [20], n_sample=100)
