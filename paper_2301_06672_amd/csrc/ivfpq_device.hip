@@ -529,11 +529,27 @@ __host__ __device__ inline Fp8Params fp8_params(int shift, int bias, int truncat
     p.sub = truncate ? p.lo : p.lo - (1 << (shift - 1));
     return p;
 }
+// The code of x, left in the TOP byte of the result (low bits undefined): the clamp is one
+// three-operand median once the upper limit sits in a vector register (`hi_v`; an instruction takes
+// one scalar operand only), the bias subtraction and the shift are one add-shift.
 template <int SHIFT>
-__device__ inline uint32_t fp8_from_f32(float x, const Fp8Params p) {
-    int b = __float_as_int(x);
-    b = min(max(b, p.lo), p.hi);
-    return (uint32_t)(b - p.sub) >> SHIFT;
+__device__ inline uint32_t fp8_code_top_byte(float x, const Fp8Params p, int hi_v) {
+    int b;
+    uint32_t t;
+    const int nsub = -p.sub;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(b) : "v"(__float_as_int(x)), "s"(p.lo), "v"(hi_v));     // clamp to [lo, hi]
+    asm("v_add_lshl_u32 %0, %1, %2, %3" : "=v"(t) : "v"(b), "s"(nsub), "n"(24 - SHIFT));            // (b - sub) << (24 - SHIFT)
+    return t;
+}
+// four codes (of f[0..3], lowest byte first) gathered from the top bytes with three byte permutes
+template <int SHIFT>
+__device__ inline uint32_t fp8_pack4(const float f[4], const Fp8Params p, int hi_v) {
+    const uint32_t t0 = fp8_code_top_byte<SHIFT>(f[0], p, hi_v), t1 = fp8_code_top_byte<SHIFT>(f[1], p, hi_v);
+    const uint32_t t2 = fp8_code_top_byte<SHIFT>(f[2], p, hi_v), t3 = fp8_code_top_byte<SHIFT>(f[3], p, hi_v);
+    // selector bytes: 0-3 pick a byte of the second operand, 4-7 of the first, 0x0c gives zero
+    const uint32_t p01 = __builtin_amdgcn_perm(t1, t0, 0x0c0c0703u);
+    const uint32_t p23 = __builtin_amdgcn_perm(t3, t2, 0x07030c0cu);
+    return p01 | p23;
 }
 template <int SHIFT>
 __device__ inline float fp8_to_f32(uint32_t b, const Fp8Params p) { return __uint_as_float((b << SHIFT) + (uint32_t)p.lo); }
@@ -558,7 +574,7 @@ __device__ inline float lut_entry(const float* cbv, const float* rq) {
 }
 
 template <int LUT>
-__device__ inline void store4(unsigned char* lut, int e, const float f[4], const Fp8Params fp8) {
+__device__ inline void store4(unsigned char* lut, int e, const float f[4], const Fp8Params fp8, int hi_v) {
     if constexpr (LUT == IVFPQ_LUT_FP32) {
         *reinterpret_cast<float4*>(lut + (size_t)e * 4) = make_float4(f[0], f[1], f[2], f[3]);
     } else if constexpr (LUT == IVFPQ_LUT_FP16) {
@@ -568,9 +584,7 @@ __device__ inline void store4(unsigned char* lut, int e, const float f[4], const
         *reinterpret_cast<uint2*>(lut + (size_t)e * 2) = v;
     } else {
         constexpr int SH = Fp8Format<LUT>::shift;
-        uint32_t v = fp8_from_f32<SH>(f[0], fp8) | (fp8_from_f32<SH>(f[1], fp8) << 8) |
-                     (fp8_from_f32<SH>(f[2], fp8) << 16) | (fp8_from_f32<SH>(f[3], fp8) << 24);
-        *reinterpret_cast<uint32_t*>(lut + e) = v;
+        *reinterpret_cast<uint32_t*>(lut + e) = fp8_pack4<SH>(f, fp8, hi_v);
     }
 }
 
@@ -620,27 +634,42 @@ __device__ __forceinline__ void visit_lut_rows256(const float* __restrict__ code
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_waves = blockDim.x >> 6;
-    const float* src = codebooks + ((size_t)wave * 256 + lane * 4) * M;
     const size_t src_step = (size_t)n_waves * 256 * M;
-    int e = wave * 256 + lane * 4;
     const int e_step = n_waves * 256;
-#pragma unroll 2
-    for (int j = wave; j < pq_dim; j += n_waves) {
-        float r[M];
-#pragma unroll
-        for (int t = 0; t < M; ++t) r[t] = rq[j * M + t];
-        float cbv[4 * M];
+    auto load_row = [&](const float* src, float (&cbv)[4 * M]) {
 #pragma unroll
         for (int v = 0; v < M; ++v) {
             float4 x = reinterpret_cast<const float4*>(src)[v];
             cbv[4 * v] = x.x; cbv[4 * v + 1] = x.y; cbv[4 * v + 2] = x.z; cbv[4 * v + 3] = x.w;
         }
+    };
+    auto finish_row = [&](const float (&cbv)[4 * M], int j, int e) {
+        float r[M];
+#pragma unroll
+        for (int t = 0; t < M; ++t) r[t] = rq[j * M + t];
         float f[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) f[u] = lut_entry<M>(cbv + u * M, r);
         sink(e, f);
-        src += src_step;
-        e += e_step;
+    };
+    const float* src = codebooks + ((size_t)wave * 256 + lane * 4) * M;
+    int e = wave * 256 + lane * 4;
+    int j = wave;
+    // two rows per trip (written out: both rows' loads are in flight before either is used; deeper
+    // prefetching costs registers, hence occupancy, and measured slower)
+    for (; j + n_waves < pq_dim; j += 2 * n_waves) {
+        float c0[4 * M], c1[4 * M];
+        load_row(src, c0);
+        load_row(src + src_step, c1);
+        finish_row(c0, j, e);
+        finish_row(c1, j + n_waves, e + e_step);
+        src += 2 * src_step;
+        e += 2 * e_step;
+    }
+    if (j < pq_dim) {
+        float c0[4 * M];
+        load_row(src, c0);
+        finish_row(c0, j, e);
     }
 }
 
@@ -698,7 +727,9 @@ __device__ __forceinline__ Fp8Params stage_table(const float* __restrict__ codeb
             fp8 = fp8_params(Fp8Format<LUT>::shift, bias, mode.truncate);
         }
     }
-    visit_lut_any_m<BITS>(codebooks, rq, pq_dim, m, [&](int e, const float (&f)[4]) { store4<LUT>(lut, e, f, fp8); });
+    int hi_v = fp8.hi;
+    asm volatile("" : "+v"(hi_v));       // the upper clamp limit, held in a vector register
+    visit_lut_any_m<BITS>(codebooks, rq, pq_dim, m, [&](int e, const float (&f)[4]) { store4<LUT>(lut, e, f, fp8, hi_v); });
     __syncthreads();
     return fp8;
 }
