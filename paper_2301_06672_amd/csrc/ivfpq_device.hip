@@ -1137,8 +1137,11 @@ int scan_threads(const ivfpq_index* idx, int lut_dtype) {
         if (v == 64 || v == 128 || v == 256 || v == 512 || v == 1024) return v;
     }
     // measured on MI355X: small tables want many 4-wave workgroups per CU; large tables want the
-    // largest workgroup of which two still fit the CU's LDS (table + residual + survivor staging)
+    // largest workgroup of which two still fit the CU's LDS (table + residual + survivor staging);
+    // long lists (24 or more 64-vector groups on average) want 2-wave workgroups: the table build of
+    // one pair then overlaps the scan of more others
     size_t lds = scan_lds_bytes(idx, lut_dtype);
+    if (idx->n_lists > 0 && idx->n / idx->n_lists >= 24 * 64 && lds <= 40 * 1024) return 128;
     if (lds <= 20 * 1024) return 256;
     if (lds <= 40 * 1024) return 512;
     if (2 * (lds + (size_t)16 * kStageCap * 8) <= kLdsBytes) return 1024;
