@@ -71,6 +71,7 @@ def _declare(L):
     L.orc_search.argtypes = [i64, i32, i32, i32, i32, vp, vp, vp, vp, vp,
                              vp, i64, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     L.orc_lut_elem_bytes.argtypes = [i32]
+    L.orc_refine.argtypes = [vp, i64, i32, vp, i64, vp, i32, i32, vp, vp]
     L.orc_lut_elem_bytes.restype = i32
 
 
@@ -338,6 +339,18 @@ def search(index: Index, queries, n_probes: int, k: int, lut_dtype: int = LUT_FP
                      _p(out_ids), _p(out_d), _p(stats))
     if return_stats:
         return out_ids, out_d, {"floored": int(stats[0]), "saturated": int(stats[1])}
+    return out_ids, out_d
+
+
+def refine(data, queries, cand_ids, k: int):
+    """Exact re-ranking: float64 distances of the candidate rows, the k smallest by (distance, id)."""
+    data, queries = _f32(data), _f32(queries)
+    cand = np.ascontiguousarray(cand_ids, dtype=np.int64)
+    nq, n_cand = cand.shape
+    assert queries.shape[0] == nq and (cand < data.shape[0]).all()
+    out_ids = np.empty((nq, k), dtype=np.int64)
+    out_d = np.empty((nq, k), dtype=np.float64)
+    lib().orc_refine(_p(data), data.shape[0], data.shape[1], _p(queries), nq, _p(cand), n_cand, k, _p(out_ids), _p(out_d))
     return out_ids, out_d
 
 

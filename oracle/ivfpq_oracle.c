@@ -483,4 +483,38 @@ void orc_search(int64_t n, int d, int n_lists, int pq_dim, int pq_bits,
     if (stats) { stats[0] = floored; stats[1] = saturated; }
 }
 
+/* ------------------------------------------------------------------ */
+/* Re-ranking of candidates with the original vectors (not in the paper; */
+/* the usual companion of a PQ search: Eq. (1) only approximates          */
+/* |q - x|^2, the stored vectors give it exactly).  For each query the     */
+/* float64 squared distance of every candidate id >= 0 (an id is a row of  */
+/* `data`), sorted by (distance, id), first k; padded with -1 / +inf.      */
+/* A candidate listed twice is ranked twice.                               */
+/* ------------------------------------------------------------------ */
+void orc_refine(const float* data, int64_t n, int d, const float* queries, int64_t nq,
+                const int64_t* cand_ids, int n_cand, int k, int64_t* out_ids, double* out_d) {
+    (void)n;
+    #pragma omp parallel
+    {
+        pair_d* buf = (pair_d*)malloc((size_t)(n_cand > 0 ? n_cand : 1) * sizeof(pair_d));
+        #pragma omp for schedule(static)
+        for (int64_t q = 0; q < nq; ++q) {
+            int m = 0;
+            for (int c = 0; c < n_cand; ++c) {
+                int64_t id = cand_ids[q * n_cand + c];
+                if (id < 0) continue;
+                buf[m].key = sqdist_f64(queries + q * d, data + id * d, d);
+                buf[m].id = id;
+                ++m;
+            }
+            qsort(buf, (size_t)m, sizeof(pair_d), cmp_pair_d);
+            for (int j = 0; j < k; ++j) {
+                if (j < m) { out_ids[q * k + j] = buf[j].id; out_d[q * k + j] = buf[j].key; }
+                else       { out_ids[q * k + j] = -1;        out_d[q * k + j] = INFINITY; }
+            }
+        }
+        free(buf);
+    }
+}
+
 int orc_lut_elem_bytes(int lut_dtype) { return lut_elem_bytes(lut_dtype); }

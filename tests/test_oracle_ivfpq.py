@@ -336,3 +336,43 @@ def test_per_table_bias_makes_search_invariant_to_power_of_two_scaling(dt):
     assert st_c["floored"] > st_a["floored"]
     _, _, st_p = oracle.search(idx_s, q * s, 6, 10, dt, per_table=True, return_stats=True)
     assert st_p["floored"] < st_c["floored"]
+
+
+def test_refine_is_exact_knn_restricted_to_the_candidates():
+    rng = _rng(31)
+    data = rng.standard_normal((500, 12)).astype(np.float32)
+    q = rng.standard_normal((9, 12)).astype(np.float32)
+    # all rows as candidates (in scrambled order): the exact k nearest neighbours
+    cand = np.stack([rng.permutation(500) for _ in range(9)])
+    ids, d2 = oracle.refine(data, q, cand, 7)
+    gt_i, gt_d = oracle.exact_knn(data, q, 7)
+    np.testing.assert_array_equal(ids, gt_i)
+    np.testing.assert_array_equal(d2, gt_d)
+    # a subset with padding entries: numpy float64 on the listed rows only; short rows are padded
+    cand = rng.integers(0, 500, size=(9, 20)).astype(np.int64)
+    cand[:, 15:] = -1
+    cand[3, 2:] = -1
+    ids, d2 = oracle.refine(data, q, cand, 5)
+    for r in range(9):
+        rows = cand[r][cand[r] >= 0]
+        dist = ((data[rows].astype(np.float64) - q[r].astype(np.float64)) ** 2).sum(1)
+        order = np.lexsort((rows, dist))[:5]
+        want_i = np.full(5, -1, dtype=np.int64); want_d = np.full(5, np.inf)
+        want_i[:len(order)] = rows[order]; want_d[:len(order)] = dist[order]
+        np.testing.assert_array_equal(ids[r], want_i)
+        np.testing.assert_allclose(d2[r], want_d, rtol=1e-12)
+    assert ids[3, 2] == -1 and np.isinf(d2[3, 2])
+
+
+def test_refine_raises_recall_of_a_pq_search():
+    w, data, idx = _tiny_index(n=10_000, n_lists=64, iters=10)
+    q = si.queries(w, 100)
+    gt, _ = oracle.exact_knn(data, q, 10)
+    ids10, _ = oracle.search(idx, q, 8, 10, oracle.LUT_E5M3)
+    ids40, _ = oracle.search(idx, q, 8, 40, oracle.LUT_E5M3)
+    ref, d2 = oracle.refine(data, q, ids40, 10)
+    assert oracle.recall(ref, gt) > oracle.recall(ids10, gt) + 0.05
+    assert np.all(np.diff(d2, axis=1) >= 0)
+    # refining the k results themselves only reorders them
+    same, _ = oracle.refine(data, q, ids10, 10)
+    np.testing.assert_array_equal(np.sort(same, axis=1), np.sort(ids10, axis=1))
