@@ -201,6 +201,20 @@ int ivfpq_dump_lut(const ivfpq_index_t* index, const float* d_query, uint32_t li
 int ivfpq_scan_list(const ivfpq_index_t* index, const float* d_query, uint32_t list_id,
                     int32_t lut_dtype, float* d_R_out, void* hip_stream);
 
+/* ---- re-ranking with the stored vectors (not part of the paper's path; the usual companion of a PQ
+ * search, whose Eq. (1) only approximates |q - x|^2) ---- */
+
+/* For each of nq queries: the exact squared distance (fp32, direct form) to each of its n_cand candidate
+ * vectors, and the k smallest, ascending, ties ordered by id.  A candidate id is a row of d_data
+ * (device [n_data][d] fp32: the vectors the index was built from, when their ids are their row numbers);
+ * ids outside [0, n_data) -- the -1 padding of a search result -- are skipped; an id listed twice is
+ * ranked twice.  d_cand_ids [nq][n_cand] i64 (device), e.g. the ids of ivfpq_search with a larger k.
+ * d_ids [nq][k] i64, d_dists [nq][k] f32 (device, out); short rows are padded with -1 / +inf.
+ * 1 <= n_cand <= IVFPQ_MAX_K, 1 <= k <= IVFPQ_MAX_K.  Asynchronous; needs no workspace. */
+int ivfpq_refine(const float* d_data, int64_t n_data, int32_t d, const float* d_queries, int64_t nq,
+                 const int64_t* d_cand_ids, int32_t n_cand, int32_t k, int64_t* d_ids, float* d_dists,
+                 void* hip_stream);
+
 /* ---- measurement aid ---- */
 
 /* When enabled, search calls record HIP events around their stages on the stream they run on.

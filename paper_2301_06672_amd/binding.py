@@ -31,7 +31,7 @@ EXPORTS = (
     "ivfpq_assign_device_workspace_bytes", "ivfpq_index_from_arrays", "ivfpq_index_info", "ivfpq_index_export", "ivfpq_free",
     "ivfpq_set_e4m4_bias", "ivfpq_set_fp8_encoding",
     "ivfpq_device_bytes", "ivfpq_upload", "ivfpq_search_workspace_bytes", "ivfpq_search",
-    "ivfpq_select_probes", "ivfpq_search_with_probes", "ivfpq_dump_lut", "ivfpq_scan_list",
+    "ivfpq_select_probes", "ivfpq_search_with_probes", "ivfpq_dump_lut", "ivfpq_scan_list", "ivfpq_refine",
     "ivfpq_set_stage_timing", "ivfpq_stage_times_ms", "ivfpq_last_error",
 )
 
@@ -86,6 +86,7 @@ def _declare(L):
     L.ivfpq_select_probes.argtypes = [vp, vp, i64, i32, vp, vp, vp, sz, vp]
     L.ivfpq_search_with_probes.argtypes = [vp, vp, i64, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     L.ivfpq_dump_lut.argtypes = [vp, vp, u32, i32, vp, vp]
+    L.ivfpq_refine.argtypes = [vp, i64, i32, vp, i64, vp, i32, i32, vp, vp, vp]
     L.ivfpq_scan_list.argtypes = [vp, vp, u32, i32, vp, vp]
     L.ivfpq_set_stage_timing.argtypes = [vp, i32]
     L.ivfpq_stage_times_ms.argtypes = [vp, c.POINTER(c.c_float * 4)]
@@ -135,6 +136,19 @@ def ivfpq_assign_device(rows, centres) -> torch.Tensor:
                                      _dp(ws), need, _stream()))
     torch.cuda.current_stream().synchronize()
     return labels
+
+
+def ivfpq_refine(data: torch.Tensor, queries, cand_ids: torch.Tensor, k: int):
+    """-> (ids [nq][k] int64, dists [nq][k] fp32): candidates re-ranked by exact distance to rows of `data` (CUDA)."""
+    assert data.is_cuda and data.dtype == torch.float32 and data.is_contiguous()
+    q = _dev_f32(queries)
+    cand = cand_ids.contiguous()
+    assert cand.is_cuda and cand.dtype == torch.int64 and cand.shape[0] == q.shape[0]
+    ids = torch.empty((q.shape[0], k), dtype=torch.int64, device="cuda")
+    dists = torch.empty((q.shape[0], k), dtype=torch.float32, device="cuda")
+    _check(lib().ivfpq_refine(_dp(data), int(data.shape[0]), int(data.shape[1]), _dp(q), int(q.shape[0]), _dp(cand),
+                              int(cand.shape[1]), int(k), _dp(ids), _dp(dists), _stream()))
+    return ids, dists
 
 
 class Index:

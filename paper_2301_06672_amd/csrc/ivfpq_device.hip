@@ -1034,6 +1034,50 @@ topk_kernel(const float* __restrict__ R, const uint32_t* __restrict__ Rpos, size
 }
 
 // ================================================================================================
+// Re-ranking with the stored vectors: per query the exact squared distances of its candidates (fp32,
+// direct form) and the k smallest by (distance, id).  One workgroup per query; a group of 8 adjacent
+// lanes per candidate (each lane sums every 8th component, then three exchange steps: a fixed order).
+// Candidate ids outside [0, n_data) are skipped.
+// ================================================================================================
+__global__ void __launch_bounds__(SEL_THREADS)
+refine_kernel(const float* __restrict__ data, long long n_data, int d, const float* __restrict__ queries,
+              const int64_t* __restrict__ cand, int n_cand, int k, int64_t* __restrict__ out_ids,
+              float* __restrict__ out_dists) {
+    __shared__ SelectShared s;
+    __shared__ uint32_t keys[SEL_CAP];
+    const int q = blockIdx.x;
+    const int tid = threadIdx.x, nth = blockDim.x;
+    const float* qv = queries + (size_t)q * d;
+    const int64_t* my = cand + (size_t)q * n_cand;
+    for (int base = 0; base < n_cand; base += nth / 8) {
+        const int c = base + (tid >> 3);
+        const bool valid = c < n_cand;
+        const long long id = valid ? (long long)my[c] : -1ll;
+        const bool ok = id >= 0 && id < n_data;
+        float acc = 0.f;
+        if (ok) {
+            const float* x = data + (size_t)id * d;
+            for (int u = tid & 7; u < d; u += 8) { const float diff = qv[u] - x[u]; acc = __builtin_fmaf(diff, diff, acc); }
+        }
+        acc += __shfl_xor(acc, 1, kWave);
+        acc += __shfl_xor(acc, 2, kWave);
+        acc += __shfl_xor(acc, 4, kWave);
+        if (valid && (tid & 7) == 0) keys[c] = ok ? __float_as_uint(acc) : kPadKey;
+    }
+    __syncthreads();
+    const int got = block_select_smallest(s, (uint32_t)n_cand, (uint32_t)k,
+        [&](uint32_t i) { return keys[i]; },
+        [&](uint32_t i) { return keys[i] == kPadKey ? 0x7FFFFFFFFFFFFFFFll : (long long)my[i]; });
+    for (int j = tid; j < k; j += nth) {
+        int64_t id = -1;
+        float dist = __uint_as_float(0x7F800000u);
+        if (j < got && s.rec_key[j] != kPadKey) { id = (int64_t)s.rec_tie[j]; dist = __uint_as_float(s.rec_key[j]); }
+        out_ids[(size_t)q * k + j] = id;
+        out_dists[(size_t)q * k + j] = dist;
+    }
+}
+
+// ================================================================================================
 // Host side
 // ================================================================================================
 struct ImageLayout {
@@ -1510,6 +1554,21 @@ int ivfpq_scan_list(const ivfpq_index_t* idx, const float* d_query, uint32_t lis
     ScanArgs a = base_scan_args(idx, lut_dtype);
     a.queries = d_query; a.R = d_R_out; a.single_list = (int)list_id; a.n_probes = 1;
     return launch_scan(idx, a, lut_dtype, dim3(1), (hipStream_t)hip_stream);
+}
+
+int ivfpq_refine(const float* d_data, int64_t n_data, int32_t d, const float* d_queries, int64_t nq,
+                 const int64_t* d_cand_ids, int32_t n_cand, int32_t k, int64_t* d_ids, float* d_dists, void* hip_stream) {
+    if (nq < 0 || n_data < 0 || d < 1) return fail(IVFPQ_EINVAL, "ivfpq_refine: bad shape");
+    if (n_cand < 1 || n_cand > IVFPQ_MAX_K) return fail(IVFPQ_EINVAL, "n_cand=%d outside [1, %d]", n_cand, IVFPQ_MAX_K);
+    if (k < 1 || k > IVFPQ_MAX_K) return fail(IVFPQ_EINVAL, "k=%d outside [1, %d]", k, IVFPQ_MAX_K);
+    if (nq == 0) return IVFPQ_OK;
+    if (!d_queries || !d_cand_ids || !d_ids || !d_dists || (n_data > 0 && !d_data))
+        return fail(IVFPQ_EINVAL, "ivfpq_refine: null pointer");
+    if (nq > 0x7FFFFFFF) return fail(IVFPQ_EUNSUPPORTED, "ivfpq_refine: nq=%lld (limit 2^31 - 1 per call)", (long long)nq);
+    hipLaunchKernelGGL(refine_kernel, dim3((unsigned)nq), dim3(SEL_THREADS), 0, (hipStream_t)hip_stream, d_data,
+                       (long long)n_data, d, d_queries, d_cand_ids, n_cand, k, d_ids, d_dists);
+    HIP_TRY(hipGetLastError());
+    return IVFPQ_OK;
 }
 
 int ivfpq_set_stage_timing(ivfpq_index_t* index, int32_t enabled) {

@@ -414,3 +414,50 @@ def test_library_builder_index_searches_like_oracle_builder(P, tiny):
     ids_lib, _ = g.ivfpq_search(q, w.n_probes, w.k, oracle.LUT_FP32)
     ids_orc, _ = oracle.search(oidx, q, w.n_probes, w.k, oracle.LUT_FP32)
     assert abs(oracle.recall(ids_lib.cpu().numpy(), gt) - oracle.recall(ids_orc, gt)) < 0.06
+
+
+# ---------------------------------------------------------------- re-ranking with the stored vectors
+
+def test_refine_matches_oracle(P, tiny):
+    w, data, oidx, gidx = tiny
+    q = si.queries(w, 200)
+    x = torch.from_numpy(data).cuda()
+    _step("refine: search k'=40, refine to 10")
+    cand, _ = gidx.ivfpq_search(q, w.n_probes, 40, P.LUT_FP8_E5M3)
+    ids_g, d_g = P.ivfpq_refine(x, q, cand, 10)
+    ids_o, d_o = oracle.refine(data, q, cand.cpu().numpy(), 10)
+    assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o.astype(np.float32), context="refine")
+    gt, _ = oracle.exact_knn(data, q, 10)
+    ids10, _ = gidx.ivfpq_search(q, w.n_probes, 10, P.LUT_FP8_E5M3)
+    r0, r1 = oracle.recall(ids10.cpu().numpy(), gt), oracle.recall(ids_g.cpu().numpy(), gt)
+    _step(f"refine: recall@10 {r0:.3f} -> {r1:.3f}")
+    assert r1 > r0 + 0.03
+
+
+@pytest.mark.parametrize("n_cand,k", [(1, 1), (7, 10), (64, 64), (1000, 100), (1024, 1024)])
+def test_refine_edge_cases(P, n_cand, k):
+    rng = np.random.default_rng(n_cand)
+    n, d, nq = 3000, 24, 33
+    data = rng.integers(-3, 4, size=(n, d)).astype(np.float32)      # integer grid: many exactly equal distances
+    q = rng.integers(-3, 4, size=(nq, d)).astype(np.float32)
+    cand = rng.integers(0, n, size=(nq, n_cand)).astype(np.int64)   # with duplicates
+    cand[rng.random(cand.shape) < 0.2] = -1                          # padding entries anywhere
+    if n_cand > 3:
+        cand[5, :] = -1                                              # a query with no candidate at all
+        cand[6, 3] = n + 5                                           # an id beyond the data: skipped
+    _step(f"refine edge n_cand={n_cand} k={k}")
+    ids_g, d_g = P.ivfpq_refine(torch.from_numpy(data).cuda(), q, torch.from_numpy(cand).cuda(), k)
+    cand_o = np.where(cand >= n, -1, cand)
+    ids_o, d_o = oracle.refine(data, q, cand_o, k)
+    # integer-valued data: fp32 distances are exact, so the result is identical, ties by id included
+    np.testing.assert_array_equal(ids_g.cpu().numpy(), ids_o)
+    np.testing.assert_array_equal(d_g.cpu().numpy().astype(np.float64), d_o)
+
+
+def test_refine_rejects_bad_arguments(P):
+    x = torch.zeros((10, 8), device="cuda")
+    q = torch.zeros((2, 8), device="cuda")
+    for n_cand, k in ((P.MAX_K + 1, 5), (4, 0), (4, P.MAX_K + 1)):
+        with pytest.raises(P.IvfpqError) as e:
+            P.ivfpq_refine(x, q, torch.zeros((2, n_cand), dtype=torch.int64, device="cuda"), k)
+        assert e.value.status == P.EINVAL
