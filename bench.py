@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--fp8-variants", action="store_true",
                     help="also time the 8-bit tables with a truncating encode and with a per-table exponent bias "
                          "(reported under by_lut as e5m3+trunc, e5m3+pertable, e4m4+pertable)")
+    ap.add_argument("--refine-from", type=int, default=0, metavar="K2",
+                    help="also time search with k=K2 followed by ivfpq_refine down to k (exact re-ranking with the "
+                         "stored vectors; reported under by_lut as <lut>+refineK2)")
     ap.add_argument("--kmeans-iters", type=int, default=6, help="Lloyd iterations of the (untimed) index build")
     ap.add_argument("--n-probes", type=int, default=None)
     ap.add_argument("--k", type=int, default=None)
@@ -134,6 +137,7 @@ def main():
     log(f"generated {w.name}: data {data.shape}, queries {queries_np.shape} in {time.time() - t0:.1f}s")
     t0 = time.time()
     builder = args.builder
+    x_dev = None
     if builder == "host":
         idx = pkg.Index.ivfpq_build_host(data, w.n_lists, w.pq_dim, w.pq_bits, args.kmeans_iters, seed=1)
     else:
@@ -142,7 +146,8 @@ def main():
         t1 = time.time()
         idx = pkg.Index.ivfpq_build_device(x_dev, w.n_lists, w.pq_dim, w.pq_bits, args.kmeans_iters, seed=1)
         log(f"ivfpq_build_device alone (data resident): {time.time() - t1:.2f}s")
-        del x_dev
+        if not args.refine_from:
+            x_dev = None
         torch.cuda.empty_cache()
     log(f"index build ({builder}, {args.kmeans_iters} Lloyd iterations) {time.time() - t0:.1f}s")
     idx.ivfpq_upload()
@@ -205,6 +210,32 @@ def main():
         r = results[name]
         log(f"lut={name}: {r['qps']:.0f} q/s, {r['ms_per_step']:.3f} ms/step, recall@{k}={r['recall']:.4f}, "
             f"stages {r['stage_ms']}")
+    if args.refine_from:
+        # search with a longer result list, then re-rank it exactly with the stored vectors
+        k2 = args.refine_from
+        if x_dev is None:
+            x_dev = torch.from_numpy(data).cuda()
+        lut = lut_ids[args.lut]
+        if args.lut in ("e5m3", "e4m4"):
+            idx.ivfpq_set_fp8_encoding(lut, 15 if args.lut == "e5m3" else e4m4_bias)
+        out2 = (torch.empty((nq, k2), dtype=torch.int64, device="cuda"), torch.empty((nq, k2), dtype=torch.float32, device="cuda"))
+
+        def one():
+            idx.ivfpq_search(q, n_probes, k2, lut, out=out2)
+            return pkg.ivfpq_refine(x_dev, q, out2[0], k)
+        for _ in range(args.warmup):
+            one()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            rid, _ = one()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        name = f"{args.lut}+refine{k2}"
+        results[name] = {"qps": nq * args.steps / dt, "ms_per_step": 1e3 * dt / args.steps,
+                         "recall": tie_aware_recall(rid[:nr], data, q[:nr], gt_d, k), "stage_ms": {}}
+        log(f"lut={name}: {results[name]['qps']:.0f} q/s, {results[name]['ms_per_step']:.3f} ms/step, "
+            f"recall@{k}={results[name]['recall']:.4f}")
     head = results[args.lut]
 
     ws_bytes = idx.ivfpq_search_workspace_bytes(nq, n_probes, k, lut_ids[args.lut])
