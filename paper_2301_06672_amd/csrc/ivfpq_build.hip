@@ -426,7 +426,7 @@ int launch_pq_codes(const BuildPlan& P, const float* X, const uint32_t* order, c
     const size_t lds = (size_t)spw * P.ksub * P.m * 4;
     dim3 grid(blocks_for(n_pos, 256), (unsigned)(P.pq_dim / spw));
     auto go = [&](auto kernel) -> int {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (int s = allow_full_lds(kernel)) return s;
         hipLaunchKernelGGL(kernel, grid, dim3(256), lds, st, X, order, labels, C, codebooks, n_pos, P.d, P.pq_dim, P.m,
                            train_labels, codes32);
         HIP_TRY(hipGetLastError());

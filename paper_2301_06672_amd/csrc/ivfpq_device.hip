@@ -1195,8 +1195,7 @@ int scan_threads(const ivfpq_index* idx, int lut_dtype) {
 template <int LUT, int BITS>
 int launch_scan_bits(const ScanArgs& a, int cw, int nch, dim3 grid, int threads, size_t lds, hipStream_t st) {
     auto go = [&](auto kernel) -> int {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (int s = allow_full_lds(kernel)) return s;
         hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, st, a);
         HIP_TRY(hipGetLastError());
         return IVFPQ_OK;
@@ -1528,8 +1527,7 @@ int ivfpq_dump_lut(const ivfpq_index_t* idx, const float* d_query, uint32_t list
     hipStream_t st = (hipStream_t)hip_stream;
     const float* centroid = idx->dev.centroids + (size_t)list_id * idx->d;
     auto go = [&](auto kernel) -> int {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (int s = allow_full_lds(kernel)) return s;
         hipLaunchKernelGGL(kernel, dim3(1), dim3(256), lds, st, d_query, centroid, idx->dev.codebooks, idx->d,
                            idx->pq_dim, idx->m(), idx->pq_bits, fp8_mode(idx, lut_dtype), (unsigned char*)d_lut_out);
         HIP_TRY(hipGetLastError());

@@ -5,6 +5,10 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+#include <utility>
+#include <vector>
+
 #include "ivfpq_internal.hpp"
 
 #define HIP_TRY(expr)                                                                               \
@@ -23,6 +27,23 @@ constexpr size_t kLdsBytes = 160 * 1024;       // LDS of one gfx950 compute unit
 constexpr size_t kAlign = 256;
 
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+
+// Lets `kernel` use dynamic LDS up to the whole compute unit's; done once per kernel and device, so
+// that later launches make no call besides the launch itself (a caller may be capturing a HIP graph).
+inline int allow_full_lds_ptr(const void* kernel) {
+    static std::mutex mu;
+    static std::vector<std::pair<const void*, int>> done;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(mu);
+    for (const auto& e : done)
+        if (e.first == kernel && e.second == dev) return IVFPQ_OK;
+    HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
+    done.emplace_back(kernel, dev);
+    return IVFPQ_OK;
+}
+template <class Kernel>
+int allow_full_lds(Kernel kernel) { return allow_full_lds_ptr(reinterpret_cast<const void*>(kernel)); }
 
 // ================================================================================================
 // Ranking values on the matrix cores (search step 1a; the assignment step of the index build).

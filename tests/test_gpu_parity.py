@@ -461,3 +461,32 @@ def test_refine_rejects_bad_arguments(P):
         with pytest.raises(P.IvfpqError) as e:
             P.ivfpq_refine(x, q, torch.zeros((2, n_cand), dtype=torch.int64, device="cuda"), k)
         assert e.value.status == P.EINVAL
+
+
+# ---------------------------------------------------------------- the search inside a HIP graph
+
+def test_search_replays_correctly_from_a_hip_graph(P, tiny):
+    # a serving loop may capture the search call once and replay it: the call only enqueues kernels
+    # (no allocation, no synchronisation, no memset), so every replay must give the eager result
+    w, data, oidx, gidx = tiny
+    qs = si.queries(w, 192)
+    q = torch.from_numpy(qs[:64]).cuda()
+    out = (torch.empty((64, w.k), dtype=torch.int64, device="cuda"), torch.empty((64, w.k), dtype=torch.float32, device="cuda"))
+    for dtype in (P.LUT_FP8_E5M3, P.LUT_FP32):
+        _step(f"graph capture lut={dtype}")
+        q.copy_(torch.from_numpy(qs[:64]))
+        gidx.ivfpq_search(q, w.n_probes, w.k, dtype, out=out)          # eager: workspace and kernel attributes in place
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            gidx.ivfpq_search(q, w.n_probes, w.k, dtype, out=out)
+        for rep in range(4):
+            q.copy_(torch.from_numpy(qs[64 * (rep % 3):64 * (rep % 3) + 64]))      # new queries in the captured buffer
+            want_i, want_d = gidx.ivfpq_search(q.clone(), w.n_probes, w.k, dtype)  # eager work between the replays
+            torch.cuda.synchronize()
+            out[0].fill_(-7)
+            out[1].fill_(-1.0)
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out[0], want_i) and torch.equal(out[1], want_d), f"replay {rep}"
+        del g

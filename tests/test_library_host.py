@@ -33,6 +33,16 @@ def test_library_exports_every_declared_symbol(P):
         assert hasattr(L, name), name
 
 
+def test_header_is_plain_c_and_links(P, tmp_path):
+    # strict C99 compile of a translation unit that uses the header, then a link against the library
+    import subprocess
+    src = os.path.join(ROOT, "tests", "abi_smoke.c")
+    obj = str(tmp_path / "abi_smoke.o")
+    subprocess.run(["gcc", "-std=c99", "-pedantic-errors", "-Wall", "-Werror", "-c", src, "-o", obj], check=True)
+    so = str(tmp_path / "libabi_smoke.so")
+    subprocess.run(["gcc", "-shared", "-o", so, obj, P.LIB_PATH], check=True)
+
+
 def test_import_export_round_trip(P):
     arrays = si.random_index_arrays(777, 32, 9, 16, 4, salt=1, empty_lists=(3,))
     idx = P.Index.ivfpq_index_from_arrays(32, 9, 16, 4, *arrays)
