@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--fp8-variants", action="store_true",
                     help="also time the 8-bit tables with a truncating encode and with a per-table exponent bias "
                          "(reported under by_lut as e5m3+trunc, e5m3+pertable, e4m4+pertable)")
+    ap.add_argument("--probe-sweep", default="", metavar="P1,P2,...",
+                    help="also time fp32 / fp16 / e5m3 at these numbers of probes (the recall-vs-throughput curves of "
+                         "Sec. III, Figs. 5-6, on the synthetic stand-in); reported under by_probes")
     ap.add_argument("--refine-from", type=int, default=0, metavar="K2",
                     help="also time search with k=K2 followed by ivfpq_refine down to k (exact re-ranking with the "
                          "stored vectors; reported under by_lut as <lut>+refineK2)")
@@ -170,7 +173,7 @@ def main():
     nr = min(args.recall_queries, nq)
     gt_i, gt_d = exact_topk_gpu(data, q[:nr], k)
 
-    def run(lut_name, steps, warmup):
+    def run(lut_name, steps, warmup, n_probes=n_probes):
         base, _, variant = lut_name.partition("+")
         lut = lut_ids[base]
         if base in ("e5m3", "e4m4"):
@@ -210,6 +213,15 @@ def main():
         r = results[name]
         log(f"lut={name}: {r['qps']:.0f} q/s, {r['ms_per_step']:.3f} ms/step, recall@{k}={r['recall']:.4f}, "
             f"stages {r['stage_ms']}")
+    by_probes = {}
+    for P in [int(v) for v in args.probe_sweep.split(",") if v]:
+        if P < 1 or P > min(w.n_lists, pkg.MAX_PROBES):
+            continue
+        by_probes[P] = {}
+        for name in ("fp32", "fp16", "e5m3"):
+            r = run(name, max(3, args.steps // 2), 1, n_probes=P)
+            by_probes[P][name] = {"qps": round(r["qps"], 1), "recall": round(r["recall"], 4)}
+        log(f"n_probes={P}: " + "  ".join(f"{n} {v['qps']:.0f} q/s @ {v['recall']:.4f}" for n, v in by_probes[P].items()))
     if args.refine_from:
         # search with a longer result list, then re-rank it exactly with the stored vectors
         k2 = args.refine_from
@@ -279,6 +291,7 @@ def main():
                        "stage_ms": {a: round(b, 4) for a, b in r["stage_ms"].items()}} for n, r in results.items()},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        **({"by_probes": by_probes} if by_probes else {}),
     }
     print(json.dumps(line), flush=True)
 
