@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth, GB/s
 # for a plain 1 GiB copy (FETCH_SIZE reads half the true KiB on this chip, WRITE_SIZE the true
 # figure): profiles/scan_kernel_<workload>_e5m3_hbm_traffic.txt.  None where no run is recorded.
 MEASURED_TRAFFIC = {
-    ("intgrid_1m", "e5m3"): 18.396e9,     # 18.34 GB fetched + 0.055 GB written (algorithmic: 30.98 GB of codes)
-    ("unitnorm_10m", "e5m3"): 9.832e9,    # 9.769 GB fetched + 0.063 GB written (algorithmic: 9.42 GB of codes)
+    ("intgrid_1m", "e5m3"): 18.449e9,     # 18.39 GB fetched + 0.055 GB written (algorithmic: 30.98 GB of codes)
+    ("unitnorm_10m", "e5m3"): 9.826e9,    # 9.763 GB fetched + 0.063 GB written (algorithmic: 9.42 GB of codes)
 }
 
 

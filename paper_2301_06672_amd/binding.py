@@ -29,7 +29,7 @@ OK, EINVAL, ENOSPACE, EHIP, EUNSUPPORTED, ESTATE = 0, -1, -2, -3, -4, -5
 EXPORTS = (
     "ivfpq_build_host", "ivfpq_build_device", "ivfpq_build_device_workspace_bytes", "ivfpq_assign_device",
     "ivfpq_assign_device_workspace_bytes", "ivfpq_index_from_arrays", "ivfpq_index_info", "ivfpq_index_export", "ivfpq_free",
-    "ivfpq_set_e4m4_bias", "ivfpq_set_fp8_encoding",
+    "ivfpq_set_e4m4_bias", "ivfpq_set_fp8_encoding", "ivfpq_set_workspace_limit",
     "ivfpq_device_bytes", "ivfpq_upload", "ivfpq_search_workspace_bytes", "ivfpq_search",
     "ivfpq_select_probes", "ivfpq_search_with_probes", "ivfpq_dump_lut", "ivfpq_scan_list", "ivfpq_refine",
     "ivfpq_set_stage_timing", "ivfpq_stage_times_ms", "ivfpq_last_error",
@@ -75,6 +75,7 @@ def _declare(L):
     L.ivfpq_index_export.argtypes = [vp, vp, vp, vp, vp, vp]
     L.ivfpq_free.argtypes = [vp]
     L.ivfpq_set_e4m4_bias.argtypes = [vp, i32]
+    L.ivfpq_set_workspace_limit.argtypes = [vp, sz]
     L.ivfpq_set_fp8_encoding.argtypes = [vp, i32, i32, i32, i32]
     L.ivfpq_free.restype = None
     L.ivfpq_device_bytes.argtypes = [vp]
@@ -223,6 +224,10 @@ class Index:
 
     def ivfpq_set_fp8_encoding(self, lut_dtype: int, bias: int, rounding: int = ROUND_NEAREST, per_table_bias: bool = False):
         _check(lib().ivfpq_set_fp8_encoding(self._h, int(lut_dtype), int(bias), int(rounding), int(per_table_bias)))
+
+    def ivfpq_set_workspace_limit(self, nbytes: int):
+        _check(lib().ivfpq_set_workspace_limit(self._h, int(nbytes)))
+        self._ws = None
 
     def ivfpq_set_e4m4_bias(self, bias: int):
         _check(lib().ivfpq_set_e4m4_bias(self._h, int(bias)))

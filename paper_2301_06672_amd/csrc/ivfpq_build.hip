@@ -89,13 +89,29 @@ nearest_kernel(const uint32_t* __restrict__ A, const float* __restrict__ X, cons
     for (int t = lane; t < d; t += 64) qn = __builtin_fmaf(x[t], x[t], qn);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) qn += __shfl_xor(qn, off, kWave);
-    // the two smallest keys this lane sees
+    // the two smallest keys this lane sees (four consecutive keys per 16-byte load when the row is
+    // aligned for it, two loads in flight; a lane meets its keys in ascending index order either way)
     uint32_t m1 = 0xFFFFFFFFu, m2 = 0xFFFFFFFFu;
     int i1 = 0x7FFFFFFF;
-    for (int c = lane; c < k; c += 64) {
-        const uint32_t v = keys[c];
+    auto see = [&](uint32_t v, int c) {
         if (v < m1) { m2 = m1; m1 = v; i1 = c; }
         else if (v < m2) m2 = v;
+    };
+    if ((k & 3) == 0) {
+        const uint4* keys4 = reinterpret_cast<const uint4*>(keys);
+        const int k4 = k >> 2;
+        int c4 = lane;
+        for (; c4 + 64 < k4; c4 += 128) {
+            const uint4 x = keys4[c4], y = keys4[c4 + 64];
+            see(x.x, 4 * c4); see(x.y, 4 * c4 + 1); see(x.z, 4 * c4 + 2); see(x.w, 4 * c4 + 3);
+            see(y.x, 4 * c4 + 256); see(y.y, 4 * c4 + 257); see(y.z, 4 * c4 + 258); see(y.w, 4 * c4 + 259);
+        }
+        if (c4 < k4) {
+            const uint4 x = keys4[c4];
+            see(x.x, 4 * c4); see(x.y, 4 * c4 + 1); see(x.z, 4 * c4 + 2); see(x.w, 4 * c4 + 3);
+        }
+    } else {
+        for (int c = lane; c < k; c += 64) see(keys[c], c);
     }
     // wave: smallest key (lowest index among equals) and the second smallest overall
     uint32_t g1 = m1, g2 = m2;

@@ -1111,7 +1111,6 @@ struct Plan {
     size_t probes, probe_d, roff, pairs, bounds, counts, D, R, Rpos, total;
 };
 
-constexpr size_t kScratchTarget = (size_t)2 << 30;   // aim for about 2 GiB of scratch (R, positions, D) per tile
 
 // given_probes: the caller chooses the clusters and may name one several times, so the bound on a
 // query's candidates is n_probes times the largest cluster rather than the n_probes largest ones
@@ -1124,7 +1123,7 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
         return fail(IVFPQ_EUNSUPPORTED, "a query may see %lld candidates (limit 2^31)", (long long)stride);
     if (stride < 64) stride = 64;
     size_t per_query = (size_t)stride * 8 + (need_D ? (size_t)idx->n_lists * 4 : 0);
-    int64_t tile = (int64_t)(kScratchTarget / per_query);
+    int64_t tile = (int64_t)(idx->workspace_limit / per_query);
     tile = std::max<int64_t>(1, std::min<int64_t>(tile, std::max<int64_t>(nq, 1)));
     plan->tile = tile;
     plan->stride = (size_t)stride;

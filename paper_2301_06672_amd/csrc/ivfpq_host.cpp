@@ -345,6 +345,13 @@ int ivfpq_set_fp8_encoding(ivfpq_index_t* index, int32_t lut_dtype, int32_t bias
     return IVFPQ_OK;
 }
 
+int ivfpq_set_workspace_limit(ivfpq_index_t* index, size_t bytes) {
+    if (!index) return fail(IVFPQ_EINVAL, "ivfpq_set_workspace_limit: null index");
+    if (bytes < ((size_t)1 << 20)) return fail(IVFPQ_EINVAL, "workspace limit of %zu bytes is below 1 MiB", bytes);
+    index->workspace_limit = bytes;
+    return IVFPQ_OK;
+}
+
 int ivfpq_set_e4m4_bias(ivfpq_index_t* index, int32_t bias) {
     if (!index) return fail(IVFPQ_EINVAL, "ivfpq_set_e4m4_bias: null index");
     const ivfpq::Fp8Options& o = index->fp8_opt[1];

@@ -51,6 +51,7 @@ struct ivfpq_index {
     ivfpq::DeviceImage dev;
     ivfpq::Fp8Options fp8_opt[2] = {{15, 0, 0}, {7, 0, 0}};   // e5m3, e4m4 (ivfpq_set_fp8_encoding)
     float centroid_norm_max = 0.f;      // largest squared centroid norm (set by ivfpq_upload)
+    size_t workspace_limit = (size_t)32 << 30;   // search scratch (R, positions, ranking values) per query tile
 
     // stage timing (hipEvent_t kept as void* so this header stays free of HIP types)
     bool timing = false;

@@ -490,3 +490,23 @@ def test_search_replays_correctly_from_a_hip_graph(P, tiny):
             torch.cuda.synchronize()
             assert torch.equal(out[0], want_i) and torch.equal(out[1], want_d), f"replay {rep}"
         del g
+
+
+def test_workspace_limit_changes_tiling_not_results(P, tiny):
+    w, data, oidx, gidx = tiny
+    q = torch.from_numpy(si.queries(w, 300)).cuda()
+    big = gidx.ivfpq_search_workspace_bytes(300, w.n_probes, w.k, P.LUT_FP8_E5M3)
+    want = gidx.ivfpq_search(q, w.n_probes, w.k, P.LUT_FP8_E5M3)
+    torch.cuda.synchronize()
+    try:
+        gidx.ivfpq_set_workspace_limit(1 << 20)             # a few queries per tile
+        small = gidx.ivfpq_search_workspace_bytes(300, w.n_probes, w.k, P.LUT_FP8_E5M3)
+        assert small < big
+        _step(f"workspace limit 1 MiB: {small} bytes instead of {big}")
+        got = gidx.ivfpq_search(q, w.n_probes, w.k, P.LUT_FP8_E5M3)
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
+        with pytest.raises(P.IvfpqError):
+            gidx.ivfpq_set_workspace_limit(1000)
+    finally:
+        gidx.ivfpq_set_workspace_limit(32 << 30)
