@@ -106,7 +106,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path shards by query across GPUs with no "
-              "communication (see DESIGN.md), and no multi-GPU figure is produced.", file=sys.stderr)
+              "communication, and no multi-GPU figure is produced.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
