@@ -198,22 +198,21 @@ def make_index(d, n_lists, pq_dim, pq_bits, centroids, codebooks, list_offsets, 
 
 
 def pack_codes(codes_per_subspace: np.ndarray, pq_bits: int) -> np.ndarray:
-    """[n][pq_dim] code values -> [n][pq_dim*pq_bits/8] bytes.  p=8: one byte per
-    sub-space; p=4: low nibble = even sub-space, high nibble = odd sub-space."""
+    """[n][pq_dim] code values -> [n][pq_dim*pq_bits/8] bytes: sub-space j in bits [j*p, (j+1)*p) of
+    the vector's bit string, least significant bit first inside every byte (p=8: one byte per
+    sub-space; p=4: low nibble = even sub-space, high nibble = odd sub-space)."""
     c = np.ascontiguousarray(codes_per_subspace, dtype=np.uint8)
-    if pq_bits == 8:
-        return c
-    assert pq_bits == 4 and c.shape[1] % 2 == 0
-    return (c[:, 0::2] | (c[:, 1::2] << 4)).astype(np.uint8)
+    assert 4 <= pq_bits <= 8 and (c.shape[1] * pq_bits) % 8 == 0
+    bits = (c[:, :, None] >> np.arange(pq_bits, dtype=np.uint8)[None, None, :]) & 1      # [n][pq_dim][p], LSB first
+    return np.packbits(bits.reshape(c.shape[0], -1), axis=1, bitorder="little")
 
 
 def unpack_codes(packed: np.ndarray, pq_bits: int) -> np.ndarray:
-    if pq_bits == 8:
-        return packed
-    out = np.empty((packed.shape[0], packed.shape[1] * 2), dtype=np.uint8)
-    out[:, 0::2] = packed & 15
-    out[:, 1::2] = packed >> 4
-    return out
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    bits = np.unpackbits(packed, axis=1, bitorder="little")
+    pq_dim = bits.shape[1] // pq_bits
+    bits = bits[:, :pq_dim * pq_bits].reshape(packed.shape[0], pq_dim, pq_bits)
+    return (bits << np.arange(pq_bits, dtype=np.uint8)[None, None, :]).sum(axis=2).astype(np.uint8)
 
 
 def build_index(data, n_lists: int, pq_dim: int, pq_bits: int, kmeans_iters: int,

@@ -386,13 +386,17 @@ int orc_lut_store(const float* F, int64_t n, int lut_dtype, int truncate, int bi
     return bias;
 }
 
-/* PQ code of sub-space j of one stored vector.  pq_bits = 8: byte j.
- * pq_bits = 4 (the paper treats p = 8 only; reading): byte j/2 holds the
- * even sub-space in its low nibble and the odd one in its high nibble. */
+/* PQ code of sub-space j of one stored vector.  The paper treats p = 8 only (byte j); reading for
+ * 4 <= p <= 8: the codes of a vector form one string of pq_dim * p bits, sub-space j in bits
+ * [j*p, (j+1)*p), bit i of the string being bit (i mod 8) of byte (i div 8).  For p = 4 that puts the
+ * even sub-space in the low nibble of byte j/2 and the odd one in the high nibble. */
 static int code_at(const uint8_t* codes, int j, int pq_bits) {
-    if (pq_bits == 8) return codes[j];
-    uint8_t byte = codes[j >> 1];
-    return (j & 1) ? (byte >> 4) : (byte & 15);
+    int code = 0;
+    for (int b = 0; b < pq_bits; ++b) {
+        int64_t i = (int64_t)j * pq_bits + b;
+        code |= ((codes[i >> 3] >> (i & 7)) & 1) << b;
+    }
+    return code;
 }
 
 /* ------------------------------------------------------------------ */

@@ -149,6 +149,21 @@ def test_pack_unpack_4bit_round_trip():
     np.testing.assert_array_equal(oracle.unpack_codes(p, 4), c)
 
 
+@pytest.mark.parametrize("pq_bits,pq_dim", [(4, 8), (5, 32), (6, 16), (7, 32), (8, 12)])
+def test_pack_codes_is_one_little_endian_bit_string(pq_bits, pq_dim):
+    # independent statement of the layout: the row's codes form the integer sum_j c_j << (j*p), stored
+    # little-endian
+    rng = _rng(140 + pq_bits)
+    c = rng.integers(0, 1 << pq_bits, size=(50, pq_dim), dtype=np.uint8)
+    packed = oracle.pack_codes(c, pq_bits)
+    nbytes = pq_dim * pq_bits // 8
+    assert packed.shape == (50, nbytes)
+    for r in range(50):
+        value = sum(int(c[r, j]) << (j * pq_bits) for j in range(pq_dim))
+        assert bytes(packed[r]) == value.to_bytes(nbytes, "little")
+    np.testing.assert_array_equal(oracle.unpack_codes(packed, pq_bits), c)
+
+
 # ------------------------------------------------------------------ probes
 
 def test_select_probes_is_stable_argsort_of_float64_distances():
@@ -280,14 +295,16 @@ def test_search_pads_when_fewer_than_k_candidates_and_given_probes_are_used():
     assert set(got_ids[1, :n2]) <= set(ids[offs[2]:offs[3]])
 
 
-def test_4bit_search_matches_unpacked_8bit_search():
-    # a 4-bit index is the same thing as an 8-bit index whose codebook has 16 used entries
-    cent, cb4, offs, codes4, ids = si.random_index_arrays(500, 16, 4, 8, 4, salt=36)
-    idx4 = oracle.make_index(16, 4, 8, 4, cent, cb4, offs, codes4, ids)
-    cb8 = np.zeros((8, 256, 2), dtype=np.float32)
-    cb8[:, :16] = cb4
-    idx8 = oracle.make_index(16, 4, 8, 8, cent, cb8, offs, oracle.unpack_codes(codes4, 4), ids)
-    q = _rng(36).standard_normal((10, 16)).astype(np.float32)
+@pytest.mark.parametrize("pq_bits,pq_dim", [(4, 8), (5, 32), (6, 16), (7, 32)])
+def test_bit_packed_search_matches_unpacked_8bit_search(pq_bits, pq_dim):
+    # a p-bit index is the same thing as an 8-bit index whose codebook has 2^p used entries
+    d = 2 * pq_dim
+    cent, cb4, offs, codes4, ids = si.random_index_arrays(500, d, 4, pq_dim, pq_bits, salt=36)
+    idx4 = oracle.make_index(d, 4, pq_dim, pq_bits, cent, cb4, offs, codes4, ids)
+    cb8 = np.zeros((pq_dim, 256, 2), dtype=np.float32)
+    cb8[:, :1 << pq_bits] = cb4
+    idx8 = oracle.make_index(d, 4, pq_dim, 8, cent, cb8, offs, oracle.unpack_codes(codes4, pq_bits), ids)
+    q = _rng(36).standard_normal((10, d)).astype(np.float32)
     for dtype in (oracle.LUT_FP32, oracle.LUT_E5M3):
         a = oracle.search(idx4, q, 3, 10, dtype)
         b = oracle.search(idx8, q, 3, 10, dtype)
