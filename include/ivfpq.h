@@ -67,7 +67,7 @@ enum { IVFPQ_MAX_K = 1024, IVFPQ_MAX_PROBES = 1024 };
  * iterations, start rows drawn from `seed`), (2) residuals to the own centroid, (3) product
  * quantisation of the residuals: pq_dim contiguous sub-vectors of d/pq_dim components, one
  * codebook of 2^pq_bits entries per sub-space, (4) the saved lists, codes and codebook.
- * data: host [n][d] fp32.  Requires d % pq_dim == 0, pq_bits in {4, 8},
+ * data: host [n][d] fp32.  Requires d % pq_dim == 0, 4 <= pq_bits <= 8 (the paper treats 8),
  * (pq_dim*pq_bits/8) % 4 == 0, 1 <= n_lists <= n.  *out receives the new handle. */
 int ivfpq_build_host(const float* data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim,
                      int32_t pq_bits, int32_t kmeans_iters, uint64_t seed, ivfpq_index_t** out);
@@ -106,8 +106,10 @@ int ivfpq_assign_device(const float* d_rows, int64_t n_rows, int32_t d, const fl
  *   centroids    [n_lists][d] f32
  *   codebooks    [pq_dim][2^pq_bits][d/pq_dim] f32
  *   list_offsets [n_lists+1] i64, non-decreasing, [0] = 0, [n_lists] = n
- *   codes        [n][pq_dim*pq_bits/8] u8 in list order; pq_bits = 8: byte j = code of sub-space j;
- *                pq_bits = 4: byte j holds sub-space 2j in its low and 2j+1 in its high nibble
+ *   codes        [n][pq_dim*pq_bits/8] u8 in list order: the codes of a vector are one string of
+ *                pq_dim*pq_bits bits, sub-space j in bits [j*p, (j+1)*p), bit i of the string = bit
+ *                (i mod 8) of byte (i div 8).  pq_bits = 8: byte j = code of sub-space j; pq_bits = 4:
+ *                byte j holds sub-space 2j in its low and 2j+1 in its high nibble
  *   ids          [n] i64 in list order (the caller's labels; returned by search) */
 int ivfpq_index_from_arrays(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,
                             const float* centroids, const float* codebooks, const int64_t* list_offsets,

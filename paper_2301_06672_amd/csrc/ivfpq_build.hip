@@ -284,19 +284,22 @@ __global__ void residual_rows_kernel(const float* __restrict__ data, const int64
     Rt[e] = data[(size_t)row * d + t] - C[(size_t)labels[row] * d + t];
 }
 
-// Nearest codeword per sub-space.  A thread handles position p (blockIdx.x * 256 + threadIdx.x) and the
-// SPW = 32 / BITS sub-spaces whose codes share the 32-bit word blockIdx.y of the packed code; their
-// codebooks sit in LDS.  Row of position p: order[p] (or p); residual = X[row] - C[labels[row]] in
+// Nearest codeword per sub-space.  The codes of a vector are one bit string, sub-space j in bits
+// [j*BITS, (j+1)*BITS); a code group is the shortest run of sub-spaces that ends on a 32-bit boundary
+// (SPG sub-spaces in WPG words: 8 in 1 for 4-bit codes, 4 in 1 for 8-bit, 32 in 5 / 16 in 3 / 32 in 7
+// for 5 / 6 / 7 bits).  A thread handles position p (blockIdx.x * 256 + threadIdx.x) and the code
+// group blockIdx.y; the group's codebooks sit in LDS.  Row of position p: order[p] (or p); residual = X[row] - C[labels[row]] in
 // fp32 (or X[row] itself when C is null).  Outputs (either may be null): train_labels[p][j] =
-// j * ksub + code; codes32[p][word] = the packed codes (low bits = lower sub-space).
+// j * ksub + code; codes32[p][...] = the group's words of the packed code.
 template <int BITS>
 __global__ void __launch_bounds__(256)
 pq_codes_kernel(const float* __restrict__ X, const uint32_t* __restrict__ order, const int32_t* __restrict__ labels,
                 const float* __restrict__ C, const float* __restrict__ codebooks, size_t n_pos, int d, int pq_dim, int m,
                 int32_t* __restrict__ train_labels, uint32_t* __restrict__ codes32) {
-    extern __shared__ float cb[];              // [SPW][ksub][m]
-    constexpr int SPW = 32 / BITS, KSUB = 1 << BITS;
-    const int word = blockIdx.y, j0 = word * SPW;
+    extern __shared__ float cb[];              // [SPG][ksub][m]
+    constexpr int G = (BITS % 8 == 0) ? 8 : (BITS % 4 == 0) ? 4 : (BITS % 2 == 0) ? 2 : 1;   // gcd(BITS, 32)
+    constexpr int SPW = 32 / G, WPG = BITS / G, KSUB = 1 << BITS;                             // SPW: sub-spaces per group
+    const int group = blockIdx.y, j0 = group * SPW;
     const int per_word = SPW * KSUB * m;
     for (int e = threadIdx.x; e < per_word; e += blockDim.x) cb[e] = codebooks[(size_t)j0 * KSUB * m + e];
     __syncthreads();
@@ -305,7 +308,9 @@ pq_codes_kernel(const float* __restrict__ X, const uint32_t* __restrict__ order,
     const size_t row = order ? order[p] : p;
     const float* x = X + row * d;
     const float* c = C ? C + (size_t)labels[row] * d : nullptr;
-    uint32_t packed = 0;
+    unsigned long long acc_bits = 0;           // codes waiting to fill a word, lowest sub-space in the low bits
+    int have = 0, word = 0;
+    const size_t words_per_code = (size_t)(pq_dim / SPW) * WPG;
     for (int s = 0; s < SPW; ++s) {
         const int j = j0 + s;
         const float* xs = x + (size_t)j * m;
@@ -331,13 +336,21 @@ pq_codes_kernel(const float* __restrict__ X, const uint32_t* __restrict__ order,
                 if (dist < best) { best = dist; arg = code; }
             }
         }
-        packed |= (uint32_t)arg << (BITS * s);
         if (train_labels) train_labels[p * pq_dim + j] = j * KSUB + arg;
+        acc_bits |= (unsigned long long)arg << have;
+        have += BITS;
+        if (have >= 32) {
+            if (codes32) codes32[p * words_per_code + (size_t)group * WPG + word] = (uint32_t)acc_bits;
+            acc_bits >>= 32;
+            have -= 32;
+            ++word;
+        }
     }
-    if (codes32) codes32[p * (size_t)(pq_dim / SPW) + word] = packed;
 }
 
 // ---- host side ----------------------------------------------------------------------------------
+inline int sub_spaces_per_group(int bits) { return bits % 8 == 0 ? 4 : bits % 4 == 0 ? 8 : bits % 2 == 0 ? 16 : 32; }
+
 inline unsigned blocks_for(size_t n, unsigned threads) { return (unsigned)((n + threads - 1) / threads); }
 
 struct BuildPlan {
@@ -438,7 +451,7 @@ int group_by_label(const BuildPlan& P, unsigned char* ws, const int32_t* labels,
 int launch_pq_codes(const BuildPlan& P, const float* X, const uint32_t* order, const int32_t* labels, const float* C,
                     const float* codebooks, size_t n_pos, int32_t* train_labels, uint32_t* codes32, hipStream_t st) {
     if (n_pos == 0) return IVFPQ_OK;
-    const int spw = 32 / P.pq_bits;
+    const int spw = sub_spaces_per_group(P.pq_bits);
     const size_t lds = (size_t)spw * P.ksub * P.m * 4;
     dim3 grid(blocks_for(n_pos, 256), (unsigned)(P.pq_dim / spw));
     auto go = [&](auto kernel) -> int {
@@ -448,7 +461,13 @@ int launch_pq_codes(const BuildPlan& P, const float* X, const uint32_t* order, c
         HIP_TRY(hipGetLastError());
         return IVFPQ_OK;
     };
-    return P.pq_bits == 8 ? go(pq_codes_kernel<8>) : go(pq_codes_kernel<4>);
+    switch (P.pq_bits) {
+        case 8: return go(pq_codes_kernel<8>);
+        case 7: return go(pq_codes_kernel<7>);
+        case 6: return go(pq_codes_kernel<6>);
+        case 5: return go(pq_codes_kernel<5>);
+        default: return go(pq_codes_kernel<4>);
+    }
 }
 
 int check_rows(const int64_t* rows, int64_t count, int64_t bound, const char* what) {
@@ -463,9 +482,9 @@ int check_build_args(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int3
     if (n < 1 || n_lists > n) return fail(IVFPQ_EINVAL, "need 1 <= n_lists <= n (n=%lld, n_lists=%d)", (long long)n, n_lists);
     if (kmeans_iters < 0) return fail(IVFPQ_EINVAL, "kmeans_iters=%d", kmeans_iters);
     if (n >= ((int64_t)1 << 31)) return fail(IVFPQ_EUNSUPPORTED, "the device builder handles n < 2^31 rows (n=%lld)", (long long)n);
-    const size_t lds = (size_t)(32 / pq_bits) * ((size_t)1 << pq_bits) * (size_t)(d / pq_dim) * 4;
+    const size_t lds = (size_t)sub_spaces_per_group(pq_bits) * ((size_t)1 << pq_bits) * (size_t)(d / pq_dim) * 4;
     if (lds > kLdsBytes)
-        return fail(IVFPQ_EUNSUPPORTED, "codebooks of one code word need %zu bytes of LDS (limit %zu)", lds, kLdsBytes);
+        return fail(IVFPQ_EUNSUPPORTED, "codebooks of one code group need %zu bytes of LDS (limit %zu)", lds, kLdsBytes);
     return IVFPQ_OK;
 }
 

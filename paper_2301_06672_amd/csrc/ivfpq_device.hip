@@ -741,21 +741,26 @@ __device__ inline float lut_get(const unsigned char* lut, uint32_t idx, const Fp
     else return fp8_to_f32<Fp8Format<LUT>::shift>(lut[idx], fp8);
 }
 
-// adds the table entries selected by the 4 code bytes of `w` (sub-spaces row0.. in ascending order)
+// Bit-packed codes: the codes of a vector are one bit string, sub-space j in bits [j*BITS, (j+1)*BITS).
+// A "code group" is the shortest run of sub-spaces that ends on a 32-bit boundary: SPG sub-spaces in
+// WPG words (8 in 1 for 4-bit codes, 4 in 1 for 8-bit, 32 in 5 / 16 in 3 / 32 in 7 for 5 / 6 / 7 bits).
+template <int BITS> struct CodeGroup {
+    static constexpr int g = (BITS % 8 == 0) ? 8 : (BITS % 4 == 0) ? 4 : (BITS % 2 == 0) ? 2 : 1;   // gcd(BITS, 32)
+    static constexpr int SPG = 32 / g, WPG = BITS / g;
+};
+
+// adds the table entries selected by the SPG codes held in w[0 .. WPG) (sub-spaces row0.. ascending)
 template <int LUT, int BITS>
-__device__ inline float add_word(float acc, const unsigned char* lut, uint32_t w, int row0, const Fp8Params fp8) {
-    if constexpr (BITS == 8) {
+__device__ inline float add_group(float acc, const unsigned char* lut, const uint32_t* w, int row0, const Fp8Params fp8) {
+    constexpr int SPG = CodeGroup<BITS>::SPG, KSUB = 1 << BITS;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            uint32_t code = (w >> (8 * b)) & 255u;
-            acc += lut_get<LUT>(lut, (uint32_t)(row0 + b) * 256u + code, fp8);
-        }
-    } else {
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            uint32_t code = (w >> (4 * b)) & 15u;
-            acc += lut_get<LUT>(lut, (uint32_t)(row0 + b) * 16u + code, fp8);
-        }
+    for (int s = 0; s < SPG; ++s) {
+        constexpr uint32_t mask = (uint32_t)KSUB - 1u;
+        const int bit = s * BITS, wi = bit >> 5, sh = bit & 31;
+        uint32_t code;
+        if (sh + BITS <= 32) code = (w[wi] >> sh) & mask;
+        else code = ((w[wi] >> sh) | (w[wi + 1] << (32 - sh))) & mask;     // the field straddles two words
+        acc += lut_get<LUT>(lut, (uint32_t)(row0 + s) * (uint32_t)KSUB + code, fp8);
     }
     return acc;
 }
@@ -846,7 +851,7 @@ scan_kernel(ScanArgs a) {
     const chunk_t* cbase = reinterpret_cast<const chunk_t*>(codes_l);
 
     constexpr int NBUF = NCH > 0 ? NCH : 1;
-    constexpr int ROWS_PER_WORD = BITS == 8 ? 4 : 8;
+    constexpr int SPG = CodeGroup<BITS>::SPG, WPG = CodeGroup<BITS>::WPG;
 
     auto load_group = [&](chunk_t (&buf)[NBUF], int g) {
 #pragma unroll
@@ -855,18 +860,16 @@ scan_kernel(ScanArgs a) {
     // Eq. (1) for the vector this lane holds in buf: sub-spaces in ascending order
     auto accumulate = [&](const chunk_t (&buf)[NBUF]) -> float {
         float acc = 0.f;
+        if constexpr (CW == 16) {
+            uint32_t w[4 * NBUF];
 #pragma unroll
-        for (int c = 0; c < NBUF; ++c) {
-            if constexpr (CW == 16) {
-                const uint32_t w[4] = {buf[c].x, buf[c].y, buf[c].z, buf[c].w};
+            for (int c = 0; c < NBUF; ++c) { w[4 * c] = buf[c].x; w[4 * c + 1] = buf[c].y; w[4 * c + 2] = buf[c].z; w[4 * c + 3] = buf[c].w; }
+            static_assert((4 * NBUF) % WPG == 0 || NCH == 0, "16-byte chunks must hold whole code groups");
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    acc = add_word<LUT, BITS>(acc, lut, w[i], (c * 4 + i) * ROWS_PER_WORD, fp8);
-            } else {
-                acc = add_word<LUT, BITS>(acc, lut, buf[c], c * ROWS_PER_WORD, fp8);
-            }
+            for (int cg = 0; cg < (4 * NBUF) / WPG; ++cg)
+                acc = add_group<LUT, BITS>(acc, lut, w + cg * WPG, cg * SPG, fp8);
         }
-        return acc;
+        return acc;      // 4-byte chunks take the loop over code groups below instead
     };
     auto flush_stage = [&]() {
         if (staged == 0) return;
@@ -926,11 +929,15 @@ scan_kernel(ScanArgs a) {
             store_R(gn, accumulate(buf_b));
         }
     } else {
+        // 4-byte chunks: one code group (WPG words) at a time
         for (; g < n_groups; g += n_waves) {
             float acc = 0.f;
-            for (int c = 0; c < nch; ++c) {
-                uint32_t w = reinterpret_cast<const uint32_t*>(codes_l)[((size_t)g * nch + c) * 64 + lane];
-                acc = add_word<LUT, BITS>(acc, lut, w, c * ROWS_PER_WORD, fp8);
+            for (int cg = 0; cg < nch / WPG; ++cg) {
+                uint32_t w[WPG];
+#pragma unroll
+                for (int u = 0; u < WPG; ++u)
+                    w[u] = reinterpret_cast<const uint32_t*>(codes_l)[((size_t)g * nch + cg * WPG + u) * 64 + lane];
+                acc = add_group<LUT, BITS>(acc, lut, w, cg * SPG, fp8);
             }
             store_R(g, acc);
         }
@@ -952,8 +959,13 @@ dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centr
     uint32_t* max_slot = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(rq) + (((size_t)d * 4 + 15) & ~(size_t)15));
     for (int t = threadIdx.x; t < d; t += blockDim.x) rq[t] = query[t] - centroid[t];
     __syncthreads();
-    if (bits == 8) (void)stage_table<LUT, 8>(codebooks, rq, pq_dim, m, lut, max_slot, fp8);
-    else (void)stage_table<LUT, 4>(codebooks, rq, pq_dim, m, lut, max_slot, fp8);
+    switch (bits) {
+        case 8: (void)stage_table<LUT, 8>(codebooks, rq, pq_dim, m, lut, max_slot, fp8); break;
+        case 7: (void)stage_table<LUT, 7>(codebooks, rq, pq_dim, m, lut, max_slot, fp8); break;
+        case 6: (void)stage_table<LUT, 6>(codebooks, rq, pq_dim, m, lut, max_slot, fp8); break;
+        case 5: (void)stage_table<LUT, 5>(codebooks, rq, pq_dim, m, lut, max_slot, fp8); break;
+        default: (void)stage_table<LUT, 4>(codebooks, rq, pq_dim, m, lut, max_slot, fp8); break;
+    }
     for (size_t i = threadIdx.x; i < lut_bytes / 4; i += blockDim.x)
         reinterpret_cast<uint32_t*>(out)[i] = reinterpret_cast<const uint32_t*>(lut)[i];
 }
@@ -1085,8 +1097,9 @@ struct ImageLayout {
 };
 
 int chunk_width(const ivfpq_index* idx) {
-    int cb = idx->code_bytes();
-    return (cb % 16 == 0 && cb / 16 <= 4) ? 16 : 4;
+    const int cb = idx->code_bytes(), p = idx->pq_bits;
+    const bool wide = cb % 16 == 0 && cb / 16 <= 4 && (p == 4 || p == 8 || (p == 6 && cb == 48));
+    return wide ? 16 : 4;
 }
 
 ImageLayout image_layout(const ivfpq_index* idx) {
@@ -1200,16 +1213,33 @@ int launch_scan_bits(const ScanArgs& a, int cw, int nch, dim3 grid, int threads,
         return IVFPQ_OK;
     };
     if (cw == 16) {
-        switch (nch) {
-            case 1: return go(scan_kernel<LUT, BITS, 16, 1>);
-            case 2: return go(scan_kernel<LUT, BITS, 16, 2>);
-            case 3: return go(scan_kernel<LUT, BITS, 16, 3>);
-            case 4: return go(scan_kernel<LUT, BITS, 16, 4>);
-            default: break;
+        // 16-byte chunks need whole code groups per vector's chunk set: always true for 4- and 8-bit
+        // codes; of the other widths only 6-bit codes with 48 bytes per vector qualify
+        if constexpr (BITS == 4 || BITS == 8) {
+            switch (nch) {
+                case 1: return go(scan_kernel<LUT, BITS, 16, 1>);
+                case 2: return go(scan_kernel<LUT, BITS, 16, 2>);
+                case 3: return go(scan_kernel<LUT, BITS, 16, 3>);
+                case 4: return go(scan_kernel<LUT, BITS, 16, 4>);
+                default: break;
+            }
+        } else if constexpr (BITS == 6) {
+            if (nch == 3) return go(scan_kernel<LUT, BITS, 16, 3>);
         }
-        return fail(IVFPQ_EUNSUPPORTED, "internal: no scan kernel for %d chunks of 16 bytes", nch);
+        return fail(IVFPQ_EUNSUPPORTED, "internal: no scan kernel for %d chunks of 16 bytes of %d-bit codes", nch, BITS);
     }
     return go(scan_kernel<LUT, BITS, 4, 0>);
+}
+
+template <int LUT>
+int launch_scan_lut(const ScanArgs& a, int bits, int cw, int nch, dim3 grid, int threads, size_t lds, hipStream_t st) {
+    switch (bits) {
+        case 8: return launch_scan_bits<LUT, 8>(a, cw, nch, grid, threads, lds, st);
+        case 7: return launch_scan_bits<LUT, 7>(a, cw, nch, grid, threads, lds, st);
+        case 6: return launch_scan_bits<LUT, 6>(a, cw, nch, grid, threads, lds, st);
+        case 5: return launch_scan_bits<LUT, 5>(a, cw, nch, grid, threads, lds, st);
+        default: return launch_scan_bits<LUT, 4>(a, cw, nch, grid, threads, lds, st);
+    }
 }
 
 int launch_scan(const ivfpq_index* idx, ScanArgs a, int lut_dtype, dim3 grid, hipStream_t st) {
@@ -1220,20 +1250,12 @@ int launch_scan(const ivfpq_index* idx, ScanArgs a, int lut_dtype, dim3 grid, hi
     const int cw = chunk_width(idx);
     const int nch = idx->code_bytes() / cw;
     a.n_chunks = nch;
-    const bool b8 = idx->pq_bits == 8;
+    const int bits = idx->pq_bits;
     switch (lut_dtype) {
-        case IVFPQ_LUT_FP32:
-            return b8 ? launch_scan_bits<IVFPQ_LUT_FP32, 8>(a, cw, nch, grid, threads, lds, st)
-                      : launch_scan_bits<IVFPQ_LUT_FP32, 4>(a, cw, nch, grid, threads, lds, st);
-        case IVFPQ_LUT_FP16:
-            return b8 ? launch_scan_bits<IVFPQ_LUT_FP16, 8>(a, cw, nch, grid, threads, lds, st)
-                      : launch_scan_bits<IVFPQ_LUT_FP16, 4>(a, cw, nch, grid, threads, lds, st);
-        case IVFPQ_LUT_FP8_E5M3:
-            return b8 ? launch_scan_bits<IVFPQ_LUT_FP8_E5M3, 8>(a, cw, nch, grid, threads, lds, st)
-                      : launch_scan_bits<IVFPQ_LUT_FP8_E5M3, 4>(a, cw, nch, grid, threads, lds, st);
-        default:
-            return b8 ? launch_scan_bits<IVFPQ_LUT_FP8_E4M4, 8>(a, cw, nch, grid, threads, lds, st)
-                      : launch_scan_bits<IVFPQ_LUT_FP8_E4M4, 4>(a, cw, nch, grid, threads, lds, st);
+        case IVFPQ_LUT_FP32: return launch_scan_lut<IVFPQ_LUT_FP32>(a, bits, cw, nch, grid, threads, lds, st);
+        case IVFPQ_LUT_FP16: return launch_scan_lut<IVFPQ_LUT_FP16>(a, bits, cw, nch, grid, threads, lds, st);
+        case IVFPQ_LUT_FP8_E5M3: return launch_scan_lut<IVFPQ_LUT_FP8_E5M3>(a, bits, cw, nch, grid, threads, lds, st);
+        default: return launch_scan_lut<IVFPQ_LUT_FP8_E4M4>(a, bits, cw, nch, grid, threads, lds, st);
     }
 }
 

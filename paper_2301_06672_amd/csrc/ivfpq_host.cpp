@@ -39,7 +39,7 @@ int check_shape(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t p
     if (n < 0 || d < 1 || n_lists < 1 || pq_dim < 1)
         return fail(IVFPQ_EINVAL, "bad shape: n=%lld d=%d n_lists=%d pq_dim=%d", (long long)n, d, n_lists, pq_dim);
     if (d % pq_dim != 0) return fail(IVFPQ_EINVAL, "d=%d is not a multiple of pq_dim=%d", d, pq_dim);
-    if (pq_bits != 4 && pq_bits != 8) return fail(IVFPQ_EINVAL, "pq_bits=%d, must be 4 or 8", pq_bits);
+    if (pq_bits < 4 || pq_bits > 8) return fail(IVFPQ_EINVAL, "pq_bits=%d, must be 4 ... 8", pq_bits);
     if ((pq_dim * pq_bits) % 32 != 0)
         return fail(IVFPQ_EINVAL, "pq_dim*pq_bits/8 = %g bytes per vector, must be a multiple of 4",
                     pq_dim * pq_bits / 8.0);
@@ -268,8 +268,14 @@ int ivfpq_build_host(const float* data, int64_t n, int32_t d, int32_t n_lists, i
     for (int64_t i = 0; i < n; ++i) {
         const uint8_t* s = &sub_codes[(size_t)i * pq_dim];
         uint8_t* o = &idx->codes[(size_t)i * cb];
-        if (pq_bits == 8) std::memcpy(o, s, (size_t)cb);
-        else for (int b = 0; b < cb; ++b) o[b] = (uint8_t)(s[2 * b] | (s[2 * b + 1] << 4));
+        // one bit string per vector: sub-space j in bits [j*p, (j+1)*p), least significant bit first
+        uint32_t acc = 0;
+        int have = 0, at = 0;
+        for (int j = 0; j < pq_dim; ++j) {
+            acc |= (uint32_t)s[j] << have;
+            have += pq_bits;
+            while (have >= 8) { o[at++] = (uint8_t)acc; acc >>= 8; have -= 8; }
+        }
     }
     finish_import(idx);
     *out = idx;

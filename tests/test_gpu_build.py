@@ -84,6 +84,9 @@ def _assert_same_index(gidx, oidx):
     (20_000, 16, 2, 16, 8, 2, 20_000, 3_000, "gauss"),      # two huge lists: groups longer than one LDS sort
     (5_000, 32, 40, 32, 8, 3, 2_500, 2_000, "intgrid"),     # m = 1, tied distances everywhere
     (3_000, 32, 48, 16, 8, 0, 1_000, 1_000, "gauss"),       # no Lloyd iteration: the start rows are the centres
+    (4_000, 64, 12, 32, 5, 2, 4_000, 2_000, "gauss"),       # 5-bit codes: 32 sub-spaces in 5 words
+    (4_000, 32, 12, 16, 6, 2, 2_000, 2_000, "gauss"),       # 6-bit codes: 16 sub-spaces in 3 words
+    (4_000, 64, 12, 32, 7, 2, 4_000, 2_000, "intgrid"),     # 7-bit codes, tied distances
 ])
 def test_build_device_is_identical_to_oracle_build(P, n, d, n_lists, pq_dim, pq_bits, iters, n_ct, n_pt, kind):
     x = _data(n, d, 100 + n + d, 0.0, kind)

@@ -57,7 +57,8 @@ def test_lut_bytes_identical_tiny(P, tiny, dtype):
 
 
 @pytest.mark.parametrize("d,pq_dim,pq_bits", [(32, 32, 8), (32, 16, 8), (32, 8, 8), (48, 16, 8), (24, 8, 4),
-                                              (128, 64, 8), (96, 48, 8), (128, 64, 4), (128, 32, 8)])
+                                              (128, 64, 8), (96, 48, 8), (128, 64, 4), (128, 32, 8),
+                                              (64, 32, 5), (96, 16, 6), (128, 64, 6), (64, 32, 7), (128, 64, 7)])
 def test_lut_bytes_identical_shapes_and_ranges(P, d, pq_dim, pq_bits):
     # sub-vector lengths 1, 2, 4 (templated) and 3 (generic); value scales that reach below the
     # smallest e5m3 value, into the half subnormals, and above the largest half / e5m3 value
@@ -186,9 +187,12 @@ def test_scan_list_R_tiny(P, tiny, dtype):
 
 
 @pytest.mark.parametrize("d,pq_dim,pq_bits", [(128, 64, 8), (96, 48, 8), (128, 64, 4), (128, 32, 8), (32, 16, 8),
-                                              (24, 24, 8), (24, 8, 4), (160, 80, 8)])
+                                              (24, 24, 8), (24, 8, 4), (160, 80, 8),
+                                              (64, 32, 5), (96, 16, 6), (128, 64, 6), (64, 32, 7), (128, 64, 7), (256, 128, 5)])
 def test_scan_list_R_code_widths(P, d, pq_dim, pq_bits):
     # 64/48/32/16-byte codes (16-byte chunk kernels) and 24/4/80-byte codes (generic 4-byte path);
+    # bit-packed 5/6/7-bit codes whose fields straddle words (20/12/28/56/80 bytes on the 4-byte path,
+    # 48 bytes of 6-bit codes on the 16-byte path);
     # list lengths that span several 64-vector groups with a ragged tail
     oidx, gidx = random_pair(P, 1500, d, 4, pq_dim, pq_bits, salt=200 + d + pq_bits)
     q = np.random.default_rng(pq_dim).standard_normal(d).astype(np.float32)
@@ -274,7 +278,8 @@ def test_search_tiny_probe_and_k_range(P, tiny, n_probes, k):
         assert_topk_matches(ids_g, d_g, ids_o, d_o, context=f"P={n_probes} k={k} dtype={dtype}")
 
 
-@pytest.mark.parametrize("d,pq_dim,pq_bits", [(128, 64, 8), (96, 48, 8), (128, 64, 4), (128, 32, 8), (24, 8, 4)])
+@pytest.mark.parametrize("d,pq_dim,pq_bits", [(128, 64, 8), (96, 48, 8), (128, 64, 4), (128, 32, 8), (24, 8, 4),
+                                              (64, 32, 5), (128, 64, 6), (32, 16, 6), (128, 64, 7)])
 def test_search_random_index_ragged_and_empty_lists(P, d, pq_dim, pq_bits):
     oidx, gidx = random_pair(P, 5000, d, 37, pq_dim, pq_bits, salt=400 + d + pq_bits, empty_lists=(0, 5, 36))
     q = np.random.default_rng(400).standard_normal((50, d)).astype(np.float32)

@@ -62,7 +62,9 @@ def test_import_export_round_trip(P):
 
 @pytest.mark.parametrize("kw,needle", [
     (dict(d=30, pq_dim=16), "multiple of pq_dim"),
-    (dict(pq_bits=5), "pq_bits"),
+    (dict(pq_bits=3), "pq_bits"),
+    (dict(pq_bits=9), "pq_bits"),
+    (dict(pq_bits=5), "multiple of 4"),
     (dict(d=6, pq_dim=6, pq_bits=4), "multiple of 4"),
     (dict(n_lists=0), "bad shape"),
 ])
@@ -152,6 +154,28 @@ def test_host_builder_structure_and_recall(P):
     np.testing.assert_array_equal(again[3], codes)
     other = P.Index.ivfpq_build_host(data, w.n_lists, w.pq_dim, w.pq_bits, w.kmeans_iters, seed=8).ivfpq_index_export()
     assert not np.array_equal(other[0], cent)
+
+
+@pytest.mark.parametrize("pq_bits", [5, 6, 7])
+def test_host_builder_bit_packed_codes(P, pq_bits):
+    # the host builder packs p-bit codes as one little-endian bit string: unpacked with the oracle's
+    # reader, each code is the nearest codeword of its residual sub-vector
+    w = si.WORKLOADS["tiny"].with_(n=1500)
+    data = si.dataset(w)                        # d = 32
+    idx = P.Index.ivfpq_build_host(data, 6, 32, pq_bits, 3, seed=2)
+    cent, cb, offs, codes, ids = idx.ivfpq_index_export()
+    assert codes.shape == (1500, 32 * pq_bits // 8) and cb.shape == (32, 1 << pq_bits, 1)
+    labels = np.repeat(np.arange(6), np.diff(offs))
+    res = data[ids] - cent[labels]
+    sub = oracle.unpack_codes(codes, pq_bits)
+    assert sub.max() < (1 << pq_bits)
+    rows = np.random.default_rng(1).choice(1500, 60, replace=False)
+    agree = 0
+    for r in rows:
+        for j in range(32):
+            dist = (cb[j, :, 0].astype(np.float64) - res[r, j]) ** 2
+            agree += int(sub[r, j] == dist.argmin())
+    assert agree >= 0.99 * 60 * 32
 
 
 def test_host_builder_4bit_codes_pack_low_nibble_first(P):
