@@ -788,6 +788,9 @@ struct ScanArgs {
     int d, pq_dim, m, bits;
     int n_chunks;                 // chunks per vector (code_bytes / CW)
     int single_list;              // >= 0: scan this cluster for query 0, R written from offset 0
+    const uint32_t* order;        // mode 2: pairs (as q * (n_probes - 1) + probe - 1) grouped by cluster, or null
+    uint32_t n_pairs;             // mode 2: number of such pairs
+    uint32_t order_block;         // mode 2: consecutive pairs of the grouped order that stay on one XCD
 };
 
 // Code layout of one cluster (written by ivfpq_upload): vectors in groups of 64 (the last one
@@ -819,9 +822,20 @@ scan_kernel(ScanArgs a) {
         if (a.mode == 1) {
             q = blockIdx.x;
             pair_idx = (size_t)q * a.n_probes;
-        } else {
+        } else if (a.order == nullptr) {
             q = blockIdx.x / (a.n_probes - 1);
             pair_idx = (size_t)q * a.n_probes + 1 + (blockIdx.x - q * (a.n_probes - 1));
+        } else {
+            // Pairs grouped by cluster, and workgroups go round-robin to the 8 XCDs: blocks of
+            // `order_block` consecutive pairs of the grouped order are dealt to the XCDs in turn, so that
+            // the workgroups scanning one cluster run on one XCD (a few, for a cluster with many pairs)
+            // at about the same time and its codes come from that XCD's L2 after the first read.
+            const uint32_t xcd = blockIdx.x & 7u, rank = blockIdx.x >> 3;
+            const uint32_t slot = ((rank / a.order_block) * 8u + xcd) * a.order_block + rank % a.order_block;
+            if (slot >= a.n_pairs) return;
+            const uint32_t lin = a.order[slot];
+            q = (int)(lin / (uint32_t)(a.n_probes - 1));
+            pair_idx = (size_t)q * a.n_probes + 1 + (lin - (uint32_t)q * (uint32_t)(a.n_probes - 1));
         }
         const uint4 pair = a.pairs[pair_idx];
         l = (int)pair.x; len = pair.y; first_group = pair.z;
@@ -968,6 +982,61 @@ dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centr
     }
     for (size_t i = threadIdx.x; i < lut_bytes / 4; i += blockDim.x)
         reinterpret_cast<uint32_t*>(out)[i] = reinterpret_cast<const uint32_t*>(lut)[i];
+}
+
+// ================================================================================================
+// The (query, probe) pairs of the filtered scan grouped by cluster (a counting sort: count, offsets,
+// scatter; the order inside a cluster is whatever the atomics give and does not affect any result).
+// ================================================================================================
+__global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ void pair_count_kernel(const uint4* __restrict__ pairs, uint32_t n_pairs, int n_probes, int n_lists,
+                                  uint32_t* __restrict__ counts) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_pairs) return;
+    const uint32_t q = i / (uint32_t)(n_probes - 1), p = 1 + i - q * (uint32_t)(n_probes - 1);
+    const uint32_t l = pairs[(size_t)q * n_probes + p].x;
+    atomicAdd(&counts[l < (uint32_t)n_lists ? l : 0u], 1u);       // a caller-given probe may be out of range
+}
+
+// offsets[l] = counts[0] + ... + counts[l-1]; one workgroup
+__global__ void __launch_bounds__(1024)
+pair_offsets_kernel(const uint32_t* __restrict__ counts, int n_lists, uint32_t* __restrict__ offsets) {
+    __shared__ uint32_t part[1024];
+    __shared__ uint32_t carry;
+    const int tid = threadIdx.x;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < n_lists; base += 1024) {
+        const int l = base + tid;
+        const uint32_t own = l < n_lists ? counts[l] : 0u;
+        part[tid] = own;
+        __syncthreads();
+        for (int off = 1; off < 1024; off <<= 1) {
+            const uint32_t v = tid >= off ? part[tid - off] : 0u;
+            __syncthreads();
+            part[tid] += v;
+            __syncthreads();
+        }
+        if (l < n_lists) offsets[l] = carry + part[tid] - own;
+        __syncthreads();
+        if (tid == 1023) carry += part[1023];
+        __syncthreads();
+    }
+}
+
+__global__ void pair_scatter_kernel(const uint4* __restrict__ pairs, uint32_t n_pairs, int n_probes, int n_lists,
+                                    const uint32_t* __restrict__ offsets, uint32_t* __restrict__ cursor,
+                                    uint32_t* __restrict__ order) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_pairs) return;
+    const uint32_t q = i / (uint32_t)(n_probes - 1), p = 1 + i - q * (uint32_t)(n_probes - 1);
+    uint32_t l = pairs[(size_t)q * n_probes + p].x;
+    if (l >= (uint32_t)n_lists) l = 0u;
+    order[offsets[l] + atomicAdd(&cursor[l], 1u)] = i;
 }
 
 // ================================================================================================
@@ -1121,7 +1190,7 @@ ImageLayout image_layout(const ivfpq_index* idx) {
 struct Plan {
     int64_t tile;           // queries per tile
     size_t stride;          // R slots per query
-    size_t probes, probe_d, roff, pairs, bounds, counts, D, R, Rpos, total;
+    size_t probes, probe_d, roff, pairs, bounds, counts, D, R, Rpos, order, list_counts, list_cursor, list_offsets, total;
 };
 
 
@@ -1151,6 +1220,10 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     plan->D = take(need_D ? (size_t)tile * idx->n_lists * 4 : 0);
     plan->R = take((size_t)tile * stride * 4);
     plan->Rpos = take((size_t)tile * stride * 4);
+    plan->order = take((size_t)tile * (n_probes > 1 ? n_probes - 1 : 0) * 4);
+    plan->list_counts = take((size_t)idx->n_lists * 4);
+    plan->list_cursor = take((size_t)idx->n_lists * 4);
+    plan->list_offsets = take((size_t)idx->n_lists * 4);
     plan->total = at;
     return IVFPQ_OK;
 }
@@ -1203,6 +1276,13 @@ int scan_threads(const ivfpq_index* idx, int lut_dtype) {
     if (2 * (lds + (size_t)16 * kStageCap * 8) <= kLdsBytes) return 1024;
     return 512;
 }
+
+// The filtered scan runs its pairs grouped by cluster unless their number does not fit the 32-bit
+// order array.  Measured on MI355X (10,000 queries): scan stage 10.4 -> 6.8 ms at 10^8 vectors,
+// 1.91 -> 1.51 ms at 10^7, 3.92 -> 3.73 ms at 10^6 (sort kernels included).
+constexpr uint32_t kOrderBlock = 64;     // consecutive pairs of the grouped order that stay on one XCD
+
+bool group_pairs_by_cluster(size_t n_pairs) { return n_pairs < ((size_t)1 << 32) - 8 * (size_t)kOrderBlock; }
 
 template <int LUT, int BITS>
 int launch_scan_bits(const ScanArgs& a, int cw, int nch, dim3 grid, int threads, size_t lds, hipStream_t st) {
@@ -1373,7 +1453,31 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
                                w_bounds, w_counts);
             HIP_TRY(hipGetLastError());
             a.mode = 2;
-            if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)((size_t)tq * (n_probes - 1))), st)) return s;
+            const size_t n_pairs = (size_t)tq * (n_probes - 1);
+            if (group_pairs_by_cluster(n_pairs)) {
+                uint32_t* w_order = (uint32_t*)(ws + plan.order);
+                uint32_t* w_lc = (uint32_t*)(ws + plan.list_counts);
+                uint32_t* w_cur = (uint32_t*)(ws + plan.list_cursor);
+                uint32_t* w_lo = (uint32_t*)(ws + plan.list_offsets);
+                const unsigned pb = (unsigned)((n_pairs + 255) / 256);
+                // counts and cursors are adjacent in the plan only up to alignment: two fills
+                hipLaunchKernelGGL(fill_u32_kernel, dim3((idx->n_lists + 255) / 256), dim3(256), 0, st, w_lc, (size_t)idx->n_lists, 0u);
+                hipLaunchKernelGGL(fill_u32_kernel, dim3((idx->n_lists + 255) / 256), dim3(256), 0, st, w_cur, (size_t)idx->n_lists, 0u);
+                hipLaunchKernelGGL(pair_count_kernel, dim3(pb), dim3(256), 0, st, w_pairs, (uint32_t)n_pairs, n_probes, idx->n_lists, w_lc);
+                hipLaunchKernelGGL(pair_offsets_kernel, dim3(1), dim3(1024), 0, st, w_lc, idx->n_lists, w_lo);
+                hipLaunchKernelGGL(pair_scatter_kernel, dim3(pb), dim3(256), 0, st, w_pairs, (uint32_t)n_pairs, n_probes, idx->n_lists,
+                                   w_lo, w_cur, w_order);
+                HIP_TRY(hipGetLastError());
+                a.order = w_order;
+                a.n_pairs = (uint32_t)n_pairs;
+                uint32_t blk = kOrderBlock;
+                if (const char* env = std::getenv("IVFPQ_ORDER_BLOCK")) blk = (uint32_t)std::max(1, std::atoi(env));
+                a.order_block = blk;
+                const size_t grid = (n_pairs + 8 * (size_t)blk - 1) / (8 * (size_t)blk) * (8 * (size_t)blk);
+                if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)grid), st)) return s;
+            } else {
+                if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)n_pairs), st)) return s;
+            }
         }
         if (int s = t1.end()) return s;
         // step 5
