@@ -28,8 +28,14 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth, GB/s
 # for a plain 1 GiB copy (FETCH_SIZE reads half the true KiB on this chip, WRITE_SIZE the true
 # figure): profiles/scan_kernel_<workload>_e5m3_hbm_traffic.txt.  None where no run is recorded.
 MEASURED_TRAFFIC = {
-    ("intgrid_1m", "e5m3"): 18.449e9,     # 18.39 GB fetched + 0.055 GB written (algorithmic: 30.98 GB of codes)
-    ("unitnorm_10m", "e5m3"): 9.826e9,    # 9.763 GB fetched + 0.063 GB written (algorithmic: 9.42 GB of codes)
+    ("intgrid_1m", "e5m3"): 1.171e9,      # 1.12 GB fetched + 0.055 GB written (algorithmic: 30.98 GB of codes,
+                                          # served by the caches: the pairs run grouped by cluster)
+    ("unitnorm_10m", "e5m3"): 1.470e9,    # 1.41 GB fetched + 0.063 GB written (algorithmic: 9.42 GB of codes)
+}
+# busy fractions of the other units during scan_kernel, same profiles (profiles/scan_kernel_*_lds_counters.txt)
+MEASURED_UNITS = {
+    ("intgrid_1m", "e5m3"): {"lds_busy": 0.96, "valu_busy": 0.96},
+    ("unitnorm_10m", "e5m3"): {"lds_busy": 0.81, "valu_busy": 1.0},
 }
 
 
@@ -259,8 +265,12 @@ def main():
         "traffic": MEASURED_TRAFFIC.get((w.name, args.lut)),
         "algorithmic_bytes_per_step": code_bytes, "scanned_vectors_per_step": scanned_vectors,
         "scan_ms_per_step": round(scan_ms, 4),
+        "other_units": MEASURED_UNITS.get((w.name, args.lut)),
         "note": "achieved, traffic and the byte counts are per step = all scan_kernel launches of one step "
-                "(one launch per query tile); the ratio equals bytes per launch / average launch time",
+                "(two launches per query tile); the ratio equals bytes per launch / average launch time. "
+                "achieved counts the algorithmic PQ-code bytes; traffic is what HBM delivered: pairs run grouped by "
+                "cluster, so most re-reads of a cluster's codes hit the L2 and the kernel is bound by the vector "
+                "ALU and the LDS (other_units), not by HBM",
     }
 
     cpu = None
