@@ -284,8 +284,17 @@ __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restric
     if (n > (uint32_t)CAND_CAP) {
         uint32_t r0, r1;
         if (!have_bound) {
-            for (int i = tid; i < CAND_CAP; i += nth) t.cand_key[i] = row[i];
-            bound = block_kth_key(s, (uint32_t)CAND_CAP, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1);
+            // the k-th smallest of the first S keys bounds the k-th smallest of the row; about k n / S keys
+            // pass it, so S grows with k n until half the LDS buffer is the expectation (a second pass
+            // over the whole row costs more than a longer sample)
+            const unsigned long long want = (unsigned long long)kk * n / (CAND_CAP / 2);
+            const uint32_t S = want <= (unsigned long long)CAND_CAP ? (uint32_t)CAND_CAP : (want < n ? (uint32_t)want : n);
+            if (S == (uint32_t)CAND_CAP) {
+                for (int i = tid; i < CAND_CAP; i += nth) t.cand_key[i] = row[i];
+                bound = block_kth_key(s, (uint32_t)CAND_CAP, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1);
+            } else {
+                bound = block_kth_key(s, S, kk, [&](uint32_t i) { return row[i]; }, &r0, &r1);
+            }
         }
         bound = widen(bound);
         const bool vec = (n & 3u) == 0 && (reinterpret_cast<uintptr_t>(row) & 15u) == 0;
