@@ -241,6 +241,35 @@ def test_select_probes_many_lists_and_exact_ties(P):
         np.testing.assert_array_equal(row, [50] + list(range(100, 110)))
 
 
+def test_select_probes_6000_lists_ties_and_outliers(P):
+    # 6000 clusters: the bound of the n_probes-th ranking value comes from a sample of the row that grows
+    # with n_probes.  Duplicated centroids far apart in the row give exact ties; a query far from
+    # everything and one on a centroid are included.
+    arrays = list(si.random_index_arrays(7000, 64, 6000, 32, 8, salt=310))
+    arrays[0][5000:5006] = arrays[0][40]        # copies of a sampled centroid among the unsampled ones
+    arrays[0][3000] = arrays[0][2999]
+    oidx = oracle.make_index(64, 6000, 32, 8, *arrays)
+    gidx = to_library(P, oidx)
+    rng = np.random.default_rng(310)
+    q = rng.standard_normal((70, 64)).astype(np.float32)
+    q[:4] = arrays[0][40] + 0.01 * rng.standard_normal((4, 64)).astype(np.float32)
+    q[4] = arrays[0][5500]
+    q[5] = 50.0
+    for n_probes in (1, 7, 64, 300, 1000):
+        _step(f"select_probes L=6000 P={n_probes}")
+        probes, pd = gidx.ivfpq_select_probes(q, n_probes)
+        probes = probes.cpu().numpy().view(np.uint32)
+        assert_probes_match(probes, oidx.centroids, q, n_probes)
+        want, want_d = oracle.select_probes(oidx, q, n_probes)
+        np.testing.assert_allclose(pd.cpu().numpy(), want_d, rtol=RTOL)
+    probes, _ = gidx.ivfpq_select_probes(q[:4], 7)
+    for row in probes.cpu().numpy().view(np.uint32):
+        np.testing.assert_array_equal(row, [40] + list(range(5000, 5006)))
+    for dtype in (oracle.LUT_FP32, oracle.LUT_E5M3):
+        ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, 64, 20, dtype)
+        assert_topk_matches(ids_g, d_g, ids_o, d_o, context=f"6000 lists dtype={dtype}")
+
+
 # ---------------------------------------------------------------- whole search (steps 1-5)
 
 def _search_both(gidx, oidx, q, n_probes, k, dtype):
