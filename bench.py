@@ -159,7 +159,9 @@ def main():
             x_dev = None
         torch.cuda.empty_cache()
     log(f"index build ({builder}, {args.kmeans_iters} Lloyd iterations) {time.time() - t0:.1f}s")
+    t0 = time.time()
     idx.ivfpq_upload()
+    log(f"ivfpq_upload (codes re-laid out on the host, copied to the device) {time.time() - t0:.2f}s")
     idx.ivfpq_set_e4m4_bias(e4m4_bias)
     cent, cb, offs, codes, ids_arr = idx.ivfpq_index_export()
     sizes = np.diff(offs)

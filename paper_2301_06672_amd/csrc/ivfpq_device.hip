@@ -21,6 +21,7 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <thread>
 #include <type_traits>
 #include <utility>
 
@@ -1563,20 +1564,30 @@ int ivfpq_upload(ivfpq_index_t* idx, void* d_buf, size_t bytes, void* hip_stream
     while (g_done < idx->total_groups) {
         const int64_t g_end = std::min<int64_t>(idx->total_groups, g_done + (int64_t)stage_groups);
         stage.assign((size_t)(g_end - g_done) * group_bytes, 0);
-        // clusters overlapping [g_done, g_end)
-        int l_first = (int)(std::upper_bound(goff.begin(), goff.end(), g_done) - goff.begin()) - 1;
-        for (int l = l_first; l < idx->n_lists; ++l) {
-            if (goff[l] >= g_end) continue;
-            const int64_t lo = idx->list_offsets[l], len = idx->list_offsets[l + 1] - lo;
-            for (int64_t g = std::max(goff[l], g_done); g < std::min(goff[l + 1], g_end); ++g) {
-                uint8_t* dst = stage.data() + (size_t)(g - g_done) * group_bytes;
-                const int64_t first = (g - goff[l]) * 64;
-                for (int v = 0; v < 64 && first + v < len; ++v) {
-                    const uint8_t* src = &idx->codes[(size_t)(lo + first + v) * cb];
-                    for (int c = 0; c < nch; ++c)
-                        std::memcpy(dst + ((size_t)c * 64 + v) * cw, src + (size_t)c * cw, (size_t)cw);
+        // clusters overlapping [g_done, g_end), dealt to a few host threads (each writes its own groups)
+        const int l_first = (int)(std::upper_bound(goff.begin(), goff.end(), g_done) - goff.begin()) - 1;
+        const int l_last = (int)(std::lower_bound(goff.begin(), goff.end(), g_end) - goff.begin());   // exclusive
+        auto interleave = [&](int t, int n_threads) {
+            for (int l = l_first + t; l < l_last && l < idx->n_lists; l += n_threads) {
+                const int64_t lo = idx->list_offsets[l], len = idx->list_offsets[l + 1] - lo;
+                for (int64_t g = std::max(goff[l], g_done); g < std::min(goff[l + 1], g_end); ++g) {
+                    uint8_t* dst = stage.data() + (size_t)(g - g_done) * group_bytes;
+                    const int64_t first = (g - goff[l]) * 64;
+                    for (int v = 0; v < 64 && first + v < len; ++v) {
+                        const uint8_t* src = &idx->codes[(size_t)(lo + first + v) * cb];
+                        for (int c = 0; c < nch; ++c)
+                            std::memcpy(dst + ((size_t)c * 64 + v) * cw, src + (size_t)c * cw, (size_t)cw);
+                    }
                 }
             }
+        };
+        const int n_threads = (int)std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
+        if (n_threads == 1 || l_last - l_first < 64) {
+            interleave(0, 1);
+        } else {
+            std::vector<std::thread> pool;
+            for (int t = 0; t < n_threads; ++t) pool.emplace_back(interleave, t, n_threads);
+            for (auto& th : pool) th.join();
         }
         HIP_TRY(hipMemcpy(base + L.codes + (size_t)g_done * group_bytes, stage.data(), stage.size(), hipMemcpyHostToDevice));
         g_done = g_end;
