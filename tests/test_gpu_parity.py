@@ -544,3 +544,41 @@ def test_workspace_limit_changes_tiling_not_results(P, tiny):
             gidx.ivfpq_set_workspace_limit(1000)
     finally:
         gidx.ivfpq_set_workspace_limit(32 << 30)
+
+
+# ---------------------------------------------------------------- seeded random configurations
+
+def test_search_seeded_random_configurations(P):
+    # thirty configurations drawn from a seeded generator: code widths 4-8 bits, sub-vector lengths 1-6,
+    # few or many clusters (some empty), any table dtype and encoding option, k and n_probes up to the
+    # limits that the configuration allows
+    rng = np.random.default_rng(20230106)
+    for case in range(30):
+        bits = int(rng.integers(4, 9))
+        unit = {4: 8, 5: 32, 6: 16, 7: 32, 8: 4}[bits]             # sub-spaces per 32-bit boundary
+        pq_dim = unit * int(rng.integers(1, 5 if unit < 32 else 3))
+        m = int(rng.choice([1, 2, 3, 4, 6]))
+        d = pq_dim * m
+        n_lists = int(rng.choice([1, 2, 7, 33, 200, 1500]))
+        n = int(rng.integers(max(n_lists, 50), 6000))
+        empty = tuple(int(v) for v in rng.choice(n_lists, size=min(3, n_lists - 1), replace=False)) if n_lists > 3 else ()
+        n_probes = int(rng.integers(1, min(n_lists, 40) + 1))
+        k = int(rng.choice([1, 5, 10, 100, 1000]))
+        dtype = int(rng.integers(0, 4))
+        trunc, per_table = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        scale = float(rng.choice([1e-3, 1.0, 30.0]))
+        oidx, gidx = random_pair(P, n, d, n_lists, pq_dim, bits, salt=7000 + case, scale=scale, empty_lists=empty)
+        q = (scale * rng.standard_normal((17, d))).astype(np.float32)
+        kw = {}
+        if dtype in FP8:
+            bias = 15 if dtype == oracle.LUT_E5M3 else 7
+            gidx.ivfpq_set_fp8_encoding(dtype, bias, int(trunc), per_table)
+            kw = dict(truncate=trunc, bias=bias, per_table=per_table)
+        _step(f"random case {case}: n={n} d={d} lists={n_lists} s={pq_dim} p={bits} P={n_probes} k={k} dtype={dtype} {kw}")
+        ids_g, d_g = gidx.ivfpq_search(q, n_probes, k, dtype)
+        probes, _ = gidx.ivfpq_select_probes(q, n_probes)
+        probes = probes.cpu().numpy().view(np.uint32)
+        assert_probes_match(probes, oidx.centroids, q, n_probes)
+        ids_o, d_o = oracle.search(oidx, q, n_probes, k, dtype, probes=probes, **kw)
+        assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"random case {case}")
+        gidx.ivfpq_free()
