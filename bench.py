@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--probe-sweep", default="", metavar="P1,P2,...",
                     help="also time fp32 / fp16 / e5m3 at these numbers of probes (the recall-vs-throughput curves of "
                          "Sec. III, Figs. 5-6, on the synthetic stand-in); reported under by_probes")
+    ap.add_argument("--batch-sweep", default="", metavar="N1,N2,...",
+                    help="also time batches of these sizes (the first rows of the query set), each call on its own and "
+                         "replayed from a captured HIP graph: milliseconds per call; reported under by_batch")
     ap.add_argument("--refine-from", type=int, default=0, metavar="K2",
                     help="also time search with k=K2 followed by ivfpq_refine down to k (exact re-ranking with the "
                          "stored vectors; reported under by_lut as <lut>+refineK2)")
@@ -230,6 +233,38 @@ def main():
             r = run(name, max(3, args.steps // 2), 1, n_probes=P)
             by_probes[P][name] = {"qps": round(r["qps"], 1), "recall": round(r["recall"], 4)}
         log(f"n_probes={P}: " + "  ".join(f"{n} {v['qps']:.0f} q/s @ {v['recall']:.4f}" for n, v in by_probes[P].items()))
+    by_batch = {}
+    for nb in [int(v) for v in args.batch_sweep.split(",") if v]:
+        nb = max(1, min(nb, nq))
+        lut = lut_ids[args.lut]
+        if args.lut in ("e5m3", "e4m4"):
+            idx.ivfpq_set_fp8_encoding(lut, 15 if args.lut == "e5m3" else e4m4_bias)
+        qb = q[:nb].contiguous()
+        ob = (torch.empty((nb, k), dtype=torch.int64, device="cuda"), torch.empty((nb, k), dtype=torch.float32, device="cuda"))
+        reps = 50 if nb <= 1024 else 10
+        for _ in range(3):
+            idx.ivfpq_search(qb, n_probes, k, lut, out=ob)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            idx.ivfpq_search(qb, n_probes, k, lut, out=ob)
+        torch.cuda.synchronize()
+        eager_ms = 1e3 * (time.perf_counter() - t) / reps
+        want = ob[0].clone()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            idx.ivfpq_search(qb, n_probes, k, lut, out=ob)
+        g.replay()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = 1e3 * (time.perf_counter() - t) / reps
+        same = bool(torch.equal(ob[0], want))
+        del g
+        by_batch[nb] = {"eager_ms": round(eager_ms, 4), "graph_ms": round(graph_ms, 4), "graph_matches_eager": same}
+        log(f"batch {nb}: {eager_ms:.3f} ms per call, {graph_ms:.3f} ms replayed from a HIP graph (same ids: {same})")
     if args.refine_from:
         # search with a longer result list, then re-rank it exactly with the stored vectors
         k2 = args.refine_from
@@ -304,6 +339,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         **({"by_probes": by_probes} if by_probes else {}),
+        **({"by_batch": by_batch} if by_batch else {}),
     }
     print(json.dumps(line), flush=True)
 
