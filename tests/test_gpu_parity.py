@@ -582,3 +582,20 @@ def test_search_seeded_random_configurations(P):
         ids_o, d_o = oracle.search(oidx, q, n_probes, k, dtype, probes=probes, **kw)
         assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"random case {case}")
         gidx.ivfpq_free()
+
+
+def test_search_index_without_vectors(P):
+    # every cluster empty: nothing faults, every result slot is padding
+    d, n_lists, pq_dim = 32, 12, 16
+    rng = np.random.default_rng(77)
+    cent = rng.standard_normal((n_lists, d)).astype(np.float32)
+    cb = rng.standard_normal((pq_dim, 256, 2)).astype(np.float32)
+    gidx = P.Index.ivfpq_index_from_arrays(d, n_lists, pq_dim, 8, cent, cb, np.zeros(n_lists + 1, np.int64),
+                                           np.zeros((0, pq_dim), np.uint8), np.zeros(0, np.int64)).ivfpq_upload()
+    q = rng.standard_normal((9, d)).astype(np.float32)
+    for n_probes in (1, 5, 12):
+        _step(f"empty index P={n_probes}")
+        ids, dist = gidx.ivfpq_search(q, n_probes, 7, P.LUT_FP8_E5M3)
+        assert (ids.cpu().numpy() == -1).all() and np.isinf(dist.cpu().numpy()).all()
+    probes, _ = gidx.ivfpq_select_probes(q, 12)
+    assert_probes_match(probes.cpu().numpy().view(np.uint32), cent, q, 12)
