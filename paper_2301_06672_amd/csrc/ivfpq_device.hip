@@ -12,9 +12,14 @@
 //                        groups of PQ codes from HBM and accumulates R = sum_j F(y_j) (Eq. 1)
 //   bound_kernel         the k-th smallest R of that nearest cluster: an upper bound of the final
 //                        k-th distance of the query
-//   scan_kernel (mode 2) steps 2-4 for the other probes; only R values under the bound are kept
+//   pair_count / pair_offsets / pair_scatter   the other (query, probe) pairs grouped by cluster
+//   scan_kernel (mode 2) steps 2-4 for the other probes, in cluster-grouped, XCD-aware order (a
+//                        cluster's codes then come from one XCD's L2); only R values under the bound
+//                        are kept
 //   topk_kernel          step 5: the k smallest R over all probed clusters of a query, ordered by
 //                        (R, id), and the map from (cluster, position) to the caller's ids
+// Beside the path: dump_lut_kernel (steps 2-3 of one pair, for inspection) and refine_kernel (exact
+// re-ranking of candidates with the stored vectors).
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
