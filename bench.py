@@ -78,6 +78,24 @@ def tie_aware_recall(found_ids_t, data_np, queries_t, gt_d, k):
     return hits / float(ids.shape[0] * k)
 
 
+def measure_read_ceiling(torch, pkg, gib=4):
+    """GB/s of the library's plain streaming-read kernel over a buffer far larger than the caches."""
+    buf = torch.empty(gib << 30, dtype=torch.uint8, device="cuda")
+    buf.zero_()
+    best = 0.0
+    for n_wg in (2048, 4096, 8192, 16384):
+        pkg.ivfpq_stream_read(buf, n_wg)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            pkg.ivfpq_stream_read(buf, n_wg)
+        b.record()
+        torch.cuda.synchronize()
+        best = max(best, 5 * buf.numel() / (a.elapsed_time(b) * 1e-3) / 1e9)
+    del buf
+    return best
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -296,9 +314,12 @@ def main():
     ws_bytes = idx.ivfpq_search_workspace_bytes(nq, n_probes, k, lut_ids[args.lut])
     scan_ms = head["stage_ms"]["scan"]
     achieved = code_bytes / (scan_ms * 1e-3) / 1e9
+    ceiling = measure_read_ceiling(torch, pkg)
+    log(f"plain streaming read on this box: {ceiling:.0f} GB/s")
     roofline = {
         "bound": "hbm", "kernel": "scan_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "streaming_read_ceiling": round(ceiling, 1), "frac_of_ceiling": round(achieved / ceiling, 4),
         "traffic": MEASURED_TRAFFIC.get((w.name, args.lut)),
         "algorithmic_bytes_per_step": code_bytes, "scanned_vectors_per_step": scanned_vectors,
         "scan_ms_per_step": round(scan_ms, 4),
@@ -318,8 +339,16 @@ def main():
         t = time.perf_counter()
         oracle.search(oidx, queries_np[:nc], n_probes, k, lut_ids[args.lut], e4m4_bias=e4m4_bias)
         dt = time.perf_counter() - t
-        cpu = {"value": round(nc / dt, 1), "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"first {nc} of the {nq} queries, same index, lut={args.lut}, {dt:.1f}s wall, one pass"}
+        cores = oracle.num_threads()
+        n1 = max(1, nc // cores)                # about the same wall time on one thread
+        oracle.set_num_threads(1)
+        t = time.perf_counter()
+        oracle.search(oidx, queries_np[:n1], n_probes, k, lut_ids[args.lut], e4m4_bias=e4m4_bias)
+        dt1 = time.perf_counter() - t
+        oracle.set_num_threads(cores)
+        cpu = {"value": round(nc / dt, 1), "unit": "queries/s", "cores": cores, "kind": "oracle",
+               "sample": f"first {nc} of the {nq} queries, same index, lut={args.lut}, {dt:.1f}s wall, one pass",
+               "one_thread": {"value": round(n1 / dt1, 1), "sample": f"first {n1} queries, {dt1:.1f}s wall"}}
         log(f"cpu oracle: {cpu}")
 
     line = {

@@ -238,6 +238,13 @@ int ivfpq_refine(const float* d_data, int64_t n_data, int32_t d, const float* d_
 int ivfpq_set_stage_timing(ivfpq_index_t* index, int32_t enabled);
 int ivfpq_stage_times_ms(ivfpq_index_t* index, float ms[4]);
 
+/* Measurement aid, not a step of the method: a plain streaming read of `bytes` bytes of device memory
+ * (16-byte loads, grid-strided, n_out workgroups of 256 threads), the achievable HBM read rate that a
+ * code scan (Section 2.2 step 4, Eq. 1) streaming every byte from HBM is priced against.  d_buf: device,
+ * 16-byte aligned, bytes a multiple of 16; d_out: device, n_out words (1..65536), word b = XOR of all
+ * 32-bit words workgroup b read.  Asynchronous on hip_stream; allocates nothing. */
+int ivfpq_stream_read(const void* d_buf, size_t bytes, uint32_t* d_out, int32_t n_out, void* hip_stream);
+
 const char* ivfpq_last_error(void);
 
 #ifdef __cplusplus

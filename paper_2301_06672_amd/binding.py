@@ -32,7 +32,7 @@ EXPORTS = (
     "ivfpq_set_e4m4_bias", "ivfpq_set_fp8_encoding", "ivfpq_set_workspace_limit",
     "ivfpq_device_bytes", "ivfpq_upload", "ivfpq_search_workspace_bytes", "ivfpq_search",
     "ivfpq_select_probes", "ivfpq_search_with_probes", "ivfpq_dump_lut", "ivfpq_scan_list", "ivfpq_refine",
-    "ivfpq_set_stage_timing", "ivfpq_stage_times_ms", "ivfpq_last_error",
+    "ivfpq_set_stage_timing", "ivfpq_stage_times_ms", "ivfpq_stream_read", "ivfpq_last_error",
 )
 
 
@@ -91,6 +91,7 @@ def _declare(L):
     L.ivfpq_scan_list.argtypes = [vp, vp, u32, i32, vp, vp]
     L.ivfpq_set_stage_timing.argtypes = [vp, i32]
     L.ivfpq_stage_times_ms.argtypes = [vp, c.POINTER(c.c_float * 4)]
+    L.ivfpq_stream_read.argtypes = [vp, sz, vp, i32, vp]
     L.ivfpq_last_error.restype = c.c_char_p
     for name in EXPORTS:
         fn = getattr(L, name)
@@ -150,6 +151,14 @@ def ivfpq_refine(data: torch.Tensor, queries, cand_ids: torch.Tensor, k: int):
     _check(lib().ivfpq_refine(_dp(data), int(data.shape[0]), int(data.shape[1]), _dp(q), int(q.shape[0]), _dp(cand),
                               int(cand.shape[1]), int(k), _dp(ids), _dp(dists), _stream()))
     return ids, dists
+
+
+def ivfpq_stream_read(buf: torch.Tensor, n_out: int = 8192) -> torch.Tensor:
+    """-> uint32-as-int32 [n_out]: per-workgroup XOR of the 32-bit words of `buf` (CUDA, size a multiple of 16 bytes)."""
+    assert buf.is_cuda and buf.is_contiguous()
+    out = torch.empty(n_out, dtype=torch.int32, device="cuda")
+    _check(lib().ivfpq_stream_read(_dp(buf), buf.numel() * buf.element_size(), _dp(out), int(n_out), _stream()))
+    return out
 
 
 class Index:

@@ -1003,6 +1003,24 @@ dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centr
 // The (query, probe) pairs of the filtered scan grouped by cluster (a counting sort: count, offsets,
 // scatter; the order inside a cluster is whatever the atomics give and does not affect any result).
 // ================================================================================================
+// Plain streaming read: every thread loads 16-byte words grid-strided and folds them into one word
+// per workgroup.  It measures the read rate this chip's HBM reaches for the simplest possible access
+// pattern - the ceiling a code scan that streams every byte from HBM could attain.
+__global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restrict__ p, size_t n16, uint32_t* __restrict__ out) {
+    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        const uint4 v = p[i];
+        acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w;
+    }
+    uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    for (int o = 32; o > 0; o >>= 1) x ^= __shfl_xor(x, o);
+    __shared__ uint32_t part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = x;
+    __syncthreads();
+    if (threadIdx.x == 0) out[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+
 __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
@@ -1716,6 +1734,17 @@ int ivfpq_refine(const float* d_data, int64_t n_data, int32_t d, const float* d_
     hipLaunchKernelGGL(refine_kernel, dim3((unsigned)nq), dim3(SEL_THREADS), 0, (hipStream_t)hip_stream, d_data,
                        (long long)n_data, d, d_queries, d_cand_ids, n_cand, k, d_ids, d_dists);
     HIP_TRY(hipGetLastError());
+    return IVFPQ_OK;
+}
+
+int ivfpq_stream_read(const void* d_buf, size_t bytes, uint32_t* d_out, int32_t n_out, void* hip_stream) {
+    if (!d_buf || !d_out) return fail(IVFPQ_EINVAL, "null pointer");
+    if (n_out < 1 || n_out > 65536) return fail(IVFPQ_EINVAL, "n_out=%d outside 1..65536", n_out);
+    if (((uintptr_t)d_buf & 15) != 0 || (bytes & 15) != 0) return fail(IVFPQ_EINVAL, "buffer and size must be multiples of 16 bytes");
+    hipLaunchKernelGGL(stream_read_kernel, dim3(n_out), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const uint4*)d_buf, bytes / 16, d_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(IVFPQ_EHIP, "stream_read_kernel launch failed: %s", hipGetErrorString(e));
     return IVFPQ_OK;
 }
 

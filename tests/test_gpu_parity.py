@@ -497,6 +497,22 @@ def test_refine_rejects_bad_arguments(P):
         assert e.value.status == P.EINVAL
 
 
+# ---------------------------------------------------------------- the streaming-read measurement kernel
+
+@pytest.mark.parametrize("n_words,n_wg", [(4, 1), (4 * 1000, 3), (4 * 300001, 64)])
+def test_stream_read_folds_every_word_once(P, n_words, n_wg):
+    rng = np.random.default_rng(n_words)
+    words = rng.integers(0, 2**32, size=n_words, dtype=np.uint64).astype(np.uint32)
+    _step(f"stream read {n_words} words, {n_wg} workgroups")
+    out = P.ivfpq_stream_read(torch.from_numpy(words.view(np.int32)).cuda(), n_wg).cpu().numpy().view(np.uint32)
+    # 16-byte word i belongs to workgroup (i // 256) % n_wg
+    w16 = np.bitwise_xor.reduce(words.reshape(-1, 4), axis=1)
+    owner = (np.arange(w16.size) // 256) % n_wg
+    want = np.zeros(n_wg, dtype=np.uint32)
+    np.bitwise_xor.at(want, owner, w16)
+    np.testing.assert_array_equal(out, want)
+
+
 # ---------------------------------------------------------------- the search inside a HIP graph
 
 def test_search_replays_correctly_from_a_hip_graph(P, tiny):

@@ -110,6 +110,12 @@ def test_fp8_encoding_setter_validates(P):
         assert e.value.status == P.EINVAL and needle in str(e.value)
 
 
+def test_stream_read_validates_before_launching(P):
+    L = P.lib()
+    for args in ((None, 64, 16, 4), (16, 64, None, 4), (16, 64, 32, 0), (16, 64, 32, 1 << 20), (8, 64, 32, 4), (16, 60, 32, 4)):
+        assert L.ivfpq_stream_read(args[0], args[1], args[2], args[3], None) == P.EINVAL
+
+
 def test_search_without_device_image_is_a_state_error(P):
     arrays = si.random_index_arrays(100, 8, 3, 4, 8, salt=3)
     idx = P.Index.ivfpq_index_from_arrays(8, 3, 4, 8, *arrays)
