@@ -415,7 +415,7 @@ int assign_rows_device(const BuildPlan& P, unsigned char* ws, const float* X, si
     HIP_TRY(hipGetLastError());
     for (size_t r0 = 0; r0 < n_rows; r0 += P.tile_rows) {
         const int tr = (int)std::min(P.tile_rows, n_rows - r0);
-        if (int s = launch_coarse(X + r0 * P.d, C, cnorm, tr, k, P.d, A, st)) return s;
+        if (int s = launch_coarse(X + r0 * P.d, C, cnorm, tr, k, P.d, A, nullptr, st)) return s;
         hipLaunchKernelGGL(nearest_kernel, dim3(blocks_for((size_t)tr, 4)), dim3(256), 0, st, A, X + r0 * P.d, C, cmax, tr,
                            k, P.d, labels + r0);
         HIP_TRY(hipGetLastError());

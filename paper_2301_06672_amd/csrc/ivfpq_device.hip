@@ -277,10 +277,16 @@ struct RowSelectShared {
 struct NoWiden { __device__ uint32_t operator()(uint32_t b) const { return b; } };
 struct NoRefine { __device__ void operator()(uint32_t) const {} };
 
+// strip_min (may be null): the smallest key of every strip of strip_w (32 or 64) consecutive row elements,
+// strip i at strip_min[i * strip_stride].  If there are at least 2 k strips, the k-th smallest strip
+// minimum bounds the k-th smallest key (k strips hold an element not above it) far more tightly than a
+// sample does, and only the strips whose minimum passes the bound are read at all.
 template <class PosFn, class TieFn, class WidenFn, class RefineFn, class WholeRowFn>
 __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
                                    bool have_bound, uint32_t bound, PosFn pos_of, TieFn tie_of_pos,
-                                   WidenFn widen, RefineFn refine, WholeRowFn whole_row) {
+                                   WidenFn widen, RefineFn refine, WholeRowFn whole_row,
+                                   const uint32_t* __restrict__ strip_min = nullptr, size_t strip_stride = 1,
+                                   uint32_t strip_w = 64) {
     SelectShared& s = t.sel;
     const int tid = threadIdx.x, nth = blockDim.x;
     const uint32_t kk = k < (uint32_t)CAND_CAP ? k : (uint32_t)CAND_CAP;
@@ -289,6 +295,19 @@ __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restric
     __syncthreads();
     if (n > (uint32_t)CAND_CAP) {
         uint32_t r0, r1;
+        const uint32_t n_strips = (n + strip_w - 1) / strip_w;
+        bool by_strip = strip_min != nullptr && n_strips >= 2 * kk;
+        // the minima are read several times: from the (still unused) record keys if they fit there
+        const bool min_in_lds = by_strip && n_strips <= (uint32_t)SEL_CAP;
+        if (min_in_lds) {
+            for (uint32_t i = tid; i < n_strips; i += nth) s.rec_key[i] = strip_min[i * strip_stride];
+            __syncthreads();
+        }
+        auto strip_low = [&](uint32_t i) { return min_in_lds ? s.rec_key[i] : strip_min[i * strip_stride]; };
+        if (by_strip) {
+            bound = block_kth_key(s, n_strips, kk, strip_low, &r0, &r1);
+            have_bound = true;
+        }
         if (!have_bound) {
             // the k-th smallest of the first S keys bounds the k-th smallest of the row; about k n / S keys
             // pass it, so S grows with k n until half the LDS buffer is the expectation (a second pass
@@ -318,7 +337,35 @@ __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restric
                     if (slot < (uint32_t)CAND_CAP) { t.cand_key[slot] = key; t.cand_pos[slot] = pos_of(i); }
                 }
             };
-            if (vec) {
+            if (by_strip) {
+                // the strips that can hold a survivor, listed in the (still unused) record array ...
+                if (tid == 0) s.n_rec = 0;
+                __syncthreads();
+                for (uint32_t i = tid; i < n_strips; i += nth)
+                    if (strip_low(i) <= bound) {
+                        const uint32_t slot = atomicAdd(&s.n_rec, 1u);
+                        if (slot < (uint32_t)SEL_CAP) s.rec_pos[slot] = i;
+                    }
+                __syncthreads();
+                const uint32_t n_hit = s.n_rec;
+                if (n_hit > (uint32_t)SEL_CAP) { by_strip = false; continue; }      // loose bound: read the whole row
+                // ... then read: a wave takes 64 / strip_w listed strips per load, four loads in flight
+                const uint32_t lane = tid & (kWave - 1), per = kWave / strip_w, sub = lane / strip_w;
+                const uint32_t step = (nth / kWave) * per;
+                constexpr int U = 4;
+                for (uint32_t j0 = (tid / kWave) * per; j0 < n_hit; j0 += U * step) {
+                    uint32_t key[U], at[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const uint32_t j = j0 + u * step + sub;
+                        at[u] = j < n_hit ? s.rec_pos[j] * strip_w + lane % strip_w : n;
+                        key[u] = at[u] < n ? row[at[u]] : 0u;
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (at[u] < n) keep(key[u], at[u]);
+                }
+            } else if (vec) {
                 const uint4* row4 = reinterpret_cast<const uint4*>(row);
                 for (uint32_t i4 = tid; i4 < n / 4; i4 += nth) {
                     const uint4 v = row4[i4];
@@ -373,9 +420,13 @@ __device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__
 // = padded candidate count (every cluster padded to a multiple of 64 vectors), and writes one
 // descriptor per (query, probe) pair -- {cluster, length, first 64-vector group, R offset} -- so
 // that a scan workgroup starts from a single 16-byte load.
+// M (may be null): minima of the ranking keys over strips of strip_w clusters, strip-major
+// [n_strips][gridDim.x] as the ranking kernel writes them; with them the workgroup reads only the
+// strips that can hold one of its probes instead of the query's whole key row.
 // ================================================================================================
 __global__ void __launch_bounds__(SEL_THREADS)
-select_probes_kernel(uint32_t* __restrict__ A, const float* __restrict__ queries,
+select_probes_kernel(uint32_t* __restrict__ A, const uint32_t* __restrict__ M, int strip_w,
+                     const float* __restrict__ queries,
                      const float* __restrict__ centroids, float centroid_norm_max, int d,
                      int n_lists, int n_probes,
                      const uint32_t* __restrict__ list_sizes, const int64_t* __restrict__ group_offsets,
@@ -471,7 +522,8 @@ select_probes_kernel(uint32_t* __restrict__ A, const float* __restrict__ queries
     int got = block_select_row_ex(t, row, (uint32_t)n_lists, (uint32_t)n_probes, false, 0u,
                                   [](uint32_t i) { return i; },
                                   [](uint32_t pos, uint32_t) { return (long long)pos; },
-                                  widen, refine, whole_row);
+                                  widen, refine, whole_row,
+                                  M ? M + q : nullptr, (size_t)gridDim.x, (uint32_t)strip_w);
     for (int p = tid; p < got; p += nth) {
         probes[(size_t)q * n_probes + p] = s.rec_pos[p];
         if (probe_dists) probe_dists[(size_t)q * n_probes + p] = __uint_as_float(s.rec_key[p]);
@@ -1223,7 +1275,7 @@ ImageLayout image_layout(const ivfpq_index* idx) {
 struct Plan {
     int64_t tile;           // queries per tile
     size_t stride;          // R slots per query
-    size_t probes, probe_d, roff, pairs, bounds, counts, D, R, Rpos, order, list_counts, list_cursor, list_offsets, total;
+    size_t probes, probe_d, roff, pairs, bounds, counts, D, M, R, Rpos, order, list_counts, list_cursor, list_offsets, total;
 };
 
 
@@ -1237,7 +1289,8 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     if (stride >= ((int64_t)1 << 31))
         return fail(IVFPQ_EUNSUPPORTED, "a query may see %lld candidates (limit 2^31)", (long long)stride);
     if (stride < 64) stride = 64;
-    size_t per_query = (size_t)stride * 8 + (need_D ? (size_t)idx->n_lists * 4 : 0);
+    const size_t strips = ((size_t)idx->n_lists + 31) / 32;      // strip minima of the ranking keys, narrowest strips
+    size_t per_query = (size_t)stride * 8 + (need_D ? ((size_t)idx->n_lists + strips) * 4 : 0);
     int64_t tile = (int64_t)(idx->workspace_limit / per_query);
     tile = std::max<int64_t>(1, std::min<int64_t>(tile, std::max<int64_t>(nq, 1)));
     plan->tile = tile;
@@ -1251,6 +1304,7 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     plan->bounds = take((size_t)tile * 4);
     plan->counts = take((size_t)tile * 4);
     plan->D = take(need_D ? (size_t)tile * idx->n_lists * 4 : 0);
+    plan->M = take(need_D ? (size_t)tile * strips * 4 : 0);
     plan->R = take((size_t)tile * stride * 4);
     plan->Rpos = take((size_t)tile * stride * 4);
     plan->order = take((size_t)tile * (n_probes > 1 ? n_probes - 1 : 0) * 4);
@@ -1448,6 +1502,7 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
     uint32_t* w_counts = (uint32_t*)(ws + plan.counts);
     uint32_t* w_Rpos = (uint32_t*)(ws + plan.Rpos);
     float* w_D = (float*)(ws + plan.D);
+    uint32_t* w_M = (uint32_t*)(ws + plan.M);
     float* w_R = (float*)(ws + plan.R);
 
     if (idx->timing) { idx->events_used = 0; idx->spans.clear(); idx->stage_valid = true; }
@@ -1460,8 +1515,9 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         StageTimer t0(idx, st, 0);
         if (int s = t0.begin()) return s;
         if (!d_probes_in) {
-            if (int s = launch_coarse(qt, idx->dev.centroids, idx->dev.centroid_norms, tq, idx->n_lists, idx->d, (uint32_t*)w_D, st)) return s;
-            hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, qt,
+            if (int s = launch_coarse(qt, idx->dev.centroids, idx->dev.centroid_norms, tq, idx->n_lists, idx->d, (uint32_t*)w_D, w_M, st)) return s;
+            hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, w_M,
+                               coarse_strip_width(tq, idx->n_lists), qt,
                                idx->dev.centroids, idx->centroid_norm_max, idx->d, idx->n_lists,
                                n_probes, idx->dev.list_sizes, idx->dev.group_offsets, w_probes, w_probe_d, w_roff, w_pairs);
             HIP_TRY(hipGetLastError());
@@ -1669,13 +1725,14 @@ int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_
         return fail(IVFPQ_ENOSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, plan.total);
     hipStream_t st = (hipStream_t)hip_stream;
     float* w_D = (float*)((unsigned char*)d_workspace + plan.D);
+    uint32_t* w_M = (uint32_t*)((unsigned char*)d_workspace + plan.M);
     for (int64_t q0 = 0; q0 < nq; q0 += plan.tile) {
         const int tq = (int)std::min<int64_t>(plan.tile, nq - q0);
         if (int s = launch_coarse(d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->dev.centroid_norms, tq,
-                                  idx->n_lists, idx->d, (uint32_t*)w_D, st))
+                                  idx->n_lists, idx->d, (uint32_t*)w_D, w_M, st))
             return s;
-        hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D,
-                           d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->centroid_norm_max, idx->d,
+        hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, w_M,
+                           coarse_strip_width(tq, idx->n_lists), d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->centroid_norm_max, idx->d,
                            idx->n_lists, n_probes, idx->dev.list_sizes, idx->dev.group_offsets, d_probes + (size_t)q0 * n_probes,
                            d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr,
                            (uint4*)nullptr);

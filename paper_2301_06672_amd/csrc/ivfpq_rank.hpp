@@ -66,6 +66,39 @@ __device__ inline float ordered_key_value(uint32_t key) {
     return __uint_as_float(key ^ ((key >> 31) ? 0x80000000u : 0xFFFFFFFFu));
 }
 
+// Minimum over the 32 lanes of a half-wave of 16 values per lane, folded so that every exchange carries
+// only the values the receiver keeps: the lane whose index bit is set keeps the upper half of the
+// remaining values and hands the lower half to its partner (8, 4, 2, 1 exchanges, then one more between
+// neighbours).  Lane l of the half-wave ends with the minimum of value l / 2.  The partners are the
+// lane 16 further (LDS swizzle) and the lanes the data-parallel permutes reach inside a row of 16:
+// mirrored row (bit 3 differs), mirrored half-row (bit 2), quad neighbours (bits 1 and 0).
+template <int CTRL>
+__device__ inline uint32_t dpp_take(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, 0xF, 0xF, false);
+}
+__device__ inline uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
+__device__ inline uint32_t half_wave_min16(const uint32_t (&low)[16], int l32) {
+    const bool b4 = (l32 & 16) != 0, b3 = (l32 & 8) != 0, b2 = (l32 & 4) != 0, b1 = (l32 & 2) != 0;
+    uint32_t a[8], b[4], c[2];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint32_t keep = b4 ? low[t + 8] : low[t], give = b4 ? low[t] : low[t + 8];
+        a[t] = umin32(keep, (uint32_t)__builtin_amdgcn_ds_swizzle((int)give, 0x401F));      // from lane ^ 16
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const uint32_t keep = b3 ? a[t + 4] : a[t], give = b3 ? a[t] : a[t + 4];
+        b[t] = umin32(keep, dpp_take<0x140>(give));                                           // row_mirror
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const uint32_t keep = b2 ? b[t + 2] : b[t], give = b2 ? b[t] : b[t + 2];
+        c[t] = umin32(keep, dpp_take<0x141>(give));                                           // row_half_mirror
+    }
+    uint32_t x = umin32(b1 ? c[1] : c[0], dpp_take<0x4E>(b1 ? c[0] : c[1]));                  // quad_perm [2,3,0,1]
+    return umin32(x, dpp_take<0xB1>(x));                                                      // quad_perm [1,0,3,2]
+}
+
 // WB = 32x32 output blocks per wave and axis; the 4 waves sit 2 x 2, so the tile edge is 64 * WB.
 // Four waves per SIMD (128 registers each, accumulators included) keep the MFMA pipe fed while other
 // waves wait at the slice barriers: measured 9-12 % faster than the three the compiler picks unasked.
@@ -73,7 +106,7 @@ template <int WB>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 coarse_rank_kernel(const float* __restrict__ queries, const float* __restrict__ centroids,
                    const float* __restrict__ centroid_norms, int nq, int n_lists, int d,
-                   uint32_t* __restrict__ A) {
+                   uint32_t* __restrict__ A, uint32_t* __restrict__ M) {
     constexpr int CT = 64 * WB;          // tile edge
     constexpr int RT = 4 * WB;           // components a thread loads per tile row and slice
     __shared__ float qs[CK][CT + 4];
@@ -140,31 +173,60 @@ coarse_rank_kernel(const float* __restrict__ queries, const float* __restrict__ 
         __syncthreads();
     }
     // accumulator layout of the 32x32 block: register v of lane L holds row 8*(v/4) + 4*(L/32) + v%4, column L%32
+    const int n_strips = (n_lists + 32 * WB - 1) / (32 * WB);
+    const int strip = blockIdx.x * 2 + wc;        // the 32*WB clusters this wave covers
+    uint32_t* stage = reinterpret_cast<uint32_t*>(&qs[0][0]);      // free after the loop's last barrier
 #pragma unroll
-    for (int i = 0; i < WB; ++i)
+    for (int i = 0; i < WB; ++i) {
+        uint32_t low[16];                         // per row: smallest key among this wave's clusters
+#pragma unroll
+        for (int v = 0; v < 16; ++v) low[v] = 0xFFFFFFFFu;
 #pragma unroll
         for (int j = 0; j < WB; ++j) {
             const int li = l0 + (wc * WB + j) * 32 + l32;
-            if (li >= n_lists) continue;
-            const float cn = centroid_norms[li];
+            const bool col_ok = li < n_lists;
+            const float cn = col_ok ? centroid_norms[li] : 0.f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int qi = q0 + (wr * WB + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (qi < nq) A[(size_t)qi * n_lists + li] = ordered_key(__builtin_fmaf(-2.f, acc[i][j][v], cn));
+                const uint32_t key = ordered_key(__builtin_fmaf(-2.f, acc[i][j][v], cn));
+                if (col_ok) {
+                    low[v] = key < low[v] ? key : low[v];
+                    if (qi < nq) A[(size_t)qi * n_lists + li] = key;
+                }
             }
         }
+        if (M) {
+            // row minima over this wave's clusters, staged so that the wave stores them contiguously
+            const uint32_t mine = half_wave_min16(low, l32);
+            const int v = l32 >> 1;
+            stage[wave * 64 + i * 32 + 8 * (v / 4) + 4 * half + (v % 4)] = mine;
+        }
+    }
+    if (M) {
+        __builtin_amdgcn_wave_barrier();          // the wave's own LDS writes above are read back below
+        const int qi = q0 + wr * WB * 32 + lane;
+        if (lane < WB * 32 && qi < nq && strip < n_strips) M[(size_t)strip * nq + qi] = stage[wave * 64 + lane];
+    }
 }
 
-// picks the tile size so that the grid still covers the chip
+// The tile size is chosen so that the grid still covers the chip.  Besides the keys A[nq][n_lists] the
+// kernel can write strip minima M[n_strips][nq] (M may be null; strip-major, so that a wave stores the
+// minima of its 64 queries contiguously): the smallest key of every strip of coarse_strip_width()
+// consecutive clusters, which lets a selection kernel skip most of a key row.
+inline bool coarse_big_tiles(int nq, int n_lists) {
+    return (long)((n_lists + 127) / 128) * ((nq + 127) / 128) >= 1024;
+}
+inline int coarse_strip_width(int nq, int n_lists) { return coarse_big_tiles(nq, n_lists) ? 64 : 32; }
+
 int launch_coarse(const float* q, const float* centroids, const float* centroid_norms, int nq, int n_lists, int d,
-                  uint32_t* A, hipStream_t st) {
-    const long big_blocks = (long)((n_lists + 127) / 128) * ((nq + 127) / 128);
-    if (big_blocks >= 1024) {
+                  uint32_t* A, uint32_t* M, hipStream_t st) {
+    if (coarse_big_tiles(nq, n_lists)) {
         dim3 grid((n_lists + 127) / 128, (nq + 127) / 128);
-        hipLaunchKernelGGL(coarse_rank_kernel<2>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A);
+        hipLaunchKernelGGL(coarse_rank_kernel<2>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A, M);
     } else {
         dim3 grid((n_lists + 63) / 64, (nq + 63) / 64);
-        hipLaunchKernelGGL(coarse_rank_kernel<1>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A);
+        hipLaunchKernelGGL(coarse_rank_kernel<1>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A, M);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(IVFPQ_EHIP, "coarse_rank_kernel launch failed: %s", hipGetErrorString(e));

@@ -270,6 +270,49 @@ def test_select_probes_6000_lists_ties_and_outliers(P):
         assert_topk_matches(ids_g, d_g, ids_o, d_o, context=f"6000 lists dtype={dtype}")
 
 
+def test_select_probes_strip_minima_large_batch(P):
+    # enough queries x clusters that the ranking GEMM runs its 128 x 128 tiles and hands the selection
+    # the minima of 64-cluster strips; n_probes on both sides of the rule that decides whether they are used
+    arrays = list(si.random_index_arrays(7000, 32, 6000, 16, 8, salt=320))
+    arrays[0][5990:5996] = arrays[0][17]        # exact ties across strips, one in the ragged last strip
+    oidx = oracle.make_index(32, 6000, 16, 8, *arrays)
+    gidx = to_library(P, oidx)
+    rng = np.random.default_rng(320)
+    q = rng.standard_normal((3000, 32)).astype(np.float32)
+    q[:6] = arrays[0][17] + 0.01 * rng.standard_normal((6, 32)).astype(np.float32)
+    for n_probes in (1, 7, 47, 48, 200):
+        _step(f"select_probes strips L=6000 nq=3000 P={n_probes}")
+        probes, pd = gidx.ivfpq_select_probes(q, n_probes)
+        probes = probes.cpu().numpy().view(np.uint32)
+        want, want_d = oracle.select_probes(oidx, q, n_probes)
+        np.testing.assert_allclose(pd.cpu().numpy(), want_d, rtol=RTOL)
+        assert (probes == want).mean() > 0.999
+        assert all(len(set(r)) == n_probes for r in probes[:200])
+    probes, _ = gidx.ivfpq_select_probes(q, 7)
+    for row in probes.cpu().numpy().view(np.uint32)[:6]:
+        np.testing.assert_array_equal(row, [17] + list(range(5990, 5996)))
+
+
+def test_select_probes_plateau_of_equal_centroids(P):
+    # 40,000 clusters, all but three with the same centroid: every strip minimum equals the bound, more
+    # strips qualify than the list holds, the whole row overflows the candidate buffer and the kernel
+    # ends in its exact whole-row selection; ties come out by ascending cluster index
+    arrays = list(si.random_index_arrays(41000, 8, 40000, 4, 8, salt=330))
+    arrays[0][:] = arrays[0][0]
+    arrays[0][[12345, 777, 39999]] += np.float32(0.25)
+    oidx = oracle.make_index(8, 40000, 4, 8, *arrays)
+    gidx = to_library(P, oidx)
+    q = np.tile(arrays[0][12345], (3, 1)).astype(np.float32)
+    q[1] = arrays[0][0]
+    for n_probes in (1, 10, 300):
+        _step(f"select_probes plateau P={n_probes}")
+        probes, pd = gidx.ivfpq_select_probes(q, n_probes)
+        probes = probes.cpu().numpy().view(np.uint32)
+        want, want_d = oracle.select_probes(oidx, q, n_probes)
+        np.testing.assert_array_equal(probes, want)
+        np.testing.assert_allclose(pd.cpu().numpy(), want_d, rtol=RTOL)
+
+
 # ---------------------------------------------------------------- whole search (steps 1-5)
 
 def _search_both(gidx, oidx, q, n_probes, k, dtype):
