@@ -123,9 +123,8 @@ nearest_kernel(const uint32_t* __restrict__ A, const float* __restrict__ X, cons
         if (o1 < g1 || (o1 == g1 && oi < gi)) { g2 = min(g1, o2); g1 = o1; gi = oi; }
         else g2 = min(g2, o1);
     }
-    // |a_computed - a_exact| <= delta (rounding of |c|^2, of the d-term fp32 dot product in any order,
-    // of the final multiply-add; factor 4 of slack)
-    const float delta = (float)(d + 8) * 2.3841858e-07f * (qn + __uint_as_float(*norm_max_bits));
+    // |a_computed - a_exact| <= delta
+    const float delta = rank_error_bound(d, qn, __uint_as_float(*norm_max_bits));
     float lim = ordered_key_value(g1) + 2.f * delta;
     lim += __builtin_fabsf(lim) * 2.3841858e-07f;
     const uint32_t limit = (lim == lim) ? ordered_key(lim) : 0xFFFFFFFFu;
@@ -360,7 +359,7 @@ struct BuildPlan {
     size_t n_group;                 // largest number of items grouped at once
     size_t k_group;                 // largest number of groups
     // offsets into the workspace
-    size_t Xt, A, C, cnorm, cmax, labels_t, labels_all, order, tmp, counts, cursor, offsets, ct_rows, pt_rows,
+    size_t Xt, A, split, C, cnorm, cmax, labels_t, labels_all, order, tmp, counts, cursor, offsets, ct_rows, pt_rows,
            init_rows, Rt, pq_labels, codebooks, codes, total;
 };
 
@@ -376,6 +375,7 @@ BuildPlan make_build_plan(int64_t n, int d, int n_lists, int pq_dim, int pq_bits
     auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
     P.Xt = take((size_t)n_ct * d * 4);
     P.A = take(P.tile_rows * (size_t)n_lists * 4);
+    P.split = take(coarse_split_bytes(P.tile_rows, (size_t)n_lists, d));
     P.C = take((size_t)n_lists * d * 4);
     P.cnorm = take((size_t)n_lists * 4);
     P.cmax = take(4);
@@ -415,7 +415,7 @@ int assign_rows_device(const BuildPlan& P, unsigned char* ws, const float* X, si
     HIP_TRY(hipGetLastError());
     for (size_t r0 = 0; r0 < n_rows; r0 += P.tile_rows) {
         const int tr = (int)std::min(P.tile_rows, n_rows - r0);
-        if (int s = launch_coarse(X + r0 * P.d, C, cnorm, tr, k, P.d, A, nullptr, st)) return s;
+        if (int s = launch_coarse(X + r0 * P.d, C, cnorm, tr, k, P.d, A, nullptr, ws + P.split, st)) return s;
         hipLaunchKernelGGL(nearest_kernel, dim3(blocks_for((size_t)tr, 4)), dim3(256), 0, st, A, X + r0 * P.d, C, cmax, tr,
                            k, P.d, labels + r0);
         HIP_TRY(hipGetLastError());

@@ -454,10 +454,8 @@ select_probes_kernel(uint32_t* __restrict__ A, const uint32_t* __restrict__ M, i
     __syncthreads();
     float qn = 0.f;
     for (int w = 0; w < n_waves; ++w) qn += s_part[w];
-    // |a_computed - a_exact| <= delta: rounding of |c|^2 (2^-24 relative), of the d-term fp32 dot
-    // product (<= d 2^-24 |q||c| for any summation order, times 2), of the final multiply-add; taken
-    // with a factor 4 of slack: (d + 8) 2^-22 (|q|^2 + max|c|^2)
-    const float delta = (float)(d + 8) * 2.3841858e-07f * (qn + centroid_norm_max);
+    // |a_computed - a_exact| <= delta
+    const float delta = rank_error_bound(d, qn, centroid_norm_max);
     // keys up to this one can belong to a cluster whose exact rank is within the bound's rank
     auto widen = [&](uint32_t key) {
         const float f = ordered_key_value(key);
@@ -1275,7 +1273,7 @@ ImageLayout image_layout(const ivfpq_index* idx) {
 struct Plan {
     int64_t tile;           // queries per tile
     size_t stride;          // R slots per query
-    size_t probes, probe_d, roff, pairs, bounds, counts, D, M, R, Rpos, order, list_counts, list_cursor, list_offsets, total;
+    size_t probes, probe_d, roff, pairs, bounds, counts, D, M, split, R, Rpos, order, list_counts, list_cursor, list_offsets, total;
 };
 
 
@@ -1290,7 +1288,7 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
         return fail(IVFPQ_EUNSUPPORTED, "a query may see %lld candidates (limit 2^31)", (long long)stride);
     if (stride < 64) stride = 64;
     const size_t strips = ((size_t)idx->n_lists + 31) / 32;      // strip minima of the ranking keys, narrowest strips
-    size_t per_query = (size_t)stride * 8 + (need_D ? ((size_t)idx->n_lists + strips) * 4 : 0);
+    size_t per_query = (size_t)stride * 8 + (need_D ? ((size_t)idx->n_lists + strips + coarse_padded_dim(idx->d)) * 4 : 0);
     int64_t tile = (int64_t)(idx->workspace_limit / per_query);
     tile = std::max<int64_t>(1, std::min<int64_t>(tile, std::max<int64_t>(nq, 1)));
     plan->tile = tile;
@@ -1305,6 +1303,7 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     plan->counts = take((size_t)tile * 4);
     plan->D = take(need_D ? (size_t)tile * idx->n_lists * 4 : 0);
     plan->M = take(need_D ? (size_t)tile * strips * 4 : 0);
+    plan->split = take(need_D ? coarse_split_bytes((size_t)tile, (size_t)idx->n_lists, idx->d) : 0);
     plan->R = take((size_t)tile * stride * 4);
     plan->Rpos = take((size_t)tile * stride * 4);
     plan->order = take((size_t)tile * (n_probes > 1 ? n_probes - 1 : 0) * 4);
@@ -1515,7 +1514,7 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         StageTimer t0(idx, st, 0);
         if (int s = t0.begin()) return s;
         if (!d_probes_in) {
-            if (int s = launch_coarse(qt, idx->dev.centroids, idx->dev.centroid_norms, tq, idx->n_lists, idx->d, (uint32_t*)w_D, w_M, st)) return s;
+            if (int s = launch_coarse(qt, idx->dev.centroids, idx->dev.centroid_norms, tq, idx->n_lists, idx->d, (uint32_t*)w_D, w_M, ws + plan.split, st)) return s;
             hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, w_M,
                                coarse_strip_width(tq, idx->n_lists), qt,
                                idx->dev.centroids, idx->centroid_norm_max, idx->d, idx->n_lists,
@@ -1729,7 +1728,7 @@ int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_
     for (int64_t q0 = 0; q0 < nq; q0 += plan.tile) {
         const int tq = (int)std::min<int64_t>(plan.tile, nq - q0);
         if (int s = launch_coarse(d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->dev.centroid_norms, tq,
-                                  idx->n_lists, idx->d, (uint32_t*)w_D, w_M, st))
+                                  idx->n_lists, idx->d, (uint32_t*)w_D, w_M, (unsigned char*)d_workspace + plan.split, st))
             return s;
         hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, w_M,
                            coarse_strip_width(tq, idx->n_lists), d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->centroid_norm_max, idx->d,

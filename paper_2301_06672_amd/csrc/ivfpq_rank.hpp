@@ -99,6 +99,52 @@ __device__ inline uint32_t half_wave_min16(const uint32_t (&low)[16], int l32) {
     return umin32(x, dpp_take<0xB1>(x));                                                      // quad_perm [1,0,3,2]
 }
 
+// Epilogue of the ranking kernels: turns the accumulated dot products of one workgroup tile (4 waves
+// 2 x 2, each WB x WB blocks of 32 x 32) into keys of a = |c|^2 - 2 q.c, stores them and, if M is given,
+// the minimum of every query over the wave's 32*WB clusters.  stage: 256 words of LDS no wave still reads.
+// Accumulator layout of a 32x32 block: register v of lane L holds row 8*(v/4) + 4*(L/32) + v%4, column L%32.
+template <int WB>
+__device__ __forceinline__ void rank_store(const floatx16 (&acc)[WB][WB], int q0, int l0, int nq, int n_lists,
+                                           const float* __restrict__ centroid_norms, uint32_t* __restrict__ A,
+                                           uint32_t* __restrict__ M, uint32_t* stage) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1, half = lane >> 5, l32 = lane & 31;
+    const int n_strips = (n_lists + 32 * WB - 1) / (32 * WB);
+    const int strip = blockIdx.x * 2 + wc;        // the 32*WB clusters this wave covers
+#pragma unroll
+    for (int i = 0; i < WB; ++i) {
+        uint32_t low[16];                         // per row: smallest key among this wave's clusters
+#pragma unroll
+        for (int v = 0; v < 16; ++v) low[v] = 0xFFFFFFFFu;
+#pragma unroll
+        for (int j = 0; j < WB; ++j) {
+            const int li = l0 + (wc * WB + j) * 32 + l32;
+            const bool col_ok = li < n_lists;
+            const float cn = col_ok ? centroid_norms[li] : 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int qi = q0 + (wr * WB + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                const uint32_t key = ordered_key(__builtin_fmaf(-2.f, acc[i][j][v], cn));
+                if (col_ok) {
+                    low[v] = key < low[v] ? key : low[v];
+                    if (qi < nq) A[(size_t)qi * n_lists + li] = key;
+                }
+            }
+        }
+        if (M) {
+            // row minima over this wave's clusters, staged so that the wave stores them contiguously
+            const uint32_t mine = half_wave_min16(low, l32);
+            const int v = l32 >> 1;
+            stage[wave * 64 + i * 32 + 8 * (v / 4) + 4 * half + (v % 4)] = mine;
+        }
+    }
+    if (M) {
+        __builtin_amdgcn_wave_barrier();          // the wave's own LDS writes above are read back below
+        const int qi = q0 + wr * WB * 32 + lane;
+        if (lane < WB * 32 && qi < nq && strip < n_strips) M[(size_t)strip * nq + qi] = stage[wave * 64 + lane];
+    }
+}
+
 // WB = 32x32 output blocks per wave and axis; the 4 waves sit 2 x 2, so the tile edge is 64 * WB.
 // Four waves per SIMD (128 registers each, accumulators included) keep the MFMA pipe fed while other
 // waves wait at the slice barriers: measured 9-12 % faster than the three the compiler picks unasked.
@@ -172,58 +218,152 @@ coarse_rank_kernel(const float* __restrict__ queries, const float* __restrict__ 
         }
         __syncthreads();
     }
-    // accumulator layout of the 32x32 block: register v of lane L holds row 8*(v/4) + 4*(L/32) + v%4, column L%32
-    const int n_strips = (n_lists + 32 * WB - 1) / (32 * WB);
-    const int strip = blockIdx.x * 2 + wc;        // the 32*WB clusters this wave covers
-    uint32_t* stage = reinterpret_cast<uint32_t*>(&qs[0][0]);      // free after the loop's last barrier
-#pragma unroll
-    for (int i = 0; i < WB; ++i) {
-        uint32_t low[16];                         // per row: smallest key among this wave's clusters
-#pragma unroll
-        for (int v = 0; v < 16; ++v) low[v] = 0xFFFFFFFFu;
-#pragma unroll
-        for (int j = 0; j < WB; ++j) {
-            const int li = l0 + (wc * WB + j) * 32 + l32;
-            const bool col_ok = li < n_lists;
-            const float cn = col_ok ? centroid_norms[li] : 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int qi = q0 + (wr * WB + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                const uint32_t key = ordered_key(__builtin_fmaf(-2.f, acc[i][j][v], cn));
-                if (col_ok) {
-                    low[v] = key < low[v] ? key : low[v];
-                    if (qi < nq) A[(size_t)qi * n_lists + li] = key;
-                }
-            }
-        }
-        if (M) {
-            // row minima over this wave's clusters, staged so that the wave stores them contiguously
-            const uint32_t mine = half_wave_min16(low, l32);
-            const int v = l32 >> 1;
-            stage[wave * 64 + i * 32 + 8 * (v / 4) + 4 * half + (v % 4)] = mine;
-        }
-    }
-    if (M) {
-        __builtin_amdgcn_wave_barrier();          // the wave's own LDS writes above are read back below
-        const int qi = q0 + wr * WB * 32 + lane;
-        if (lane < WB * 32 && qi < nq && strip < n_strips) M[(size_t)strip * nq + qi] = stage[wave * 64 + lane];
-    }
+    rank_store<WB>(acc, q0, l0, nq, n_lists, centroid_norms, A, M, reinterpret_cast<uint32_t*>(&qs[0][0]));
 }
 
-// The tile size is chosen so that the grid still covers the chip.  Besides the keys A[nq][n_lists] the
-// kernel can write strip minima M[n_strips][nq] (M may be null; strip-major, so that a wave stores the
-// minima of its 64 queries contiguously): the smallest key of every strip of coarse_strip_width()
-// consecutive clusters, which lets a selection kernel skip most of a key row.
+// ------------------------------------------------------------------------------------------------
+// Large problems: the same dot products from bf16 matrix instructions, 16 times the fp32 rate.
+// Every fp32 operand x is split once into hi = bf16(x) and lo = bf16(x - hi) (x - hi is exact in fp32,
+// |x - hi - lo| <= 2^-16 |x|) and q.c is taken as qh.ch + qh.cl + ql.ch with v_mfma_f32_32x32x16_bf16
+// (bf16 products are exact in fp32; the sums are fp32).  What is dropped - ql.cl and the two split
+// remainders - is at most 3.02 * 2^-16 |q||c|, which rank_error_bound() carries, so the exactness
+// argument of the consumers is unchanged.
+// ------------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int BK = 16;        // components per LDS slice = one matrix instruction deep
+constexpr int BPITCH = 24;    // LDS row pitch in bf16: 48 bytes, so 8 consecutive rows' 16-byte reads cover all banks
+
+__device__ inline uint32_t bf16_round(float f) {          // round to nearest even; Inf stays Inf, NaN stays NaN
+    const uint32_t b = __float_as_uint(f);
+    if ((b & 0x7F800000u) == 0x7F800000u) return (b >> 16) | ((b & 0xFFFFu) ? 0x40u : 0u);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+
+// X[rows][d] fp32 -> hi, lo [rows][dp] bf16, components d..dp-1 zero; one thread per 8 components
+__global__ void __launch_bounds__(256)
+split_bf16_kernel(const float* __restrict__ X, size_t rows, int d, int dp, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo) {
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int per_row = dp / 8;
+    const size_t row = t / per_row;
+    const int k0 = (int)(t % per_row) * 8;
+    if (row >= rows) return;
+    uint32_t h[8], l[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const float x = k0 + u < d ? X[row * d + k0 + u] : 0.f;
+        h[u] = bf16_round(x);
+        const float rest = x - __uint_as_float(h[u] << 16);
+        l[u] = (rest == rest) ? bf16_round(rest) : 0u;       // Inf - Inf: the hi part already carries it
+    }
+    uint4 H = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    uint4 L = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+    *reinterpret_cast<uint4*>(hi + row * dp + k0) = H;
+    *reinterpret_cast<uint4*>(lo + row * dp + k0) = L;
+}
+
+// 128 queries x 128 clusters per workgroup; wave w stages operand array w (Qh, Ql, Ch, Cl) of the slice.
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+coarse_rank_split_kernel(const uint16_t* __restrict__ Qh, const uint16_t* __restrict__ Ql,
+                         const uint16_t* __restrict__ Ch, const uint16_t* __restrict__ Cl,
+                         const float* __restrict__ centroid_norms, int nq, int n_lists, int dp,
+                         uint32_t* __restrict__ A, uint32_t* __restrict__ M) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[4][128 * BPITCH];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1, half = lane >> 5, l32 = lane & 31;
+    const int q0 = blockIdx.y * 128, l0 = blockIdx.x * 128;
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const uint16_t* src = wave == 0 ? Qh : (wave == 1 ? Ql : (wave == 2 ? Ch : Cl));
+    const int row0 = wave < 2 ? q0 : l0, n_rows = wave < 2 ? nq : n_lists;
+    uint4 pre[4];
+    // a slice of one operand array is 128 rows x 32 bytes = 256 16-byte pieces, four per lane
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int piece = c * 64 + lane, r = row0 + (piece >> 1);
+            pre[c] = r < n_rows ? *reinterpret_cast<const uint4*>(src + (size_t)r * dp + k0 + (piece & 1) * 8)
+                                : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < dp; k0 += BK) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int piece = c * 64 + lane;
+            *reinterpret_cast<uint4*>(&tile[wave][(piece >> 1) * BPITCH + (piece & 1) * 8]) = pre[c];
+        }
+        __syncthreads();
+        if (k0 + BK < dp) fetch(k0 + BK);      // the next slice travels while this one is multiplied
+        // operand of lane L: row L % 32, components 8 * (L / 32) .. + 7
+        bf16x8 ah[2], al[2], bh[2], bl[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int at = ((wr * 2 + i) * 32 + l32) * BPITCH + half * 8;
+            ah[i] = *reinterpret_cast<const bf16x8*>(&tile[0][at]);
+            al[i] = *reinterpret_cast<const bf16x8*>(&tile[1][at]);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int at = ((wc * 2 + j) * 32 + l32) * BPITCH + half * 8;
+            bh[j] = *reinterpret_cast<const bf16x8*>(&tile[2][at]);
+            bl[j] = *reinterpret_cast<const bf16x8*>(&tile[3][at]);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
+            }
+        __syncthreads();
+    }
+    rank_store<2>(acc, q0, l0, nq, n_lists, centroid_norms, A, M, reinterpret_cast<uint32_t*>(&tile[0][0]));
+}
+
+// |a_computed - a_exact| <= this, for either ranking kernel (qn = |q|^2, cmax = max |c|^2): the split
+// remainders, 3.02 * 2^-16 |q||c| on the dot product, so 3.02 * 2^-16 (|q|^2 + |c|^2) on a; the fp32 sum
+// of up to 3 d exact products in any order (3 d 2^-24 relative to the sum of their magnitudes, taken with
+// a factor 4 of slack for whatever rounding the matrix unit applies); the rounding of |c|^2 and of the
+// final multiply-add (the + 8).
+__device__ inline float rank_error_bound(int d, float qn, float cmax) {
+    return ((float)(3 * d + 8) * 2.3841858e-07f + 5.0e-05f) * (qn + cmax);
+}
+
+// Tile choice: 128 x 128 tiles on the bf16 kernel when they still cover the chip, else 64 x 64 in fp32.
+// Besides the keys A[nq][n_lists] the kernels can write strip minima M[n_strips][nq] (M may be null;
+// strip-major, so that a wave stores the minima of its 64 queries contiguously): the smallest key of
+// every strip of coarse_strip_width() consecutive clusters, which lets a selection kernel skip most of a
+// key row.  split_ws: coarse_split_bytes() bytes of device scratch for the bf16 operands.
 inline bool coarse_big_tiles(int nq, int n_lists) {
     return (long)((n_lists + 127) / 128) * ((nq + 127) / 128) >= 1024;
 }
 inline int coarse_strip_width(int nq, int n_lists) { return coarse_big_tiles(nq, n_lists) ? 64 : 32; }
+inline int coarse_padded_dim(int d) { return (d + BK - 1) / BK * BK; }
+inline size_t coarse_split_bytes(size_t nq_max, size_t n_lists, int d) {
+    return 2 * (align_up(nq_max * coarse_padded_dim(d) * 2) + align_up(n_lists * coarse_padded_dim(d) * 2));
+}
 
 int launch_coarse(const float* q, const float* centroids, const float* centroid_norms, int nq, int n_lists, int d,
-                  uint32_t* A, uint32_t* M, hipStream_t st) {
+                  uint32_t* A, uint32_t* M, void* split_ws, hipStream_t st) {
     if (coarse_big_tiles(nq, n_lists)) {
+        const int dp = coarse_padded_dim(d);
+        const size_t q_bytes = align_up((size_t)nq * dp * 2), c_bytes = align_up((size_t)n_lists * dp * 2);
+        uint16_t* qh = (uint16_t*)split_ws;
+        uint16_t* ql = (uint16_t*)((unsigned char*)split_ws + q_bytes);
+        uint16_t* ch = (uint16_t*)((unsigned char*)split_ws + 2 * q_bytes);
+        uint16_t* cl = (uint16_t*)((unsigned char*)split_ws + 2 * q_bytes + c_bytes);
+        const size_t q_threads = (size_t)nq * (dp / 8), c_threads = (size_t)n_lists * (dp / 8);
+        hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((q_threads + 255) / 256)), dim3(256), 0, st, q, (size_t)nq, d, dp, qh, ql);
+        hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((c_threads + 255) / 256)), dim3(256), 0, st, centroids, (size_t)n_lists, d, dp, ch, cl);
         dim3 grid((n_lists + 127) / 128, (nq + 127) / 128);
-        hipLaunchKernelGGL(coarse_rank_kernel<2>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A, M);
+        hipLaunchKernelGGL(coarse_rank_split_kernel, grid, dim3(256), 0, st, qh, ql, ch, cl, centroid_norms, nq, n_lists, dp, A, M);
     } else {
         dim3 grid((n_lists + 63) / 64, (nq + 63) / 64);
         hipLaunchKernelGGL(coarse_rank_kernel<1>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A, M);
