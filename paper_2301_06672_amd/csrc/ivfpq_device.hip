@@ -277,16 +277,10 @@ struct RowSelectShared {
 struct NoWiden { __device__ uint32_t operator()(uint32_t b) const { return b; } };
 struct NoRefine { __device__ void operator()(uint32_t) const {} };
 
-// strip_min (may be null): the smallest key of every strip of strip_w (32 or 64) consecutive row elements,
-// strip i at strip_min[i * strip_stride].  If there are at least 2 k strips, the k-th smallest strip
-// minimum bounds the k-th smallest key (k strips hold an element not above it) far more tightly than a
-// sample does, and only the strips whose minimum passes the bound are read at all.
 template <class PosFn, class TieFn, class WidenFn, class RefineFn, class WholeRowFn>
 __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
                                    bool have_bound, uint32_t bound, PosFn pos_of, TieFn tie_of_pos,
-                                   WidenFn widen, RefineFn refine, WholeRowFn whole_row,
-                                   const uint32_t* __restrict__ strip_min = nullptr, size_t strip_stride = 1,
-                                   uint32_t strip_w = 64) {
+                                   WidenFn widen, RefineFn refine, WholeRowFn whole_row) {
     SelectShared& s = t.sel;
     const int tid = threadIdx.x, nth = blockDim.x;
     const uint32_t kk = k < (uint32_t)CAND_CAP ? k : (uint32_t)CAND_CAP;
@@ -295,19 +289,6 @@ __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restric
     __syncthreads();
     if (n > (uint32_t)CAND_CAP) {
         uint32_t r0, r1;
-        const uint32_t n_strips = (n + strip_w - 1) / strip_w;
-        bool by_strip = strip_min != nullptr && n_strips >= 2 * kk;
-        // the minima are read several times: from the (still unused) record keys if they fit there
-        const bool min_in_lds = by_strip && n_strips <= (uint32_t)SEL_CAP;
-        if (min_in_lds) {
-            for (uint32_t i = tid; i < n_strips; i += nth) s.rec_key[i] = strip_min[i * strip_stride];
-            __syncthreads();
-        }
-        auto strip_low = [&](uint32_t i) { return min_in_lds ? s.rec_key[i] : strip_min[i * strip_stride]; };
-        if (by_strip) {
-            bound = block_kth_key(s, n_strips, kk, strip_low, &r0, &r1);
-            have_bound = true;
-        }
         if (!have_bound) {
             // the k-th smallest of the first S keys bounds the k-th smallest of the row; about k n / S keys
             // pass it, so S grows with k n until half the LDS buffer is the expectation (a second pass
@@ -337,35 +318,7 @@ __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restric
                     if (slot < (uint32_t)CAND_CAP) { t.cand_key[slot] = key; t.cand_pos[slot] = pos_of(i); }
                 }
             };
-            if (by_strip) {
-                // the strips that can hold a survivor, listed in the (still unused) record array ...
-                if (tid == 0) s.n_rec = 0;
-                __syncthreads();
-                for (uint32_t i = tid; i < n_strips; i += nth)
-                    if (strip_low(i) <= bound) {
-                        const uint32_t slot = atomicAdd(&s.n_rec, 1u);
-                        if (slot < (uint32_t)SEL_CAP) s.rec_pos[slot] = i;
-                    }
-                __syncthreads();
-                const uint32_t n_hit = s.n_rec;
-                if (n_hit > (uint32_t)SEL_CAP) { by_strip = false; continue; }      // loose bound: read the whole row
-                // ... then read: a wave takes 64 / strip_w listed strips per load, four loads in flight
-                const uint32_t lane = tid & (kWave - 1), per = kWave / strip_w, sub = lane / strip_w;
-                const uint32_t step = (nth / kWave) * per;
-                constexpr int U = 4;
-                for (uint32_t j0 = (tid / kWave) * per; j0 < n_hit; j0 += U * step) {
-                    uint32_t key[U], at[U];
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const uint32_t j = j0 + u * step + sub;
-                        at[u] = j < n_hit ? s.rec_pos[j] * strip_w + lane % strip_w : n;
-                        key[u] = at[u] < n ? row[at[u]] : 0u;
-                    }
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        if (at[u] < n) keep(key[u], at[u]);
-                }
-            } else if (vec) {
+            if (vec) {
                 const uint4* row4 = reinterpret_cast<const uint4*>(row);
                 for (uint32_t i4 = tid; i4 < n / 4; i4 += nth) {
                     const uint4 v = row4[i4];
@@ -420,12 +373,15 @@ __device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__
 // = padded candidate count (every cluster padded to a multiple of 64 vectors), and writes one
 // descriptor per (query, probe) pair -- {cluster, length, first 64-vector group, R offset} -- so
 // that a scan workgroup starts from a single 16-byte load.
-// M (may be null): minima of the ranking keys over strips of strip_w clusters, strip-major
-// [n_strips][gridDim.x] as the ranking kernel writes them; with them the workgroup reads only the
-// strips that can hold one of its probes instead of the query's whole key row.
+// S (may be null): instead of the keys, the ranking kernel's summary of every strip of strip_w clusters
+// (its two smallest keys, tagged with the cluster's position in the strip), strip-major
+// [n_strips][gridDim.x]; the host passes it when there are at least 2 n_probes strips.  The n_probes-th
+// smallest strip minimum then bounds the n_probes-th smallest key; a strip whose minimum passes the
+// (widened) bound yields its best cluster, or all its clusters if its second key passes too, and all of
+// these get their exact distance.  A is then only scratch for the whole-row fallback.
 // ================================================================================================
 __global__ void __launch_bounds__(SEL_THREADS)
-select_probes_kernel(uint32_t* __restrict__ A, const uint32_t* __restrict__ M, int strip_w,
+select_probes_kernel(uint32_t* __restrict__ A, const uint2* __restrict__ S, int strip_w,
                      const float* __restrict__ queries,
                      const float* __restrict__ centroids, float centroid_norm_max, int d,
                      int n_lists, int n_probes,
@@ -517,11 +473,67 @@ select_probes_kernel(uint32_t* __restrict__ A, const uint32_t* __restrict__ M, i
         return block_select_smallest(s, (uint32_t)n_lists, (uint32_t)n_probes,
             [&](uint32_t i) { return row[i]; }, [&](uint32_t i) { return (long long)i; });
     };
-    int got = block_select_row_ex(t, row, (uint32_t)n_lists, (uint32_t)n_probes, false, 0u,
+    int got;
+    if (S) {
+        const uint32_t n_strips = ((uint32_t)n_lists + strip_w - 1) / strip_w, sw = (uint32_t)strip_w;
+        const size_t stride = gridDim.x;
+        const uint2* mine = S + q;
+        // the summaries are read several times: from the (still unused) record arrays if they fit there
+        const bool in_lds = n_strips <= (uint32_t)SEL_CAP;
+        if (in_lds)
+            for (uint32_t i = tid; i < n_strips; i += nth) {
+                const uint2 v = mine[i * stride];
+                s.rec_key[i] = v.x; s.rec_pos[i] = v.y;
+            }
+        __syncthreads();
+        auto low1 = [&](uint32_t i) { return in_lds ? s.rec_key[i] : mine[i * stride].x; };
+        auto low2 = [&](uint32_t i) { return in_lds ? s.rec_pos[i] : mine[i * stride].y; };
+        uint32_t r0, r1;
+        const uint32_t kk = (uint32_t)n_probes < n_strips ? (uint32_t)n_probes : n_strips;
+        // kk strips hold a key not above this, so it bounds the kk-th smallest key of the row
+        const uint32_t bound = widen(block_kth_key(s, n_strips, kk, [&](uint32_t i) { return low1(i) | 63u; }, &r0, &r1));
+        __syncthreads();
+        if (tid == 0) t.n_cand = 0;
+        __syncthreads();
+        for (uint32_t i = tid; i < n_strips; i += nth) {
+            const uint32_t a1 = low1(i), first = i * sw;
+            if ((a1 & ~63u) > bound) continue;
+            if ((low2(i) & ~63u) > bound) {           // one key of the strip can pass: its best cluster
+                const uint32_t c = first + (a1 & 63u);
+                if (c < (uint32_t)n_lists) {
+                    const uint32_t slot = atomicAdd(&t.n_cand, 1u);
+                    if (slot < (uint32_t)CAND_CAP) t.cand_pos[slot] = c;
+                }
+            } else {                                   // several may: all its clusters
+                const uint32_t cnt = (uint32_t)n_lists - first < sw ? (uint32_t)n_lists - first : sw;
+                const uint32_t slot = atomicAdd(&t.n_cand, cnt);
+                for (uint32_t c = 0; c < cnt; ++c)
+                    if (slot + c < (uint32_t)CAND_CAP) t.cand_pos[slot + c] = first + c;
+            }
+        }
+        __syncthreads();
+        const uint32_t n_cand = t.n_cand;
+        if (n_cand >= (uint32_t)n_probes && n_cand <= (uint32_t)CAND_CAP) {
+            for (uint32_t base = 0; base < n_cand; base += nth / 8) {
+                const uint32_t j = base + (tid >> 3);
+                const bool valid = j < n_cand;
+                const float dist = exact8(valid ? t.cand_pos[j] : 0u, valid);
+                if (valid && (tid & 7) == 0) t.cand_key[j] = __float_as_uint(dist);
+            }
+            __syncthreads();
+            got = block_select_smallest(s, n_cand, (uint32_t)n_probes,
+                [&](uint32_t i) { return t.cand_key[i]; }, [&](uint32_t i) { return (long long)t.cand_pos[i]; });
+            for (int j = tid; j < got; j += nth) s.rec_pos[j] = t.cand_pos[s.rec_pos[j]];
+        } else {
+            got = whole_row();       // a plateau of equal ranking values (or not-a-number keys)
+        }
+        __syncthreads();
+    } else {
+        got = block_select_row_ex(t, row, (uint32_t)n_lists, (uint32_t)n_probes, false, 0u,
                                   [](uint32_t i) { return i; },
                                   [](uint32_t pos, uint32_t) { return (long long)pos; },
-                                  widen, refine, whole_row,
-                                  M ? M + q : nullptr, (size_t)gridDim.x, (uint32_t)strip_w);
+                                  widen, refine, whole_row);
+    }
     for (int p = tid; p < got; p += nth) {
         probes[(size_t)q * n_probes + p] = s.rec_pos[p];
         if (probe_dists) probe_dists[(size_t)q * n_probes + p] = __uint_as_float(s.rec_key[p]);
@@ -1273,7 +1285,7 @@ ImageLayout image_layout(const ivfpq_index* idx) {
 struct Plan {
     int64_t tile;           // queries per tile
     size_t stride;          // R slots per query
-    size_t probes, probe_d, roff, pairs, bounds, counts, D, M, split, R, Rpos, order, list_counts, list_cursor, list_offsets, total;
+    size_t probes, probe_d, roff, pairs, bounds, counts, D, S, split, R, Rpos, order, list_counts, list_cursor, list_offsets, total;
 };
 
 
@@ -1287,8 +1299,8 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     if (stride >= ((int64_t)1 << 31))
         return fail(IVFPQ_EUNSUPPORTED, "a query may see %lld candidates (limit 2^31)", (long long)stride);
     if (stride < 64) stride = 64;
-    const size_t strips = ((size_t)idx->n_lists + 31) / 32;      // strip minima of the ranking keys, narrowest strips
-    size_t per_query = (size_t)stride * 8 + (need_D ? ((size_t)idx->n_lists + strips + coarse_padded_dim(idx->d)) * 4 : 0);
+    const size_t strips = ((size_t)idx->n_lists + 31) / 32;      // strip summaries of the ranking keys, narrowest strips
+    size_t per_query = (size_t)stride * 8 + (need_D ? ((size_t)idx->n_lists + 2 * strips + coarse_padded_dim(idx->d)) * 4 : 0);
     int64_t tile = (int64_t)(idx->workspace_limit / per_query);
     tile = std::max<int64_t>(1, std::min<int64_t>(tile, std::max<int64_t>(nq, 1)));
     plan->tile = tile;
@@ -1302,7 +1314,7 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     plan->bounds = take((size_t)tile * 4);
     plan->counts = take((size_t)tile * 4);
     plan->D = take(need_D ? (size_t)tile * idx->n_lists * 4 : 0);
-    plan->M = take(need_D ? (size_t)tile * strips * 4 : 0);
+    plan->S = take(need_D ? (size_t)tile * strips * 8 : 0);
     plan->split = take(need_D ? coarse_split_bytes((size_t)tile, (size_t)idx->n_lists, idx->d) : 0);
     plan->R = take((size_t)tile * stride * 4);
     plan->Rpos = take((size_t)tile * stride * 4);
@@ -1501,7 +1513,7 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
     uint32_t* w_counts = (uint32_t*)(ws + plan.counts);
     uint32_t* w_Rpos = (uint32_t*)(ws + plan.Rpos);
     float* w_D = (float*)(ws + plan.D);
-    uint32_t* w_M = (uint32_t*)(ws + plan.M);
+    uint2* w_S = (uint2*)(ws + plan.S);
     float* w_R = (float*)(ws + plan.R);
 
     if (idx->timing) { idx->events_used = 0; idx->spans.clear(); idx->stage_valid = true; }
@@ -1514,8 +1526,9 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         StageTimer t0(idx, st, 0);
         if (int s = t0.begin()) return s;
         if (!d_probes_in) {
-            if (int s = launch_coarse(qt, idx->dev.centroids, idx->dev.centroid_norms, tq, idx->n_lists, idx->d, (uint32_t*)w_D, w_M, ws + plan.split, st)) return s;
-            hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, w_M,
+            uint2* strips = coarse_use_strips(tq, idx->n_lists, n_probes) ? w_S : nullptr;
+            if (int s = launch_coarse(qt, idx->dev.centroids, idx->dev.centroid_norms, tq, idx->n_lists, idx->d, (uint32_t*)w_D, strips, ws + plan.split, st)) return s;
+            hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, (const uint2*)strips,
                                coarse_strip_width(tq, idx->n_lists), qt,
                                idx->dev.centroids, idx->centroid_norm_max, idx->d, idx->n_lists,
                                n_probes, idx->dev.list_sizes, idx->dev.group_offsets, w_probes, w_probe_d, w_roff, w_pairs);
@@ -1724,13 +1737,14 @@ int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_
         return fail(IVFPQ_ENOSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, plan.total);
     hipStream_t st = (hipStream_t)hip_stream;
     float* w_D = (float*)((unsigned char*)d_workspace + plan.D);
-    uint32_t* w_M = (uint32_t*)((unsigned char*)d_workspace + plan.M);
+    uint2* w_S = (uint2*)((unsigned char*)d_workspace + plan.S);
     for (int64_t q0 = 0; q0 < nq; q0 += plan.tile) {
         const int tq = (int)std::min<int64_t>(plan.tile, nq - q0);
+        uint2* strips = coarse_use_strips(tq, idx->n_lists, n_probes) ? w_S : nullptr;
         if (int s = launch_coarse(d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->dev.centroid_norms, tq,
-                                  idx->n_lists, idx->d, (uint32_t*)w_D, w_M, (unsigned char*)d_workspace + plan.split, st))
+                                  idx->n_lists, idx->d, (uint32_t*)w_D, strips, (unsigned char*)d_workspace + plan.split, st))
             return s;
-        hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, w_M,
+        hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, (const uint2*)strips,
                            coarse_strip_width(tq, idx->n_lists), d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->centroid_norm_max, idx->d,
                            idx->n_lists, n_probes, idx->dev.list_sizes, idx->dev.group_offsets, d_probes + (size_t)q0 * n_probes,
                            d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr,

@@ -66,56 +66,87 @@ __device__ inline float ordered_key_value(uint32_t key) {
     return __uint_as_float(key ^ ((key >> 31) ? 0x80000000u : 0xFFFFFFFFu));
 }
 
-// Minimum over the 32 lanes of a half-wave of 16 values per lane, folded so that every exchange carries
-// only the values the receiver keeps: the lane whose index bit is set keeps the upper half of the
-// remaining values and hands the lower half to its partner (8, 4, 2, 1 exchanges, then one more between
-// neighbours).  Lane l of the half-wave ends with the minimum of value l / 2.  The partners are the
-// lane 16 further (LDS swizzle) and the lanes the data-parallel permutes reach inside a row of 16:
-// mirrored row (bit 3 differs), mirrored half-row (bit 2), quad neighbours (bits 1 and 0).
+// The two smallest, over the 32 lanes of a half-wave, of 16 values per lane (each lane brings its own two
+// smallest, lo1 <= lo2), folded so that every exchange carries only what the receiver keeps: the lane
+// whose index bit is set keeps the upper half of the remaining values and hands the lower half to its
+// partner (8, 4, 2, 1 exchanges, then one more between neighbours).  Lane l of the half-wave ends with
+// the result for value l / 2.  The partners are the lane 16 further (LDS swizzle) and the lanes the
+// data-parallel permutes reach inside a row of 16: mirrored row (bit 3 differs), mirrored half-row
+// (bit 2), quad neighbours (bits 1 and 0).
 template <int CTRL>
 __device__ inline uint32_t dpp_take(uint32_t x) {
     return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, 0xF, 0xF, false);
 }
+__device__ inline uint32_t swizzle_take16(uint32_t x) { return (uint32_t)__builtin_amdgcn_ds_swizzle((int)x, 0x401F); }
 __device__ inline uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
-__device__ inline uint32_t half_wave_min16(const uint32_t (&low)[16], int l32) {
+__device__ inline uint32_t umax32(uint32_t a, uint32_t b) { return a < b ? b : a; }
+struct Low2 { uint32_t m1, m2; };                 // smallest and second smallest
+// two sorted pairs -> the two smallest of the four
+__device__ inline Low2 merge_low2(Low2 a, Low2 b) {
+    return Low2{umin32(a.m1, b.m1), umin32(umax32(a.m1, b.m1), umin32(a.m2, b.m2))};
+}
+__device__ inline Low2 half_wave_low2x16(const uint32_t (&lo1)[16], const uint32_t (&lo2)[16], int l32) {
     const bool b4 = (l32 & 16) != 0, b3 = (l32 & 8) != 0, b2 = (l32 & 4) != 0, b1 = (l32 & 2) != 0;
-    uint32_t a[8], b[4], c[2];
+    Low2 a[8], b[4], c[2];
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-        const uint32_t keep = b4 ? low[t + 8] : low[t], give = b4 ? low[t] : low[t + 8];
-        a[t] = umin32(keep, (uint32_t)__builtin_amdgcn_ds_swizzle((int)give, 0x401F));      // from lane ^ 16
+        const Low2 keep{b4 ? lo1[t + 8] : lo1[t], b4 ? lo2[t + 8] : lo2[t]};
+        const Low2 give{b4 ? lo1[t] : lo1[t + 8], b4 ? lo2[t] : lo2[t + 8]};
+        a[t] = merge_low2(keep, Low2{swizzle_take16(give.m1), swizzle_take16(give.m2)});         // from lane ^ 16
     }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        const uint32_t keep = b3 ? a[t + 4] : a[t], give = b3 ? a[t] : a[t + 4];
-        b[t] = umin32(keep, dpp_take<0x140>(give));                                           // row_mirror
+        const Low2 keep = b3 ? a[t + 4] : a[t], give = b3 ? a[t] : a[t + 4];
+        b[t] = merge_low2(keep, Low2{dpp_take<0x140>(give.m1), dpp_take<0x140>(give.m2)});       // row_mirror
     }
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-        const uint32_t keep = b2 ? b[t + 2] : b[t], give = b2 ? b[t] : b[t + 2];
-        c[t] = umin32(keep, dpp_take<0x141>(give));                                           // row_half_mirror
+        const Low2 keep = b2 ? b[t + 2] : b[t], give = b2 ? b[t] : b[t + 2];
+        c[t] = merge_low2(keep, Low2{dpp_take<0x141>(give.m1), dpp_take<0x141>(give.m2)});       // row_half_mirror
     }
-    uint32_t x = umin32(b1 ? c[1] : c[0], dpp_take<0x4E>(b1 ? c[0] : c[1]));                  // quad_perm [2,3,0,1]
-    return umin32(x, dpp_take<0xB1>(x));                                                      // quad_perm [1,0,3,2]
+    const Low2 keep = b1 ? c[1] : c[0], give = b1 ? c[0] : c[1];
+    const Low2 x = merge_low2(keep, Low2{dpp_take<0x4E>(give.m1), dpp_take<0x4E>(give.m2)});     // quad_perm [2,3,0,1]
+    return merge_low2(x, Low2{dpp_take<0xB1>(x.m1), dpp_take<0xB1>(x.m2)});                      // quad_perm [1,0,3,2]
 }
 
 // Epilogue of the ranking kernels: turns the accumulated dot products of one workgroup tile (4 waves
-// 2 x 2, each WB x WB blocks of 32 x 32) into keys of a = |c|^2 - 2 q.c, stores them and, if M is given,
-// the minimum of every query over the wave's 32*WB clusters.  stage: 256 words of LDS no wave still reads.
+// 2 x 2, each WB x WB blocks of 32 x 32) into order-preserving keys of a = |c|^2 - 2 q.c.
+// Either all keys are stored, A[nq][n_lists] (S null), or only a summary of every strip of 32*WB
+// consecutive clusters (the ones a wave covers), S[n_strips][nq] (strip-major, so that a wave stores the
+// summaries of its 64 queries contiguously): the two smallest keys of the strip, each with its low six
+// bits replaced by the cluster's position in the strip.  Clearing those bits lowers a key by less than
+// 2^-17 |a|; a consumer takes (x & ~63) as a lower and (x | 63) as an upper bound of the key.  All-ones
+// means "no such cluster".  stage: 512 words of LDS that no wave still reads.
 // Accumulator layout of a 32x32 block: register v of lane L holds row 8*(v/4) + 4*(L/32) + v%4, column L%32.
 template <int WB>
 __device__ __forceinline__ void rank_store(const floatx16 (&acc)[WB][WB], int q0, int l0, int nq, int n_lists,
                                            const float* __restrict__ centroid_norms, uint32_t* __restrict__ A,
-                                           uint32_t* __restrict__ M, uint32_t* stage) {
+                                           uint2* __restrict__ S, uint2* stage) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1, half = lane >> 5, l32 = lane & 31;
+    if (!S) {
+#pragma unroll
+        for (int i = 0; i < WB; ++i)
+#pragma unroll
+            for (int j = 0; j < WB; ++j) {
+                const int li = l0 + (wc * WB + j) * 32 + l32;
+                if (li >= n_lists) continue;
+                const float cn = centroid_norms[li];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int qi = q0 + (wr * WB + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                    if (qi < nq) A[(size_t)qi * n_lists + li] = ordered_key(__builtin_fmaf(-2.f, acc[i][j][v], cn));
+                }
+            }
+        return;
+    }
     const int n_strips = (n_lists + 32 * WB - 1) / (32 * WB);
-    const int strip = blockIdx.x * 2 + wc;        // the 32*WB clusters this wave covers
+    const int strip = blockIdx.x * 2 + wc;
 #pragma unroll
     for (int i = 0; i < WB; ++i) {
-        uint32_t low[16];                         // per row: smallest key among this wave's clusters
+        uint32_t lo1[16], lo2[16];                // per row: the two smallest tagged keys among this lane's clusters
 #pragma unroll
-        for (int v = 0; v < 16; ++v) low[v] = 0xFFFFFFFFu;
+        for (int v = 0; v < 16; ++v) { lo1[v] = 0xFFFFFFFFu; lo2[v] = 0xFFFFFFFFu; }
 #pragma unroll
         for (int j = 0; j < WB; ++j) {
             const int li = l0 + (wc * WB + j) * 32 + l32;
@@ -123,26 +154,19 @@ __device__ __forceinline__ void rank_store(const floatx16 (&acc)[WB][WB], int q0
             const float cn = col_ok ? centroid_norms[li] : 0.f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int qi = q0 + (wr * WB + i) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
                 const uint32_t key = ordered_key(__builtin_fmaf(-2.f, acc[i][j][v], cn));
-                if (col_ok) {
-                    low[v] = key < low[v] ? key : low[v];
-                    if (qi < nq) A[(size_t)qi * n_lists + li] = key;
-                }
+                const uint32_t tagged = col_ok ? ((key & ~63u) | (uint32_t)(j * 32 + l32)) : 0xFFFFFFFFu;
+                lo2[v] = umin32(lo2[v], umax32(lo1[v], tagged));
+                lo1[v] = umin32(lo1[v], tagged);
             }
         }
-        if (M) {
-            // row minima over this wave's clusters, staged so that the wave stores them contiguously
-            const uint32_t mine = half_wave_min16(low, l32);
-            const int v = l32 >> 1;
-            stage[wave * 64 + i * 32 + 8 * (v / 4) + 4 * half + (v % 4)] = mine;
-        }
+        const Low2 mine = half_wave_low2x16(lo1, lo2, l32);
+        const int v = l32 >> 1;
+        stage[wave * 64 + i * 32 + 8 * (v / 4) + 4 * half + (v % 4)] = make_uint2(mine.m1, mine.m2);
     }
-    if (M) {
-        __builtin_amdgcn_wave_barrier();          // the wave's own LDS writes above are read back below
-        const int qi = q0 + wr * WB * 32 + lane;
-        if (lane < WB * 32 && qi < nq && strip < n_strips) M[(size_t)strip * nq + qi] = stage[wave * 64 + lane];
-    }
+    __builtin_amdgcn_wave_barrier();              // the wave's own LDS writes above are read back below
+    const int qi = q0 + wr * WB * 32 + lane;
+    if (lane < WB * 32 && qi < nq && strip < n_strips) S[(size_t)strip * nq + qi] = stage[wave * 64 + lane];
 }
 
 // WB = 32x32 output blocks per wave and axis; the 4 waves sit 2 x 2, so the tile edge is 64 * WB.
@@ -152,7 +176,7 @@ template <int WB>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 coarse_rank_kernel(const float* __restrict__ queries, const float* __restrict__ centroids,
                    const float* __restrict__ centroid_norms, int nq, int n_lists, int d,
-                   uint32_t* __restrict__ A, uint32_t* __restrict__ M) {
+                   uint32_t* __restrict__ A, uint2* __restrict__ S) {
     constexpr int CT = 64 * WB;          // tile edge
     constexpr int RT = 4 * WB;           // components a thread loads per tile row and slice
     __shared__ float qs[CK][CT + 4];
@@ -218,7 +242,7 @@ coarse_rank_kernel(const float* __restrict__ queries, const float* __restrict__ 
         }
         __syncthreads();
     }
-    rank_store<WB>(acc, q0, l0, nq, n_lists, centroid_norms, A, M, reinterpret_cast<uint32_t*>(&qs[0][0]));
+    rank_store<WB>(acc, q0, l0, nq, n_lists, centroid_norms, A, S, reinterpret_cast<uint2*>(&qs[0][0]));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -266,7 +290,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))
 coarse_rank_split_kernel(const uint16_t* __restrict__ Qh, const uint16_t* __restrict__ Ql,
                          const uint16_t* __restrict__ Ch, const uint16_t* __restrict__ Cl,
                          const float* __restrict__ centroid_norms, int nq, int n_lists, int dp,
-                         uint32_t* __restrict__ A, uint32_t* __restrict__ M) {
+                         uint32_t* __restrict__ A, uint2* __restrict__ S) {
     __shared__ __attribute__((aligned(16))) uint16_t tile[4][128 * BPITCH];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1, half = lane >> 5, l32 = lane & 31;
@@ -324,7 +348,7 @@ coarse_rank_split_kernel(const uint16_t* __restrict__ Qh, const uint16_t* __rest
             }
         __syncthreads();
     }
-    rank_store<2>(acc, q0, l0, nq, n_lists, centroid_norms, A, M, reinterpret_cast<uint32_t*>(&tile[0][0]));
+    rank_store<2>(acc, q0, l0, nq, n_lists, centroid_norms, A, S, reinterpret_cast<uint2*>(&tile[0][0]));
 }
 
 // |a_computed - a_exact| <= this, for either ranking kernel (qn = |q|^2, cmax = max |c|^2): the split
@@ -337,21 +361,25 @@ __device__ inline float rank_error_bound(int d, float qn, float cmax) {
 }
 
 // Tile choice: 128 x 128 tiles on the bf16 kernel when they still cover the chip, else 64 x 64 in fp32.
-// Besides the keys A[nq][n_lists] the kernels can write strip minima M[n_strips][nq] (M may be null;
-// strip-major, so that a wave stores the minima of its 64 queries contiguously): the smallest key of
-// every strip of coarse_strip_width() consecutive clusters, which lets a selection kernel skip most of a
-// key row.  split_ws: coarse_split_bytes() bytes of device scratch for the bf16 operands.
+// The kernels store either every key, A[nq][n_lists] (S null), or only the strip summaries
+// S[n_strips][nq] for strips of coarse_strip_width() clusters (see rank_store).
+// split_ws: coarse_split_bytes() bytes of device scratch for the bf16 operands.
 inline bool coarse_big_tiles(int nq, int n_lists) {
     return (long)((n_lists + 127) / 128) * ((nq + 127) / 128) >= 1024;
 }
 inline int coarse_strip_width(int nq, int n_lists) { return coarse_big_tiles(nq, n_lists) ? 64 : 32; }
+// whether a selection of the k smallest per row should work from strip summaries instead of all keys
+inline bool coarse_use_strips(int nq, int n_lists, int k) {
+    const int w = coarse_strip_width(nq, n_lists);
+    return n_lists > 1024 && (n_lists + w - 1) / w >= 2 * k;
+}
 inline int coarse_padded_dim(int d) { return (d + BK - 1) / BK * BK; }
 inline size_t coarse_split_bytes(size_t nq_max, size_t n_lists, int d) {
     return 2 * (align_up(nq_max * coarse_padded_dim(d) * 2) + align_up(n_lists * coarse_padded_dim(d) * 2));
 }
 
 int launch_coarse(const float* q, const float* centroids, const float* centroid_norms, int nq, int n_lists, int d,
-                  uint32_t* A, uint32_t* M, void* split_ws, hipStream_t st) {
+                  uint32_t* A, uint2* S, void* split_ws, hipStream_t st) {
     if (coarse_big_tiles(nq, n_lists)) {
         const int dp = coarse_padded_dim(d);
         const size_t q_bytes = align_up((size_t)nq * dp * 2), c_bytes = align_up((size_t)n_lists * dp * 2);
@@ -363,10 +391,10 @@ int launch_coarse(const float* q, const float* centroids, const float* centroid_
         hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((q_threads + 255) / 256)), dim3(256), 0, st, q, (size_t)nq, d, dp, qh, ql);
         hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((c_threads + 255) / 256)), dim3(256), 0, st, centroids, (size_t)n_lists, d, dp, ch, cl);
         dim3 grid((n_lists + 127) / 128, (nq + 127) / 128);
-        hipLaunchKernelGGL(coarse_rank_split_kernel, grid, dim3(256), 0, st, qh, ql, ch, cl, centroid_norms, nq, n_lists, dp, A, M);
+        hipLaunchKernelGGL(coarse_rank_split_kernel, grid, dim3(256), 0, st, qh, ql, ch, cl, centroid_norms, nq, n_lists, dp, A, S);
     } else {
         dim3 grid((n_lists + 63) / 64, (nq + 63) / 64);
-        hipLaunchKernelGGL(coarse_rank_kernel<1>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A, M);
+        hipLaunchKernelGGL(coarse_rank_kernel<1>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A, S);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(IVFPQ_EHIP, "coarse_rank_kernel launch failed: %s", hipGetErrorString(e));
