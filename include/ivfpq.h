@@ -100,8 +100,8 @@ int ivfpq_build_device(const float* d_data, int64_t n, int32_t d, int32_t n_list
 
 /* Build step 1's assignment alone, for inspection: d_labels[i] (device, int32) = the centre nearest to
  * row i of d_rows (device [n_rows][d]) among d_centres (device [n_centres][d]), decided as above.
- * d_workspace >= ivfpq_assign_device_workspace_bytes(n_rows, n_centres).  Asynchronous. */
-size_t ivfpq_assign_device_workspace_bytes(int64_t n_rows, int32_t n_centres);
+ * d_workspace >= ivfpq_assign_device_workspace_bytes(n_rows, d, n_centres).  Asynchronous. */
+size_t ivfpq_assign_device_workspace_bytes(int64_t n_rows, int32_t d, int32_t n_centres);
 int ivfpq_assign_device(const float* d_rows, int64_t n_rows, int32_t d, const float* d_centres, int32_t n_centres,
                         int32_t* d_labels, void* d_workspace, size_t workspace_bytes, void* hip_stream);
 

@@ -67,7 +67,7 @@ def _declare(L):
     L.ivfpq_build_device_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i64, i64]
     L.ivfpq_build_device_workspace_bytes.restype = sz
     L.ivfpq_build_device.argtypes = [vp, i64, i32, i32, i32, i32, i32, vp, i64, vp, vp, i64, vp, u64, vp, sz, vp, pp]
-    L.ivfpq_assign_device_workspace_bytes.argtypes = [i64, i32]
+    L.ivfpq_assign_device_workspace_bytes.argtypes = [i64, i32, i32]
     L.ivfpq_assign_device_workspace_bytes.restype = sz
     L.ivfpq_assign_device.argtypes = [vp, i64, i32, vp, i32, vp, vp, sz, vp]
     L.ivfpq_index_from_arrays.argtypes = [i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, pp]
@@ -131,7 +131,7 @@ def ivfpq_assign_device(rows, centres) -> torch.Tensor:
     """-> int32 CUDA tensor: the nearest centre of every row (k-means assignment step)."""
     x, c = _dev_f32(rows), _dev_f32(centres)
     assert x.shape[1] == c.shape[1]
-    need = lib().ivfpq_assign_device_workspace_bytes(int(x.shape[0]), int(c.shape[0]))
+    need = lib().ivfpq_assign_device_workspace_bytes(int(x.shape[0]), int(x.shape[1]), int(c.shape[0]))
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
     labels = torch.empty(int(x.shape[0]), dtype=torch.int32, device="cuda")
     _check(lib().ivfpq_assign_device(_dp(x), int(x.shape[0]), int(x.shape[1]), _dp(c), int(c.shape[0]), _dp(labels),

@@ -9,9 +9,10 @@
 // implementation with the same definitions therefore produces the same bits.
 //
 // Kernels:
-//   coarse_rank_kernel     fp32 MFMA ranking values |c|^2 - 2 x.c of a tile of rows x all centres
-//   nearest_kernel         per row the smallest ranking value; a second value within the rigorous
-//                          error bound of the first sends the row to exact float64 distances
+//   coarse_rank_*_kernel   MFMA ranking values |c|^2 - 2 x.c of a tile of rows x all centres (all of them for
+//                          few centres, else the two smallest of every strip of 32 / 64 centres)
+//   nearest_kernel, nearest_strips_kernel   per row the smallest ranking value; a second value within the
+//                          rigorous error bound of the first sends the row to exact float64 distances
 //   count/offsets/scatter/sort_groups   rows grouped by label, ascending inside a group
 //   update_centres_kernel  ordered float64 mean of every group
 //   residual_rows_kernel   x - centroid of the own cluster (fp32), for the PQ training rows
@@ -152,6 +153,68 @@ nearest_kernel(const uint32_t* __restrict__ A, const float* __restrict__ X, cons
 }
 
 // ---- rows grouped by label ----------------------------------------------------------------------
+// The same decision from the ranking kernel's strip summaries S[n_strips][n_rows] (the two smallest
+// tagged keys of every strip of strip_w centres): 64 rows per workgroup, four threads per row that each
+// scan a quarter of the strips.  The smallest key and the second smallest of everything else decide: if
+// the second lies beyond the first by more than the error bound, the strip's best centre is the answer;
+// otherwise the strips that can hold the nearest centre are compared by float64 distances (their best
+// centre, or all their centres if the strip's second key is within the bound as well).
+__global__ void __launch_bounds__(256)
+nearest_strips_kernel(const uint2* __restrict__ S, int strip_w, const float* __restrict__ X, const float* __restrict__ C,
+                      const uint32_t* __restrict__ norm_max_bits, int n_rows, int k, int d, int32_t* __restrict__ labels) {
+    __shared__ uint32_t s_b1[4][64], s_b2[4][64], s_i1[4][64];
+    const int r = threadIdx.x & 63, sl = threadIdx.x >> 6;
+    const int row = blockIdx.x * 64 + r;
+    const int n_strips = (k + strip_w - 1) / strip_w;
+    const size_t stride = (size_t)n_rows;
+    uint32_t b1 = 0xFFFFFFFFu, b2 = 0xFFFFFFFFu, i1 = 0u;
+    if (row < n_rows)
+        for (int i = sl; i < n_strips; i += 4) {
+            const uint2 v = S[(size_t)i * stride + row];
+            if (v.x < b1) { b2 = b1 < v.y ? b1 : v.y; b1 = v.x; i1 = (uint32_t)i; }
+            else if (v.x < b2) b2 = v.x;
+        }
+    s_b1[sl][r] = b1; s_b2[sl][r] = b2; s_i1[sl][r] = i1;
+    __syncthreads();
+    if (sl != 0 || row >= n_rows) return;
+    for (int o = 1; o < 4; ++o) {
+        const uint32_t c1 = s_b1[o][r], c2 = s_b2[o][r], ci = s_i1[o][r];
+        if (c1 < b1 || (c1 == b1 && ci < i1)) { b2 = b1 < c2 ? b1 : c2; b1 = c1; i1 = ci; }
+        else if (c1 < b2) b2 = c1;
+    }
+    const float* x = X + (size_t)row * d;
+    float qn = 0.f;
+    for (int t = 0; t < d; ++t) qn = __builtin_fmaf(x[t], x[t], qn);
+    const float delta = rank_error_bound(d, qn, __uint_as_float(*norm_max_bits));
+    float lim = ordered_key_value(b1 | 63u) + 2.f * delta;
+    lim += __builtin_fabsf(lim) * 2.3841858e-07f;
+    const uint32_t limit = (lim == lim) ? ordered_key(lim) : 0xFFFFFFFFu;
+    int first = (int)(i1 * (uint32_t)strip_w + (b1 & 63u));
+    if (first >= k) first = 0;                 // only if every key is the all-ones pattern
+    if ((b2 & ~63u) > limit) { labels[row] = first; return; }
+    double best = __longlong_as_double(0x7FF0000000000000ll);
+    int arg = 0x7FFFFFFF;
+    auto try_centre = [&](int c) {
+        const float* cc = C + (size_t)c * d;
+        double dist = 0.0;
+        for (int t = 0; t < d; ++t) { const double diff = (double)x[t] - (double)cc[t]; dist += diff * diff; }
+        if (dist < best) { best = dist; arg = c; }        // centres come in ascending order: ties stay with the lower
+    };
+    for (int i = 0; i < n_strips; ++i) {
+        const uint2 v = S[(size_t)i * stride + row];
+        if ((v.x & ~63u) > limit) continue;
+        const int c0 = i * strip_w;
+        if ((v.y & ~63u) > limit) {
+            const int c = c0 + (int)(v.x & 63u);
+            if (c < k) try_centre(c);
+        } else {
+            const int c1 = c0 + strip_w < k ? c0 + strip_w : k;
+            for (int c = c0; c < c1; ++c) try_centre(c);
+        }
+    }
+    labels[row] = arg < k ? arg : first;       // no finite distance (NaN inputs): stay in range
+}
+
 __global__ void count_labels_kernel(const int32_t* __restrict__ labels, size_t n, uint32_t* __restrict__ counts) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) atomicAdd(&counts[labels[i]], 1u);
@@ -359,26 +422,39 @@ struct BuildPlan {
     size_t n_group;                 // largest number of items grouped at once
     size_t k_group;                 // largest number of groups
     // offsets into the workspace
-    size_t Xt, A, split, C, cnorm, cmax, labels_t, labels_all, order, tmp, counts, cursor, offsets, ct_rows, pt_rows,
+    bool use_strips;                // nearest centres from strip summaries instead of all ranking values
+    size_t Xt, A, S, split, C, cnorm, cmax, labels_t, labels_all, order, tmp, counts, cursor, offsets, ct_rows, pt_rows,
            init_rows, Rt, pq_labels, codebooks, codes, total;
 };
+
+// Scratch of the nearest-centre step for up to n_rows_max rows against k centres: the tile height and
+// the offsets of A (all ranking values; few centres) or S (strip summaries), of the bf16 operands, of the
+// centre norms and their maximum.
+template <class Take>
+void plan_nearest(BuildPlan& P, size_t n_rows_max, int k, int d, Take&& take) {
+    const size_t strips = ((size_t)k + 31) / 32;
+    P.use_strips = k >= 256;
+    const size_t per_row = (P.use_strips ? strips * 8 : (size_t)k * 4) + (size_t)coarse_padded_dim(d) * 4;
+    P.tile_rows = std::max<size_t>(1, std::min<size_t>(kRankTileBytes / per_row, (size_t)2 << 20));
+    P.tile_rows = std::min<size_t>(P.tile_rows, std::max<size_t>(n_rows_max, 1));
+    P.A = take(P.use_strips ? 0 : P.tile_rows * (size_t)k * 4);
+    P.S = take(P.use_strips ? P.tile_rows * strips * 8 : 0);
+    P.split = take(coarse_split_bytes(P.tile_rows, (size_t)k, d));
+    P.cnorm = take((size_t)k * 4);
+    P.cmax = take(4);
+}
 
 BuildPlan make_build_plan(int64_t n, int d, int n_lists, int pq_dim, int pq_bits, int64_t n_ct, int64_t n_pt) {
     BuildPlan P{};
     P.n = n; P.n_ct = n_ct; P.n_pt = n_pt; P.d = d; P.n_lists = n_lists; P.pq_dim = pq_dim; P.pq_bits = pq_bits;
     P.m = d / pq_dim; P.ksub = 1 << pq_bits;
-    P.tile_rows = std::max<size_t>(1, std::min<size_t>(kRankTileBytes / ((size_t)n_lists * 4), (size_t)2 << 20));
-    P.tile_rows = std::min<size_t>(P.tile_rows, (size_t)std::max<int64_t>(n, n_ct));
     P.n_group = std::max<size_t>((size_t)n, (size_t)n_pt * pq_dim);
     P.k_group = std::max<size_t>((size_t)n_lists, (size_t)pq_dim * P.ksub);
     size_t at = 0;
     auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
     P.Xt = take((size_t)n_ct * d * 4);
-    P.A = take(P.tile_rows * (size_t)n_lists * 4);
-    P.split = take(coarse_split_bytes(P.tile_rows, (size_t)n_lists, d));
+    plan_nearest(P, (size_t)std::max<int64_t>(n, n_ct), n_lists, d, take);
     P.C = take((size_t)n_lists * d * 4);
-    P.cnorm = take((size_t)n_lists * 4);
-    P.cmax = take(4);
     P.labels_t = take((size_t)n_ct * 4);
     P.labels_all = take((size_t)n * 4);
     P.order = take(P.n_group * 4);
@@ -410,14 +486,19 @@ int assign_rows_device(const BuildPlan& P, unsigned char* ws, const float* X, si
     float* cnorm = (float*)(ws + P.cnorm);
     uint32_t* cmax = (uint32_t*)(ws + P.cmax);
     uint32_t* A = (uint32_t*)(ws + P.A);
+    uint2* S = (uint2*)(ws + P.S);
     if (int s = fill_u32(cmax, 1, 0u, st)) return s;
     hipLaunchKernelGGL(centre_norms_kernel, dim3(blocks_for((size_t)k, 4)), dim3(256), 0, st, C, k, P.d, cnorm, cmax);
     HIP_TRY(hipGetLastError());
     for (size_t r0 = 0; r0 < n_rows; r0 += P.tile_rows) {
         const int tr = (int)std::min(P.tile_rows, n_rows - r0);
-        if (int s = launch_coarse(X + r0 * P.d, C, cnorm, tr, k, P.d, A, nullptr, ws + P.split, st)) return s;
-        hipLaunchKernelGGL(nearest_kernel, dim3(blocks_for((size_t)tr, 4)), dim3(256), 0, st, A, X + r0 * P.d, C, cmax, tr,
-                           k, P.d, labels + r0);
+        if (int s = launch_coarse(X + r0 * P.d, C, cnorm, tr, k, P.d, A, P.use_strips ? S : nullptr, ws + P.split, st)) return s;
+        if (P.use_strips)
+            hipLaunchKernelGGL(nearest_strips_kernel, dim3(blocks_for((size_t)tr, 64)), dim3(256), 0, st, (const uint2*)S,
+                               coarse_strip_width(tr, k), X + r0 * P.d, C, cmax, tr, k, P.d, labels + r0);
+        else
+            hipLaunchKernelGGL(nearest_kernel, dim3(blocks_for((size_t)tr, 4)), dim3(256), 0, st, A, X + r0 * P.d, C, cmax, tr,
+                               k, P.d, labels + r0);
         HIP_TRY(hipGetLastError());
     }
     return IVFPQ_OK;
@@ -508,24 +589,20 @@ int ivfpq_assign_device(const float* d_rows, int64_t n_rows, int32_t d, const fl
     if (n_rows == 0) return IVFPQ_OK;
     BuildPlan P{};
     P.d = d;
-    P.tile_rows = std::max<size_t>(1, std::min<size_t>(kRankTileBytes / ((size_t)n_centres * 4), (size_t)2 << 20));
-    P.tile_rows = std::min<size_t>(P.tile_rows, (size_t)n_rows);
     size_t at = 0;
-    auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
-    P.A = take(P.tile_rows * (size_t)n_centres * 4);
-    P.cnorm = take((size_t)n_centres * 4);
-    P.cmax = take(4);
+    plan_nearest(P, (size_t)n_rows, n_centres, d, [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; });
     if (!d_workspace || workspace_bytes < at)
         return fail(IVFPQ_ENOSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, at);
     return assign_rows_device(P, (unsigned char*)d_workspace, d_rows, (size_t)n_rows, d_centres, n_centres, d_labels,
                               (hipStream_t)hip_stream);
 }
 
-size_t ivfpq_assign_device_workspace_bytes(int64_t n_rows, int32_t n_centres) {
-    if (n_rows < 0 || n_centres < 1) { set_error("ivfpq_assign_device_workspace_bytes: bad shape"); return 0; }
-    size_t tile = std::max<size_t>(1, std::min<size_t>(kRankTileBytes / ((size_t)n_centres * 4), (size_t)2 << 20));
-    tile = std::min<size_t>(tile, (size_t)std::max<int64_t>(n_rows, 1));
-    return align_up(tile * (size_t)n_centres * 4) + align_up((size_t)n_centres * 4) + align_up(4);
+size_t ivfpq_assign_device_workspace_bytes(int64_t n_rows, int32_t d, int32_t n_centres) {
+    if (n_rows < 0 || d < 1 || n_centres < 1) { set_error("ivfpq_assign_device_workspace_bytes: bad shape"); return 0; }
+    BuildPlan P{};
+    size_t at = 0;
+    plan_nearest(P, (size_t)n_rows, n_centres, d, [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; });
+    return at;
 }
 
 int ivfpq_build_device(const float* d_data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,

@@ -40,7 +40,12 @@ def _data(n, d, seed, offset=0.0, kind="gauss"):
 
 @pytest.mark.parametrize("n,d,k,offset,kind", [(5000, 48, 300, 0.0, "gauss"), (3000, 32, 64, 500.0, "gauss"),
                                                (4000, 16, 200, 0.0, "intgrid"), (1000, 7, 3, 0.0, "gauss"),
-                                               (700, 128, 1, 0.0, "gauss")])
+                                               (700, 128, 1, 0.0, "gauss"),
+                                               # 256 centres or more: decided from strip summaries of the ranking values
+                                               (20000, 32, 2000, 0.0, "gauss"),      # 128 x 128 bf16 tiles, 64-centre strips
+                                               (6000, 16, 700, 0.0, "intgrid"),      # ties, ragged last 32-centre strip
+                                               (5000, 24, 1000, 500.0, "gauss"),     # most rows through the float64 path
+                                               (40000, 8, 4000, 0.0, "intgrid")])    # ties under the bf16 tiles
 def test_assign_device_equals_oracle(P, n, d, k, offset, kind):
     # offset 500: norms dwarf the distances, so many rows go through the exact float64 path;
     # intgrid: exactly tied distances, decided by the lower index
@@ -87,6 +92,7 @@ def _assert_same_index(gidx, oidx):
     (4_000, 64, 12, 32, 5, 2, 4_000, 2_000, "gauss"),       # 5-bit codes: 32 sub-spaces in 5 words
     (4_000, 32, 12, 16, 6, 2, 2_000, 2_000, "gauss"),       # 6-bit codes: 16 sub-spaces in 3 words
     (4_000, 64, 12, 32, 7, 2, 4_000, 2_000, "intgrid"),     # 7-bit codes, tied distances
+    (30_000, 32, 512, 16, 8, 3, 15_000, 4_000, "gauss"),    # 512 lists: nearest centres from strip summaries
 ])
 def test_build_device_is_identical_to_oracle_build(P, n, d, n_lists, pq_dim, pq_bits, iters, n_ct, n_pt, kind):
     x = _data(n, d, 100 + n + d, 0.0, kind)
