@@ -1097,6 +1097,54 @@ __global__ void pair_count_kernel(const uint4* __restrict__ pairs, uint32_t n_pa
     atomicAdd(&counts[l < (uint32_t)n_lists ? l : 0u], 1u);       // a caller-given probe may be out of range
 }
 
+// The same two steps for few clusters, where many pairs name the same cluster and one global atomic per
+// pair would serialise: a workgroup of 1024 threads takes kPairChunk pairs, counts them per cluster in LDS
+// and issues one global atomic per cluster it met.  Dynamic LDS: n_lists words (count) or 2 n_lists (scatter).
+constexpr uint32_t kPairChunk = 8192;
+constexpr int kPairLdsLists = 8192;       // up to this many clusters
+
+__device__ inline uint32_t pair_cluster(const uint4* __restrict__ pairs, uint32_t i, int n_probes, int n_lists) {
+    const uint32_t q = i / (uint32_t)(n_probes - 1), p = 1 + i - q * (uint32_t)(n_probes - 1);
+    const uint32_t l = pairs[(size_t)q * n_probes + p].x;
+    return l < (uint32_t)n_lists ? l : 0u;                        // a caller-given probe may be out of range
+}
+
+__global__ void __launch_bounds__(1024)
+pair_count_lds_kernel(const uint4* __restrict__ pairs, uint32_t n_pairs, int n_probes, int n_lists,
+                      uint32_t* __restrict__ counts) {
+    extern __shared__ uint32_t s_cnt[];
+    for (int l = threadIdx.x; l < n_lists; l += blockDim.x) s_cnt[l] = 0;
+    __syncthreads();
+    const uint32_t i0 = blockIdx.x * kPairChunk, i1 = i0 + kPairChunk < n_pairs ? i0 + kPairChunk : n_pairs;
+    for (uint32_t i = i0 + threadIdx.x; i < i1; i += blockDim.x) atomicAdd(&s_cnt[pair_cluster(pairs, i, n_probes, n_lists)], 1u);
+    __syncthreads();
+    for (int l = threadIdx.x; l < n_lists; l += blockDim.x)
+        if (s_cnt[l]) atomicAdd(&counts[l], s_cnt[l]);
+}
+
+__global__ void __launch_bounds__(1024)
+pair_scatter_lds_kernel(const uint4* __restrict__ pairs, uint32_t n_pairs, int n_probes, int n_lists,
+                        const uint32_t* __restrict__ offsets, uint32_t* __restrict__ cursor, uint32_t* __restrict__ order) {
+    extern __shared__ uint32_t s_mem[];
+    uint32_t* s_cnt = s_mem;                  // pairs of this chunk per cluster, then the running rank
+    uint32_t* s_base = s_mem + n_lists;       // first slot of this chunk's pairs inside the cluster's range
+    for (int l = threadIdx.x; l < n_lists; l += blockDim.x) s_cnt[l] = 0;
+    __syncthreads();
+    const uint32_t i0 = blockIdx.x * kPairChunk, i1 = i0 + kPairChunk < n_pairs ? i0 + kPairChunk : n_pairs;
+    for (uint32_t i = i0 + threadIdx.x; i < i1; i += blockDim.x) atomicAdd(&s_cnt[pair_cluster(pairs, i, n_probes, n_lists)], 1u);
+    __syncthreads();
+    for (int l = threadIdx.x; l < n_lists; l += blockDim.x) {
+        const uint32_t c = s_cnt[l];
+        s_base[l] = c ? offsets[l] + atomicAdd(&cursor[l], c) : 0u;
+        s_cnt[l] = 0;
+    }
+    __syncthreads();
+    for (uint32_t i = i0 + threadIdx.x; i < i1; i += blockDim.x) {
+        const uint32_t l = pair_cluster(pairs, i, n_probes, n_lists);
+        order[s_base[l] + atomicAdd(&s_cnt[l], 1u)] = i;
+    }
+}
+
 // offsets[l] = counts[0] + ... + counts[l-1]; one workgroup
 __global__ void __launch_bounds__(1024)
 pair_offsets_kernel(const uint32_t* __restrict__ counts, int n_lists, uint32_t* __restrict__ offsets) {
@@ -1564,10 +1612,20 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
                 // counts and cursors are adjacent in the plan only up to alignment: two fills
                 hipLaunchKernelGGL(fill_u32_kernel, dim3((idx->n_lists + 255) / 256), dim3(256), 0, st, w_lc, (size_t)idx->n_lists, 0u);
                 hipLaunchKernelGGL(fill_u32_kernel, dim3((idx->n_lists + 255) / 256), dim3(256), 0, st, w_cur, (size_t)idx->n_lists, 0u);
-                hipLaunchKernelGGL(pair_count_kernel, dim3(pb), dim3(256), 0, st, w_pairs, (uint32_t)n_pairs, n_probes, idx->n_lists, w_lc);
-                hipLaunchKernelGGL(pair_offsets_kernel, dim3(1), dim3(1024), 0, st, w_lc, idx->n_lists, w_lo);
-                hipLaunchKernelGGL(pair_scatter_kernel, dim3(pb), dim3(256), 0, st, w_pairs, (uint32_t)n_pairs, n_probes, idx->n_lists,
-                                   w_lo, w_cur, w_order);
+                if (idx->n_lists <= kPairLdsLists) {
+                    const unsigned cb = (unsigned)((n_pairs + kPairChunk - 1) / kPairChunk);
+                    const size_t lds = (size_t)idx->n_lists * 4;
+                    if (int s = allow_full_lds(pair_scatter_lds_kernel)) return s;
+                    hipLaunchKernelGGL(pair_count_lds_kernel, dim3(cb), dim3(1024), lds, st, w_pairs, (uint32_t)n_pairs, n_probes, idx->n_lists, w_lc);
+                    hipLaunchKernelGGL(pair_offsets_kernel, dim3(1), dim3(1024), 0, st, w_lc, idx->n_lists, w_lo);
+                    hipLaunchKernelGGL(pair_scatter_lds_kernel, dim3(cb), dim3(1024), 2 * lds, st, w_pairs, (uint32_t)n_pairs, n_probes,
+                                       idx->n_lists, w_lo, w_cur, w_order);
+                } else {
+                    hipLaunchKernelGGL(pair_count_kernel, dim3(pb), dim3(256), 0, st, w_pairs, (uint32_t)n_pairs, n_probes, idx->n_lists, w_lc);
+                    hipLaunchKernelGGL(pair_offsets_kernel, dim3(1), dim3(1024), 0, st, w_lc, idx->n_lists, w_lo);
+                    hipLaunchKernelGGL(pair_scatter_kernel, dim3(pb), dim3(256), 0, st, w_pairs, (uint32_t)n_pairs, n_probes, idx->n_lists,
+                                       w_lo, w_cur, w_order);
+                }
                 HIP_TRY(hipGetLastError());
                 a.order = w_order;
                 a.n_pairs = (uint32_t)n_pairs;
