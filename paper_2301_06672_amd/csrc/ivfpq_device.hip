@@ -11,12 +11,12 @@
 //                        built in LDS as fp32 / half / e5m3 / e4m4, then every wave streams 64-vector
 //                        groups of PQ codes from HBM and accumulates R = sum_j F(y_j) (Eq. 1)
 //   bound_kernel         the k-th smallest R of that nearest cluster: an upper bound of the final
-//                        k-th distance of the query
+//                        k-th distance of the query; the cluster's values under it start the survivor list
 //   pair_count / pair_offsets / pair_scatter   the other (query, probe) pairs grouped by cluster
 //   scan_kernel (mode 2) steps 2-4 for the other probes, in cluster-grouped, XCD-aware order (a
 //                        cluster's codes then come from one XCD's L2); only R values under the bound
 //                        are kept
-//   topk_kernel          step 5: the k smallest R over all probed clusters of a query, ordered by
+//   topk_kernel          step 5: the k smallest R among the survivors of a query, ordered by
 //                        (R, id), and the map from (cluster, position) to the caller's ids
 // Beside the path: dump_lut_kernel (steps 2-3 of one pair, for inspection) and refine_kernel (exact
 // re-ranking of candidates with the stored vectors).
@@ -248,6 +248,45 @@ __device__ int block_select_smallest(SelectShared& s, uint32_t n, uint32_t k, Ke
     return (int)kk;
 }
 
+// The same selection for few elements (n <= kFewMax <= blockDim.x; key_of must be cheap, every thread
+// calls it n times): thread i ranks element i by counting the elements that precede it in (key, tie,
+// index) order, three barriers in all.  It costs about n instructions per thread where the radix select
+// and the sort cost several hundred whatever n is.  Tie keys are fetched only for elements with fewer than
+// k smaller keys, and wait in the upper half of the record array while the ranks are settled.
+constexpr uint32_t kFewMax = 128;
+template <class KeyFn, class TieFn>
+__device__ int block_select_few(SelectShared& s, uint32_t n, uint32_t k, KeyFn key_of, TieFn tie_of) {
+    const uint32_t kk = k < n ? k : n;
+    if (kk == 0) return 0;
+    const uint32_t e = threadIdx.x;
+    constexpr uint32_t SCR = SEL_CAP / 2;
+    __syncthreads();
+    const uint32_t key = e < n ? key_of(e) : 0xFFFFFFFFu;
+    uint32_t less = 0, same = 0;
+    if (e < n)
+        for (uint32_t j = 0; j < n; ++j) {
+            const uint32_t kj = key_of(j);
+            less += kj < key ? 1u : 0u;
+            same += kj == key ? 1u : 0u;
+        }
+    const bool cand = e < n && less < kk;
+    long long tie = 0;
+    if (cand) { tie = tie_of(e); s.rec_tie[SCR + e] = tie; }
+    __syncthreads();
+    if (cand) {
+        uint32_t r = less;
+        if (same > 1)                        // elements with the same key all have their tie key in place
+            for (uint32_t j = 0; j < n; ++j) {
+                if (j == e || key_of(j) != key) continue;
+                const long long tj = s.rec_tie[SCR + j];
+                r += (tj < tie || (tj == tie && j < e)) ? 1u : 0u;
+            }
+        if (r < kk) { s.rec_key[r] = key; s.rec_tie[r] = tie; s.rec_pos[r] = e; }
+    }
+    __syncthreads();
+    return (int)kk;
+}
+
 // ------------------------------------------------------------------------------------------------
 // The k smallest of a long row of keys in global memory (tens of thousands per query).
 // The k-th smallest key among the first CAND_CAP elements is an upper bound of the k-th smallest
@@ -272,10 +311,11 @@ struct RowSelectShared {
 // (at least k elements of the row are <= it).
 // Hooks for rows whose keys are only approximate (probe selection): widen(bound) is applied to every
 // bound before it filters (it must return a key that no element the exact selection could need
-// exceeds); refine(n_cand) runs once the candidates sit in LDS and may replace their keys by exact
-// ones; whole_row() is the fallback when compaction fails and must return the selection itself.
+// exceeds); refine(n_cand) runs once the candidates sit in LDS, may replace their keys by exact ones and
+// drop candidates (it returns how many remain, at the front of the candidate arrays); whole_row() is the
+// fallback when compaction fails and must return the selection itself.
 struct NoWiden { __device__ uint32_t operator()(uint32_t b) const { return b; } };
-struct NoRefine { __device__ void operator()(uint32_t) const {} };
+struct NoRefine { __device__ uint32_t operator()(uint32_t n) const { return n; } };
 
 template <class PosFn, class TieFn, class WidenFn, class RefineFn, class WholeRowFn>
 __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
@@ -340,10 +380,11 @@ __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restric
     }
     int got;
     if (compact) {
-        refine(n_cand);
-        got = block_select_smallest(s, n_cand, k,
-            [&](uint32_t i) { return t.cand_key[i]; },
-            [&](uint32_t i) -> long long { return tie_of_pos(t.cand_pos[i], t.cand_key[i]); });
+        n_cand = refine(n_cand);
+        auto key_of = [&](uint32_t i) { return t.cand_key[i]; };
+        auto tie_of = [&](uint32_t i) -> long long { return tie_of_pos(t.cand_pos[i], t.cand_key[i]); };
+        got = n_cand <= kFewMax ? block_select_few(s, n_cand, k, key_of, tie_of)
+                                : block_select_smallest(s, n_cand, k, key_of, tie_of);
         for (int j = tid; j < got; j += nth) s.rec_pos[j] = t.cand_pos[s.rec_pos[j]];   // back to logical positions
     } else {
         got = whole_row();
@@ -435,9 +476,9 @@ select_probes_kernel(uint32_t* __restrict__ A, const uint2* __restrict__ S, int 
     };
     // candidates in LDS: keep those whose a() is within 2 delta of the n_probes-th smallest a() among
     // them (every cluster of the exact answer is among these), give them their exact distance
-    auto refine = [&](uint32_t n_cand) {
+    auto refine = [&](uint32_t n_cand) -> uint32_t {
         const uint32_t kk = (uint32_t)n_probes < n_cand ? (uint32_t)n_probes : n_cand;
-        if (kk == 0) return;
+        if (kk == 0) return n_cand;
         uint32_t r0, r1;
         const uint32_t limit = widen(block_kth_key(s, n_cand, kk, [&](uint32_t i) { return t.cand_key[i]; }, &r0, &r1));
         __syncthreads();
@@ -458,6 +499,14 @@ select_probes_kernel(uint32_t* __restrict__ A, const uint2* __restrict__ S, int 
             if (valid && (tid & 7) == 0) t.cand_key[i] = __float_as_uint(dist);
         }
         __syncthreads();
+        if (n_short > kFewMax) return n_cand;        // the others keep the all-ones key and are never selected
+        // few enough for the counting selection: move the short list to the front
+        const uint32_t i = (uint32_t)tid < n_short ? s.rec_pos[tid] : 0u;
+        const uint32_t mk = t.cand_key[i], mp = t.cand_pos[i];
+        __syncthreads();
+        if ((uint32_t)tid < n_short) { t.cand_key[tid] = mk; t.cand_pos[tid] = mp; }
+        __syncthreads();
+        return n_short;
     };
     // compaction failed (a plateau of equal ranking values): exact distances of all clusters
     auto whole_row = [&]() -> int {
@@ -521,8 +570,10 @@ select_probes_kernel(uint32_t* __restrict__ A, const uint2* __restrict__ S, int 
                 if (valid && (tid & 7) == 0) t.cand_key[j] = __float_as_uint(dist);
             }
             __syncthreads();
-            got = block_select_smallest(s, n_cand, (uint32_t)n_probes,
-                [&](uint32_t i) { return t.cand_key[i]; }, [&](uint32_t i) { return (long long)t.cand_pos[i]; });
+            auto key_of = [&](uint32_t i) { return t.cand_key[i]; };
+            auto tie_of = [&](uint32_t i) { return (long long)t.cand_pos[i]; };
+            got = n_cand <= kFewMax ? block_select_few(s, n_cand, (uint32_t)n_probes, key_of, tie_of)
+                                    : block_select_smallest(s, n_cand, (uint32_t)n_probes, key_of, tie_of);
             for (int j = tid; j < got; j += nth) s.rec_pos[j] = t.cand_pos[s.rec_pos[j]];
         } else {
             got = whole_row();       // a plateau of equal ranking values (or not-a-number keys)
@@ -1185,37 +1236,52 @@ __global__ void pair_scatter_kernel(const uint4* __restrict__ pairs, uint32_t n_
 // ================================================================================================
 // Between the two scan launches: per query, an upper bound of the k-th smallest R, taken from the
 // nearest probed cluster (whose R values are all in place): its k-th smallest R.  With fewer than
-// k vectors there the bound admits everything.  Also clears the query's survivor counter.
+// k vectors there the bound admits everything.  The values of that cluster that are not above the
+// bound become the first entries of the query's survivor list (behind the cluster's segment of the R
+// row: value + position), which the filtered scan extends; the top-k step then reads that list only.
 // ================================================================================================
 constexpr uint32_t kAdmitAll = 0xFFFFFFFEu;   // every real R is below this, the padding key is above
 
 __global__ void __launch_bounds__(SEL_THREADS)
-bound_kernel(const float* __restrict__ R, size_t stride, const uint4* __restrict__ pairs, int n_probes, int k,
-             uint32_t* __restrict__ bounds, uint32_t* __restrict__ counts) {
+bound_kernel(float* __restrict__ R, uint32_t* __restrict__ Rpos, size_t stride, const uint4* __restrict__ pairs,
+             int n_probes, int k, uint32_t* __restrict__ bounds, uint32_t* __restrict__ counts) {
     __shared__ SelectShared s;
     __shared__ uint32_t keys[CAND_CAP];
     const int q = blockIdx.x;
     const int tid = threadIdx.x, nth = blockDim.x;
     const uint32_t seg0 = n_probes > 1 ? pairs[(size_t)q * n_probes + 1].w : 0u;
     const uint32_t len0 = pairs[(size_t)q * n_probes].y;       // real values in the segment (the rest is padding)
-    const uint32_t* row = reinterpret_cast<const uint32_t*>(R + (size_t)q * stride);
+    uint32_t* row = reinterpret_cast<uint32_t*>(R + (size_t)q * stride);
+    uint32_t* row_pos = Rpos + (size_t)q * stride;
+    const bool in_lds = seg0 <= (uint32_t)CAND_CAP;
+    if (in_lds)
+        for (uint32_t i = tid; i < seg0; i += nth) keys[i] = row[i];
     uint32_t bound = kAdmitAll;
     if (len0 >= (uint32_t)k && seg0 >= len0) {
         uint32_t r0, r1;
-        if (seg0 <= (uint32_t)CAND_CAP) {
-            for (uint32_t i = tid; i < seg0; i += nth) keys[i] = row[i];
-            bound = block_kth_key(s, seg0, (uint32_t)k, [&](uint32_t i) { return keys[i]; }, &r0, &r1);
-        } else {
-            bound = block_kth_key(s, seg0, (uint32_t)k, [&](uint32_t i) { return row[i]; }, &r0, &r1);
+        if (in_lds) bound = block_kth_key(s, seg0, (uint32_t)k, [&](uint32_t i) { return keys[i]; }, &r0, &r1);
+        else bound = block_kth_key(s, seg0, (uint32_t)k, [&](uint32_t i) { return row[i]; }, &r0, &r1);
+    }
+    __syncthreads();
+    if (tid == 0) s.n_rec = 0;
+    __syncthreads();
+    const uint32_t real = len0 < seg0 ? len0 : seg0;
+    for (uint32_t i = tid; i < real; i += nth) {
+        const uint32_t key = in_lds ? keys[i] : row[i];
+        if (key <= bound) {
+            const uint32_t slot = seg0 + atomicAdd(&s.n_rec, 1u);
+            row[slot] = key;
+            row_pos[slot] = i;
         }
     }
-    if (tid == 0) { bounds[q] = bound; counts[q] = 0; }
+    __syncthreads();
+    if (tid == 0) { bounds[q] = bound; counts[q] = s.n_rec; }
 }
 
 // ================================================================================================
-// Step 5: per query, the k smallest R over all probed clusters, ordered by (R, id), by one exact
-// selection over the query's R row -- the nearest probe's segment followed by the survivors the
-// filtered scan appended -- and the map from (cluster, position) to the caller's id.
+// Step 5: the k smallest (R, id) of a query.  With several probes the candidates are the survivor list
+// (the nearest cluster's values under the bound, then what the filtered scan kept); with one probe, the
+// cluster's segment itself.
 // ================================================================================================
 __global__ void __launch_bounds__(SEL_THREADS)
 topk_kernel(const float* __restrict__ R, const uint32_t* __restrict__ Rpos, size_t stride,
@@ -1230,12 +1296,13 @@ topk_kernel(const float* __restrict__ R, const uint32_t* __restrict__ Rpos, size
     const uint32_t* s_roff = roff + (size_t)q * (n_probes + 1);     // read through the vector cache:
     const uint32_t* s_probe = probes + (size_t)q * n_probes;        // only the few survivors look them up
     const uint32_t seg0 = s_roff[1];          // padded length of the nearest probe's segment (a multiple of 64)
-    const uint32_t n = seg0 + (n_probes > 1 ? counts[q] : 0u);
-    const uint32_t* row = reinterpret_cast<const uint32_t*>(R + (size_t)q * stride);
-    const uint32_t* row_pos = Rpos + (size_t)q * stride;
+    const bool listed = n_probes > 1;         // candidates = the survivor list behind that segment
+    const uint32_t n = listed ? counts[q] : seg0;
+    const uint32_t* row = reinterpret_cast<const uint32_t*>(R + (size_t)q * stride) + (listed ? seg0 : 0u);
+    const uint32_t* row_pos = Rpos + (size_t)q * stride + (listed ? seg0 : 0u);
 
-    // position of row element i in the unfiltered layout (probe segments back to back)
-    auto pos_of = [&](uint32_t i) { return i < seg0 ? i : row_pos[i]; };
+    // position of candidate i in the unfiltered layout (probe segments back to back)
+    auto pos_of = [&](uint32_t i) { return listed ? row_pos[i] : i; };
     // tie key = the caller's id of the candidate at that position (padding slots sort last)
     auto id_of = [&](uint32_t pos, uint32_t key) -> long long {
         if (key == kPadKey) return 0x7FFFFFFFFFFFFFFFll;
@@ -1344,6 +1411,8 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     int64_t stride = given_probes
         ? (int64_t)n_probes * (idx->sorted_padded_sizes.empty() ? 0 : idx->sorted_padded_sizes[0])
         : idx->max_padded_candidates(n_probes);
+    // the survivor list of a query also takes the nearest cluster's values under the bound
+    stride += idx->sorted_padded_sizes.empty() ? 0 : idx->sorted_padded_sizes[0];
     if (stride >= ((int64_t)1 << 31))
         return fail(IVFPQ_EUNSUPPORTED, "a query may see %lld candidates (limit 2^31)", (long long)stride);
     if (stride < 64) stride = 64;
@@ -1598,7 +1667,7 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         a.mode = 1;
         if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)tq), st)) return s;
         if (n_probes > 1) {
-            hipLaunchKernelGGL(bound_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_R, plan.stride, w_pairs, n_probes, k,
+            hipLaunchKernelGGL(bound_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_R, w_Rpos, plan.stride, w_pairs, n_probes, k,
                                w_bounds, w_counts);
             HIP_TRY(hipGetLastError());
             a.mode = 2;
