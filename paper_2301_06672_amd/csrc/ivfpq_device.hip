@@ -2,17 +2,20 @@
 // (arXiv 2301.06672, Sec. I-C second enumeration, Sec. I-D, Sec. II) for gfx950 (MI355X, wave64).
 //
 // Kernels, in the order one search call runs them (per tile of queries):
-//   coarse_rank_kernel   step 1a: ranking values |c|^2 - 2 q.c of every (query, cluster) pair on the
-//                        matrix cores (fp32 MFMA)
-//   select_probes_kernel step 1b: short list by ranking value with a rigorous error bound, exact
-//                        direct-form distances for the short list, exact selection of the n_probes
-//                        nearest clusters; per-pair descriptors and R offsets
+//   coarse_rank_*_kernel step 1a: ranking values |c|^2 - 2 q.c of every (query, cluster) pair on the
+//                        matrix cores: bf16 instructions on operands split in two for large problems,
+//                        fp32 otherwise; stored as all keys (few clusters) or as the two smallest
+//                        tagged keys of every strip of 32 / 64 clusters
+//   select_probes_kernel step 1b: candidates by ranking value with a rigorous error bound, exact
+//                        direct-form distances for them, exact selection of the n_probes nearest
+//                        clusters; per-pair descriptors and R offsets
 //   scan_kernel (mode 1) steps 2-4 for the nearest probe of every query: query residual, lookup table F
 //                        built in LDS as fp32 / half / e5m3 / e4m4, then every wave streams 64-vector
 //                        groups of PQ codes from HBM and accumulates R = sum_j F(y_j) (Eq. 1)
 //   bound_kernel         the k-th smallest R of that nearest cluster: an upper bound of the final
 //                        k-th distance of the query; the cluster's values under it start the survivor list
 //   pair_count / pair_offsets / pair_scatter   the other (query, probe) pairs grouped by cluster
+//                        (counts per workgroup in LDS first when there are few clusters)
 //   scan_kernel (mode 2) steps 2-4 for the other probes, in cluster-grouped, XCD-aware order (a
 //                        cluster's codes then come from one XCD's L2); only R values under the bound
 //                        are kept

@@ -1,5 +1,6 @@
 // Device code shared by the search kernels and the index builder: HIP error macro, small constants,
-// order-preserving float keys and the fp32 MFMA ranking GEMM |c|^2 - 2 x.c.
+// order-preserving float keys and the MFMA ranking GEMMs |c|^2 - 2 x.c (fp32, and bf16 on split operands)
+// with their epilogue (all keys, or per-strip summaries) and the bound of their error.
 // Included by .hip translation units only; everything has internal linkage.
 #pragma once
 
@@ -48,11 +49,12 @@ int allow_full_lds(Kernel kernel) { return allow_full_lds_ptr(reinterpret_cast<c
 // ================================================================================================
 // Ranking values on the matrix cores (search step 1a; the assignment step of the index build).
 // For ranking the clusters of one query |q - c|^2 can be replaced by a(q, c) = |c|^2 - 2 q.c (the
-// |q|^2 term is common).  The dot products are one fp32 GEMM: v_mfma_f32_32x32x2_f32, a tile of
-// 128 queries x 128 clusters (or 64 x 64 for small problems) per 256-thread workgroup, operands
-// staged through LDS in slices of 16 components.  The expanded form cancels, so these values only
-// SHORT-LIST clusters: the kernels that consume them bound the error of a() rigorously and recompute
-// the distances of everything inside that bound in direct form, so their decisions are exact.
+// |q|^2 term is common).  The dot products are one GEMM: a tile of 64 queries x 64 clusters per
+// 256-thread workgroup on v_mfma_f32_32x32x2_f32 for small problems, 128 x 128 on the bf16 instruction
+// with split operands for large ones, operands staged through LDS in slices of 16 components.  The
+// expanded form cancels, so these values only SHORT-LIST clusters: the kernels that consume them bound the
+// error of a() rigorously (rank_error_bound) and recompute the distances of everything inside that bound
+// in direct form, so their decisions are exact.
 // Values are stored as order-preserving unsigned keys (a() can be negative).
 // ================================================================================================
 constexpr int CK = 16;   // components per LDS slice
