@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth, GB/s
+LDS_PEAK_LOOKUPS = 256 * 32 * 2.4e9     # conflict-free wave-wide LDS reads: 32 lanes per clock and CU
 
 # Memory-side traffic of the scan kernel per step (all launches of one step), in bytes, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads
@@ -324,6 +325,10 @@ def main():
         "algorithmic_bytes_per_step": code_bytes, "scanned_vectors_per_step": scanned_vectors,
         "scan_ms_per_step": round(scan_ms, 4),
         "other_units": MEASURED_UNITS.get((w.name, args.lut)),
+        # the unit that does bound the kernel: table lookups against a conflict-free LDS
+        # (256 CUs x 32 lanes per clock x 2.4 GHz; a 256-entry row of 1-byte entries cannot beat half of it)
+        "lds": {"achieved": round(scanned_vectors * w.pq_dim / (scan_ms * 1e-3), 1), "peak": LDS_PEAK_LOOKUPS,
+                "unit": "lookups/s", "frac": round(scanned_vectors * w.pq_dim / (scan_ms * 1e-3) / LDS_PEAK_LOOKUPS, 4)},
         "note": "achieved, traffic and the byte counts are per step = all scan_kernel launches of one step "
                 "(two launches per query tile); the ratio equals bytes per launch / average launch time. "
                 "achieved counts the algorithmic PQ-code bytes; traffic is what HBM delivered: pairs run grouped by "

@@ -116,8 +116,8 @@ __device__ inline Low2 half_wave_low2x16(const uint32_t (&lo1)[16], const uint32
 // Either all keys are stored, A[nq][n_lists] (S null), or only a summary of every strip of 32*WB
 // consecutive clusters (the ones a wave covers), S[n_strips][nq] (strip-major, so that a wave stores the
 // summaries of its 64 queries contiguously): the two smallest keys of the strip, each with its low six
-// bits replaced by the cluster's position in the strip.  Clearing those bits lowers a key by less than
-// 2^-17 |a|; a consumer takes (x & ~63) as a lower and (x | 63) as an upper bound of the key.  All-ones
+// bits replaced by the cluster's position in the strip.  Clearing those bits lowers a key by at most 63
+// units in the last place; a consumer takes (x & ~63) as a lower and (x | 63) as an upper bound of the key.  All-ones
 // means "no such cluster".  stage: 512 words of LDS that no wave still reads.
 // Accumulator layout of a 32x32 block: register v of lane L holds row 8*(v/4) + 4*(L/32) + v%4, column L%32.
 template <int WB>
