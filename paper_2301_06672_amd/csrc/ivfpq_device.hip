@@ -1199,30 +1199,26 @@ pair_scatter_lds_kernel(const uint4* __restrict__ pairs, uint32_t n_pairs, int n
     }
 }
 
-// offsets[l] = counts[0] + ... + counts[l-1]; one workgroup
+// offsets[l] = counts[0] + ... + counts[l-1]; one workgroup: every thread adds up a contiguous run of
+// counters, one scan over the 1024 run totals, then every thread writes the offsets of its run
 __global__ void __launch_bounds__(1024)
 pair_offsets_kernel(const uint32_t* __restrict__ counts, int n_lists, uint32_t* __restrict__ offsets) {
     __shared__ uint32_t part[1024];
-    __shared__ uint32_t carry;
     const int tid = threadIdx.x;
-    if (tid == 0) carry = 0;
+    const int run = (n_lists + 1023) / 1024;
+    const int l0 = tid * run, l1 = l0 + run < n_lists ? l0 + run : n_lists;
+    uint32_t own = 0;
+    for (int l = l0; l < l1; ++l) own += counts[l];
+    part[tid] = own;
     __syncthreads();
-    for (int base = 0; base < n_lists; base += 1024) {
-        const int l = base + tid;
-        const uint32_t own = l < n_lists ? counts[l] : 0u;
-        part[tid] = own;
+    for (int off = 1; off < 1024; off <<= 1) {
+        const uint32_t v = tid >= off ? part[tid - off] : 0u;
         __syncthreads();
-        for (int off = 1; off < 1024; off <<= 1) {
-            const uint32_t v = tid >= off ? part[tid - off] : 0u;
-            __syncthreads();
-            part[tid] += v;
-            __syncthreads();
-        }
-        if (l < n_lists) offsets[l] = carry + part[tid] - own;
-        __syncthreads();
-        if (tid == 1023) carry += part[1023];
+        part[tid] += v;
         __syncthreads();
     }
+    uint32_t at = part[tid] - own;
+    for (int l = l0; l < l1; ++l) { offsets[l] = at; at += counts[l]; }
 }
 
 __global__ void pair_scatter_kernel(const uint4* __restrict__ pairs, uint32_t n_pairs, int n_probes, int n_lists,
