@@ -45,7 +45,8 @@ def _data(n, d, seed, offset=0.0, kind="gauss"):
                                                (20000, 32, 2000, 0.0, "gauss"),      # 128 x 128 bf16 tiles, 64-centre strips
                                                (6000, 16, 700, 0.0, "intgrid"),      # ties, ragged last 32-centre strip
                                                (5000, 24, 1000, 500.0, "gauss"),     # most rows through the float64 path
-                                               (40000, 8, 4000, 0.0, "intgrid")])    # ties under the bf16 tiles
+                                               (40000, 8, 4000, 0.0, "intgrid"),     # ties under the bf16 tiles
+                                               (30000, 20, 3000, 0.0, "gauss")])     # d not a multiple of the bf16 slices
 def test_assign_device_equals_oracle(P, n, d, k, offset, kind):
     # offset 500: norms dwarf the distances, so many rows go through the exact float64 path;
     # intgrid: exactly tied distances, decided by the lower index

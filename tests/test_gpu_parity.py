@@ -293,6 +293,49 @@ def test_select_probes_strip_minima_large_batch(P):
         np.testing.assert_array_equal(row, [17] + list(range(5990, 5996)))
 
 
+def test_select_probes_bf16_tiles_with_padded_dimension(P):
+    # d = 24 is not a multiple of the 16-component slices of the bf16 kernel: the split pads with zeros
+    arrays = list(si.random_index_arrays(7000, 24, 6000, 12, 8, salt=340))
+    oidx = oracle.make_index(24, 6000, 12, 8, *arrays)
+    gidx = to_library(P, oidx)
+    q = np.random.default_rng(340).standard_normal((3000, 24)).astype(np.float32)
+    for n_probes in (5, 33):
+        _step(f"select_probes d=24 L=6000 nq=3000 P={n_probes}")
+        probes, pd = gidx.ivfpq_select_probes(q, n_probes)
+        want, want_d = oracle.select_probes(oidx, q, n_probes)
+        np.testing.assert_allclose(pd.cpu().numpy(), want_d, rtol=RTOL)
+        assert (probes.cpu().numpy().view(np.uint32) == want).mean() > 0.999
+
+
+@pytest.mark.parametrize("nq", [40, 3000])
+def test_non_finite_queries_stay_in_range(P, nq):
+    # NaN, infinite and huge queries: the call returns, every index it returns is valid, and the finite
+    # queries of the same batch get their exact answer (40 queries: fp32 tiles and all ranking keys;
+    # 3000: bf16 tiles and strip summaries)
+    arrays = list(si.random_index_arrays(7000, 32, 6000, 16, 8, salt=350))
+    oidx = oracle.make_index(32, 6000, 16, 8, *arrays)
+    gidx = to_library(P, oidx)
+    q = np.random.default_rng(350).standard_normal((nq, 32)).astype(np.float32)
+    bad = [1, 7, 20, 33]
+    q[1, 3] = np.nan
+    q[7, :] = np.inf
+    q[20, 0] = -np.inf
+    q[33, :] = 3.0e38
+    good = np.setdiff1d(np.arange(nq), bad)
+    _step(f"non-finite queries nq={nq}: probes")
+    probes, _ = gidx.ivfpq_select_probes(q, 12)
+    probes = probes.cpu().numpy().view(np.uint32)
+    assert probes.max() < 6000
+    want, _ = oracle.select_probes(oidx, q[good], 12)
+    assert (probes[good] == want).mean() > 0.999
+    _step(f"non-finite queries nq={nq}: search")
+    ids, dist = gidx.ivfpq_search(q, 12, 10, P.LUT_FP8_E5M3)
+    ids = ids.cpu().numpy()
+    assert ids.min() >= -1 and ids.max() < 7000
+    ids_o, d_o = oracle.search(oidx, q[good], 12, 10, oracle.LUT_E5M3, probes=probes[good])
+    assert_topk_matches(ids[good], dist.cpu().numpy()[good], ids_o, d_o, context="finite queries beside non-finite ones")
+
+
 def test_select_probes_plateau_of_equal_centroids(P):
     # 40,000 clusters, all but three with the same centroid: every strip minimum equals the bound, more
     # strips qualify than the list holds, the whole row overflows the candidate buffer and the kernel
