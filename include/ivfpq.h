@@ -18,9 +18,10 @@
  *  - Row-major everywhere.  Distances are squared L2 (Sec. I-B).
  *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *    Search calls only enqueue work; they do not synchronise.
- *  - Two environment variables override launch heuristics, for tuning experiments only:
- *    IVFPQ_SCAN_THREADS (64 ... 1024: workgroup size of the scan kernel) and IVFPQ_ORDER_BLOCK
- *    (consecutive (query, probe) pairs of the cluster-grouped order that stay on one XCD).
+ *  - Three environment variables override launch heuristics, for tuning experiments only:
+ *    IVFPQ_SCAN_THREADS (64 ... 1024: workgroup size of the scan kernel), IVFPQ_ORDER_BLOCK
+ *    (consecutive (query, probe) pairs of the cluster-grouped order that stay on one XCD) and
+ *    IVFPQ_SCAN_TWO (0 / 1: never / wherever possible scan two pairs of one cluster per workgroup).
  */
 #ifndef IVFPQ_H
 #define IVFPQ_H

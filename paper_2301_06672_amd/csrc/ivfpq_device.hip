@@ -1090,6 +1090,201 @@ scan_kernel(ScanArgs a) {
     if (filtered) flush_stage();
 }
 
+// ------------------------------------------------------------------------------------------------
+// The filtered scan for two (query, probe) pairs of the SAME cluster per workgroup (8-bit codes in
+// 16-byte chunks, 8-bit table dtypes with fixed encoding constants).  In the cluster-grouped order
+// neighbouring pairs almost always share their cluster, and then everything that depends on the cluster
+// alone is done once for both queries: every codebook entry is loaded once and turned into two table
+// entries, every code chunk is loaded once and every code byte extracted once for two lookups (5
+// instead of 6 vector instructions per pair of lookups).  The two tables are interleaved row by row
+// (row j of query g at byte (2 j + g) * 256), so both lookups of a code share one address register and
+// differ in the instruction's immediate offset.  Per query the arithmetic and its order are those of
+// scan_kernel: identical results.  A workgroup whose two pairs differ in cluster (the seam between two
+// clusters, or the odd pair at the end) runs them one after the other.
+// LDS: tables (pq_dim * 512) | residuals 2 x d floats | per wave and query kStageCap staged survivors.
+// ------------------------------------------------------------------------------------------------
+template <int LUT, int NCH, int G>
+__device__ __forceinline__ void scan_run(const ScanArgs& a, unsigned char* smem, const int (&q)[2], const uint4 (&pair)[2]) {
+    static_assert(kIsFp8<LUT>, "two-query scan: 8-bit tables only");
+    constexpr int SH = Fp8Format<LUT>::shift;
+    const uint32_t len = pair[0].y;
+    if (len == 0) return;
+    const int l = (int)pair[0].x;
+    unsigned char* lut = smem;
+    float* rq = reinterpret_cast<float*>(smem + (size_t)a.pq_dim * 512);
+    unsigned char* after_rq = reinterpret_cast<unsigned char*>(rq) + (((size_t)2 * a.d * 4 + 15) & ~(size_t)15);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const Fp8Params fp8 = a.fp8.fixed;
+    uint32_t bound[G], seg0[G], row_pos0[G], staged[G];
+    uint2* stage[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        bound[g] = a.bounds[q[g]];
+        seg0[g] = a.pairs[(size_t)q[g] * a.n_probes + 1].w;
+        row_pos0[g] = pair[g].w;
+        staged[g] = 0;
+        stage[g] = reinterpret_cast<uint2*>(after_rq) + ((size_t)wave * 2 + g) * kStageCap;
+    }
+    const int n_groups = (int)((len + 63u) >> 6);
+    const uint4* cbase = reinterpret_cast<const uint4*>(a.codes + (size_t)pair[0].z * 64 * ((size_t)NCH * 16));
+    auto load_group = [&](uint4 (&buf)[NCH], int grp) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) buf[c] = cbase[((size_t)grp * NCH + c) * 64 + lane];
+    };
+    uint4 buf_a[NCH], buf_b[NCH];
+    int grp = wave;
+    if (grp < n_groups) load_group(buf_a, grp);
+
+    // step 2: both residuals against the cluster's centroid
+    for (int t = threadIdx.x; t < a.d; t += blockDim.x) {
+        const float c = a.centroids[(size_t)l * a.d + t];
+#pragma unroll
+        for (int g = 0; g < G; ++g) rq[g * a.d + t] = a.queries[(size_t)q[g] * a.d + t] - c;
+    }
+    __syncthreads();
+    // step 3: both tables from one pass over the codebooks (a wave takes whole rows, 4 entries per lane)
+    {
+        int hi_v = fp8.hi;
+        asm volatile("" : "+v"(hi_v));
+        auto rows = [&](auto m_tag) {
+            constexpr int M = decltype(m_tag)::value;
+            auto load_row = [&](int j, float (&cbv)[4 * M]) {
+                const float4* src = reinterpret_cast<const float4*>(a.codebooks + ((size_t)j * 256 + lane * 4) * M);
+#pragma unroll
+                for (int v = 0; v < M; ++v) {
+                    const float4 x = src[v];
+                    cbv[4 * v] = x.x; cbv[4 * v + 1] = x.y; cbv[4 * v + 2] = x.z; cbv[4 * v + 3] = x.w;
+                }
+            };
+            auto finish_row = [&](int j, const float (&cbv)[4 * M]) {
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float r[M], f[4];
+#pragma unroll
+                    for (int t = 0; t < M; ++t) r[t] = rq[g * a.d + j * M + t];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) f[u] = lut_entry<M>(cbv + u * M, r);
+                    store4<LUT>(lut, (2 * j + g) * 256 + lane * 4, f, fp8, hi_v);
+                }
+            };
+            // two rows per trip: both rows' loads are in flight before either is used
+            int j = wave;
+            for (; j + n_waves < a.pq_dim; j += 2 * n_waves) {
+                float c0[4 * M], c1[4 * M];
+                load_row(j, c0);
+                load_row(j + n_waves, c1);
+                finish_row(j, c0);
+                finish_row(j + n_waves, c1);
+            }
+            if (j < a.pq_dim) {
+                float c0[4 * M];
+                load_row(j, c0);
+                finish_row(j, c0);
+            }
+        };
+        switch (a.m) {
+            case 1: rows(std::integral_constant<int, 1>{}); break;
+            case 2: rows(std::integral_constant<int, 2>{}); break;
+            default: rows(std::integral_constant<int, 4>{}); break;      // the host admits m = 1, 2, 4 only
+        }
+    }
+    __syncthreads();
+
+    // step 4: Eq. (1) for both queries, sub-spaces in ascending order
+    auto accumulate = [&](const uint4 (&buf)[NCH], float (&acc)[G]) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) acc[g] = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const uint32_t w[4] = {buf[c].x, buf[c].y, buf[c].z, buf[c].w};
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t code = (w[u] >> (8 * b)) & 255u;
+                    const int row = (c * 4 + u) * 4 + b;
+#pragma unroll
+                    for (int g = 0; g < G; ++g) acc[g] += fp8_to_f32<SH>(lut[(uint32_t)(2 * row + g) * 256u + code], fp8);
+                }
+        }
+    };
+    auto flush = [&](int g) {
+        if (staged[g] == 0) return;
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&a.counts[q[g]], staged[g]);
+        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+        uint32_t* dst_key = reinterpret_cast<uint32_t*>(a.R) + (size_t)q[g] * a.stride + seg0[g] + base;
+        uint32_t* dst_pos = a.Rpos + (size_t)q[g] * a.stride + seg0[g] + base;
+        for (uint32_t j = lane; j < staged[g]; j += kWave) {
+            const uint2 e = stage[g][j];
+            dst_key[j] = e.x;
+            dst_pos[j] = e.y;
+        }
+        staged[g] = 0;
+    };
+    auto keep = [&](int grp_i, const float (&acc)[G]) {
+        const uint32_t i = (uint32_t)grp_i * 64u + lane;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const bool ok = i < len && __float_as_uint(acc[g]) <= bound[g];
+            const unsigned long long m = __ballot(ok);
+            if (m != 0) {
+                if (staged[g] + 64u > (uint32_t)kStageCap) flush(g);
+                if (ok) stage[g][staged[g] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = make_uint2(__float_as_uint(acc[g]), row_pos0[g] + i);
+                staged[g] += (uint32_t)__popcll(m);
+            }
+        }
+    };
+    float acc[G];
+    while (grp < n_groups) {
+        const int gn = grp + n_waves;
+        if (gn < n_groups) load_group(buf_b, gn);
+        accumulate(buf_a, acc);
+        keep(grp, acc);
+        if (gn >= n_groups) break;
+        grp = gn + n_waves;
+        if (grp < n_groups) load_group(buf_a, grp);
+        accumulate(buf_b, acc);
+        keep(gn, acc);
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) flush(g);
+}
+
+template <int LUT, int NCH>
+__global__ void __launch_bounds__(1024)
+scan_two_kernel(ScanArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    // pairs (2 slot, 2 slot + 1) of the cluster-grouped order; the slots are dealt to the XCDs in blocks
+    // of order_block / 2, which is the dealing of scan_kernel's pairs in blocks of order_block
+    const uint32_t n_slots = (a.n_pairs + 1u) / 2u, blk = a.order_block / 2u;
+    const uint32_t xcd = blockIdx.x & 7u, rank = blockIdx.x >> 3;
+    const uint32_t slot = ((rank / blk) * 8u + xcd) * blk + rank % blk;
+    if (slot >= n_slots) return;
+    const bool two = 2u * slot + 1u < a.n_pairs;
+    int q[2];
+    uint4 pair[2];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const uint32_t lin = a.order[2u * slot + ((g == 1 && two) ? 1u : 0u)];
+        q[g] = (int)(lin / (uint32_t)(a.n_probes - 1));
+        pair[g] = a.pairs[(size_t)q[g] * a.n_probes + 1 + (lin - (uint32_t)q[g] * (uint32_t)(a.n_probes - 1))];
+    }
+    if (two && pair[0].x == pair[1].x) {
+        scan_run<LUT, NCH, 2>(a, smem, q, pair);
+    } else {
+        scan_run<LUT, NCH, 1>(a, smem, q, pair);
+        if (two) {
+            __syncthreads();                  // the first run's table is still being read by slower waves
+            const int q1[2] = {q[1], q[1]};
+            const uint4 p1[2] = {pair[1], pair[1]};
+            scan_run<LUT, NCH, 1>(a, smem, q1, p1);
+        }
+    }
+}
+
 // Steps 2-3 only: the table of one pair, copied out of LDS byte for byte.
 template <int LUT>
 __global__ void __launch_bounds__(256)
@@ -1536,6 +1731,55 @@ int launch_scan_lut(const ScanArgs& a, int bits, int cw, int nch, dim3 grid, int
     }
 }
 
+// The two-pairs-per-workgroup kernel serves the filtered scan of 8-bit codes in 16-byte chunks with an
+// 8-bit table of fixed encoding and sub-vectors of 1, 2 or 4 components, when both tables leave room for
+// several workgroups per compute unit.  Measured on MI355X it pays for long lists (scan stage -10 % at
+// 10^8 vectors in 50,000 lists), is neutral at 1,000 vectors per list and loses where the doubled table
+// costs occupancy (64 sub-spaces), so it is used for lists of 1,536 vectors or more on average.
+// IVFPQ_SCAN_TWO=0 switches it off, =1 on wherever it can run.
+size_t scan_two_lds_bytes(const ivfpq_index* idx, int threads) {
+    return (size_t)idx->pq_dim * 512 + (((size_t)2 * idx->d * 4 + 15) & ~(size_t)15) + (size_t)(threads / 64) * 2 * kStageCap * 8;
+}
+bool scan_two_applies(const ivfpq_index* idx, int lut_dtype, const Fp8Mode& fp8, uint32_t order_block) {
+    int forced = -1;
+    if (const char* env = std::getenv("IVFPQ_SCAN_TWO")) forced = std::atoi(env) != 0;
+    if (forced == 0) return false;
+    if (lut_dtype != IVFPQ_LUT_FP8_E5M3 && lut_dtype != IVFPQ_LUT_FP8_E4M4) return false;
+    if (fp8.per_table || idx->pq_bits != 8 || chunk_width(idx) != 16) return false;
+    const int m = idx->d / idx->pq_dim;
+    if (m != 1 && m != 2 && m != 4) return false;
+    if (order_block < 2 || (order_block & 1u)) return false;
+    if (scan_two_lds_bytes(idx, scan_threads(idx, lut_dtype)) > kLdsBytes / 3) return false;
+    return forced == 1 || (idx->n_lists > 0 && idx->n / idx->n_lists >= 24 * 64);
+}
+int launch_scan_two(const ivfpq_index* idx, const ScanArgs& a, int lut_dtype, hipStream_t st) {
+    const int threads = scan_threads(idx, lut_dtype);
+    const size_t lds = scan_two_lds_bytes(idx, threads);
+    const uint32_t n_slots = (a.n_pairs + 1u) / 2u, per = 8u * (a.order_block / 2u);
+    const dim3 grid((n_slots + per - 1) / per * per);
+    auto go = [&](auto kernel) -> int {
+        if (int s = allow_full_lds(kernel)) return s;
+        hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, st, a);
+        HIP_TRY(hipGetLastError());
+        return IVFPQ_OK;
+    };
+    const int nch = idx->code_bytes() / 16;
+    if (lut_dtype == IVFPQ_LUT_FP8_E5M3) {
+        switch (nch) {
+            case 1: return go(scan_two_kernel<IVFPQ_LUT_FP8_E5M3, 1>);
+            case 2: return go(scan_two_kernel<IVFPQ_LUT_FP8_E5M3, 2>);
+            case 3: return go(scan_two_kernel<IVFPQ_LUT_FP8_E5M3, 3>);
+            default: return go(scan_two_kernel<IVFPQ_LUT_FP8_E5M3, 4>);
+        }
+    }
+    switch (nch) {
+        case 1: return go(scan_two_kernel<IVFPQ_LUT_FP8_E4M4, 1>);
+        case 2: return go(scan_two_kernel<IVFPQ_LUT_FP8_E4M4, 2>);
+        case 3: return go(scan_two_kernel<IVFPQ_LUT_FP8_E4M4, 3>);
+        default: return go(scan_two_kernel<IVFPQ_LUT_FP8_E4M4, 4>);
+    }
+}
+
 int launch_scan(const ivfpq_index* idx, ScanArgs a, int lut_dtype, dim3 grid, hipStream_t st) {
     const int threads = scan_threads(idx, lut_dtype);
     const size_t lds = scan_lds_bytes_staged(idx, lut_dtype, threads);
@@ -1700,8 +1944,13 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
                 uint32_t blk = kOrderBlock;
                 if (const char* env = std::getenv("IVFPQ_ORDER_BLOCK")) blk = (uint32_t)std::max(1, std::atoi(env));
                 a.order_block = blk;
-                const size_t grid = (n_pairs + 8 * (size_t)blk - 1) / (8 * (size_t)blk) * (8 * (size_t)blk);
-                if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)grid), st)) return s;
+                if (scan_two_applies(idx, lut_dtype, a.fp8, blk)) {
+                    a.n_chunks = idx->code_bytes() / 16;
+                    if (int s = launch_scan_two(idx, a, lut_dtype, st)) return s;
+                } else {
+                    const size_t grid = (n_pairs + 8 * (size_t)blk - 1) / (8 * (size_t)blk) * (8 * (size_t)blk);
+                    if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)grid), st)) return s;
+                }
             } else {
                 if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)n_pairs), st)) return s;
             }

@@ -599,6 +599,30 @@ def test_stream_read_folds_every_word_once(P, n_words, n_wg):
     np.testing.assert_array_equal(out, want)
 
 
+# ---------------------------------------------------------------- two pairs of one cluster per workgroup
+
+@pytest.mark.parametrize("d,pq_dim,n_lists,n_probes,k,dtype_name", [
+    (32, 16, 7, 5, 10, "e5m3"),        # m = 2, few clusters: most neighbouring pairs share theirs
+    (64, 16, 33, 8, 100, "e4m4"),      # m = 4
+    (48, 48, 200, 40, 10, "e5m3"),     # m = 1, three 16-byte chunks, many seams between clusters
+    (128, 64, 3, 3, 1000, "e5m3"),     # four chunks; two pairs per query: odd and even runs
+])
+def test_search_two_pairs_per_workgroup(P, monkeypatch, d, pq_dim, n_lists, n_probes, k, dtype_name):
+    # the kernel that shares a cluster's codes and codebooks between two queries is forced on; results
+    # must be those of the oracle, and identical to the one-pair kernel's
+    dtype = {"e5m3": oracle.LUT_E5M3, "e4m4": oracle.LUT_E4M4}[dtype_name]
+    oidx, gidx = random_pair(P, 9000, d, n_lists, pq_dim, 8, salt=900 + d, empty_lists=(1,) if n_lists > 3 else ())
+    q = np.random.default_rng(900 + d).standard_normal((257, d)).astype(np.float32)
+    monkeypatch.setenv("IVFPQ_SCAN_TWO", "0")
+    ids_one, d_one = gidx.ivfpq_search(q, n_probes, k, dtype)
+    monkeypatch.setenv("IVFPQ_SCAN_TWO", "1")
+    _step(f"two pairs per workgroup d={d} s={pq_dim} L={n_lists} P={n_probes} k={k} {dtype_name}")
+    ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, n_probes, k, dtype)
+    assert_topk_matches(ids_g, d_g, ids_o, d_o, context="two pairs per workgroup")
+    np.testing.assert_array_equal(d_g, d_one.cpu().numpy())
+    np.testing.assert_array_equal(ids_g, ids_one.cpu().numpy())
+
+
 # ---------------------------------------------------------------- the search inside a HIP graph
 
 def test_search_replays_correctly_from_a_hip_graph(P, tiny):
