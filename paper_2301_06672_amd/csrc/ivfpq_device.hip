@@ -1394,26 +1394,38 @@ pair_scatter_lds_kernel(const uint4* __restrict__ pairs, uint32_t n_pairs, int n
     }
 }
 
-// offsets[l] = counts[0] + ... + counts[l-1]; one workgroup: every thread adds up a contiguous run of
-// counters, one scan over the 1024 run totals, then every thread writes the offsets of its run
+// offsets[l] = counts[0] + ... + counts[l-1]; one workgroup, 4096 counters per trip: four consecutive
+// counters per thread (coalesced), a scan inside each wave, the 16 wave totals through LDS
 __global__ void __launch_bounds__(1024)
 pair_offsets_kernel(const uint32_t* __restrict__ counts, int n_lists, uint32_t* __restrict__ offsets) {
-    __shared__ uint32_t part[1024];
-    const int tid = threadIdx.x;
-    const int run = (n_lists + 1023) / 1024;
-    const int l0 = tid * run, l1 = l0 + run < n_lists ? l0 + run : n_lists;
-    uint32_t own = 0;
-    for (int l = l0; l < l1; ++l) own += counts[l];
-    part[tid] = own;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-        const uint32_t v = tid >= off ? part[tid - off] : 0u;
+    __shared__ uint32_t wave_total[16];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    uint32_t carry = 0;
+    for (int base = 0; base < n_lists; base += 4096) {
+        const int i = base + tid * 4;
+        uint32_t c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) c[u] = i + u < n_lists ? counts[i + u] : 0u;
+        const uint32_t own = c[0] + c[1] + c[2] + c[3];
+        const uint32_t incl = wave_inclusive_scan(own);
+        if (lane == kWave - 1) wave_total[wave] = incl;
         __syncthreads();
-        part[tid] += v;
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const uint32_t t = wave_total[w];
+            before += w < wave ? t : 0u;
+            total += t;
+        }
+        uint32_t at = carry + before + incl - own;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (i + u < n_lists) offsets[i + u] = at;
+            at += c[u];
+        }
+        carry += total;
         __syncthreads();
     }
-    uint32_t at = part[tid] - own;
-    for (int l = l0; l < l1; ++l) { offsets[l] = at; at += counts[l]; }
 }
 
 __global__ void pair_scatter_kernel(const uint4* __restrict__ pairs, uint32_t n_pairs, int n_probes, int n_lists,
