@@ -19,6 +19,8 @@
 //   scan_kernel (mode 2) steps 2-4 for the other probes, in cluster-grouped, XCD-aware order (a
 //                        cluster's codes then come from one XCD's L2); only R values under the bound
 //                        are kept
+//   scan_two_kernel      the same for two neighbouring pairs of one cluster per workgroup (long lists,
+//                        8-bit codes and tables): codebooks and codes are read once for both queries
 //   topk_kernel          step 5: the k smallest R among the survivors of a query, ordered by
 //                        (R, id), and the map from (cluster, position) to the caller's ids
 // Beside the path: dump_lut_kernel (steps 2-3 of one pair, for inspection) and refine_kernel (exact
