@@ -18,10 +18,12 @@
  *  - Row-major everywhere.  Distances are squared L2 (Sec. I-B).
  *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *    Search calls only enqueue work; they do not synchronise.
- *  - Three environment variables override launch heuristics, for tuning experiments only:
+ *  - Four environment variables override launch heuristics, for tuning experiments only:
  *    IVFPQ_SCAN_THREADS (64 ... 1024: workgroup size of the scan kernel), IVFPQ_ORDER_BLOCK
- *    (consecutive (query, probe) pairs of the cluster-grouped order that stay on one XCD) and
- *    IVFPQ_SCAN_TWO (0 / 1: never / wherever possible scan two pairs of one cluster per workgroup).
+ *    (consecutive (query, probe) pairs of the cluster-grouped order that stay on one XCD),
+ *    IVFPQ_SCAN_TWO (0 / 1: never / wherever possible scan two pairs of one cluster per workgroup) and
+ *    IVFPQ_EARLY_EXIT (0: the filtered scan adds up every sub-space of every vector, even when all 64
+ *    partial sums of a group are already over the query's bound; results are the same either way).
  */
 #ifndef IVFPQ_H
 #define IVFPQ_H

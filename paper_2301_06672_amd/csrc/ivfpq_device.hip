@@ -924,6 +924,7 @@ struct ScanArgs {
     const uint32_t* order;        // mode 2: pairs (as q * (n_probes - 1) + probe - 1) grouped by cluster, or null
     uint32_t n_pairs;             // mode 2: number of such pairs
     uint32_t order_block;         // mode 2: consecutive pairs of the grouped order that stay on one XCD
+    int early_exit;               // mode 2: stop adding for a 64-vector group once every partial sum is over the bound
 };
 
 // Code layout of one cluster (written by ivfpq_upload): vectors in groups of 64 (the last one
@@ -977,6 +978,7 @@ scan_kernel(ScanArgs a) {
     }
     if (len == 0) return;     // empty cluster (or a caller-given probe that was out of range)
     const bool filtered = a.single_list < 0 && a.mode == 2;
+    const bool prune = filtered && a.early_exit != 0;
     uint32_t bound = 0, seg0 = 0;
     if (filtered) {
         bound = a.bounds[q];
@@ -1012,9 +1014,21 @@ scan_kernel(ScanArgs a) {
 #pragma unroll
             for (int c = 0; c < NBUF; ++c) { w[4 * c] = buf[c].x; w[4 * c + 1] = buf[c].y; w[4 * c + 2] = buf[c].z; w[4 * c + 3] = buf[c].w; }
             static_assert((4 * NBUF) % WPG == 0 || NCH == 0, "16-byte chunks must hold whole code groups");
+            // Table entries are never negative, so the partial sums only grow: once those of all 64
+            // vectors are over the query's bound none of them can survive, and the rest of their
+            // lookups is skipped (checked every 16 sub-spaces; the partial sum then fails the filter).
+            constexpr int NG = (4 * NBUF) / WPG, EVERY = 16 / SPG > 0 ? 16 / SPG : 1, NBLK = (NG + EVERY - 1) / EVERY;
+            bool over = false;                       // wave-uniform
 #pragma unroll
-            for (int cg = 0; cg < (4 * NBUF) / WPG; ++cg)
-                acc = add_group<LUT, BITS>(acc, lut, w + cg * WPG, cg * SPG, fp8);
+            for (int blk = 0; blk < NBLK; ++blk) {
+                if (over) continue;
+#pragma unroll
+                for (int e = 0; e < EVERY; ++e) {
+                    const int cg = blk * EVERY + e;
+                    if (cg < NG) acc = add_group<LUT, BITS>(acc, lut, w + cg * WPG, cg * SPG, fp8);
+                }
+                if (blk + 1 < NBLK && prune) over = __ballot(__float_as_uint(acc) <= bound) == 0;
+            }
         }
         return acc;      // 4-byte chunks take the loop over code groups below instead
     };
@@ -1079,12 +1093,14 @@ scan_kernel(ScanArgs a) {
         // 4-byte chunks: one code group (WPG words) at a time
         for (; g < n_groups; g += n_waves) {
             float acc = 0.f;
-            for (int cg = 0; cg < nch / WPG; ++cg) {
+            const int ncg = nch / WPG;
+            for (int cg = 0; cg < ncg; ++cg) {
                 uint32_t w[WPG];
 #pragma unroll
                 for (int u = 0; u < WPG; ++u)
                     w[u] = reinterpret_cast<const uint32_t*>(codes_l)[((size_t)g * nch + cg * WPG + u) * 64 + lane];
                 acc = add_group<LUT, BITS>(acc, lut, w, cg * SPG, fp8);
+                if (prune && ((cg + 1) * SPG) % 16 == 0 && cg + 1 < ncg && __ballot(__float_as_uint(acc) <= bound) == 0) break;
             }
             store_R(g, acc);
         }
@@ -1195,21 +1211,53 @@ __device__ __forceinline__ void scan_run(const ScanArgs& a, unsigned char* smem,
     __syncthreads();
 
     // step 4: Eq. (1) for both queries, sub-spaces in ascending order
-    auto accumulate = [&](const uint4 (&buf)[NCH], float (&acc)[G]) {
+    // A query whose 64 partial sums are all over its bound after a chunk drops out of the rest of the
+    // group's lookups, as in scan_kernel; the other one then goes on alone.
+    auto chunk_all = [&](const uint4& v, int c, float (&acc)[G]) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int g = 0; g < G; ++g) acc[g] = 0.f;
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t code = (w[u] >> (8 * b)) & 255u;
+                const int row = (c * 4 + u) * 4 + b;
+#pragma unroll
+                for (int g = 0; g < G; ++g) acc[g] += fp8_to_f32<SH>(lut[(uint32_t)(2 * row + g) * 256u + code], fp8);
+            }
+    };
+    auto chunk_one = [&](const uint4& v, int c, int g, float& acc_g) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        const unsigned char* lut_g = lut + g * 256;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t code = (w[u] >> (8 * b)) & 255u;
+                const int row = (c * 4 + u) * 4 + b;
+                acc_g += fp8_to_f32<SH>(lut_g[(uint32_t)(2 * row) * 256u + code], fp8);
+            }
+    };
+    auto accumulate = [&](const uint4 (&buf)[NCH], float (&acc)[G]) {
+        bool alive[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) { acc[g] = 0.f; alive[g] = true; }
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            const uint32_t w[4] = {buf[c].x, buf[c].y, buf[c].z, buf[c].w};
+            bool all = true, any = false;
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int g = 0; g < G; ++g) { all = all && alive[g]; any = any || alive[g]; }
+            if (all) {
+                chunk_all(buf[c], c, acc);
+            } else if (any) {
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const uint32_t code = (w[u] >> (8 * b)) & 255u;
-                    const int row = (c * 4 + u) * 4 + b;
+                for (int g = 0; g < G; ++g)
+                    if (alive[g]) chunk_one(buf[c], c, g, acc[g]);
+            }
+            if (c + 1 < NCH && a.early_exit && any) {
 #pragma unroll
-                    for (int g = 0; g < G; ++g) acc[g] += fp8_to_f32<SH>(lut[(uint32_t)(2 * row + g) * 256u + code], fp8);
-                }
+                for (int g = 0; g < G; ++g)
+                    if (alive[g]) alive[g] = __ballot(__float_as_uint(acc[g]) <= bound[g]) != 0;
+            }
         }
     };
     auto flush = [&](int g) {
@@ -1747,10 +1795,10 @@ int launch_scan_lut(const ScanArgs& a, int bits, int cw, int nch, dim3 grid, int
 
 // The two-pairs-per-workgroup kernel serves the filtered scan of 8-bit codes in 16-byte chunks with an
 // 8-bit table of fixed encoding and sub-vectors of 1, 2 or 4 components, when both tables leave room for
-// several workgroups per compute unit.  Measured on MI355X it pays for long lists (scan stage -10 % at
-// 10^8 vectors in 50,000 lists), is neutral at 1,000 vectors per list and loses where the doubled table
-// costs occupancy (64 sub-spaces), so it is used for lists of 1,536 vectors or more on average.
-// IVFPQ_SCAN_TWO=0 switches it off, =1 on wherever it can run.
+// enough workgroups per compute unit.  Measured on MI355X (scan stage, 10,000 queries): 6.5 -> 5.7 ms at
+// 10^8 vectors in 50,000 lists (32 sub-spaces: 21 KB of LDS per workgroup), 1.29 -> 1.23 ms at 10^7
+// vectors (48 sub-spaces, 33 KB), but 2.06 -> 2.30 ms with 64 sub-spaces (41 KB: three workgroups per
+// compute unit), so the limit is 36 KB.  IVFPQ_SCAN_TWO=0 switches it off, =1 on wherever it can run.
 size_t scan_two_lds_bytes(const ivfpq_index* idx, int threads) {
     return (size_t)idx->pq_dim * 512 + (((size_t)2 * idx->d * 4 + 15) & ~(size_t)15) + (size_t)(threads / 64) * 2 * kStageCap * 8;
 }
@@ -1763,8 +1811,8 @@ bool scan_two_applies(const ivfpq_index* idx, int lut_dtype, const Fp8Mode& fp8,
     const int m = idx->d / idx->pq_dim;
     if (m != 1 && m != 2 && m != 4) return false;
     if (order_block < 2 || (order_block & 1u)) return false;
-    if (scan_two_lds_bytes(idx, scan_threads(idx, lut_dtype)) > kLdsBytes / 3) return false;
-    return forced == 1 || (idx->n_lists > 0 && idx->n / idx->n_lists >= 24 * 64);
+    const size_t lds = scan_two_lds_bytes(idx, scan_threads(idx, lut_dtype));
+    return forced == 1 ? lds <= kLdsBytes / 3 : lds <= 36 * 1024;
 }
 int launch_scan_two(const ivfpq_index* idx, const ScanArgs& a, int lut_dtype, hipStream_t st) {
     const int threads = scan_threads(idx, lut_dtype);
@@ -1834,6 +1882,8 @@ ScanArgs base_scan_args(const ivfpq_index* idx, int lut_dtype) {
     a.n_lists = idx->n_lists;
     a.fp8 = fp8_mode(idx, lut_dtype);
     a.single_list = -1;
+    a.early_exit = 1;
+    if (const char* env = std::getenv("IVFPQ_EARLY_EXIT")) a.early_exit = std::atoi(env) != 0;
     return a;
 }
 
