@@ -35,8 +35,9 @@ MEASURED_TRAFFIC = {
 }
 # busy fractions of the other units during scan_kernel, same profiles (profiles/scan_kernel_*_lds_counters.txt)
 MEASURED_UNITS = {
-    ("intgrid_1m", "e5m3"): {"lds_busy": 0.96, "valu_busy": 0.96},
-    ("unitnorm_10m", "e5m3"): {"lds_busy": 0.81, "valu_busy": 1.0},
+    # without the early exit (every lookup made) / with it (the default)
+    ("intgrid_1m", "e5m3"): {"lds_busy": 0.96, "valu_busy": 0.96, "lds_busy_early_exit": 0.80, "valu_busy_early_exit": 1.0},
+    ("unitnorm_10m", "e5m3"): {"lds_busy": 0.77, "valu_busy": 0.88, "lds_busy_early_exit": 0.56, "valu_busy_early_exit": 0.88},
 }
 
 
@@ -116,6 +117,10 @@ def main():
     ap.add_argument("--batch-sweep", default="", metavar="N1,N2,...",
                     help="also time batches of these sizes (the first rows of the query set), each call on its own and "
                          "replayed from a captured HIP graph: milliseconds per call; reported under by_batch")
+    ap.add_argument("--early-exit", type=int, choices=(0, 1), default=None,
+                    help="force the filtered scan's early exit off / on for every run (default: the library's, on)")
+    ap.add_argument("--no-full-run", action="store_true",
+                    help="skip the extra headline run without early exit (profiling runs: keeps the number of search calls fixed)")
     ap.add_argument("--refine-from", type=int, default=0, metavar="K2",
                     help="also time search with k=K2 followed by ivfpq_refine down to k (exact re-ranking with the "
                          "stored vectors; reported under by_lut as <lut>+refineK2)")
@@ -136,6 +141,8 @@ def main():
         print("bench.py: this build runs on ONE GPU; the path shards by query across GPUs with no "
               "communication, and no multi-GPU figure is produced.", file=sys.stderr)
         sys.exit(2)
+    if args.early_exit is not None:
+        os.environ["IVFPQ_EARLY_EXIT"] = str(args.early_exit)
 
     import numpy as np
     import torch
@@ -243,6 +250,18 @@ def main():
         r = results[name]
         log(f"lut={name}: {r['qps']:.0f} q/s, {r['ms_per_step']:.3f} ms/step, recall@{k}={r['recall']:.4f}, "
             f"stages {r['stage_ms']}")
+    # the same headline run with the filtered scan adding up every sub-space of every vector (no exit once a
+    # group's partial sums are all over the bound): same results, the rate a kernel without that test has
+    if args.no_full_run:
+        full = results[args.lut]
+    else:
+        os.environ["IVFPQ_EARLY_EXIT"] = "0"
+        full = run(args.lut, max(3, args.steps // 2), 1)
+        if args.early_exit is None:
+            del os.environ["IVFPQ_EARLY_EXIT"]
+        else:
+            os.environ["IVFPQ_EARLY_EXIT"] = str(args.early_exit)
+        log(f"lut={args.lut} without early exit: {full['qps']:.0f} q/s, {full['ms_per_step']:.3f} ms/step, stages {full['stage_ms']}")
     by_probes = {}
     for P in [int(v) for v in args.probe_sweep.split(",") if v]:
         if P < 1 or P > min(w.n_lists, pkg.MAX_PROBES):
@@ -314,6 +333,7 @@ def main():
 
     ws_bytes = idx.ivfpq_search_workspace_bytes(nq, n_probes, k, lut_ids[args.lut])
     scan_ms = head["stage_ms"]["scan"]
+    scan_ms_full = full["stage_ms"]["scan"]
     achieved = code_bytes / (scan_ms * 1e-3) / 1e9
     ceiling = measure_read_ceiling(torch, pkg)
     log(f"plain streaming read on this box: {ceiling:.0f} GB/s")
@@ -327,13 +347,19 @@ def main():
         "other_units": MEASURED_UNITS.get((w.name, args.lut)),
         # the unit that does bound the kernel: table lookups against a conflict-free LDS
         # (256 CUs x 32 lanes per clock x 2.4 GHz; a 256-entry row of 1-byte entries cannot beat half of it)
-        "lds": {"achieved": round(scanned_vectors * w.pq_dim / (scan_ms * 1e-3), 1), "peak": LDS_PEAK_LOOKUPS,
-                "unit": "lookups/s", "frac": round(scanned_vectors * w.pq_dim / (scan_ms * 1e-3) / LDS_PEAK_LOOKUPS, 4)},
+        # (priced on the run without early exit, which performs every lookup of the definition)
+        "lds": {"achieved": round(scanned_vectors * w.pq_dim / (scan_ms_full * 1e-3), 1), "peak": LDS_PEAK_LOOKUPS,
+                "unit": "lookups/s", "frac": round(scanned_vectors * w.pq_dim / (scan_ms_full * 1e-3) / LDS_PEAK_LOOKUPS, 4)},
+        "without_early_exit": {"achieved": round(code_bytes / (scan_ms_full * 1e-3) / 1e9, 1),
+                               "frac": round(code_bytes / (scan_ms_full * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                               "scan_ms_per_step": round(scan_ms_full, 4)},
         "note": "achieved, traffic and the byte counts are per step = all scan_kernel launches of one step "
                 "(two launches per query tile); the ratio equals bytes per launch / average launch time. "
                 "achieved counts the algorithmic PQ-code bytes; traffic is what HBM delivered: pairs run grouped by "
                 "cluster, so most re-reads of a cluster's codes hit the L2 and the kernel is bound by the vector "
-                "ALU and the LDS (other_units), not by HBM",
+                "ALU and the LDS (other_units, measured without the early exit), not by HBM. By default a 64-vector "
+                "group stops adding once all its partial sums are over the query's bound (same results): "
+                "without_early_exit holds the figures with that switched off",
     }
 
     cpu = None
@@ -370,6 +396,10 @@ def main():
         "recall_at_k": round(head["recall"], 4),
         "by_lut": {n: {"qps": round(r["qps"], 1), "recall": round(r["recall"], 4),
                        "stage_ms": {a: round(b, 4) for a, b in r["stage_ms"].items()}} for n, r in results.items()},
+        "without_early_exit": None if args.no_full_run else {
+            "qps": round(full["qps"], 1), "ms_per_step": round(full["ms_per_step"], 4),
+            "stage_ms": {a: round(b, 4) for a, b in full["stage_ms"].items()}},
+        "early_exit": "library default (on)" if args.early_exit is None else bool(args.early_exit),
         "roofline": roofline,
         "cpu_baseline": cpu,
         **({"by_probes": by_probes} if by_probes else {}),
