@@ -623,6 +623,31 @@ def test_search_two_pairs_per_workgroup(P, monkeypatch, d, pq_dim, n_lists, n_pr
     np.testing.assert_array_equal(ids_g, ids_one.cpu().numpy())
 
 
+@pytest.mark.parametrize("d,pq_dim,pq_bits,dtype", [
+    (128, 64, 8, oracle.LUT_E5M3), (128, 64, 8, oracle.LUT_FP32),     # four 16-byte chunks
+    (96, 48, 8, oracle.LUT_FP16),                                     # three
+    (64, 64, 4, oracle.LUT_E5M3),                                     # 4-bit codes: 32 sub-spaces per chunk
+    (64, 32, 6, oracle.LUT_E4M4),                                     # 6-bit codes in 4-byte chunks
+    (128, 64, 6, oracle.LUT_E5M3),                                    # 6-bit codes, 48 bytes: 16-byte chunks
+    (40, 40, 8, oracle.LUT_E5M3),                                     # 40-byte codes: 4-byte chunks
+])
+def test_early_exit_changes_nothing(P, monkeypatch, d, pq_dim, pq_bits, dtype):
+    # a group whose partial sums are all over the bound stops early: the survivors, hence the results, are the same
+    oidx, gidx = random_pair(P, 12000, d, 9, pq_dim, pq_bits, salt=950 + d + pq_bits)
+    q = np.random.default_rng(950 + d).standard_normal((130, d)).astype(np.float32)
+    out = {}
+    for mode in ("0", "1"):
+        monkeypatch.setenv("IVFPQ_EARLY_EXIT", mode)
+        _step(f"early exit {mode}: d={d} s={pq_dim} p={pq_bits} dtype={dtype}")
+        ids, dist = gidx.ivfpq_search(q, 6, 10, dtype)
+        out[mode] = (ids.cpu().numpy(), dist.cpu().numpy())
+    np.testing.assert_array_equal(out["0"][0], out["1"][0])
+    np.testing.assert_array_equal(out["0"][1], out["1"][1])
+    monkeypatch.delenv("IVFPQ_EARLY_EXIT")
+    ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, 6, 10, dtype)
+    assert_topk_matches(ids_g, d_g, ids_o, d_o, context="early exit")
+
+
 # ---------------------------------------------------------------- the search inside a HIP graph
 
 def test_search_replays_correctly_from_a_hip_graph(P, tiny):
