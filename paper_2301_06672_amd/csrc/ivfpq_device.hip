@@ -725,9 +725,9 @@ __device__ inline void store4(unsigned char* lut, int e, const float f[4], const
 // sink(first entry index, values) (ksub is 16 or 256, so 4 consecutive entries never straddle
 // sub-spaces).  codebooks: global [pq_dim][ksub][M]; rq: LDS [pq_dim*M].
 template <int M, class Sink>
-__device__ __forceinline__ void visit_lut(const float* __restrict__ codebooks, const float* rq, int n_entries,
+__device__ __forceinline__ void visit_lut(const float* __restrict__ codebooks, const float* rq, int e_begin, int n_entries,
                                  int bits, int m_runtime, Sink sink) {
-    for (int e = threadIdx.x * 4; e < n_entries; e += blockDim.x * 4) {
+    for (int e = e_begin + threadIdx.x * 4; e < n_entries; e += blockDim.x * 4) {
         const int j = e >> bits;
         float f[4];
         if constexpr (M > 0) {
@@ -763,7 +763,7 @@ __device__ __forceinline__ void visit_lut(const float* __restrict__ codebooks, c
 // (row index wave-uniform: residual components are read once per row, addresses advance by a
 // constant stride).
 template <int M, class Sink>
-__device__ __forceinline__ void visit_lut_rows256(const float* __restrict__ codebooks, const float* rq, int pq_dim, Sink sink) {
+__device__ __forceinline__ void visit_lut_rows256(const float* __restrict__ codebooks, const float* rq, int row0, int pq_dim, Sink sink) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_waves = blockDim.x >> 6;
@@ -785,9 +785,9 @@ __device__ __forceinline__ void visit_lut_rows256(const float* __restrict__ code
         for (int u = 0; u < 4; ++u) f[u] = lut_entry<M>(cbv + u * M, r);
         sink(e, f);
     };
-    const float* src = codebooks + ((size_t)wave * 256 + lane * 4) * M;
-    int e = wave * 256 + lane * 4;
-    int j = wave;
+    const float* src = codebooks + ((size_t)(row0 + wave) * 256 + lane * 4) * M;
+    int e = (row0 + wave) * 256 + lane * 4;
+    int j = row0 + wave;
     // two rows per trip (written out: both rows' loads are in flight before either is used; deeper
     // prefetching costs registers, hence occupancy, and measured slower)
     for (; j + n_waves < pq_dim; j += 2 * n_waves) {
@@ -806,22 +806,23 @@ __device__ __forceinline__ void visit_lut_rows256(const float* __restrict__ code
     }
 }
 
+// rows (sub-spaces) row0 .. row1 - 1 of the table
 template <int BITS, class Sink>
-__device__ __forceinline__ void visit_lut_any_m(const float* __restrict__ codebooks, const float* rq, int pq_dim, int m, Sink sink) {
-    const int n_entries = pq_dim << BITS;
+__device__ __forceinline__ void visit_lut_any_m(const float* __restrict__ codebooks, const float* rq, int row0, int row1, int m, Sink sink) {
+    const int e_begin = row0 << BITS, e_end = row1 << BITS;
     if constexpr (BITS == 8) {
         switch (m) {
-            case 1: visit_lut_rows256<1>(codebooks, rq, pq_dim, sink); return;
-            case 2: visit_lut_rows256<2>(codebooks, rq, pq_dim, sink); return;
-            case 4: visit_lut_rows256<4>(codebooks, rq, pq_dim, sink); return;
+            case 1: visit_lut_rows256<1>(codebooks, rq, row0, row1, sink); return;
+            case 2: visit_lut_rows256<2>(codebooks, rq, row0, row1, sink); return;
+            case 4: visit_lut_rows256<4>(codebooks, rq, row0, row1, sink); return;
             default: break;
         }
     }
     switch (m) {
-        case 1: visit_lut<1>(codebooks, rq, n_entries, BITS, m, sink); break;
-        case 2: visit_lut<2>(codebooks, rq, n_entries, BITS, m, sink); break;
-        case 4: visit_lut<4>(codebooks, rq, n_entries, BITS, m, sink); break;
-        default: visit_lut<0>(codebooks, rq, n_entries, BITS, m, sink); break;
+        case 1: visit_lut<1>(codebooks, rq, e_begin, e_end, BITS, m, sink); break;
+        case 2: visit_lut<2>(codebooks, rq, e_begin, e_end, BITS, m, sink); break;
+        case 4: visit_lut<4>(codebooks, rq, e_begin, e_end, BITS, m, sink); break;
+        default: visit_lut<0>(codebooks, rq, e_begin, e_end, BITS, m, sink); break;
     }
 }
 
@@ -837,16 +838,19 @@ struct Fp8Mode {
 // Per-table bias (a power-of-two scale of the table, expressed as a shift of the format's exponent
 // bias): a first pass over the entries finds the largest one; with e its FP32 exponent, the bias is
 // top_exp - e, so that the entry's binade becomes the format's top binade; a second pass encodes.
+// row0, row1: only these rows (sub-spaces) are built (the whole table for a per-table bias, which needs its
+// largest entry).
 template <int LUT, int BITS>
 __device__ __forceinline__ Fp8Params stage_table(const float* __restrict__ codebooks, const float* rq, int pq_dim, int m,
-                                        unsigned char* lut, uint32_t* max_slot, const Fp8Mode mode) {
+                                        unsigned char* lut, uint32_t* max_slot, const Fp8Mode mode, int row0, int row1) {
     Fp8Params fp8 = mode.fixed;
     if constexpr (kIsFp8<LUT>) {
         if (mode.per_table) {
             if (threadIdx.x == 0) *max_slot = 0u;
             __syncthreads();
             float mx = 0.f;                       // entries are sums of squares: never negative
-            visit_lut_any_m<BITS>(codebooks, rq, pq_dim, m, [&](int, const float (&f)[4]) {
+            row0 = 0; row1 = pq_dim;
+            visit_lut_any_m<BITS>(codebooks, rq, 0, pq_dim, m, [&](int, const float (&f)[4]) {
                 mx = fmaxf(fmaxf(mx, f[0]), fmaxf(f[1], fmaxf(f[2], f[3])));
             });
 #pragma unroll
@@ -862,7 +866,7 @@ __device__ __forceinline__ Fp8Params stage_table(const float* __restrict__ codeb
     }
     int hi_v = fp8.hi;
     asm volatile("" : "+v"(hi_v));       // the upper clamp limit, held in a vector register
-    visit_lut_any_m<BITS>(codebooks, rq, pq_dim, m, [&](int e, const float (&f)[4]) { store4<LUT>(lut, e, f, fp8, hi_v); });
+    visit_lut_any_m<BITS>(codebooks, rq, row0, row1, m, [&](int e, const float (&f)[4]) { store4<LUT>(lut, e, f, fp8, hi_v); });
     __syncthreads();
     return fp8;
 }
@@ -898,6 +902,7 @@ __device__ inline float add_group(float acc, const unsigned char* lut, const uin
     return acc;
 }
 
+constexpr int kAliveCap = 64;    // groups of a wave that the first pass of the split scan can note for the second
 constexpr int kStageCap = 128;   // survivors a wave stages in LDS before it appends them (8 bytes each)
 
 struct ScanArgs {
@@ -1007,7 +1012,12 @@ scan_kernel(ScanArgs a) {
         for (int c = 0; c < NBUF; ++c) buf[c] = cbase[((size_t)g * NBUF + c) * 64 + lane];
     };
     // Eq. (1) for the vector this lane holds in buf: sub-spaces in ascending order
-    auto accumulate = [&](const chunk_t (&buf)[NBUF]) -> float {
+    // (blocks_tag: how many blocks of kBlockSub sub-spaces to add, the leading ones; NBLK = all)
+    constexpr int NG = CW == 16 ? (4 * NBUF) / WPG : 0;                          // code groups per vector
+    constexpr int EVERY = 16 / SPG > 0 ? 16 / SPG : 1;                           // code groups per block of 16 sub-spaces
+    constexpr int NBLK = (NG + EVERY - 1) / EVERY;
+    auto accumulate = [&](const chunk_t (&buf)[NBUF], auto blocks_tag) -> float {
+        constexpr int BLOCKS = decltype(blocks_tag)::value;
         float acc = 0.f;
         if constexpr (CW == 16) {
             uint32_t w[4 * NBUF];
@@ -1017,17 +1027,16 @@ scan_kernel(ScanArgs a) {
             // Table entries are never negative, so the partial sums only grow: once those of all 64
             // vectors are over the query's bound none of them can survive, and the rest of their
             // lookups is skipped (checked every 16 sub-spaces; the partial sum then fails the filter).
-            constexpr int NG = (4 * NBUF) / WPG, EVERY = 16 / SPG > 0 ? 16 / SPG : 1, NBLK = (NG + EVERY - 1) / EVERY;
             bool over = false;                       // wave-uniform
 #pragma unroll
-            for (int blk = 0; blk < NBLK; ++blk) {
+            for (int blk = 0; blk < BLOCKS; ++blk) {
                 if (over) continue;
 #pragma unroll
                 for (int e = 0; e < EVERY; ++e) {
                     const int cg = blk * EVERY + e;
                     if (cg < NG) acc = add_group<LUT, BITS>(acc, lut, w + cg * WPG, cg * SPG, fp8);
                 }
-                if (blk + 1 < NBLK && prune) over = __ballot(__float_as_uint(acc) <= bound) == 0;
+                if (blk + 1 < BLOCKS && prune) over = __ballot(__float_as_uint(acc) <= bound) == 0;
             }
         }
         return acc;      // 4-byte chunks take the loop over code groups below instead
@@ -1074,8 +1083,74 @@ scan_kernel(ScanArgs a) {
     for (int t = threadIdx.x; t < a.d; t += blockDim.x)
         rq[t] = a.queries[(size_t)q * a.d + t] - a.centroids[(size_t)l * a.d + t];
     __syncthreads();
+    // Filtered scan with early exit, tables of two or more chunks' worth of rows: most groups are over the
+    // bound after the first half of the sub-spaces, so the second half of the table is built only if some
+    // group of this pair is still in the race.  Pass 1 builds the leading rows and adds them up for every
+    // group, noting the groups with a partial sum under the bound; if there are any, the remaining rows are
+    // built and those groups are added up from the start (same order: same R).
+    constexpr int HBLK = (NBLK + 1) / 2;                             // blocks of the first pass
+    constexpr int HROWS = HBLK * EVERY * SPG;                        // table rows they use
+    constexpr int HCH = (HBLK * EVERY * WPG + 3) / 4;                // 16-byte chunks that hold their codes
+    // Worth it only if the first pass weeds out most groups and the rows it saves are expensive.  Measured
+    // (scan stage, 10,000 queries): 64 sub-spaces of 8-bit codes, first pass 32: 2.13 -> 1.68 ms (e5m3), 3.06 ->
+    // 2.74 ms (fp32); 48 sub-spaces, first pass 32: 2.20 -> 2.47 ms (fp32); 32 sub-spaces, first pass 16: 6.5 ->
+    // 8.1 ms (most groups went through twice); 4-bit codes (16-entry rows cost nothing to build): 6.8 -> 9.7 ms.
+    // Hence: 8-bit codes, four chunks, the first pass takes half of them.
+    constexpr bool kCanSplit = BITS == 8 && NCH == 4 && HROWS >= 32 && 2 * HBLK == NBLK;
+    bool lazy = false;
+    if constexpr (kCanSplit) lazy = prune && !(kIsFp8<LUT> && a.fp8.per_table);
+    if constexpr (kCanSplit) {
+        if (lazy) {
+            uint32_t* any_alive = max_slot + 1;
+            uint16_t* alive = reinterpret_cast<uint16_t*>(after_rq + 16 + (size_t)n_waves * kStageCap * 8) + (size_t)wave * kAliveCap;
+            if (threadIdx.x == 0) *any_alive = 0u;
+            fp8 = stage_table<LUT, BITS>(a.codebooks, rq, a.pq_dim, a.m, lut, max_slot, a.fp8, 0, HROWS);
+            uint32_t n_alive = 0;                // wave-uniform
+            bool redo_all = false;               // more groups in the race than the list holds: take them all again
+            auto load_head = [&](chunk_t (&buf)[NBUF], int grp) {
+#pragma unroll
+                for (int c = 0; c < HCH; ++c) buf[c] = cbase[((size_t)grp * NBUF + c) * 64 + lane];
+            };
+            auto first_pass = [&](int grp, const chunk_t (&buf)[NBUF]) {
+                const float acc = accumulate(buf, std::integral_constant<int, HBLK>{});
+                const bool in_race = (uint32_t)grp * 64u + lane < len && __float_as_uint(acc) <= bound;
+                if (__ballot(in_race) != 0) {
+                    if (n_alive < (uint32_t)kAliveCap && grp / n_waves < 65536) { if (lane == 0) alive[n_alive] = (uint16_t)(grp / n_waves); ++n_alive; }
+                    else redo_all = true;
+                }
+            };
+            // (the loads of the wave's first group were issued in full above; later groups load the head only)
+            while (g < n_groups) {
+                const int gn = g + n_waves;
+                if (gn < n_groups) load_head(buf_b, gn);
+                first_pass(g, buf_a);
+                if (gn >= n_groups) break;
+                g = gn + n_waves;
+                if (g < n_groups) load_head(buf_a, g);
+                first_pass(gn, buf_b);
+            }
+            if (lane == 0 && (n_alive != 0 || redo_all)) atomicOr(any_alive, 1u);
+            __syncthreads();
+            if (*any_alive == 0u) return;
+            (void)stage_table<LUT, BITS>(a.codebooks, rq, a.pq_dim, a.m, lut, max_slot, a.fp8, HROWS, a.pq_dim);
+            if (redo_all) {
+                for (g = wave; g < n_groups; g += n_waves) {
+                    load_group(buf_a, g);
+                    store_R(g, accumulate(buf_a, std::integral_constant<int, NBLK>{}));
+                }
+            } else {
+                for (uint32_t t = 0; t < n_alive; ++t) {
+                    g = (int)alive[t] * n_waves + wave;
+                    load_group(buf_a, g);
+                    store_R(g, accumulate(buf_a, std::integral_constant<int, NBLK>{}));
+                }
+            }
+            flush_stage();
+            return;
+        }
+    }
     // step 3: the table
-    fp8 = stage_table<LUT, BITS>(a.codebooks, rq, a.pq_dim, a.m, lut, max_slot, a.fp8);
+    fp8 = stage_table<LUT, BITS>(a.codebooks, rq, a.pq_dim, a.m, lut, max_slot, a.fp8, 0, a.pq_dim);
 
     // step 4: Eq. (1), one lane per coded vector; the next group is loaded into the other register
     // buffer while the current one is looked up
@@ -1083,11 +1158,11 @@ scan_kernel(ScanArgs a) {
         while (g < n_groups) {
             int gn = g + n_waves;
             if (gn < n_groups) load_group(buf_b, gn);
-            store_R(g, accumulate(buf_a));
+            store_R(g, accumulate(buf_a, std::integral_constant<int, NBLK>{}));
             if (gn >= n_groups) break;
             g = gn + n_waves;
             if (g < n_groups) load_group(buf_a, g);
-            store_R(gn, accumulate(buf_b));
+            store_R(gn, accumulate(buf_b, std::integral_constant<int, NBLK>{}));
         }
     } else {
         // 4-byte chunks: one code group (WPG words) at a time
@@ -1350,11 +1425,11 @@ dump_lut_kernel(const float* __restrict__ query, const float* __restrict__ centr
     for (int t = threadIdx.x; t < d; t += blockDim.x) rq[t] = query[t] - centroid[t];
     __syncthreads();
     switch (bits) {
-        case 8: (void)stage_table<LUT, 8>(codebooks, rq, pq_dim, m, lut, max_slot, fp8); break;
-        case 7: (void)stage_table<LUT, 7>(codebooks, rq, pq_dim, m, lut, max_slot, fp8); break;
-        case 6: (void)stage_table<LUT, 6>(codebooks, rq, pq_dim, m, lut, max_slot, fp8); break;
-        case 5: (void)stage_table<LUT, 5>(codebooks, rq, pq_dim, m, lut, max_slot, fp8); break;
-        default: (void)stage_table<LUT, 4>(codebooks, rq, pq_dim, m, lut, max_slot, fp8); break;
+        case 8: (void)stage_table<LUT, 8>(codebooks, rq, pq_dim, m, lut, max_slot, fp8, 0, pq_dim); break;
+        case 7: (void)stage_table<LUT, 7>(codebooks, rq, pq_dim, m, lut, max_slot, fp8, 0, pq_dim); break;
+        case 6: (void)stage_table<LUT, 6>(codebooks, rq, pq_dim, m, lut, max_slot, fp8, 0, pq_dim); break;
+        case 5: (void)stage_table<LUT, 5>(codebooks, rq, pq_dim, m, lut, max_slot, fp8, 0, pq_dim); break;
+        default: (void)stage_table<LUT, 4>(codebooks, rq, pq_dim, m, lut, max_slot, fp8, 0, pq_dim); break;
     }
     for (size_t i = threadIdx.x; i < lut_bytes / 4; i += blockDim.x)
         reinterpret_cast<uint32_t*>(out)[i] = reinterpret_cast<const uint32_t*>(lut)[i];
@@ -1719,7 +1794,7 @@ size_t scan_lds_bytes(const ivfpq_index* idx, int lut_dtype) {
 }
 // plus the per-wave survivor staging of the filtered scan
 size_t scan_lds_bytes_staged(const ivfpq_index* idx, int lut_dtype, int threads) {
-    return scan_lds_bytes(idx, lut_dtype) + (size_t)(threads / 64) * kStageCap * 8;
+    return scan_lds_bytes(idx, lut_dtype) + (size_t)(threads / 64) * (kStageCap * 8 + kAliveCap * 2);
 }
 
 int check_device(const ivfpq_index* idx) {
