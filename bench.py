@@ -29,14 +29,14 @@ LDS_PEAK_LOOKUPS = 256 * 32 * 2.4e9     # conflict-free wave-wide LDS reads: 32 
 # for a plain 1 GiB copy (FETCH_SIZE reads half the true KiB on this chip, WRITE_SIZE the true
 # figure): profiles/scan_kernel_<workload>_e5m3_hbm_traffic.txt.  None where no run is recorded.
 MEASURED_TRAFFIC = {
-    ("intgrid_1m", "e5m3"): 1.171e9,      # 1.12 GB fetched + 0.055 GB written (algorithmic: 30.98 GB of codes,
+    ("intgrid_1m", "e5m3"): 1.088e9,      # 1.03 GB fetched + 0.055 GB written (algorithmic: 30.98 GB of codes,
                                           # served by the caches: the pairs run grouped by cluster)
     ("unitnorm_10m", "e5m3"): 1.470e9,    # 1.41 GB fetched + 0.063 GB written (algorithmic: 9.42 GB of codes)
 }
 # busy fractions of the other units during scan_kernel, same profiles (profiles/scan_kernel_*_lds_counters.txt)
 MEASURED_UNITS = {
     # without the early exit (every lookup made) / with it (the default)
-    ("intgrid_1m", "e5m3"): {"lds_busy": 0.96, "valu_busy": 0.96, "lds_busy_early_exit": 0.80, "valu_busy_early_exit": 1.0},
+    ("intgrid_1m", "e5m3"): {"lds_busy": 0.96, "valu_busy": 0.96, "lds_busy_early_exit": 0.91, "valu_busy_early_exit": 1.0},
     ("unitnorm_10m", "e5m3"): {"lds_busy": 0.77, "valu_busy": 0.88, "lds_busy_early_exit": 0.56, "valu_busy_early_exit": 0.88},
 }
 
