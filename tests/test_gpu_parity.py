@@ -648,6 +648,25 @@ def test_early_exit_changes_nothing(P, monkeypatch, d, pq_dim, pq_bits, dtype):
     assert_topk_matches(ids_g, d_g, ids_o, d_o, context="early exit")
 
 
+def test_split_scan_when_every_group_stays_in_the_race(P):
+    # 64 sub-spaces of 8-bit codes: the filtered scan builds half the table first.  Here the nearest cluster
+    # holds fewer than k vectors, so the bound admits everything: every group of the big cluster needs the
+    # second half, more groups per wave than the first pass can note (it then takes them all again)
+    n, d = 21000, 128
+    cent, cb, _, codes, ids = si.random_index_arrays(n, d, 3, 64, 8, salt=810)
+    offs = np.array([0, 40, 20040, 21000], dtype=np.int64)
+    oidx = oracle.make_index(d, 3, 64, 8, cent, cb, offs, codes, ids)
+    gidx = to_library(P, oidx)
+    q = np.random.default_rng(810).standard_normal((6, d)).astype(np.float32)
+    for probes_row, k in (([0, 1], 100), ([0, 1, 2], 1000), ([2, 1], 10), ([1, 2, 0], 10)):
+        probes = np.tile(np.array([probes_row], dtype=np.uint32), (6, 1))
+        for dtype in (oracle.LUT_FP32, oracle.LUT_E5M3):
+            _step(f"split scan, everything in the race: probes={probes_row} k={k} dtype={dtype}")
+            ids_g, d_g = gidx.ivfpq_search_with_probes(q, probes, k, dtype)
+            ids_o, d_o = oracle.search(oidx, q, len(probes_row), k, dtype, probes=probes)
+            assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"probes={probes_row} k={k}")
+
+
 # ---------------------------------------------------------------- the search inside a HIP graph
 
 def test_search_replays_correctly_from_a_hip_graph(P, tiny):
