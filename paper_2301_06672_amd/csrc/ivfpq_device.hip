@@ -51,6 +51,8 @@ constexpr uint32_t kPadKey = 0xFFFFFFFFu;      // R of a padding lane: sorts aft
 // digits finds the k-th smallest key; everything below it and the needed share of the ties is
 // collected into LDS records and sorted there (bitonic).
 // ================================================================================================
+// (the helpers below are force-inlined: left to the inliner, a few lines more in one of them turned it into a
+// real call with its arguments on the stack, and the probe-selection kernel took twice as long)
 constexpr int SEL_THREADS = 256;
 constexpr int SEL_CAP = 1024;      // record capacity = IVFPQ_MAX_K: the selected elements always fit
 
@@ -76,7 +78,7 @@ __device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
 // hist holds digit counts; finds the digit that contains the `need`-th smallest element
 // (1-based).  Result in s.digit (the digit), s.need (rank inside that digit), s.count (its count).
 // Called by all threads; contains barriers.
-__device__ inline void find_digit(SelectShared& s, uint32_t need) {
+__device__ __forceinline__ void find_digit(SelectShared& s, uint32_t need) {
     __syncthreads();
     if (threadIdx.x < kWave) {
         const int t = threadIdx.x;
@@ -104,7 +106,7 @@ __device__ inline bool rec_less(uint32_t ka, long long ta, uint32_t pa, uint32_t
 }
 
 // sorts records [0, np2) ascending by (key, tie, pos); np2 is a power of two <= SEL_CAP
-__device__ inline void sort_records(SelectShared& s, int np2) {
+__device__ __forceinline__ void sort_records(SelectShared& s, int np2) {
     for (int size = 2; size <= np2; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
             __syncthreads();
@@ -130,7 +132,7 @@ __device__ inline void sort_records(SelectShared& s, int np2) {
 // One histogram increment per active lane, with the increments of a wave folded into a single
 // LDS atomic when all its active lanes hit the same bin (the usual case for the leading digit of
 // distances of similar magnitude, where per-lane atomics on one address would serialise).
-__device__ inline void hist_add(uint32_t* hist, uint32_t digit, bool active) {
+__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t digit, bool active) {
     const unsigned long long act = __ballot(active);
     if (act == 0) return;
     const int first = __ffsll((long long)act) - 1;
@@ -147,7 +149,7 @@ __device__ inline void hist_add(uint32_t* hist, uint32_t digit, bool active) {
 // *rank_in_ties = how many elements equal to the result rank at or below kk (1..*n_ties),
 // *n_ties = number of elements equal to the result.  Called by every thread of the workgroup.
 template <class KeyFn>
-__device__ uint32_t block_kth_key(SelectShared& s, uint32_t n, uint32_t kk, KeyFn key_of,
+__device__ __forceinline__ uint32_t block_kth_key(SelectShared& s, uint32_t n, uint32_t kk, KeyFn key_of,
                                   uint32_t* rank_in_ties, uint32_t* n_ties) {
     const int tid = threadIdx.x, nth = blockDim.x;
     uint32_t prefix = 0, need = kk, n_eq = 0;
@@ -177,7 +179,7 @@ __device__ uint32_t block_kth_key(SelectShared& s, uint32_t n, uint32_t kk, KeyF
 // On return records [0, min(k, n)) hold the selected elements in ascending (key, tie, pos) order.
 // Returns min(k, n).  Must be called by every thread of the workgroup.
 template <class KeyFn, class TieFn>
-__device__ int block_select_smallest(SelectShared& s, uint32_t n, uint32_t k, KeyFn key_of, TieFn tie_of) {
+__device__ __forceinline__ int block_select_smallest(SelectShared& s, uint32_t n, uint32_t k, KeyFn key_of, TieFn tie_of) {
     const uint32_t kk = k < n ? k : n;
     if (kk == 0) return 0;
     const int tid = threadIdx.x, nth = blockDim.x;
@@ -260,7 +262,7 @@ __device__ int block_select_smallest(SelectShared& s, uint32_t n, uint32_t k, Ke
 // k smaller keys, and wait in the upper half of the record array while the ranks are settled.
 constexpr uint32_t kFewMax = 128;
 template <class KeyFn, class TieFn>
-__device__ int block_select_few(SelectShared& s, uint32_t n, uint32_t k, KeyFn key_of, TieFn tie_of) {
+__device__ __forceinline__ int block_select_few(SelectShared& s, uint32_t n, uint32_t k, KeyFn key_of, TieFn tie_of) {
     const uint32_t kk = k < n ? k : n;
     if (kk == 0) return 0;
     const uint32_t e = threadIdx.x;
@@ -323,7 +325,7 @@ struct NoWiden { __device__ uint32_t operator()(uint32_t b) const { return b; } 
 struct NoRefine { __device__ uint32_t operator()(uint32_t n) const { return n; } };
 
 template <class PosFn, class TieFn, class WidenFn, class RefineFn, class WholeRowFn>
-__device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
+__device__ __forceinline__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
                                    bool have_bound, uint32_t bound, PosFn pos_of, TieFn tie_of_pos,
                                    WidenFn widen, RefineFn refine, WholeRowFn whole_row) {
     SelectShared& s = t.sel;
@@ -348,7 +350,7 @@ __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restric
             }
         }
         bound = widen(bound);
-        const bool vec = (n & 3u) == 0 && (reinterpret_cast<uintptr_t>(row) & 15u) == 0;
+        const bool vec = (reinterpret_cast<uintptr_t>(row) & 15u) == 0;      // 16-byte loads, the last n % 4 keys one by one
         compact = false;
         // Each pass keeps the elements not above the bound.  If they overflow the LDS buffer, the
         // k-th smallest of the ones that were kept is a tighter valid bound (they are all members
@@ -369,6 +371,7 @@ __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restric
                     const uint4 v = row4[i4];
                     keep(v.x, i4 * 4); keep(v.y, i4 * 4 + 1); keep(v.z, i4 * 4 + 2); keep(v.w, i4 * 4 + 3);
                 }
+                for (uint32_t i = (n & ~3u) + tid; i < n; i += nth) keep(row[i], i);
             } else {
                 for (uint32_t i = tid; i < n; i += nth) keep(row[i], i);
             }
@@ -399,7 +402,7 @@ __device__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restric
 }
 
 template <class PosFn, class TieFn>
-__device__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
+__device__ __forceinline__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
                                 bool have_bound, uint32_t bound, PosFn pos_of, TieFn tie_of_pos) {
     SelectShared& s = t.sel;
     return block_select_row_ex(t, row, n, k, have_bound, bound, pos_of, tie_of_pos, NoWiden{}, NoRefine{},
@@ -1644,8 +1647,11 @@ topk_kernel(const float* __restrict__ R, const uint32_t* __restrict__ Rpos, size
         }
         return (long long)ids[list_offsets[s_probe[lo]] + (int64_t)(pos - s_roff[lo])];
     };
-    const bool have_bound = n_probes > 1;
-    const int got = block_select_row(t, row, n, (uint32_t)k, have_bound, have_bound ? bounds[q] : 0u, pos_of, id_of);
+    // a bound that admits everything (fewer than k vectors in the nearest cluster) filters nothing: let the
+    // selection take its own from a sample, or a long survivor list goes through several passes
+    const uint32_t known = listed ? bounds[q] : kAdmitAll;
+    const bool have_bound = known != kAdmitAll;
+    const int got = block_select_row(t, row, n, (uint32_t)k, have_bound, have_bound ? known : 0u, pos_of, id_of);
     for (int j = tid; j < k; j += nth) {
         int64_t id = -1;
         float dist = __uint_as_float(0x7F800000u);
