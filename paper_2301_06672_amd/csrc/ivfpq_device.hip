@@ -436,7 +436,7 @@ select_probes_kernel(uint32_t* __restrict__ A, const uint2* __restrict__ S, int 
                      int n_lists, int n_probes,
                      const uint32_t* __restrict__ list_sizes, const int64_t* __restrict__ group_offsets,
                      uint32_t* __restrict__ probes, float* __restrict__ probe_dists,
-                     uint32_t* __restrict__ roff, uint4* __restrict__ pairs) {
+                     uint32_t* __restrict__ roff, uint4* __restrict__ pairs, int k_hint) {
     __shared__ RowSelectShared t;
     __shared__ float s_part[SEL_THREADS / kWave];
     SelectShared& s = t.sel;
@@ -593,19 +593,46 @@ select_probes_kernel(uint32_t* __restrict__ A, const uint2* __restrict__ S, int 
                                   [](uint32_t pos, uint32_t) { return (long long)pos; },
                                   widen, refine, whole_row);
     }
-    for (int p = tid; p < got; p += nth) {
-        probes[(size_t)q * n_probes + p] = s.rec_pos[p];
-        if (probe_dists) probe_dists[(size_t)q * n_probes + p] = __uint_as_float(s.rec_key[p]);
+    if (!roff) {             // the caller's probe lists: nearest first
+        for (int p = tid; p < got; p += nth) {
+            probes[(size_t)q * n_probes + p] = s.rec_pos[p];
+            if (probe_dists) probe_dists[(size_t)q * n_probes + p] = __uint_as_float(s.rec_key[p]);
+        }
+        return;
     }
-    if (roff && tid == 0) {
+    // The search's own lists.  Slot 0 is the cluster that is scanned unfiltered and whose k-th smallest R
+    // bounds the rest: the nearest one that holds at least k_hint vectors (a smaller one gives no bound, and
+    // then every vector of every other probe would be kept); the others follow in order of distance.
+    // (lengths and first groups of all probes are fetched in parallel; got <= 1024 = the candidate buffer)
+    for (int p = tid; p < got; p += nth) {
+        const uint32_t l = s.rec_pos[p];
+        t.cand_key[p] = list_sizes[l];
+        t.cand_pos[p] = (uint32_t)group_offsets[l];
+    }
+    uint32_t* slot_of = reinterpret_cast<uint32_t*>(s.rec_tie);          // 2048 words: slot of probe p, then offsets
+    uint32_t* offs = slot_of + SEL_CAP;
+    __syncthreads();
+    if (tid == 0) {
+        int pivot = 0;
+        if (k_hint > 0)
+            for (int p = 0; p < got; ++p)
+                if (t.cand_key[p] >= (uint32_t)k_hint) { pivot = p; break; }
         uint32_t at = 0;
-        for (int p = 0; p < got; ++p) {
-            const uint32_t l = s.rec_pos[p], len = list_sizes[l];
-            roff[(size_t)q * (n_probes + 1) + p] = at;
-            pairs[(size_t)q * n_probes + p] = make_uint4(l, len, (uint32_t)group_offsets[l], at);
-            at += (len + 63u) & ~63u;
+        for (int i = 0; i < got; ++i) {
+            const int p = i == 0 ? pivot : (i <= pivot ? i - 1 : i);
+            slot_of[p] = (uint32_t)i;
+            offs[p] = at;
+            at += (t.cand_key[p] + 63u) & ~63u;
         }
         roff[(size_t)q * (n_probes + 1) + got] = at;
+    }
+    __syncthreads();
+    for (int p = tid; p < got; p += nth) {
+        const uint32_t i = slot_of[p], l = s.rec_pos[p], at = offs[p];
+        probes[(size_t)q * n_probes + i] = l;
+        if (probe_dists) probe_dists[(size_t)q * n_probes + i] = __uint_as_float(s.rec_key[p]);
+        roff[(size_t)q * (n_probes + 1) + i] = at;
+        pairs[(size_t)q * n_probes + i] = make_uint4(l, t.cand_key[p], t.cand_pos[p], at);
     }
 }
 
@@ -2036,7 +2063,7 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
             hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, (const uint2*)strips,
                                coarse_strip_width(tq, idx->n_lists), qt,
                                idx->dev.centroids, idx->centroid_norm_max, idx->d, idx->n_lists,
-                               n_probes, idx->dev.list_sizes, idx->dev.group_offsets, w_probes, w_probe_d, w_roff, w_pairs);
+                               n_probes, idx->dev.list_sizes, idx->dev.group_offsets, w_probes, w_probe_d, w_roff, w_pairs, k);
             HIP_TRY(hipGetLastError());
         } else {
             hipLaunchKernelGGL(layout_probes_kernel, dim3((tq + 255) / 256), dim3(256), 0, st,
@@ -2268,7 +2295,7 @@ int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_
                            coarse_strip_width(tq, idx->n_lists), d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->centroid_norm_max, idx->d,
                            idx->n_lists, n_probes, idx->dev.list_sizes, idx->dev.group_offsets, d_probes + (size_t)q0 * n_probes,
                            d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr,
-                           (uint4*)nullptr);
+                           (uint4*)nullptr, 0);
         HIP_TRY(hipGetLastError());
     }
     return IVFPQ_OK;

@@ -667,6 +667,24 @@ def test_split_scan_when_every_group_stays_in_the_race(P):
             assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"probes={probes_row} k={k}")
 
 
+def test_search_nearest_cluster_smaller_than_k(P):
+    # the cluster nearest to these queries holds 5 vectors, fewer than k: the search takes its bound from the
+    # next probe that holds at least k (and scans that one unfiltered); the answer is the oracle's all the same
+    n, d = 6000, 32
+    cent, cb, _, codes, ids = si.random_index_arrays(n, d, 5, 16, 8, salt=820)
+    offs = np.array([0, 5, 8, 3000, 3000, 6000], dtype=np.int64)          # 5, 3, 2992, 0 and 3000 vectors
+    oidx = oracle.make_index(d, 5, 16, 8, cent, cb, offs, codes, ids)
+    gidx = to_library(P, oidx)
+    rng = np.random.default_rng(820)
+    q = (cent[0] + 0.05 * rng.standard_normal((40, d))).astype(np.float32)
+    q[20:] = (cent[1] + 0.05 * rng.standard_normal((20, d))).astype(np.float32)
+    for n_probes, k in ((5, 10), (2, 10), (3, 4), (5, 1000), (1, 10)):
+        for dtype in (oracle.LUT_FP32, oracle.LUT_E5M3):
+            _step(f"nearest cluster smaller than k: P={n_probes} k={k} dtype={dtype}")
+            ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, n_probes, k, dtype)
+            assert_topk_matches(ids_g, d_g, ids_o, d_o, context=f"tiny nearest cluster P={n_probes} k={k}")
+
+
 # ---------------------------------------------------------------- the search inside a HIP graph
 
 def test_search_replays_correctly_from_a_hip_graph(P, tiny):
