@@ -160,7 +160,7 @@ nearest_kernel(const uint32_t* __restrict__ A, const float* __restrict__ X, cons
 // otherwise the strips that can hold the nearest centre are compared by float64 distances (their best
 // centre, or all their centres if the strip's second key is within the bound as well).
 __global__ void __launch_bounds__(256)
-nearest_strips_kernel(const uint2* __restrict__ S, int strip_w, const float* __restrict__ X, const float* __restrict__ C,
+nearest_strips_kernel(const StripSummary* __restrict__ S, int strip_w, const float* __restrict__ X, const float* __restrict__ C,
                       const uint32_t* __restrict__ norm_max_bits, int n_rows, int k, int d, int32_t* __restrict__ labels) {
     __shared__ uint32_t s_b1[4][64], s_b2[4][64], s_i1[4][64];
     const int r = threadIdx.x & 63, sl = threadIdx.x >> 6;
@@ -170,7 +170,7 @@ nearest_strips_kernel(const uint2* __restrict__ S, int strip_w, const float* __r
     uint32_t b1 = 0xFFFFFFFFu, b2 = 0xFFFFFFFFu, i1 = 0u;
     if (row < n_rows)
         for (int i = sl; i < n_strips; i += 4) {
-            const uint2 v = S[(size_t)i * stride + row];
+            const StripSummary v = S[(size_t)i * stride + row];
             if (v.x < b1) { b2 = b1 < v.y ? b1 : v.y; b1 = v.x; i1 = (uint32_t)i; }
             else if (v.x < b2) b2 = v.x;
         }
@@ -201,12 +201,17 @@ nearest_strips_kernel(const uint2* __restrict__ S, int strip_w, const float* __r
         if (dist < best) { best = dist; arg = c; }        // centres come in ascending order: ties stay with the lower
     };
     for (int i = 0; i < n_strips; ++i) {
-        const uint2 v = S[(size_t)i * stride + row];
+        const StripSummary v = S[(size_t)i * stride + row];
         if ((v.x & ~63u) > limit) continue;
         const int c0 = i * strip_w;
         if ((v.y & ~63u) > limit) {
             const int c = c0 + (int)(v.x & 63u);
             if (c < k) try_centre(c);
+        } else if ((v.z & ~63u) > limit) {         // its best two, in ascending order of the centre index
+            const int ca = c0 + (int)(v.x & 63u), cb = c0 + (int)(v.y & 63u);
+            const int lo = ca < cb ? ca : cb, hi = ca < cb ? cb : ca;
+            if (lo < k) try_centre(lo);
+            if (hi < k) try_centre(hi);
         } else {
             const int c1 = c0 + strip_w < k ? c0 + strip_w : k;
             for (int c = c0; c < c1; ++c) try_centre(c);
@@ -434,11 +439,11 @@ template <class Take>
 void plan_nearest(BuildPlan& P, size_t n_rows_max, int k, int d, Take&& take) {
     const size_t strips = ((size_t)k + 31) / 32;
     P.use_strips = k >= 256;
-    const size_t per_row = (P.use_strips ? strips * 8 : (size_t)k * 4) + (size_t)coarse_padded_dim(d) * 4;
+    const size_t per_row = (P.use_strips ? strips * sizeof(StripSummary) : (size_t)k * 4) + (size_t)coarse_padded_dim(d) * 4;
     P.tile_rows = std::max<size_t>(1, std::min<size_t>(kRankTileBytes / per_row, (size_t)2 << 20));
     P.tile_rows = std::min<size_t>(P.tile_rows, std::max<size_t>(n_rows_max, 1));
     P.A = take(P.use_strips ? 0 : P.tile_rows * (size_t)k * 4);
-    P.S = take(P.use_strips ? P.tile_rows * strips * 8 : 0);
+    P.S = take(P.use_strips ? P.tile_rows * strips * sizeof(StripSummary) : 0);
     P.split = take(coarse_split_bytes(P.tile_rows, (size_t)k, d));
     P.cnorm = take((size_t)k * 4);
     P.cmax = take(4);
@@ -486,7 +491,7 @@ int assign_rows_device(const BuildPlan& P, unsigned char* ws, const float* X, si
     float* cnorm = (float*)(ws + P.cnorm);
     uint32_t* cmax = (uint32_t*)(ws + P.cmax);
     uint32_t* A = (uint32_t*)(ws + P.A);
-    uint2* S = (uint2*)(ws + P.S);
+    StripSummary* S = (StripSummary*)(ws + P.S);
     if (int s = fill_u32(cmax, 1, 0u, st)) return s;
     hipLaunchKernelGGL(centre_norms_kernel, dim3(blocks_for((size_t)k, 4)), dim3(256), 0, st, C, k, P.d, cnorm, cmax);
     HIP_TRY(hipGetLastError());
@@ -494,7 +499,7 @@ int assign_rows_device(const BuildPlan& P, unsigned char* ws, const float* X, si
         const int tr = (int)std::min(P.tile_rows, n_rows - r0);
         if (int s = launch_coarse(X + r0 * P.d, C, cnorm, tr, k, P.d, A, P.use_strips ? S : nullptr, ws + P.split, st)) return s;
         if (P.use_strips)
-            hipLaunchKernelGGL(nearest_strips_kernel, dim3(blocks_for((size_t)tr, 64)), dim3(256), 0, st, (const uint2*)S,
+            hipLaunchKernelGGL(nearest_strips_kernel, dim3(blocks_for((size_t)tr, 64)), dim3(256), 0, st, (const StripSummary*)S,
                                coarse_strip_width(tr, k), X + r0 * P.d, C, cmax, tr, k, P.d, labels + r0);
         else
             hipLaunchKernelGGL(nearest_kernel, dim3(blocks_for((size_t)tr, 4)), dim3(256), 0, st, A, X + r0 * P.d, C, cmax, tr,

@@ -423,14 +423,15 @@ __device__ __forceinline__ int block_select_row(RowSelectShared& t, const uint32
 // descriptor per (query, probe) pair -- {cluster, length, first 64-vector group, R offset} -- so
 // that a scan workgroup starts from a single 16-byte load.
 // S (may be null): instead of the keys, the ranking kernel's summary of every strip of strip_w clusters
-// (its two smallest keys, tagged with the cluster's position in the strip), strip-major
+// (its three smallest keys, tagged with the cluster's position in the strip), strip-major
 // [n_strips][gridDim.x]; the host passes it when there are at least 2 n_probes strips.  The n_probes-th
 // smallest strip minimum then bounds the n_probes-th smallest key; a strip whose minimum passes the
-// (widened) bound yields its best cluster, or all its clusters if its second key passes too, and all of
+// (widened) bound yields its best cluster, its best two if the second key passes too, or all its clusters if
+// the third does as well, and all of
 // these get their exact distance.  A is then only scratch for the whole-row fallback.
 // ================================================================================================
 __global__ void __launch_bounds__(SEL_THREADS)
-select_probes_kernel(uint32_t* __restrict__ A, const uint2* __restrict__ S, int strip_w,
+select_probes_kernel(uint32_t* __restrict__ A, const StripSummary* __restrict__ S, int strip_w,
                      const float* __restrict__ queries,
                      const float* __restrict__ centroids, float centroid_norm_max, int d,
                      int n_lists, int n_probes,
@@ -534,17 +535,18 @@ select_probes_kernel(uint32_t* __restrict__ A, const uint2* __restrict__ S, int 
     if (S) {
         const uint32_t n_strips = ((uint32_t)n_lists + strip_w - 1) / strip_w, sw = (uint32_t)strip_w;
         const size_t stride = gridDim.x;
-        const uint2* mine = S + q;
-        // the summaries are read several times: from the (still unused) record arrays if they fit there
+        const StripSummary* mine = S + q;
+        // the summaries are read several times: from the (still unused) record and candidate-key arrays if they fit
         const bool in_lds = n_strips <= (uint32_t)SEL_CAP;
         if (in_lds)
             for (uint32_t i = tid; i < n_strips; i += nth) {
-                const uint2 v = mine[i * stride];
-                s.rec_key[i] = v.x; s.rec_pos[i] = v.y;
+                const StripSummary v = mine[i * stride];
+                s.rec_key[i] = v.x; s.rec_pos[i] = v.y; t.cand_key[i] = v.z;
             }
         __syncthreads();
         auto low1 = [&](uint32_t i) { return in_lds ? s.rec_key[i] : mine[i * stride].x; };
         auto low2 = [&](uint32_t i) { return in_lds ? s.rec_pos[i] : mine[i * stride].y; };
+        auto low3 = [&](uint32_t i) { return in_lds ? t.cand_key[i] : mine[i * stride].z; };
         uint32_t r0, r1;
         const uint32_t kk = (uint32_t)n_probes < n_strips ? (uint32_t)n_probes : n_strips;
         // kk strips hold a key not above this, so it bounds the kk-th smallest key of the row
@@ -555,13 +557,18 @@ select_probes_kernel(uint32_t* __restrict__ A, const uint2* __restrict__ S, int 
         for (uint32_t i = tid; i < n_strips; i += nth) {
             const uint32_t a1 = low1(i), first = i * sw;
             if ((a1 & ~63u) > bound) continue;
-            if ((low2(i) & ~63u) > bound) {           // one key of the strip can pass: its best cluster
-                const uint32_t c = first + (a1 & 63u);
-                if (c < (uint32_t)n_lists) {
-                    const uint32_t slot = atomicAdd(&t.n_cand, 1u);
-                    if (slot < (uint32_t)CAND_CAP) t.cand_pos[slot] = c;
+            const uint32_t a2 = low2(i);
+            if ((a2 & ~63u) > bound || (low3(i) & ~63u) > bound) {
+                // only its best cluster can pass, or its best two
+                const uint32_t n_take = (a2 & ~63u) > bound ? 1u : 2u;
+                for (uint32_t u = 0; u < n_take; ++u) {
+                    const uint32_t c = first + ((u == 0 ? a1 : a2) & 63u);
+                    if (c < (uint32_t)n_lists) {
+                        const uint32_t slot = atomicAdd(&t.n_cand, 1u);
+                        if (slot < (uint32_t)CAND_CAP) t.cand_pos[slot] = c;
+                    }
                 }
-            } else {                                   // several may: all its clusters
+            } else {                                   // more may: all its clusters
                 const uint32_t cnt = (uint32_t)n_lists - first < sw ? (uint32_t)n_lists - first : sw;
                 const uint32_t slot = atomicAdd(&t.n_cand, cnt);
                 for (uint32_t c = 0; c < cnt; ++c)
@@ -1781,7 +1788,7 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
         return fail(IVFPQ_EUNSUPPORTED, "a query may see %lld candidates (limit 2^31)", (long long)stride);
     if (stride < 64) stride = 64;
     const size_t strips = ((size_t)idx->n_lists + 31) / 32;      // strip summaries of the ranking keys, narrowest strips
-    size_t per_query = (size_t)stride * 8 + (need_D ? ((size_t)idx->n_lists + 2 * strips + coarse_padded_dim(idx->d)) * 4 : 0);
+    size_t per_query = (size_t)stride * 8 + (need_D ? ((size_t)idx->n_lists + 4 * strips + coarse_padded_dim(idx->d)) * 4 : 0);
     int64_t tile = (int64_t)(idx->workspace_limit / per_query);
     tile = std::max<int64_t>(1, std::min<int64_t>(tile, std::max<int64_t>(nq, 1)));
     plan->tile = tile;
@@ -1795,7 +1802,7 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     plan->bounds = take((size_t)tile * 4);
     plan->counts = take((size_t)tile * 4);
     plan->D = take(need_D ? (size_t)tile * idx->n_lists * 4 : 0);
-    plan->S = take(need_D ? (size_t)tile * strips * 8 : 0);
+    plan->S = take(need_D ? (size_t)tile * strips * sizeof(StripSummary) : 0);
     plan->split = take(need_D ? coarse_split_bytes((size_t)tile, (size_t)idx->n_lists, idx->d) : 0);
     plan->R = take((size_t)tile * stride * 4);
     plan->Rpos = take((size_t)tile * stride * 4);
@@ -2045,7 +2052,7 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
     uint32_t* w_counts = (uint32_t*)(ws + plan.counts);
     uint32_t* w_Rpos = (uint32_t*)(ws + plan.Rpos);
     float* w_D = (float*)(ws + plan.D);
-    uint2* w_S = (uint2*)(ws + plan.S);
+    StripSummary* w_S = (StripSummary*)(ws + plan.S);
     float* w_R = (float*)(ws + plan.R);
 
     if (idx->timing) { idx->events_used = 0; idx->spans.clear(); idx->stage_valid = true; }
@@ -2058,9 +2065,9 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         StageTimer t0(idx, st, 0);
         if (int s = t0.begin()) return s;
         if (!d_probes_in) {
-            uint2* strips = coarse_use_strips(tq, idx->n_lists, n_probes) ? w_S : nullptr;
+            StripSummary* strips = coarse_use_strips(tq, idx->n_lists, n_probes) ? w_S : nullptr;
             if (int s = launch_coarse(qt, idx->dev.centroids, idx->dev.centroid_norms, tq, idx->n_lists, idx->d, (uint32_t*)w_D, strips, ws + plan.split, st)) return s;
-            hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, (const uint2*)strips,
+            hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, (const StripSummary*)strips,
                                coarse_strip_width(tq, idx->n_lists), qt,
                                idx->dev.centroids, idx->centroid_norm_max, idx->d, idx->n_lists,
                                n_probes, idx->dev.list_sizes, idx->dev.group_offsets, w_probes, w_probe_d, w_roff, w_pairs, k);
@@ -2284,14 +2291,14 @@ int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_
         return fail(IVFPQ_ENOSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, plan.total);
     hipStream_t st = (hipStream_t)hip_stream;
     float* w_D = (float*)((unsigned char*)d_workspace + plan.D);
-    uint2* w_S = (uint2*)((unsigned char*)d_workspace + plan.S);
+    StripSummary* w_S = (StripSummary*)((unsigned char*)d_workspace + plan.S);
     for (int64_t q0 = 0; q0 < nq; q0 += plan.tile) {
         const int tq = (int)std::min<int64_t>(plan.tile, nq - q0);
-        uint2* strips = coarse_use_strips(tq, idx->n_lists, n_probes) ? w_S : nullptr;
+        StripSummary* strips = coarse_use_strips(tq, idx->n_lists, n_probes) ? w_S : nullptr;
         if (int s = launch_coarse(d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->dev.centroid_norms, tq,
                                   idx->n_lists, idx->d, (uint32_t*)w_D, strips, (unsigned char*)d_workspace + plan.split, st))
             return s;
-        hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, (const uint2*)strips,
+        hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, (const StripSummary*)strips,
                            coarse_strip_width(tq, idx->n_lists), d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->centroid_norm_max, idx->d,
                            idx->n_lists, n_probes, idx->dev.list_sizes, idx->dev.group_offsets, d_probes + (size_t)q0 * n_probes,
                            d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr,

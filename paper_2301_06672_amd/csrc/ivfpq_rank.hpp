@@ -68,8 +68,8 @@ __device__ inline float ordered_key_value(uint32_t key) {
     return __uint_as_float(key ^ ((key >> 31) ? 0x80000000u : 0xFFFFFFFFu));
 }
 
-// The two smallest, over the 32 lanes of a half-wave, of 16 values per lane (each lane brings its own two
-// smallest, lo1 <= lo2), folded so that every exchange carries only what the receiver keeps: the lane
+// The three smallest, over the 32 lanes of a half-wave, of 16 values per lane (each lane brings its own
+// three smallest, lo1 <= lo2 <= lo3), folded so that every exchange carries only what the receiver keeps: the lane
 // whose index bit is set keeps the upper half of the remaining values and hands the lower half to its
 // partner (8, 4, 2, 1 exchanges, then one more between neighbours).  Lane l of the half-wave ends with
 // the result for value l / 2.  The partners are the lane 16 further (LDS swizzle) and the lanes the
@@ -82,48 +82,56 @@ __device__ inline uint32_t dpp_take(uint32_t x) {
 __device__ inline uint32_t swizzle_take16(uint32_t x) { return (uint32_t)__builtin_amdgcn_ds_swizzle((int)x, 0x401F); }
 __device__ inline uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
 __device__ inline uint32_t umax32(uint32_t a, uint32_t b) { return a < b ? b : a; }
-struct Low2 { uint32_t m1, m2; };                 // smallest and second smallest
-// two sorted pairs -> the two smallest of the four
-__device__ inline Low2 merge_low2(Low2 a, Low2 b) {
-    return Low2{umin32(a.m1, b.m1), umin32(umax32(a.m1, b.m1), umin32(a.m2, b.m2))};
+struct Low3 { uint32_t m1, m2, m3; };             // the three smallest, ascending
+__device__ inline uint32_t umin3(uint32_t a, uint32_t b, uint32_t c) { return umin32(umin32(a, b), c); }
+// two sorted triples -> the three smallest of the six
+__device__ inline Low3 merge_low3(Low3 a, Low3 b) {
+    const uint32_t x = umax32(a.m1, b.m1), y = umin32(a.m2, b.m2);
+    return Low3{umin32(a.m1, b.m1), umin32(x, y), umin3(umax32(x, y), a.m3, b.m3)};
 }
-__device__ inline Low2 half_wave_low2x16(const uint32_t (&lo1)[16], const uint32_t (&lo2)[16], int l32) {
+template <int CTRL>
+__device__ inline Low3 dpp_take3(Low3 v) { return Low3{dpp_take<CTRL>(v.m1), dpp_take<CTRL>(v.m2), dpp_take<CTRL>(v.m3)}; }
+__device__ inline Low3 half_wave_low3x16(const uint32_t (&lo1)[16], const uint32_t (&lo2)[16], const uint32_t (&lo3)[16], int l32) {
     const bool b4 = (l32 & 16) != 0, b3 = (l32 & 8) != 0, b2 = (l32 & 4) != 0, b1 = (l32 & 2) != 0;
-    Low2 a[8], b[4], c[2];
+    Low3 a[8], b[4], c[2];
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-        const Low2 keep{b4 ? lo1[t + 8] : lo1[t], b4 ? lo2[t + 8] : lo2[t]};
-        const Low2 give{b4 ? lo1[t] : lo1[t + 8], b4 ? lo2[t] : lo2[t + 8]};
-        a[t] = merge_low2(keep, Low2{swizzle_take16(give.m1), swizzle_take16(give.m2)});         // from lane ^ 16
+        const Low3 keep{b4 ? lo1[t + 8] : lo1[t], b4 ? lo2[t + 8] : lo2[t], b4 ? lo3[t + 8] : lo3[t]};
+        const Low3 give{b4 ? lo1[t] : lo1[t + 8], b4 ? lo2[t] : lo2[t + 8], b4 ? lo3[t] : lo3[t + 8]};
+        a[t] = merge_low3(keep, Low3{swizzle_take16(give.m1), swizzle_take16(give.m2), swizzle_take16(give.m3)});   // from lane ^ 16
     }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        const Low2 keep = b3 ? a[t + 4] : a[t], give = b3 ? a[t] : a[t + 4];
-        b[t] = merge_low2(keep, Low2{dpp_take<0x140>(give.m1), dpp_take<0x140>(give.m2)});       // row_mirror
+        const Low3 keep = b3 ? a[t + 4] : a[t], give = b3 ? a[t] : a[t + 4];
+        b[t] = merge_low3(keep, dpp_take3<0x140>(give));       // row_mirror
     }
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-        const Low2 keep = b2 ? b[t + 2] : b[t], give = b2 ? b[t] : b[t + 2];
-        c[t] = merge_low2(keep, Low2{dpp_take<0x141>(give.m1), dpp_take<0x141>(give.m2)});       // row_half_mirror
+        const Low3 keep = b2 ? b[t + 2] : b[t], give = b2 ? b[t] : b[t + 2];
+        c[t] = merge_low3(keep, dpp_take3<0x141>(give));       // row_half_mirror
     }
-    const Low2 keep = b1 ? c[1] : c[0], give = b1 ? c[0] : c[1];
-    const Low2 x = merge_low2(keep, Low2{dpp_take<0x4E>(give.m1), dpp_take<0x4E>(give.m2)});     // quad_perm [2,3,0,1]
-    return merge_low2(x, Low2{dpp_take<0xB1>(x.m1), dpp_take<0xB1>(x.m2)});                      // quad_perm [1,0,3,2]
+    const Low3 keep = b1 ? c[1] : c[0], give = b1 ? c[0] : c[1];
+    const Low3 x = merge_low3(keep, dpp_take3<0x4E>(give));    // quad_perm [2,3,0,1]
+    return merge_low3(x, dpp_take3<0xB1>(x));                  // quad_perm [1,0,3,2]
 }
+
+// What the ranking kernels store per (row, strip) when they do not store every key: the three smallest
+// tagged keys of the strip, ascending (.w unused).
+typedef uint4 StripSummary;
 
 // Epilogue of the ranking kernels: turns the accumulated dot products of one workgroup tile (4 waves
 // 2 x 2, each WB x WB blocks of 32 x 32) into order-preserving keys of a = |c|^2 - 2 q.c.
 // Either all keys are stored, A[nq][n_lists] (S null), or only a summary of every strip of 32*WB
 // consecutive clusters (the ones a wave covers), S[n_strips][nq] (strip-major, so that a wave stores the
-// summaries of its 64 queries contiguously): the two smallest keys of the strip, each with its low six
+// summaries of its 64 queries contiguously): the three smallest keys of the strip, each with its low six
 // bits replaced by the cluster's position in the strip.  Clearing those bits lowers a key by at most 63
 // units in the last place; a consumer takes (x & ~63) as a lower and (x | 63) as an upper bound of the key.  All-ones
-// means "no such cluster".  stage: 512 words of LDS that no wave still reads.
+// means "no such cluster".  stage: 1024 words of LDS that no wave still reads.
 // Accumulator layout of a 32x32 block: register v of lane L holds row 8*(v/4) + 4*(L/32) + v%4, column L%32.
 template <int WB>
 __device__ __forceinline__ void rank_store(const floatx16 (&acc)[WB][WB], int q0, int l0, int nq, int n_lists,
                                            const float* __restrict__ centroid_norms, uint32_t* __restrict__ A,
-                                           uint2* __restrict__ S, uint2* stage) {
+                                           StripSummary* __restrict__ S, StripSummary* stage) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1, half = lane >> 5, l32 = lane & 31;
     if (!S) {
@@ -146,9 +154,9 @@ __device__ __forceinline__ void rank_store(const floatx16 (&acc)[WB][WB], int q0
     const int strip = blockIdx.x * 2 + wc;
 #pragma unroll
     for (int i = 0; i < WB; ++i) {
-        uint32_t lo1[16], lo2[16];                // per row: the two smallest tagged keys among this lane's clusters
+        uint32_t lo1[16], lo2[16], lo3[16];       // per row: the smallest tagged keys among this lane's clusters
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { lo1[v] = 0xFFFFFFFFu; lo2[v] = 0xFFFFFFFFu; }
+        for (int v = 0; v < 16; ++v) { lo1[v] = 0xFFFFFFFFu; lo2[v] = 0xFFFFFFFFu; lo3[v] = 0xFFFFFFFFu; }
 #pragma unroll
         for (int j = 0; j < WB; ++j) {
             const int li = l0 + (wc * WB + j) * 32 + l32;
@@ -158,13 +166,14 @@ __device__ __forceinline__ void rank_store(const floatx16 (&acc)[WB][WB], int q0
             for (int v = 0; v < 16; ++v) {
                 const uint32_t key = ordered_key(__builtin_fmaf(-2.f, acc[i][j][v], cn));
                 const uint32_t tagged = col_ok ? ((key & ~63u) | (uint32_t)(j * 32 + l32)) : 0xFFFFFFFFu;
+                lo3[v] = umin32(lo3[v], umax32(lo2[v], tagged));
                 lo2[v] = umin32(lo2[v], umax32(lo1[v], tagged));
                 lo1[v] = umin32(lo1[v], tagged);
             }
         }
-        const Low2 mine = half_wave_low2x16(lo1, lo2, l32);
+        const Low3 mine = half_wave_low3x16(lo1, lo2, lo3, l32);
         const int v = l32 >> 1;
-        stage[wave * 64 + i * 32 + 8 * (v / 4) + 4 * half + (v % 4)] = make_uint2(mine.m1, mine.m2);
+        stage[wave * 64 + i * 32 + 8 * (v / 4) + 4 * half + (v % 4)] = make_uint4(mine.m1, mine.m2, mine.m3, 0xFFFFFFFFu);
     }
     __builtin_amdgcn_wave_barrier();              // the wave's own LDS writes above are read back below
     const int qi = q0 + wr * WB * 32 + lane;
@@ -178,10 +187,10 @@ template <int WB>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 coarse_rank_kernel(const float* __restrict__ queries, const float* __restrict__ centroids,
                    const float* __restrict__ centroid_norms, int nq, int n_lists, int d,
-                   uint32_t* __restrict__ A, uint2* __restrict__ S) {
+                   uint32_t* __restrict__ A, StripSummary* __restrict__ S) {
     constexpr int CT = 64 * WB;          // tile edge
     constexpr int RT = 4 * WB;           // components a thread loads per tile row and slice
-    __shared__ float qs[CK][CT + 4];
+    __shared__ __attribute__((aligned(16))) float qs[CK][CT + 4];      // also the epilogue's staging area (16-byte stores)
     __shared__ float cs[CK][CT + 4];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -244,7 +253,7 @@ coarse_rank_kernel(const float* __restrict__ queries, const float* __restrict__ 
         }
         __syncthreads();
     }
-    rank_store<WB>(acc, q0, l0, nq, n_lists, centroid_norms, A, S, reinterpret_cast<uint2*>(&qs[0][0]));
+    rank_store<WB>(acc, q0, l0, nq, n_lists, centroid_norms, A, S, reinterpret_cast<StripSummary*>(&qs[0][0]));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -292,7 +301,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))
 coarse_rank_split_kernel(const uint16_t* __restrict__ Qh, const uint16_t* __restrict__ Ql,
                          const uint16_t* __restrict__ Ch, const uint16_t* __restrict__ Cl,
                          const float* __restrict__ centroid_norms, int nq, int n_lists, int dp,
-                         uint32_t* __restrict__ A, uint2* __restrict__ S) {
+                         uint32_t* __restrict__ A, StripSummary* __restrict__ S) {
     __shared__ __attribute__((aligned(16))) uint16_t tile[4][128 * BPITCH];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1, half = lane >> 5, l32 = lane & 31;
@@ -350,7 +359,7 @@ coarse_rank_split_kernel(const uint16_t* __restrict__ Qh, const uint16_t* __rest
             }
         __syncthreads();
     }
-    rank_store<2>(acc, q0, l0, nq, n_lists, centroid_norms, A, S, reinterpret_cast<uint2*>(&tile[0][0]));
+    rank_store<2>(acc, q0, l0, nq, n_lists, centroid_norms, A, S, reinterpret_cast<StripSummary*>(&tile[0][0]));
 }
 
 // |a_computed - a_exact| <= this, for either ranking kernel (qn = |q|^2, cmax = max |c|^2): the split
@@ -381,7 +390,7 @@ inline size_t coarse_split_bytes(size_t nq_max, size_t n_lists, int d) {
 }
 
 int launch_coarse(const float* q, const float* centroids, const float* centroid_norms, int nq, int n_lists, int d,
-                  uint32_t* A, uint2* S, void* split_ws, hipStream_t st) {
+                  uint32_t* A, StripSummary* S, void* split_ws, hipStream_t st) {
     if (coarse_big_tiles(nq, n_lists)) {
         const int dp = coarse_padded_dim(d);
         const size_t q_bytes = align_up((size_t)nq * dp * 2), c_bytes = align_up((size_t)n_lists * dp * 2);
