@@ -56,6 +56,13 @@ constexpr uint32_t kPadKey = 0xFFFFFFFFu;      // R of a padding lane: sorts aft
 constexpr int SEL_THREADS = 256;
 constexpr int SEL_CAP = 1024;      // record capacity = IVFPQ_MAX_K: the selected elements always fit
 
+// what block_kth_key alone needs
+struct KthShared {
+    uint32_t hist[256];
+    uint32_t digit, need, count;
+    uint32_t n_rec;
+};
+
 struct SelectShared {
     uint32_t hist[256];
     uint32_t rec_key[SEL_CAP];
@@ -78,7 +85,8 @@ __device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
 // hist holds digit counts; finds the digit that contains the `need`-th smallest element
 // (1-based).  Result in s.digit (the digit), s.need (rank inside that digit), s.count (its count).
 // Called by all threads; contains barriers.
-__device__ __forceinline__ void find_digit(SelectShared& s, uint32_t need) {
+template <class Shared>
+__device__ __forceinline__ void find_digit(Shared& s, uint32_t need) {
     __syncthreads();
     if (threadIdx.x < kWave) {
         const int t = threadIdx.x;
@@ -148,8 +156,8 @@ __device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t digit, bool ac
 // The kk-th smallest (1-based, 1 <= kk <= n) of n keys, by four 8-bit digits from the top.
 // *rank_in_ties = how many elements equal to the result rank at or below kk (1..*n_ties),
 // *n_ties = number of elements equal to the result.  Called by every thread of the workgroup.
-template <class KeyFn>
-__device__ __forceinline__ uint32_t block_kth_key(SelectShared& s, uint32_t n, uint32_t kk, KeyFn key_of,
+template <class Shared, class KeyFn>
+__device__ __forceinline__ uint32_t block_kth_key(Shared& s, uint32_t n, uint32_t kk, KeyFn key_of,
                                   uint32_t* rank_in_ties, uint32_t* n_ties) {
     const int tid = threadIdx.x, nth = blockDim.x;
     uint32_t prefix = 0, need = kk, n_eq = 0;
@@ -1613,15 +1621,16 @@ constexpr uint32_t kAdmitAll = 0xFFFFFFFEu;   // every real R is below this, the
 __global__ void __launch_bounds__(SEL_THREADS)
 bound_kernel(float* __restrict__ R, uint32_t* __restrict__ Rpos, size_t stride, const uint4* __restrict__ pairs,
              int n_probes, int k, uint32_t* __restrict__ bounds, uint32_t* __restrict__ counts) {
-    __shared__ SelectShared s;
-    __shared__ uint32_t keys[CAND_CAP];
+    constexpr uint32_t KEYS = 4096;         // segments up to this length are selected from LDS
+    __shared__ KthShared s;
+    __shared__ uint32_t keys[KEYS];
     const int q = blockIdx.x;
     const int tid = threadIdx.x, nth = blockDim.x;
     const uint32_t seg0 = n_probes > 1 ? pairs[(size_t)q * n_probes + 1].w : 0u;
     const uint32_t len0 = pairs[(size_t)q * n_probes].y;       // real values in the segment (the rest is padding)
     uint32_t* row = reinterpret_cast<uint32_t*>(R + (size_t)q * stride);
     uint32_t* row_pos = Rpos + (size_t)q * stride;
-    const bool in_lds = seg0 <= (uint32_t)CAND_CAP;
+    const bool in_lds = seg0 <= KEYS;
     if (in_lds)
         for (uint32_t i = tid; i < seg0; i += nth) keys[i] = row[i];
     uint32_t bound = kAdmitAll;
