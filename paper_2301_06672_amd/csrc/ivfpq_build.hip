@@ -176,48 +176,104 @@ nearest_strips_kernel(const StripSummary* __restrict__ S, int strip_w, const flo
         }
     s_b1[sl][r] = b1; s_b2[sl][r] = b2; s_i1[sl][r] = i1;
     __syncthreads();
-    if (sl != 0 || row >= n_rows) return;
-    for (int o = 1; o < 4; ++o) {
-        const uint32_t c1 = s_b1[o][r], c2 = s_b2[o][r], ci = s_i1[o][r];
-        if (c1 < b1 || (c1 == b1 && ci < i1)) { b2 = b1 < c2 ? b1 : c2; b1 = c1; i1 = ci; }
-        else if (c1 < b2) b2 = c1;
-    }
-    const float* x = X + (size_t)row * d;
-    float qn = 0.f;
-    for (int t = 0; t < d; ++t) qn = __builtin_fmaf(x[t], x[t], qn);
-    const float delta = rank_error_bound(d, qn, __uint_as_float(*norm_max_bits));
-    float lim = ordered_key_value(b1 | 63u) + 2.f * delta;
-    lim += __builtin_fabsf(lim) * 2.3841858e-07f;
-    const uint32_t limit = (lim == lim) ? ordered_key(lim) : 0xFFFFFFFFu;
-    int first = (int)(i1 * (uint32_t)strip_w + (b1 & 63u));
-    if (first >= k) first = 0;                 // only if every key is the all-ones pattern
-    if ((b2 & ~63u) > limit) { labels[row] = first; return; }
-    double best = __longlong_as_double(0x7FF0000000000000ll);
-    int arg = 0x7FFFFFFF;
-    auto try_centre = [&](int c) {
-        const float* cc = C + (size_t)c * d;
-        double dist = 0.0;
-        for (int t = 0; t < d; ++t) { const double diff = (double)x[t] - (double)cc[t]; dist += diff * diff; }
-        if (dist < best) { best = dist; arg = c; }        // centres come in ascending order: ties stay with the lower
-    };
-    for (int i = 0; i < n_strips; ++i) {
-        const StripSummary v = S[(size_t)i * stride + row];
-        if ((v.x & ~63u) > limit) continue;
-        const int c0 = i * strip_w;
-        if ((v.y & ~63u) > limit) {
-            const int c = c0 + (int)(v.x & 63u);
-            if (c < k) try_centre(c);
-        } else if ((v.z & ~63u) > limit) {         // its best two, in ascending order of the centre index
-            const int ca = c0 + (int)(v.x & 63u), cb = c0 + (int)(v.y & 63u);
-            const int lo = ca < cb ? ca : cb, hi = ca < cb ? cb : ca;
-            if (lo < k) try_centre(lo);
-            if (hi < k) try_centre(hi);
+    // rows whose second key is within the error bound of the first wait here for the float64 comparison,
+    // which the whole workgroup makes row by row
+    __shared__ uint32_t s_slow[64], s_limit[64];
+    __shared__ int s_first[64];
+    __shared__ uint32_t s_n_slow, s_n_cand;
+    __shared__ int s_cand[1024];
+    __shared__ double s_best[256];
+    __shared__ int s_arg[256];
+    if (threadIdx.x == 0) s_n_slow = 0u;
+    __syncthreads();
+    if (sl == 0 && row < n_rows) {
+        for (int o = 1; o < 4; ++o) {
+            const uint32_t c1 = s_b1[o][r], c2 = s_b2[o][r], ci = s_i1[o][r];
+            if (c1 < b1 || (c1 == b1 && ci < i1)) { b2 = b1 < c2 ? b1 : c2; b1 = c1; i1 = ci; }
+            else if (c1 < b2) b2 = c1;
+        }
+        const float* x = X + (size_t)row * d;
+        float qn = 0.f;
+        for (int t = 0; t < d; ++t) qn = __builtin_fmaf(x[t], x[t], qn);
+        const float delta = rank_error_bound(d, qn, __uint_as_float(*norm_max_bits));
+        float lim = ordered_key_value(b1 | 63u) + 2.f * delta;
+        lim += __builtin_fabsf(lim) * 2.3841858e-07f;
+        const uint32_t limit = (lim == lim) ? ordered_key(lim) : 0xFFFFFFFFu;
+        int first = (int)(i1 * (uint32_t)strip_w + (b1 & 63u));
+        if (first >= k) first = 0;             // only if every key is the all-ones pattern
+        if ((b2 & ~63u) > limit) {
+            labels[row] = first;
         } else {
-            const int c1 = c0 + strip_w < k ? c0 + strip_w : k;
-            for (int c = c0; c < c1; ++c) try_centre(c);
+            const uint32_t slot = atomicAdd(&s_n_slow, 1u);
+            s_slow[slot] = (uint32_t)r; s_limit[slot] = limit; s_first[slot] = first;
         }
     }
-    labels[row] = arg < k ? arg : first;       // no finite distance (NaN inputs): stay in range
+    __syncthreads();
+    const uint32_t n_slow = s_n_slow;
+    const int tid = threadIdx.x;
+    for (uint32_t w = 0; w < n_slow; ++w) {
+        const int srow = blockIdx.x * 64 + (int)s_slow[w];
+        const uint32_t limit = s_limit[w];
+        const float* x = X + (size_t)srow * d;
+        if (tid == 0) s_n_cand = 0u;
+        __syncthreads();
+        // the centres that can be the nearest: per strip inside the bound its best one, its best two, or all
+        for (int i = tid; i < n_strips; i += 256) {
+            const StripSummary v = S[(size_t)i * stride + srow];
+            if ((v.x & ~63u) > limit) continue;
+            const int c0 = i * strip_w;
+            int take[2], n_take = 0;
+            bool all = false;
+            if ((v.y & ~63u) > limit) { take[n_take++] = c0 + (int)(v.x & 63u); }
+            else if ((v.z & ~63u) > limit) { take[n_take++] = c0 + (int)(v.x & 63u); take[n_take++] = c0 + (int)(v.y & 63u); }
+            else all = true;
+            if (all) {
+                const int c1 = c0 + strip_w < k ? c0 + strip_w : k;
+                const uint32_t slot = atomicAdd(&s_n_cand, (uint32_t)(c1 - c0));
+                for (int c = c0; c < c1; ++c)
+                    if (slot + (uint32_t)(c - c0) < 1024u) s_cand[slot + (uint32_t)(c - c0)] = c;
+            } else {
+                for (int u = 0; u < n_take; ++u)
+                    if (take[u] < k) {
+                        const uint32_t slot = atomicAdd(&s_n_cand, 1u);
+                        if (slot < 1024u) s_cand[slot] = take[u];
+                    }
+            }
+        }
+        __syncthreads();
+        const uint32_t n_cand = s_n_cand;
+        double best = __longlong_as_double(0x7FF0000000000000ll);
+        int arg = 0x7FFFFFFF;
+        auto try_centre = [&](int c) {
+            const float* cc = C + (size_t)c * d;
+            double dist = 0.0;
+            for (int t = 0; t < d; ++t) { const double diff = (double)x[t] - (double)cc[t]; dist += diff * diff; }
+            if (dist < best || (dist == best && c < arg)) { best = dist; arg = c; }
+        };
+        if (n_cand <= 1024u) {
+            for (uint32_t j = tid; j < n_cand; j += 256) try_centre(s_cand[j]);
+        } else {
+            // more than the list holds (a plateau of equal ranking values): every thread takes whole strips
+            for (int i = tid; i < n_strips; i += 256) {
+                const StripSummary v = S[(size_t)i * stride + srow];
+                if ((v.x & ~63u) > limit) continue;
+                const int c0 = i * strip_w, c1 = c0 + strip_w < k ? c0 + strip_w : k;
+                for (int c = c0; c < c1; ++c) try_centre(c);
+            }
+        }
+        s_best[tid] = best; s_arg[tid] = arg;
+        __syncthreads();
+        for (int off = 128; off > 0; off >>= 1) {
+            if (tid < off) {
+                const double ob = s_best[tid + off];
+                const int oa = s_arg[tid + off];
+                if (ob < s_best[tid] || (ob == s_best[tid] && oa < s_arg[tid])) { s_best[tid] = ob; s_arg[tid] = oa; }
+            }
+            __syncthreads();
+        }
+        if (tid == 0) labels[srow] = s_arg[0] < k ? s_arg[0] : s_first[w];      // no finite distance (NaN inputs): stay in range
+        __syncthreads();
+    }
 }
 
 __global__ void count_labels_kernel(const int32_t* __restrict__ labels, size_t n, uint32_t* __restrict__ counts) {
