@@ -13,17 +13,13 @@
  *    non-OK return on the calling thread.
  *  - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
  *    memory of the current device.  The caller owns every buffer it passes; the
- *    library never allocates or frees device memory (the entry points whose
- *    comment says so excepted: none at present).
+ *    library never allocates or frees device memory.
  *  - Row-major everywhere.  Distances are squared L2 (Sec. I-B).
  *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *    Search calls only enqueue work; they do not synchronise.
- *  - Four environment variables override launch heuristics, for tuning experiments only:
- *    IVFPQ_SCAN_THREADS (64 ... 1024: workgroup size of the scan kernel), IVFPQ_ORDER_BLOCK
- *    (consecutive (query, probe) pairs of the cluster-grouped order that stay on one XCD),
- *    IVFPQ_SCAN_TWO (0 / 1: never / wherever possible scan two pairs of one cluster per workgroup) and
- *    IVFPQ_EARLY_EXIT (0: the filtered scan adds up every sub-space of every vector, even when all 64
- *    partial sums of a group are already over the query's bound; results are the same either way).
+ *  - The library reads no environment variable; launch heuristics can be overridden per index with
+ *    ivfpq_set_tuning (for tuning experiments and tests only).
+ *  - No function throws: a C++ exception inside the library (host memory exhausted) comes back as a status.
  */
 #ifndef IVFPQ_H
 #define IVFPQ_H
@@ -169,6 +165,21 @@ int ivfpq_upload(ivfpq_index_t* index, void* d_buf, size_t bytes, void* hip_stre
 size_t ivfpq_search_workspace_bytes(const ivfpq_index_t* index, int64_t nq, int32_t n_probes,
                                     int32_t k, int32_t lut_dtype);
 
+/* Overrides one launch heuristic of searches on this index (tuning experiments, tests); value 0 restores
+ * the library's own choice.  No knob changes any result.  Takes effect at the next call. */
+typedef enum {
+    IVFPQ_TUNE_SCAN_THREADS = 0, /* workgroup size of the scan kernels: 64, 128, 256, 512 or 1024 */
+    IVFPQ_TUNE_ORDER_BLOCK = 1,  /* consecutive (query, probe) pairs of the cluster-grouped order that stay on one
+                                    XCD (>= 1; the scan that shares a workgroup between pairs needs an even value) */
+    IVFPQ_TUNE_SCAN_SHARE = 2,   /* 1: one (query, probe) pair per scan workgroup; 2: two pairs of one cluster per
+                                    workgroup wherever the kernel for it applies */
+    IVFPQ_TUNE_EARLY_EXIT = 3,   /* 1: on (the default: a 64-vector group stops adding once all its partial sums are
+                                    over the query's bound); -1: off, every lookup of Eq. (1) is made */
+    IVFPQ_TUNE_LDS_PAD = 4       /* extra bytes of LDS requested per scan workgroup (lowers occupancy without
+                                    changing the table: separates the two effects of a smaller table dtype) */
+} ivfpq_tuning_t;
+int ivfpq_set_tuning(ivfpq_index_t* index, int32_t knob, int32_t value);
+
 /* The workspace limit of searches on this index, in bytes (default 32 GiB; at least 1 MiB).  A query's
  * share of the scratch is sized for the worst case (every vector of its n_probes largest clusters kept),
  * so big indexes split a batch into tiles; fewer, larger tiles run faster (measured: 10,000 queries on
@@ -233,17 +244,26 @@ int ivfpq_refine(const float* d_data, int64_t n_data, int32_t d, const float* d_
 
 /* ---- measurement aid ---- */
 
-/* When enabled, search calls record HIP events around their stages on the stream they run on.
+/* When enabled, search calls record HIP events around their stages on the stream they run on (the events
+ * and their bookkeeping live in the handle: while enabled, search calls on one index must not overlap).
  * After the stream has been synchronised, ivfpq_stage_times_ms reports the last call's
- * milliseconds: ms[0] = probe selection (step 1: ranking GEMM + selection), ms[1] = table build +
- * code scan (steps 2-4: the scan kernel over the nearest probe, the bound kernel, the scan kernel
- * over the remaining probes), ms[2] = top-k (step 5), ms[3] = whole call; summed over query tiles. */
+ * milliseconds, summed over query tiles: ms[0] = probe selection (step 1: ranking GEMM + selection),
+ * ms[1] = table build + code scan (steps 2-4: the scan kernel over the nearest probe, the bound kernel,
+ * the grouping of the other pairs by cluster, the scan kernel over the remaining probes), ms[2] = top-k
+ * (step 5), ms[3] = whole call; and single launches inside those stages: ms[4] = the ranking GEMM of
+ * step 1, ms[5] = the scan kernel over the nearest probes, ms[6] = the scan kernel over the remaining
+ * probes (the dominant kernel), ms[7] = 0 (reserved). */
 int ivfpq_set_stage_timing(ivfpq_index_t* index, int32_t enabled);
-int ivfpq_stage_times_ms(ivfpq_index_t* index, float ms[4]);
+int ivfpq_stage_times_ms(ivfpq_index_t* index, float ms[8]);
+
+/* Writes into buf (host, buf_bytes > 0, always terminated) the name, workgroup size and LDS request of the
+ * kernel that scans the probes other than the nearest one (the dominant kernel of a search) for this index,
+ * table dtype and current tuning: what to look for in a profiler's kernel list. */
+int ivfpq_scan_kernel_info(const ivfpq_index_t* index, int32_t lut_dtype, char* buf, size_t buf_bytes);
 
 /* Measurement aid, not a step of the method: a plain streaming read of `bytes` bytes of device memory
  * (16-byte loads, grid-strided, n_out workgroups of 256 threads), the achievable HBM read rate that a
- * code scan (Section 2.2 step 4, Eq. 1) streaming every byte from HBM is priced against.  d_buf: device,
+ * code scan (Sec. I-C, search step 4, Eq. 1) streaming every byte from HBM is priced against.  d_buf: device,
  * 16-byte aligned, bytes a multiple of 16; d_out: device, n_out words (1..65536), word b = XOR of all
  * 32-bit words workgroup b read.  Asynchronous on hip_stream; allocates nothing. */
 int ivfpq_stream_read(const void* d_buf, size_t bytes, uint32_t* d_out, int32_t n_out, void* hip_stream);

@@ -22,6 +22,7 @@ LUT_BYTES = {LUT_FP32: 4, LUT_FP16: 2, LUT_FP8_E5M3: 1, LUT_FP8_E4M4: 1}
 ROUND_NEAREST, ROUND_TRUNCATE = 0, 1
 MAX_K = 1024
 MAX_PROBES = 1024
+TUNE_SCAN_THREADS, TUNE_ORDER_BLOCK, TUNE_SCAN_SHARE, TUNE_EARLY_EXIT, TUNE_LDS_PAD = 0, 1, 2, 3, 4
 
 OK, EINVAL, ENOSPACE, EHIP, EUNSUPPORTED, ESTATE = 0, -1, -2, -3, -4, -5
 
@@ -29,10 +30,10 @@ OK, EINVAL, ENOSPACE, EHIP, EUNSUPPORTED, ESTATE = 0, -1, -2, -3, -4, -5
 EXPORTS = (
     "ivfpq_build_host", "ivfpq_build_device", "ivfpq_build_device_workspace_bytes", "ivfpq_assign_device",
     "ivfpq_assign_device_workspace_bytes", "ivfpq_index_from_arrays", "ivfpq_index_info", "ivfpq_index_export", "ivfpq_free",
-    "ivfpq_set_e4m4_bias", "ivfpq_set_fp8_encoding", "ivfpq_set_workspace_limit",
+    "ivfpq_set_e4m4_bias", "ivfpq_set_fp8_encoding", "ivfpq_set_workspace_limit", "ivfpq_set_tuning",
     "ivfpq_device_bytes", "ivfpq_upload", "ivfpq_search_workspace_bytes", "ivfpq_search",
     "ivfpq_select_probes", "ivfpq_search_with_probes", "ivfpq_dump_lut", "ivfpq_scan_list", "ivfpq_refine",
-    "ivfpq_set_stage_timing", "ivfpq_stage_times_ms", "ivfpq_stream_read", "ivfpq_last_error",
+    "ivfpq_set_stage_timing", "ivfpq_stage_times_ms", "ivfpq_scan_kernel_info", "ivfpq_stream_read", "ivfpq_last_error",
 )
 
 
@@ -77,6 +78,7 @@ def _declare(L):
     L.ivfpq_set_e4m4_bias.argtypes = [vp, i32]
     L.ivfpq_set_workspace_limit.argtypes = [vp, sz]
     L.ivfpq_set_fp8_encoding.argtypes = [vp, i32, i32, i32, i32]
+    L.ivfpq_set_tuning.argtypes = [vp, i32, i32]
     L.ivfpq_free.restype = None
     L.ivfpq_device_bytes.argtypes = [vp]
     L.ivfpq_device_bytes.restype = sz
@@ -90,7 +92,8 @@ def _declare(L):
     L.ivfpq_refine.argtypes = [vp, i64, i32, vp, i64, vp, i32, i32, vp, vp, vp]
     L.ivfpq_scan_list.argtypes = [vp, vp, u32, i32, vp, vp]
     L.ivfpq_set_stage_timing.argtypes = [vp, i32]
-    L.ivfpq_stage_times_ms.argtypes = [vp, c.POINTER(c.c_float * 4)]
+    L.ivfpq_stage_times_ms.argtypes = [vp, c.POINTER(c.c_float * 8)]
+    L.ivfpq_scan_kernel_info.argtypes = [vp, i32, c.c_char_p, sz]
     L.ivfpq_stream_read.argtypes = [vp, sz, vp, i32, vp]
     L.ivfpq_last_error.restype = c.c_char_p
     for name in EXPORTS:
@@ -238,6 +241,9 @@ class Index:
         _check(lib().ivfpq_set_workspace_limit(self._h, int(nbytes)))
         self._ws = None
 
+    def ivfpq_set_tuning(self, knob: int, value: int):
+        _check(lib().ivfpq_set_tuning(self._h, int(knob), int(value)))
+
     def ivfpq_set_e4m4_bias(self, bias: int):
         _check(lib().ivfpq_set_e4m4_bias(self._h, int(bias)))
 
@@ -328,7 +334,13 @@ class Index:
     def ivfpq_set_stage_timing(self, enabled: bool):
         _check(lib().ivfpq_set_stage_timing(self._h, int(enabled)))
 
+    def ivfpq_scan_kernel_info(self, lut_dtype: int) -> str:
+        buf = ctypes.create_string_buffer(256)
+        _check(lib().ivfpq_scan_kernel_info(self._h, int(lut_dtype), buf, 256))
+        return buf.value.decode()
+
     def ivfpq_stage_times_ms(self):
-        ms = (ctypes.c_float * 4)()
+        ms = (ctypes.c_float * 8)()
         _check(lib().ivfpq_stage_times_ms(self._h, ctypes.byref(ms)))
-        return {"probe_select": ms[0], "scan": ms[1], "topk": ms[2], "total": ms[3]}
+        return {"probe_select": ms[0], "scan": ms[1], "topk": ms[2], "total": ms[3],
+                "rank_gemm": ms[4], "scan_nearest_kernel": ms[5], "scan_filtered_kernel": ms[6]}

@@ -22,6 +22,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <memory>
 #include <vector>
 
 #include "ivfpq_internal.hpp"
@@ -666,7 +667,10 @@ size_t ivfpq_assign_device_workspace_bytes(int64_t n_rows, int32_t d, int32_t n_
     return at;
 }
 
-int ivfpq_build_device(const float* d_data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,
+}  // extern "C"
+
+namespace {
+int build_device_impl(const float* d_data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,
                        int32_t kmeans_iters, const int64_t* coarse_train_rows, int64_t n_coarse_train,
                        const int64_t* coarse_init_rows, const int64_t* pq_train_rows, int64_t n_pq_train,
                        const int64_t* pq_init_rows, uint64_t seed, void* d_workspace, size_t workspace_bytes,
@@ -772,7 +776,8 @@ int ivfpq_build_device(const float* d_data, int64_t n, int32_t d, int32_t n_list
     if (int s = group_by_label(P, ws, labels_all, (size_t)n, n_lists, st)) return s;
     if (int s = launch_pq_codes(P, d_data, order, labels_all, C, codebooks, (size_t)n, nullptr, codes32, st)) return s;
 
-    auto* idx = new ivfpq_index;
+    std::unique_ptr<ivfpq_index> owner(new ivfpq_index);
+    ivfpq_index* idx = owner.get();
     idx->n = n; idx->d = d; idx->n_lists = n_lists; idx->pq_dim = pq_dim; idx->pq_bits = pq_bits;
     idx->centroids.resize((size_t)n_lists * d);
     idx->codebooks.resize((size_t)pq_dim * ksub * m);
@@ -789,11 +794,26 @@ int ivfpq_build_device(const float* d_data, int64_t n, int32_t d, int32_t n_list
         HIP_TRY(hipStreamSynchronize(st));
         return IVFPQ_OK;
     };
-    if (int s = copy_out()) { delete idx; return s; }
+    if (int s = copy_out()) return s;
     for (int64_t i = 0; i < n; ++i) idx->ids[(size_t)i] = (int64_t)order_h[(size_t)i];
     finish_import(idx);
-    *out = idx;
+    *out = owner.release();
     return IVFPQ_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int ivfpq_build_device(const float* d_data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,
+                       int32_t kmeans_iters, const int64_t* coarse_train_rows, int64_t n_coarse_train,
+                       const int64_t* coarse_init_rows, const int64_t* pq_train_rows, int64_t n_pq_train,
+                       const int64_t* pq_init_rows, uint64_t seed, void* d_workspace, size_t workspace_bytes,
+                       void* hip_stream, ivfpq_index_t** out) {
+    return guarded("ivfpq_build_device", [&] {
+        return build_device_impl(d_data, n, d, n_lists, pq_dim, pq_bits, kmeans_iters, coarse_train_rows, n_coarse_train,
+                                 coarse_init_rows, pq_train_rows, n_pq_train, pq_init_rows, seed, d_workspace,
+                                 workspace_bytes, hip_stream, out);
+    });
 }
 
 }  // extern "C"

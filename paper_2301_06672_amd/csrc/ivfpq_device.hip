@@ -29,7 +29,6 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
-#include <cstdlib>
 #include <cstring>
 #include <thread>
 #include <type_traits>
@@ -1786,7 +1785,10 @@ struct Plan {
 
 // given_probes: the caller chooses the clusters and may name one several times, so the bound on a
 // query's candidates is n_probes times the largest cluster rather than the n_probes largest ones
-int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_probes, Plan* plan) {
+// limit: the bytes the plan should stay within (0: the index's workspace limit); a tile holds at least one
+// query, so the caller compares plan->total with what it has.
+int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_probes, Plan* plan, size_t limit = 0) {
+    if (limit == 0) limit = idx->workspace_limit;
     const bool need_D = !given_probes;
     int64_t stride = given_probes
         ? (int64_t)n_probes * (idx->sorted_padded_sizes.empty() ? 0 : idx->sorted_padded_sizes[0])
@@ -1798,7 +1800,11 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     if (stride < 64) stride = 64;
     const size_t strips = ((size_t)idx->n_lists + 31) / 32;      // strip summaries of the ranking keys, narrowest strips
     size_t per_query = (size_t)stride * 8 + (need_D ? ((size_t)idx->n_lists + 4 * strips + coarse_padded_dim(idx->d)) * 4 : 0);
-    int64_t tile = (int64_t)(idx->workspace_limit / per_query);
+    // what does not grow with the tile: three per-cluster counter arrays, the centroids' bf16 halves, alignment slack
+    const size_t fixed = 3 * align_up((size_t)idx->n_lists * 4)
+                         + (need_D ? coarse_split_bytes(0, (size_t)idx->n_lists, idx->d) : 0) + 24 * kAlign;
+    per_query += (size_t)n_probes * 28 + 16;      // probe lists, distances, offsets, descriptors, order, bound, counter
+    int64_t tile = limit > fixed ? (int64_t)((limit - fixed) / per_query) : 1;
     tile = std::max<int64_t>(1, std::min<int64_t>(tile, std::max<int64_t>(nq, 1)));
     plan->tile = tile;
     plan->stride = (size_t)stride;
@@ -1843,7 +1849,8 @@ size_t scan_lds_bytes(const ivfpq_index* idx, int lut_dtype) {
 }
 // plus the per-wave survivor staging of the filtered scan
 size_t scan_lds_bytes_staged(const ivfpq_index* idx, int lut_dtype, int threads) {
-    return scan_lds_bytes(idx, lut_dtype) + (size_t)(threads / 64) * (kStageCap * 8 + kAliveCap * 2);
+    return scan_lds_bytes(idx, lut_dtype) + (size_t)(threads / 64) * (kStageCap * 8 + kAliveCap * 2)
+           + (size_t)idx->tuning.lds_pad;      // the pad sits behind everything the kernel addresses
 }
 
 int check_device(const ivfpq_index* idx) {
@@ -1856,10 +1863,7 @@ int check_device(const ivfpq_index* idx) {
 }
 
 int scan_threads(const ivfpq_index* idx, int lut_dtype) {
-    if (const char* env = std::getenv("IVFPQ_SCAN_THREADS")) {
-        int v = std::atoi(env);
-        if (v == 64 || v == 128 || v == 256 || v == 512 || v == 1024) return v;
-    }
+    if (idx->tuning.scan_threads) return idx->tuning.scan_threads;       // validated by ivfpq_set_tuning
     // measured on MI355X: small tables want many 4-wave workgroups per CU; large tables want the
     // largest workgroup of which two still fit the CU's LDS (table + residual + survivor staging);
     // long lists (24 or more 64-vector groups on average) want 2-wave workgroups: the table build of
@@ -1922,13 +1926,12 @@ int launch_scan_lut(const ScanArgs& a, int bits, int cw, int nch, dim3 grid, int
 // enough workgroups per compute unit.  Measured on MI355X (scan stage, 10,000 queries): 6.5 -> 5.7 ms at
 // 10^8 vectors in 50,000 lists (32 sub-spaces: 21 KB of LDS per workgroup), 1.29 -> 1.23 ms at 10^7
 // vectors (48 sub-spaces, 33 KB), but 2.06 -> 2.30 ms with 64 sub-spaces (41 KB: three workgroups per
-// compute unit), so the limit is 36 KB.  IVFPQ_SCAN_TWO=0 switches it off, =1 on wherever it can run.
+// compute unit), so the limit is 36 KB.  ivfpq_set_tuning(IVFPQ_TUNE_SCAN_SHARE) forces it off (1) or on wherever it can run (2).
 size_t scan_two_lds_bytes(const ivfpq_index* idx, int threads) {
     return (size_t)idx->pq_dim * 512 + (((size_t)2 * idx->d * 4 + 15) & ~(size_t)15) + (size_t)(threads / 64) * 2 * kStageCap * 8;
 }
 bool scan_two_applies(const ivfpq_index* idx, int lut_dtype, const Fp8Mode& fp8, uint32_t order_block) {
-    int forced = -1;
-    if (const char* env = std::getenv("IVFPQ_SCAN_TWO")) forced = std::atoi(env) != 0;
+    const int forced = idx->tuning.scan_share == 0 ? -1 : (idx->tuning.scan_share >= 2 ? 1 : 0);
     if (forced == 0) return false;
     if (lut_dtype != IVFPQ_LUT_FP8_E5M3 && lut_dtype != IVFPQ_LUT_FP8_E4M4) return false;
     if (fp8.per_table || idx->pq_bits != 8 || chunk_width(idx) != 16) return false;
@@ -1940,7 +1943,8 @@ bool scan_two_applies(const ivfpq_index* idx, int lut_dtype, const Fp8Mode& fp8,
 }
 int launch_scan_two(const ivfpq_index* idx, const ScanArgs& a, int lut_dtype, hipStream_t st) {
     const int threads = scan_threads(idx, lut_dtype);
-    const size_t lds = scan_two_lds_bytes(idx, threads);
+    const size_t lds = scan_two_lds_bytes(idx, threads) + (size_t)idx->tuning.lds_pad;
+    if (lds > kLdsBytes) return fail(IVFPQ_EUNSUPPORTED, "tables + staging + pad need %zu bytes of LDS (limit %zu)", lds, kLdsBytes);
     const uint32_t n_slots = (a.n_pairs + 1u) / 2u, per = 8u * (a.order_block / 2u);
     const dim3 grid((n_slots + per - 1) / per * per);
     auto go = [&](auto kernel) -> int {
@@ -2006,13 +2010,12 @@ ScanArgs base_scan_args(const ivfpq_index* idx, int lut_dtype) {
     a.n_lists = idx->n_lists;
     a.fp8 = fp8_mode(idx, lut_dtype);
     a.single_list = -1;
-    a.early_exit = 1;
-    if (const char* env = std::getenv("IVFPQ_EARLY_EXIT")) a.early_exit = std::atoi(env) != 0;
+    a.early_exit = idx->tuning.early_exit >= 0;
     return a;
 }
 
 // ---- stage timing ----
-int timing_mark(ivfpq_index* idx, hipStream_t st, void** out) {
+int timing_mark(const ivfpq_index* idx, hipStream_t st, void** out) {
     if (idx->events_used == idx->event_pool.size()) {
         hipEvent_t e;
         HIP_TRY(hipEventCreate(&e));
@@ -2025,8 +2028,8 @@ int timing_mark(ivfpq_index* idx, hipStream_t st, void** out) {
 }
 
 struct StageTimer {
-    ivfpq_index* idx; hipStream_t st; int stage; void* a = nullptr; bool on;
-    StageTimer(ivfpq_index* i, hipStream_t s, int stage_) : idx(i), st(s), stage(stage_), on(i->timing) {}
+    const ivfpq_index* idx; hipStream_t st; int stage; void* a = nullptr; bool on;
+    StageTimer(const ivfpq_index* i, hipStream_t s, int stage_) : idx(i), st(s), stage(stage_), on(i->timing) {}
     int begin() { return on ? timing_mark(idx, st, &a) : IVFPQ_OK; }
     int end() {
         if (!on) return IVFPQ_OK;
@@ -2037,7 +2040,7 @@ struct StageTimer {
     }
 };
 
-int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint32_t* d_probes_in,
+int search_impl(const ivfpq_index* idx, const float* d_queries, int64_t nq, const uint32_t* d_probes_in,
                 int32_t n_probes, int32_t k, int32_t lut_dtype, int64_t* d_ids, float* d_dists,
                 void* d_ws, size_t ws_bytes, void* hip_stream) {
     if (int s = check_search_args(idx, d_queries, nq, n_probes, k, lut_dtype, true)) return s;
@@ -2075,7 +2078,10 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         if (int s = t0.begin()) return s;
         if (!d_probes_in) {
             StripSummary* strips = coarse_use_strips(tq, idx->n_lists, n_probes) ? w_S : nullptr;
+            StageTimer t4(idx, st, 4);
+            if (int s = t4.begin()) return s;
             if (int s = launch_coarse(qt, idx->dev.centroids, idx->dev.centroid_norms, tq, idx->n_lists, idx->d, (uint32_t*)w_D, strips, ws + plan.split, st)) return s;
+            if (int s = t4.end()) return s;
             hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, (const StripSummary*)strips,
                                coarse_strip_width(tq, idx->n_lists), qt,
                                idx->dev.centroids, idx->centroid_norm_max, idx->d, idx->n_lists,
@@ -2096,7 +2102,11 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
         a.queries = qt; a.pairs = w_pairs; a.R = w_R; a.stride = plan.stride;
         a.n_probes = n_probes; a.bounds = w_bounds; a.counts = w_counts; a.Rpos = w_Rpos;
         a.mode = 1;
+        StageTimer t5(idx, st, 5);
+        if (int s = t5.begin()) return s;
         if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)tq), st)) return s;
+        if (int s = t5.end()) return s;
+        StageTimer t6(idx, st, 6);
         if (n_probes > 1) {
             hipLaunchKernelGGL(bound_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_R, w_Rpos, plan.stride, w_pairs, n_probes, k,
                                w_bounds, w_counts);
@@ -2129,9 +2139,9 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
                 HIP_TRY(hipGetLastError());
                 a.order = w_order;
                 a.n_pairs = (uint32_t)n_pairs;
-                uint32_t blk = kOrderBlock;
-                if (const char* env = std::getenv("IVFPQ_ORDER_BLOCK")) blk = (uint32_t)std::max(1, std::atoi(env));
+                const uint32_t blk = idx->tuning.order_block > 0 ? (uint32_t)idx->tuning.order_block : kOrderBlock;
                 a.order_block = blk;
+                if (int s = t6.begin()) return s;
                 if (scan_two_applies(idx, lut_dtype, a.fp8, blk)) {
                     a.n_chunks = idx->code_bytes() / 16;
                     if (int s = launch_scan_two(idx, a, lut_dtype, st)) return s;
@@ -2140,8 +2150,10 @@ int search_impl(ivfpq_index* idx, const float* d_queries, int64_t nq, const uint
                     if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)grid), st)) return s;
                 }
             } else {
+                if (int s = t6.begin()) return s;
                 if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)n_pairs), st)) return s;
             }
+            if (int s = t6.end()) return s;
         }
         if (int s = t1.end()) return s;
         // step 5
@@ -2173,7 +2185,10 @@ size_t ivfpq_device_bytes(const ivfpq_index_t* index) {
     return image_layout(index).total;
 }
 
-int ivfpq_upload(ivfpq_index_t* idx, void* d_buf, size_t bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+int upload_impl(ivfpq_index_t* idx, void* d_buf, size_t bytes, void* hip_stream) {
     if (!idx || !d_buf) return fail(IVFPQ_EINVAL, "ivfpq_upload: null pointer");
     const ImageLayout L = image_layout(idx);
     if (bytes < L.total) return fail(IVFPQ_ENOSPACE, "device buffer of %zu bytes given, %zu needed", bytes, L.total);
@@ -2260,6 +2275,13 @@ int ivfpq_upload(ivfpq_index_t* idx, void* d_buf, size_t bytes, void* hip_stream
     idx->dev.ids = (const int64_t*)(base + L.ids);
     return IVFPQ_OK;
 }
+}  // namespace
+
+extern "C" {
+
+int ivfpq_upload(ivfpq_index_t* idx, void* d_buf, size_t bytes, void* hip_stream) {
+    return guarded("ivfpq_upload", [&] { return upload_impl(idx, d_buf, bytes, hip_stream); });
+}
 
 size_t ivfpq_search_workspace_bytes(const ivfpq_index_t* index, int64_t nq, int32_t n_probes, int32_t k,
                                     int32_t lut_dtype) {
@@ -2274,8 +2296,10 @@ size_t ivfpq_search_workspace_bytes(const ivfpq_index_t* index, int64_t nq, int3
 int ivfpq_search(const ivfpq_index_t* index, const float* d_queries, int64_t nq, int32_t n_probes, int32_t k,
                  int32_t lut_dtype, int64_t* d_ids, float* d_dists, void* d_workspace, size_t workspace_bytes,
                  void* hip_stream) {
-    return search_impl(const_cast<ivfpq_index_t*>(index), d_queries, nq, nullptr, n_probes, k, lut_dtype, d_ids,
-                       d_dists, d_workspace, workspace_bytes, hip_stream);
+    return guarded("ivfpq_search", [&] {
+        return search_impl(index, d_queries, nq, nullptr, n_probes, k, lut_dtype, d_ids, d_dists, d_workspace,
+                           workspace_bytes, hip_stream);
+    });
 }
 
 int ivfpq_search_with_probes(const ivfpq_index_t* index, const float* d_queries, int64_t nq,
@@ -2283,8 +2307,10 @@ int ivfpq_search_with_probes(const ivfpq_index_t* index, const float* d_queries,
                              int64_t* d_ids, float* d_dists, void* d_workspace, size_t workspace_bytes,
                              void* hip_stream) {
     if (nq > 0 && !d_probes) return fail(IVFPQ_EINVAL, "ivfpq_search_with_probes: null probes");
-    return search_impl(const_cast<ivfpq_index_t*>(index), d_queries, nq, d_probes, n_probes, k, lut_dtype, d_ids,
-                       d_dists, d_workspace, workspace_bytes, hip_stream);
+    return guarded("ivfpq_search_with_probes", [&] {
+        return search_impl(index, d_queries, nq, d_probes, n_probes, k, lut_dtype, d_ids, d_dists, d_workspace,
+                           workspace_bytes, hip_stream);
+    });
 }
 
 int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_t nq, int32_t n_probes,
@@ -2381,6 +2407,21 @@ int ivfpq_stream_read(const void* d_buf, size_t bytes, uint32_t* d_out, int32_t 
     return IVFPQ_OK;
 }
 
+int ivfpq_scan_kernel_info(const ivfpq_index_t* idx, int32_t lut_dtype, char* buf, size_t buf_bytes) {
+    if (!idx || !buf || buf_bytes == 0) return fail(IVFPQ_EINVAL, "ivfpq_scan_kernel_info: null pointer");
+    if (lut_dtype < 0 || lut_dtype > 3) return fail(IVFPQ_EINVAL, "unknown lut_dtype %d", lut_dtype);
+    static const char* const names[4] = {"fp32", "fp16", "e5m3", "e4m4"};
+    const int threads = scan_threads(idx, lut_dtype), cw = chunk_width(idx), nch = idx->code_bytes() / cw;
+    const uint32_t blk = idx->tuning.order_block > 0 ? (uint32_t)idx->tuning.order_block : kOrderBlock;
+    if (scan_two_applies(idx, lut_dtype, fp8_mode(idx, lut_dtype), blk))
+        snprintf(buf, buf_bytes, "scan_two_kernel<%s, %d chunks> %d threads, %zu bytes of LDS", names[lut_dtype], nch, threads,
+                 scan_two_lds_bytes(idx, threads) + (size_t)idx->tuning.lds_pad);
+    else
+        snprintf(buf, buf_bytes, "scan_kernel<%s, %d-bit codes, %d-byte chunks x %d> %d threads, %zu bytes of LDS", names[lut_dtype],
+                 idx->pq_bits, cw, cw == 16 ? nch : 0, threads, scan_lds_bytes_staged(idx, lut_dtype, threads));
+    return IVFPQ_OK;
+}
+
 int ivfpq_set_stage_timing(ivfpq_index_t* index, int32_t enabled) {
     if (!index) return fail(IVFPQ_EINVAL, "null index");
     index->timing = enabled != 0;
@@ -2388,10 +2429,10 @@ int ivfpq_set_stage_timing(ivfpq_index_t* index, int32_t enabled) {
     return IVFPQ_OK;
 }
 
-int ivfpq_stage_times_ms(ivfpq_index_t* index, float ms[4]) {
+int ivfpq_stage_times_ms(ivfpq_index_t* index, float ms[8]) {
     if (!index || !ms) return fail(IVFPQ_EINVAL, "null pointer");
     if (!index->timing || !index->stage_valid) return fail(IVFPQ_ESTATE, "no timed search call recorded");
-    for (int i = 0; i < 4; ++i) ms[i] = 0.f;
+    for (int i = 0; i < 8; ++i) ms[i] = 0.f;
     for (const auto& sp : index->spans) {
         float t = 0.f;
         HIP_TRY(hipEventElapsedTime(&t, (hipEvent_t)sp.a, (hipEvent_t)sp.b));

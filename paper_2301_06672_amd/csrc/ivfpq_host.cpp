@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstring>
 #include <limits>
+#include <memory>
 #include <numeric>
 #include <unordered_set>
 
@@ -192,15 +193,16 @@ extern "C" {
 
 const char* ivfpq_last_error(void) { return g_error.c_str(); }
 
-int ivfpq_build_host(const float* data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim,
-                     int32_t pq_bits, int32_t kmeans_iters, uint64_t seed, ivfpq_index_t** out) {
+static int build_host_impl(const float* data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim,
+                           int32_t pq_bits, int32_t kmeans_iters, uint64_t seed, ivfpq_index_t** out) {
     if (!data || !out) return fail(IVFPQ_EINVAL, "ivfpq_build_host: null pointer");
     *out = nullptr;
     if (int st = check_shape(n, d, n_lists, pq_dim, pq_bits)) return st;
     if (n < 1 || n_lists > n) return fail(IVFPQ_EINVAL, "need 1 <= n_lists <= n (n=%lld, n_lists=%d)", (long long)n, n_lists);
     if (kmeans_iters < 0) return fail(IVFPQ_EINVAL, "kmeans_iters=%d", kmeans_iters);
 
-    auto* idx = new ivfpq_index;
+    std::unique_ptr<ivfpq_index> owner(new ivfpq_index);
+    ivfpq_index* idx = owner.get();
     idx->n = n; idx->d = d; idx->n_lists = n_lists; idx->pq_dim = pq_dim; idx->pq_bits = pq_bits;
     const int m = d / pq_dim, ksub = 1 << pq_bits, cb = idx->code_bytes();
     SplitMix64 rng(seed ^ 0x2301066720230117ull);
@@ -278,11 +280,16 @@ int ivfpq_build_host(const float* data, int64_t n, int32_t d, int32_t n_lists, i
         }
     }
     finish_import(idx);
-    *out = idx;
+    *out = owner.release();
     return IVFPQ_OK;
 }
 
-int ivfpq_index_from_arrays(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,
+int ivfpq_build_host(const float* data, int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim,
+                     int32_t pq_bits, int32_t kmeans_iters, uint64_t seed, ivfpq_index_t** out) {
+    return guarded("ivfpq_build_host", [&] { return build_host_impl(data, n, d, n_lists, pq_dim, pq_bits, kmeans_iters, seed, out); });
+}
+
+static int from_arrays_impl(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,
                             const float* centroids, const float* codebooks, const int64_t* list_offsets,
                             const uint8_t* codes, const int64_t* ids, ivfpq_index_t** out) {
     if (!out) return fail(IVFPQ_EINVAL, "ivfpq_index_from_arrays: null out pointer");
@@ -298,7 +305,8 @@ int ivfpq_index_from_arrays(int64_t n, int32_t d, int32_t n_lists, int32_t pq_di
         if (len < 0) return fail(IVFPQ_EINVAL, "list_offsets decreases at list %d", l);
         if (len > (int64_t)1 << 30) return fail(IVFPQ_EUNSUPPORTED, "list %d has %lld vectors (limit 2^30)", l, (long long)len);
     }
-    auto* idx = new ivfpq_index;
+    std::unique_ptr<ivfpq_index> owner(new ivfpq_index);
+    ivfpq_index* idx = owner.get();
     idx->n = n; idx->d = d; idx->n_lists = n_lists; idx->pq_dim = pq_dim; idx->pq_bits = pq_bits;
     const size_t m = (size_t)d / pq_dim, ksub = (size_t)1 << pq_bits, cb = (size_t)idx->code_bytes();
     idx->centroids.assign(centroids, centroids + (size_t)n_lists * d);
@@ -309,8 +317,16 @@ int ivfpq_index_from_arrays(int64_t n, int32_t d, int32_t n_lists, int32_t pq_di
         idx->ids.assign(ids, ids + n);
     }
     finish_import(idx);
-    *out = idx;
+    *out = owner.release();
     return IVFPQ_OK;
+}
+
+int ivfpq_index_from_arrays(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits,
+                            const float* centroids, const float* codebooks, const int64_t* list_offsets,
+                            const uint8_t* codes, const int64_t* ids, ivfpq_index_t** out) {
+    return guarded("ivfpq_index_from_arrays", [&] {
+        return from_arrays_impl(n, d, n_lists, pq_dim, pq_bits, centroids, codebooks, list_offsets, codes, ids, out);
+    });
 }
 
 int ivfpq_index_info(const ivfpq_index_t* index, int64_t* n, int32_t* d, int32_t* n_lists,
@@ -356,6 +372,35 @@ int ivfpq_set_workspace_limit(ivfpq_index_t* index, size_t bytes) {
     if (bytes < ((size_t)1 << 20)) return fail(IVFPQ_EINVAL, "workspace limit of %zu bytes is below 1 MiB", bytes);
     index->workspace_limit = bytes;
     return IVFPQ_OK;
+}
+
+int ivfpq_set_tuning(ivfpq_index_t* index, int32_t knob, int32_t value) {
+    if (!index) return fail(IVFPQ_EINVAL, "ivfpq_set_tuning: null index");
+    switch (knob) {
+        case IVFPQ_TUNE_SCAN_THREADS:
+            if (value != 0 && value != 64 && value != 128 && value != 256 && value != 512 && value != 1024)
+                return fail(IVFPQ_EINVAL, "scan threads %d (0, 64, 128, 256, 512 or 1024)", value);
+            index->tuning.scan_threads = value;
+            return IVFPQ_OK;
+        case IVFPQ_TUNE_ORDER_BLOCK:
+            if (value < 0 || value > (1 << 20)) return fail(IVFPQ_EINVAL, "order block %d outside [0, 2^20]", value);
+            index->tuning.order_block = value;
+            return IVFPQ_OK;
+        case IVFPQ_TUNE_SCAN_SHARE:
+            if (value < 0 || value > 2) return fail(IVFPQ_EINVAL, "scan share %d (0, 1 or 2)", value);
+            index->tuning.scan_share = value;
+            return IVFPQ_OK;
+        case IVFPQ_TUNE_EARLY_EXIT:
+            if (value < -1 || value > 1) return fail(IVFPQ_EINVAL, "early exit %d (-1, 0 or 1)", value);
+            index->tuning.early_exit = value;
+            return IVFPQ_OK;
+        case IVFPQ_TUNE_LDS_PAD:
+            if (value < 0 || value > 160 * 1024 || (value & 15)) return fail(IVFPQ_EINVAL, "LDS pad %d (a multiple of 16 in [0, 163840])", value);
+            index->tuning.lds_pad = value;
+            return IVFPQ_OK;
+        default:
+            return fail(IVFPQ_EINVAL, "unknown tuning knob %d", knob);
+    }
 }
 
 int ivfpq_set_e4m4_bias(ivfpq_index_t* index, int32_t bias) {

@@ -4,6 +4,8 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <exception>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -16,6 +18,15 @@ struct Fp8Options {
     int32_t bias;        // exponent bias of the format
     int32_t truncate;    // 0: round to nearest, ties up; 1: truncate
     int32_t per_table;   // 1: the bias is chosen per (query, cluster) table from its largest entry
+};
+
+// Launch heuristics a caller may override per index (ivfpq_set_tuning); 0 = the library's own choice.
+struct Tuning {
+    int32_t scan_threads = 0;   // workgroup size of the scan kernels (64 ... 1024)
+    int32_t order_block = 0;    // consecutive pairs of the cluster-grouped order that stay on one XCD
+    int32_t scan_share = 0;     // 0: heuristic; 1: one (query, probe) pair per workgroup; 2: two pairs of a cluster wherever possible
+    int32_t early_exit = 0;     // 0: on (default); 1: on; -1: off (every lookup of Eq. (1) is made)
+    int32_t lds_pad = 0;        // extra bytes of LDS requested per scan workgroup (occupancy experiments)
 };
 
 // Device image of an index.  All pointers point into the single buffer the caller handed to
@@ -53,13 +64,16 @@ struct ivfpq_index {
     float centroid_norm_max = 0.f;      // largest squared centroid norm (set by ivfpq_upload)
     size_t workspace_limit = (size_t)32 << 30;   // search scratch (R, positions, ranking values) per query tile
 
-    // stage timing (hipEvent_t kept as void* so this header stays free of HIP types)
+    ivfpq::Tuning tuning;               // ivfpq_set_tuning
+
+    // stage timing (hipEvent_t kept as void* so this header stays free of HIP types).  Search calls take the
+    // handle as const and record into these: with timing enabled, calls on one index must not overlap.
     bool timing = false;
-    bool stage_valid = false;
+    mutable bool stage_valid = false;
     struct Span { void* a; void* b; int stage; };
-    std::vector<void*> event_pool;
-    std::vector<Span> spans;
-    size_t events_used = 0;
+    mutable std::vector<void*> event_pool;
+    mutable std::vector<Span> spans;
+    mutable size_t events_used = 0;
 
     int32_t ksub() const { return 1 << pq_bits; }
     int32_t m() const { return d / pq_dim; }
@@ -77,6 +91,20 @@ namespace ivfpq {
 
 void set_error(const char* fmt, ...);
 int fail(int status, const char* fmt, ...);
+
+// Runs `body` (-> int status) and turns a C++ exception into a status: nothing throws across the C ABI.
+template <class Body>
+int guarded(const char* what, Body&& body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return fail(IVFPQ_ENOSPACE, "%s: out of host memory", what);
+    } catch (const std::exception& e) {
+        return fail(IVFPQ_EINVAL, "%s: %s", what, e.what());
+    } catch (...) {
+        return fail(IVFPQ_EINVAL, "%s: unknown exception", what);
+    }
+}
 
 // validates shape parameters common to build and import; returns IVFPQ_OK or sets the error
 int check_shape(int64_t n, int32_t d, int32_t n_lists, int32_t pq_dim, int32_t pq_bits);

@@ -19,8 +19,19 @@ def _step(msg):
     print(f"[full-size] {msg}", flush=True)
 
 
+_DATA = {}      # the last generated data set, kept for the next test on the same rows (51 GB at 10^8 vectors)
+
+
+def _dataset(w):
+    key = (w.kind, w.n, w.d, w.salt)
+    if key not in _DATA:
+        _DATA.clear()
+        _DATA[key] = si.dataset(w)
+    return _DATA[key]
+
+
 def _build(P, w, builder):
-    data = si.dataset(w)
+    data = _dataset(w)
     if builder == "host":
         idx = P.Index.ivfpq_build_host(data, w.n_lists, w.pq_dim, w.pq_bits, 4, seed=1)
     else:
@@ -159,3 +170,9 @@ def test_intgrid_100m_p8_full_batch(P):
     # the size of the paper's experiments: 10^8 vectors, 50,000 clusters, 64 probes, k = 100 (about 90 s:
     # 51 GB of synthetic data, the index built on the GPU, a sampled comparison with the oracle)
     _check_workload(P, "intgrid_100m_p8", "device", [64], n_sample=40, min_recall=0.4)
+
+
+def test_intgrid_100m_p4_full_batch(P):
+    # the same 10^8 vectors with 64 sub-spaces of 4-bit codes (16-entry table rows, two codes per byte)
+    _check_workload(P, "intgrid_100m_p4", "device", [64], n_sample=40, min_recall=0.35)
+    _DATA.clear()

@@ -523,6 +523,10 @@ def test_stage_timing_reports(P, tiny):
     gidx.ivfpq_set_stage_timing(False)
     assert ms["total"] > 0 and ms["scan"] > 0
     assert ms["probe_select"] + ms["scan"] + ms["topk"] <= ms["total"] * 1.05 + 0.05
+    # single launches inside the stages
+    assert 0 < ms["rank_gemm"] <= ms["probe_select"] * 1.05 + 0.05
+    assert ms["scan_nearest_kernel"] > 0 and ms["scan_filtered_kernel"] > 0
+    assert ms["scan_nearest_kernel"] + ms["scan_filtered_kernel"] <= ms["scan"] * 1.05 + 0.05
 
 
 def test_library_builder_index_searches_like_oracle_builder(P, tiny):
@@ -607,15 +611,15 @@ def test_stream_read_folds_every_word_once(P, n_words, n_wg):
     (48, 48, 200, 40, 10, "e5m3"),     # m = 1, three 16-byte chunks, many seams between clusters
     (128, 64, 3, 3, 1000, "e5m3"),     # four chunks; two pairs per query: odd and even runs
 ])
-def test_search_two_pairs_per_workgroup(P, monkeypatch, d, pq_dim, n_lists, n_probes, k, dtype_name):
+def test_search_two_pairs_per_workgroup(P, d, pq_dim, n_lists, n_probes, k, dtype_name):
     # the kernel that shares a cluster's codes and codebooks between two queries is forced on; results
     # must be those of the oracle, and identical to the one-pair kernel's
     dtype = {"e5m3": oracle.LUT_E5M3, "e4m4": oracle.LUT_E4M4}[dtype_name]
     oidx, gidx = random_pair(P, 9000, d, n_lists, pq_dim, 8, salt=900 + d, empty_lists=(1,) if n_lists > 3 else ())
     q = np.random.default_rng(900 + d).standard_normal((257, d)).astype(np.float32)
-    monkeypatch.setenv("IVFPQ_SCAN_TWO", "0")
+    gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, 1)
     ids_one, d_one = gidx.ivfpq_search(q, n_probes, k, dtype)
-    monkeypatch.setenv("IVFPQ_SCAN_TWO", "1")
+    gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, 2)
     _step(f"two pairs per workgroup d={d} s={pq_dim} L={n_lists} P={n_probes} k={k} {dtype_name}")
     ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, n_probes, k, dtype)
     assert_topk_matches(ids_g, d_g, ids_o, d_o, context="two pairs per workgroup")
@@ -631,19 +635,19 @@ def test_search_two_pairs_per_workgroup(P, monkeypatch, d, pq_dim, n_lists, n_pr
     (128, 64, 6, oracle.LUT_E5M3),                                    # 6-bit codes, 48 bytes: 16-byte chunks
     (40, 40, 8, oracle.LUT_E5M3),                                     # 40-byte codes: 4-byte chunks
 ])
-def test_early_exit_changes_nothing(P, monkeypatch, d, pq_dim, pq_bits, dtype):
+def test_early_exit_changes_nothing(P, d, pq_dim, pq_bits, dtype):
     # a group whose partial sums are all over the bound stops early: the survivors, hence the results, are the same
     oidx, gidx = random_pair(P, 12000, d, 9, pq_dim, pq_bits, salt=950 + d + pq_bits)
     q = np.random.default_rng(950 + d).standard_normal((130, d)).astype(np.float32)
     out = {}
     for mode in ("0", "1"):
-        monkeypatch.setenv("IVFPQ_EARLY_EXIT", mode)
+        gidx.ivfpq_set_tuning(P.TUNE_EARLY_EXIT, 1 if mode == "1" else -1)
         _step(f"early exit {mode}: d={d} s={pq_dim} p={pq_bits} dtype={dtype}")
         ids, dist = gidx.ivfpq_search(q, 6, 10, dtype)
         out[mode] = (ids.cpu().numpy(), dist.cpu().numpy())
     np.testing.assert_array_equal(out["0"][0], out["1"][0])
     np.testing.assert_array_equal(out["0"][1], out["1"][1])
-    monkeypatch.delenv("IVFPQ_EARLY_EXIT")
+    gidx.ivfpq_set_tuning(P.TUNE_EARLY_EXIT, 0)
     ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, 6, 10, dtype)
     assert_topk_matches(ids_g, d_g, ids_o, d_o, context="early exit")
 

@@ -110,6 +110,27 @@ def test_fp8_encoding_setter_validates(P):
         assert e.value.status == P.EINVAL and needle in str(e.value)
 
 
+def test_tuning_setter_validates(P):
+    idx = P.Index.ivfpq_index_from_arrays(32, 9, 16, 4, *si.random_index_arrays(100, 32, 9, 16, 4, salt=2))
+    for knob, good in ((P.TUNE_SCAN_THREADS, (0, 64, 1024)), (P.TUNE_ORDER_BLOCK, (0, 1, 64)), (P.TUNE_SCAN_SHARE, (0, 1, 2)),
+                       (P.TUNE_EARLY_EXIT, (-1, 0, 1)), (P.TUNE_LDS_PAD, (0, 16, 65536))):
+        for v in good:
+            idx.ivfpq_set_tuning(knob, v)
+        idx.ivfpq_set_tuning(knob, 0)
+    for knob, bad in ((P.TUNE_SCAN_THREADS, 100), (P.TUNE_ORDER_BLOCK, -1), (P.TUNE_SCAN_SHARE, 3), (P.TUNE_EARLY_EXIT, 2),
+                      (P.TUNE_LDS_PAD, 8), (P.TUNE_LDS_PAD, 1 << 20), (99, 0)):
+        with pytest.raises(P.IvfpqError) as e:
+            idx.ivfpq_set_tuning(knob, bad)
+        assert e.value.status == P.EINVAL
+
+
+def test_library_reads_no_environment_variable():
+    # tuning is per index (ivfpq_set_tuning): no hidden process-global state
+    for name in ("ivfpq_device.hip", "ivfpq_build.hip", "ivfpq_host.cpp", "ivfpq_rank.hpp", "ivfpq_internal.hpp"):
+        text = open(os.path.join(ROOT, "paper_2301_06672_amd", "csrc", name)).read()
+        assert "getenv" not in text, name
+
+
 def test_stream_read_validates_before_launching(P):
     L = P.lib()
     for args in ((None, 64, 16, 4), (16, 64, None, 4), (16, 64, 32, 0), (16, 64, 32, 1 << 20), (8, 64, 32, 4), (16, 60, 32, 4)):
