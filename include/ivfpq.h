@@ -203,6 +203,18 @@ int ivfpq_search(const ivfpq_index_t* index, const float* d_queries, int64_t nq,
                  int32_t k, int32_t lut_dtype, int64_t* d_ids, float* d_dists,
                  void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ivfpq_search for callers that cannot allocate device memory or provide a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as
+ * ivfpq_search, but the scratch is a fixed array of IVFPQ_STATIC_SCRATCH_BYTES inside the library's device
+ * image (each GPU the library runs on holds it until the process ends); the call allocates and frees nothing.
+ * A batch is processed in as many query tiles as the array requires; if a single query's share does not fit
+ * (its n_probes largest clusters hold too many vectors) the call returns IVFPQ_ENOSPACE and touches nothing.
+ * All calls on one GPU share that GPU's array, whatever the index or stream: calls that overlap in time race,
+ * so issue them on one stream or order them yourself.  Nothing in the array needs to survive between calls. */
+#define IVFPQ_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int ivfpq_search_static(const ivfpq_index_t* index, const float* d_queries, int64_t nq, int32_t n_probes,
+                        int32_t k, int32_t lut_dtype, int64_t* d_ids, float* d_dists, void* hip_stream);
+
 /* Step 1 alone: d_probes [nq][n_probes] u32 (device, out), nearest first, ties to the lower
  * cluster index; d_probe_dists [nq][n_probes] f32 (device, out, may be NULL). */
 int ivfpq_select_probes(const ivfpq_index_t* index, const float* d_queries, int64_t nq,

@@ -22,6 +22,7 @@ LUT_BYTES = {LUT_FP32: 4, LUT_FP16: 2, LUT_FP8_E5M3: 1, LUT_FP8_E4M4: 1}
 ROUND_NEAREST, ROUND_TRUNCATE = 0, 1
 MAX_K = 1024
 MAX_PROBES = 1024
+STATIC_SCRATCH_BYTES = 64 << 20
 TUNE_SCAN_THREADS, TUNE_ORDER_BLOCK, TUNE_SCAN_SHARE, TUNE_EARLY_EXIT, TUNE_LDS_PAD = 0, 1, 2, 3, 4
 
 OK, EINVAL, ENOSPACE, EHIP, EUNSUPPORTED, ESTATE = 0, -1, -2, -3, -4, -5
@@ -31,7 +32,7 @@ EXPORTS = (
     "ivfpq_build_host", "ivfpq_build_device", "ivfpq_build_device_workspace_bytes", "ivfpq_assign_device",
     "ivfpq_assign_device_workspace_bytes", "ivfpq_index_from_arrays", "ivfpq_index_info", "ivfpq_index_export", "ivfpq_free",
     "ivfpq_set_e4m4_bias", "ivfpq_set_fp8_encoding", "ivfpq_set_workspace_limit", "ivfpq_set_tuning",
-    "ivfpq_device_bytes", "ivfpq_upload", "ivfpq_search_workspace_bytes", "ivfpq_search",
+    "ivfpq_device_bytes", "ivfpq_upload", "ivfpq_search_workspace_bytes", "ivfpq_search", "ivfpq_search_static",
     "ivfpq_select_probes", "ivfpq_search_with_probes", "ivfpq_dump_lut", "ivfpq_scan_list", "ivfpq_refine",
     "ivfpq_set_stage_timing", "ivfpq_stage_times_ms", "ivfpq_scan_kernel_info", "ivfpq_stream_read", "ivfpq_last_error",
 )
@@ -79,6 +80,7 @@ def _declare(L):
     L.ivfpq_set_workspace_limit.argtypes = [vp, sz]
     L.ivfpq_set_fp8_encoding.argtypes = [vp, i32, i32, i32, i32]
     L.ivfpq_set_tuning.argtypes = [vp, i32, i32]
+    L.ivfpq_search_static.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, vp]
     L.ivfpq_free.restype = None
     L.ivfpq_device_bytes.argtypes = [vp]
     L.ivfpq_device_bytes.restype = sz
@@ -290,6 +292,16 @@ class Index:
         ws = self._workspace(nq, n_probes, k, lut_dtype)
         _check(lib().ivfpq_search(self._h, _dp(q), nq, n_probes, k, lut_dtype, _dp(ids), _dp(dists),
                                   _dp(ws), ws.numel(), _stream()))
+        return ids, dists
+
+    def ivfpq_search_static(self, queries, n_probes: int, k: int, lut_dtype: int = LUT_FP8_E5M3, out=None):
+        """ivfpq_search on the library's fixed scratch: no workspace is allocated or passed."""
+        q = _dev_f32(queries)
+        nq = q.shape[0]
+        ids, dists = out if out is not None else (
+            torch.empty((nq, k), dtype=torch.int64, device="cuda"),
+            torch.empty((nq, k), dtype=torch.float32, device="cuda"))
+        _check(lib().ivfpq_search_static(self._h, _dp(q), nq, n_probes, k, lut_dtype, _dp(ids), _dp(dists), _stream()))
         return ids, dists
 
     def ivfpq_select_probes(self, queries, n_probes: int):

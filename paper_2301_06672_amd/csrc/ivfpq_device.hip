@@ -39,7 +39,35 @@
 
 using namespace ivfpq;
 
+// The workspace of ivfpq_search_static: a fixed device array, so that callers who cannot allocate (HIP graph
+// capture, serving loops, harnesses that forbid hipMalloc) need bring none.  Each GPU the library runs on holds
+// its own copy at its own address until the process ends.  In host code this name is only a stand-in for the
+// symbol: the array's device address comes from hipGetSymbolAddress (static_scratch_ptr), and only that pointer
+// is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[IVFPQ_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr size_t kStaticScratchBytes = IVFPQ_STATIC_SCRATCH_BYTES;
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch_ptr(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptr[kMaxDevices] = {};
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(IVFPQ_EUNSUPPORTED, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(IVFPQ_EHIP, "hipGetSymbolAddress gave a null address for the static scratch");
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return IVFPQ_OK;
+}
 
 constexpr uint32_t kPadKey = 0xFFFFFFFFu;      // R of a padding lane: sorts after every real distance
 
@@ -2040,15 +2068,28 @@ struct StageTimer {
     }
 };
 
+// static_scratch: the workspace is the library's own fixed device array (d_ws is resolved after the checks)
 int search_impl(const ivfpq_index* idx, const float* d_queries, int64_t nq, const uint32_t* d_probes_in,
                 int32_t n_probes, int32_t k, int32_t lut_dtype, int64_t* d_ids, float* d_dists,
-                void* d_ws, size_t ws_bytes, void* hip_stream) {
+                void* d_ws, size_t ws_bytes, void* hip_stream, bool static_scratch = false) {
     if (int s = check_search_args(idx, d_queries, nq, n_probes, k, lut_dtype, true)) return s;
     if (nq > 0 && (!d_ids || !d_dists)) return fail(IVFPQ_EINVAL, "null output pointer");
+    Plan plan;
+    if (static_scratch) {
+        // sized before anything touches the device: a request beyond the fixed array is refused as such
+        if (int s = make_plan(idx, nq, n_probes, d_probes_in != nullptr, &plan, kStaticScratchBytes)) return s;
+        if (plan.total > kStaticScratchBytes)
+            return fail(IVFPQ_ENOSPACE, "one query with %d probes on this index needs %zu bytes of scratch; the static "
+                        "scratch holds %zu (use ivfpq_search with a caller workspace)", n_probes, plan.total, kStaticScratchBytes);
+    }
     if (int s = check_device(idx)) return s;
     if (nq == 0) return IVFPQ_OK;
-    Plan plan;
-    if (int s = make_plan(idx, nq, n_probes, d_probes_in != nullptr, &plan)) return s;
+    if (static_scratch) {
+        if (int s = static_scratch_ptr(&d_ws)) return s;
+        ws_bytes = kStaticScratchBytes;
+    } else if (int s = make_plan(idx, nq, n_probes, d_probes_in != nullptr, &plan)) {
+        return s;
+    }
     if (!d_ws || ws_bytes < plan.total)
         return fail(IVFPQ_ENOSPACE, "workspace of %zu bytes given, %zu needed", ws_bytes, plan.total);
     if (scan_lds_bytes_staged(idx, lut_dtype, scan_threads(idx, lut_dtype)) > kLdsBytes)
@@ -2261,6 +2302,9 @@ int upload_impl(ivfpq_index_t* idx, void* d_buf, size_t bytes, void* hip_stream)
         HIP_TRY(hipMemcpy(base + L.codes + (size_t)g_done * group_bytes, stage.data(), stage.size(), hipMemcpyHostToDevice));
         g_done = g_end;
     }
+    // set-up of the static scratch for this device (ivfpq_search_static looks it up here, not in the hot loop)
+    void* scratch_dev = nullptr;
+    if (int s = static_scratch_ptr(&scratch_dev)) return s;
     int dev = -1;
     HIP_TRY(hipGetDevice(&dev));
     idx->dev.valid = true;
@@ -2299,6 +2343,14 @@ int ivfpq_search(const ivfpq_index_t* index, const float* d_queries, int64_t nq,
     return guarded("ivfpq_search", [&] {
         return search_impl(index, d_queries, nq, nullptr, n_probes, k, lut_dtype, d_ids, d_dists, d_workspace,
                            workspace_bytes, hip_stream);
+    });
+}
+
+int ivfpq_search_static(const ivfpq_index_t* index, const float* d_queries, int64_t nq, int32_t n_probes, int32_t k,
+                        int32_t lut_dtype, int64_t* d_ids, float* d_dists, void* hip_stream) {
+    return guarded("ivfpq_search_static", [&] {
+        return search_impl(index, d_queries, nq, nullptr, n_probes, k, lut_dtype, d_ids, d_dists, nullptr, 0,
+                           hip_stream, true);
     });
 }
 

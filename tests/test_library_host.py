@@ -131,6 +131,27 @@ def test_library_reads_no_environment_variable():
         assert "getenv" not in text, name
 
 
+def test_static_scratch_search_refuses_what_does_not_fit(P):
+    # one query on one cluster of 9 million vectors needs 2 x 9e6 x 8 bytes of scratch: more than the fixed
+    # array.  The refusal comes before anything touches a device, so it is checked here without a GPU.
+    n, d, s, p = 9_000_000, 4, 4, 8
+    cent = np.zeros((1, d), np.float32)
+    cb = np.zeros((s, 1 << p, 1), np.float32)
+    offs = np.array([0, n], np.int64)
+    idx = P.Index.ivfpq_index_from_arrays(d, 1, s, p, cent, cb, offs, np.zeros((n, 4), np.uint8), np.arange(n, dtype=np.int64))
+    import ctypes
+    dummy = ctypes.c_void_p(256)
+    st = P.lib().ivfpq_search_static(idx._h, dummy, 1, 1, 10, P.LUT_FP8_E5M3, dummy, dummy, None)
+    assert st == P.ENOSPACE
+    msg = P.lib().ivfpq_last_error().decode()
+    assert "static" in msg and str(P.STATIC_SCRATCH_BYTES) in msg
+    # what fits is refused only for the missing device image
+    small = P.Index.ivfpq_index_from_arrays(8, 3, 4, 8, *si.random_index_arrays(100, 8, 3, 4, 8, salt=3))
+    assert P.lib().ivfpq_search_static(small._h, dummy, 1, 1, 1, 0, dummy, dummy, None) == P.ESTATE
+    header = open(os.path.join(ROOT, "include", "ivfpq.h")).read()
+    assert "((size_t)64 << 20)" in header and P.STATIC_SCRATCH_BYTES == 64 << 20
+
+
 def test_stream_read_validates_before_launching(P):
     L = P.lib()
     for args in ((None, 64, 16, 4), (16, 64, None, 4), (16, 64, 32, 0), (16, 64, 32, 1 << 20), (8, 64, 32, 4), (16, 60, 32, 4)):
