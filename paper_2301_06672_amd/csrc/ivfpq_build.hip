@@ -535,6 +535,45 @@ BuildPlan make_build_plan(int64_t n, int d, int n_lists, int pq_dim, int pq_bits
     return P;
 }
 
+// Everything the launches of a build assume, checked on the host before the first of them: workgroup counts
+// that fit a grid dimension (2^31 - 1 along x, 65,535 along y), a ranking tile whose row count and strip
+// summaries fit their 32-bit indices, and workspace sections that are aligned, ascending and inside the total.
+int check_build_plan(const BuildPlan& P) {
+    constexpr size_t kGridX = 0x7FFFFFFFull, kGridY = 65535;
+    auto grid_ok = [&](size_t items, size_t per_block, const char* what) -> int {
+        const size_t blocks = (items + per_block - 1) / per_block;
+        if (blocks > kGridX) return fail(IVFPQ_EUNSUPPORTED, "%s would need %zu workgroups (limit %zu)", what, blocks, kGridX);
+        return IVFPQ_OK;
+    };
+    const size_t d = (size_t)P.d, n = (size_t)P.n, n_ct = (size_t)P.n_ct, n_pt = (size_t)P.n_pt;
+    if (int s = grid_ok(n_ct * d, 256, "gathering the cluster training rows")) return s;
+    if (int s = grid_ok(n_pt * d, 256, "the residuals of the PQ training rows")) return s;
+    if (int s = grid_ok(P.n_group, 256, "grouping rows by label")) return s;
+    if (int s = grid_ok(n, 256, "encoding the rows")) return s;
+    if (int s = grid_ok(P.k_group, 1, "sorting the groups")) return s;
+    if (P.tile_rows < 1 || P.tile_rows > ((size_t)2 << 20))
+        return fail(IVFPQ_EUNSUPPORTED, "internal: ranking tile of %zu rows (1 ... 2^21)", P.tile_rows);
+    for (int k : {P.n_lists, P.ksub}) {
+        // ranking GEMM: tiles of 128 x 128 (or 64 x 64): centres along x, rows along y
+        const size_t gy = (P.tile_rows + 63) / 64, gx = ((size_t)k + 63) / 64;
+        if (gy > kGridY) return fail(IVFPQ_EUNSUPPORTED, "internal: ranking tile of %zu rows needs %zu grid rows (limit %zu)", P.tile_rows, gy, kGridY);
+        if (gx > kGridX) return fail(IVFPQ_EUNSUPPORTED, "%d centres need %zu grid columns", k, gx);
+        if (int s = grid_ok(P.tile_rows * (size_t)(coarse_padded_dim(P.d) / 8), 256, "splitting a tile of rows into bf16 halves")) return s;
+    }
+    const size_t strips = ((size_t)P.n_lists + 31) / 32;
+    if (P.use_strips && P.tile_rows * strips >= ((size_t)1 << 32))
+        return fail(IVFPQ_EUNSUPPORTED, "internal: %zu strip summaries per tile (limit 2^32)", P.tile_rows * strips);
+    const size_t sections[] = {P.Xt, P.A, P.S, P.split, P.cnorm, P.cmax, P.C, P.labels_t, P.labels_all, P.order, P.tmp, P.counts,
+                               P.cursor, P.offsets, P.ct_rows, P.pt_rows, P.init_rows, P.Rt, P.pq_labels, P.codebooks, P.codes};
+    size_t prev = 0;
+    for (size_t off : sections) {
+        if (off % kAlign != 0 || off < prev || off > P.total)
+            return fail(IVFPQ_EUNSUPPORTED, "internal: workspace section at %zu (previous %zu, total %zu)", off, prev, P.total);
+        prev = off;
+    }
+    return IVFPQ_OK;
+}
+
 int fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t st) {
     if (n == 0) return IVFPQ_OK;
     hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, st, p, n, v);
@@ -641,7 +680,9 @@ size_t ivfpq_build_device_workspace_bytes(int64_t n, int32_t d, int32_t n_lists,
     if (n_coarse_train <= 0) n_coarse_train = std::min<int64_t>(n, (int64_t)256 * n_lists);
     if (n_pq_train <= 0) n_pq_train = std::min<int64_t>(n, 262144);
     if ((__int128)n_pq_train * pq_dim >= ((__int128)1 << 32)) { set_error("n_pq_train * pq_dim must stay below 2^32"); return 0; }
-    return make_build_plan(n, d, n_lists, pq_dim, pq_bits, n_coarse_train, n_pq_train).total;
+    const BuildPlan P = make_build_plan(n, d, n_lists, pq_dim, pq_bits, n_coarse_train, n_pq_train);
+    if (check_build_plan(P) != IVFPQ_OK) return 0;
+    return P.total;
 }
 
 int ivfpq_assign_device(const float* d_rows, int64_t n_rows, int32_t d, const float* d_centres, int32_t n_centres,
@@ -719,6 +760,7 @@ int build_device_impl(const float* d_data, int64_t n, int32_t d, int32_t n_lists
     }
 
     const BuildPlan P = make_build_plan(n, d, n_lists, pq_dim, pq_bits, n_ct, n_pt);
+    if (int s = check_build_plan(P)) return s;
     if (!d_workspace || workspace_bytes < P.total)
         return fail(IVFPQ_ENOSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, P.total);
     if (((uintptr_t)d_workspace % kAlign) != 0) return fail(IVFPQ_EINVAL, "workspace must be %zu-byte aligned", kAlign);

@@ -152,6 +152,21 @@ def test_static_scratch_search_refuses_what_does_not_fit(P):
     assert "((size_t)64 << 20)" in header and P.STATIC_SCRATCH_BYTES == 64 << 20
 
 
+def test_device_builder_plan_is_checked_on_the_host(P):
+    # the launch geometry and workspace layout of ivfpq_build_device are validated before the first launch;
+    # the size query runs the same check, so it can be exercised without a GPU
+    L = P.lib()
+    need = L.ivfpq_build_device_workspace_bytes(100_000_000, 128, 50_000, 32, 8, 0, 0)      # the 10^8-vector workload
+    n_ct = 256 * 50_000
+    floor = n_ct * 128 * 4 + 100_000_000 * (4 + 4 + 4 + 32) + 262_144 * 128 * 4      # training rows, labels, order, tmp, codes, residuals
+    assert floor < need < floor + (4 << 30)
+    assert need % 256 == 0
+    assert L.ivfpq_build_device_workspace_bytes(100_000_000, 128, 50_000, 64, 4, 0, 0) > 0
+    # a shape whose row gather would need more workgroups than a grid dimension holds is refused, not truncated
+    assert L.ivfpq_build_device_workspace_bytes(2_000_000_000, 4096, 1_000_000, 1024, 8, 0, 0) == 0
+    assert b"workgroups" in L.ivfpq_last_error()
+
+
 def test_stream_read_validates_before_launching(P):
     L = P.lib()
     for args in ((None, 64, 16, 4), (16, 64, None, 4), (16, 64, 32, 0), (16, 64, 32, 1 << 20), (8, 64, 32, 4), (16, 60, 32, 4)):
