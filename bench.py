@@ -145,8 +145,14 @@ def main():
                     help="only run a plain elementwise copy (read BYTES, write BYTES) three times and exit: "
                          "reference for scaling the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--only-headline", action="store_true", help="skip the other table dtypes (for profiling runs)")
+    ap.add_argument("--profile-run", action="store_true",
+                    help="for runs under rocprofv3: --only-headline --no-cpu-baseline --no-full-run --no-recall, one stage-timing "
+                         "repetition and no streaming-read measurement, so that the process makes warmup + steps + 1 search calls "
+                         "and nothing else on the GPU besides the probe lists for the byte count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
+    if args.profile_run:
+        args.only_headline = args.no_cpu_baseline = args.no_full_run = args.no_recall = True
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path shards by query across GPUs with no "
               "communication, and no multi-GPU figure is produced.", file=sys.stderr)
@@ -276,7 +282,7 @@ def main():
         # stage and kernel times of further (untimed) steps, from HIP events the library records on the search
         # stream around its launches: median over the repetitions
         idx.ivfpq_set_stage_timing(True)
-        reps = 5
+        reps = 1 if args.profile_run else 5
         seen = {}
         for _ in range(reps):
             idx.ivfpq_search(q, n_probes, k, lut, out=out)
@@ -386,7 +392,7 @@ def main():
     head = results[args.lut]
 
     ws_bytes = idx.ivfpq_search_workspace_bytes(nq, n_probes, k, lut_ids[args.lut])
-    ceiling = measure_read_ceiling(torch, pkg)
+    ceiling = 0.0 if args.profile_run else measure_read_ceiling(torch, pkg)
     log(f"plain streaming read on this box: {ceiling:.0f} GB/s")
     # The dominant kernel: the scan over every probe but the one scanned unfiltered (one launch per step when the
     # batch is one query tile).  Its units are known exactly for the run without early exit.
