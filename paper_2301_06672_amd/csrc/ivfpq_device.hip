@@ -4,7 +4,7 @@
 // Kernels, in the order one search call runs them (per tile of queries):
 //   coarse_rank_*_kernel step 1a: ranking values |c|^2 - 2 q.c of every (query, cluster) pair on the
 //                        matrix cores: bf16 instructions on operands split in two for large problems,
-//                        fp32 otherwise; stored as all keys (few clusters) or as the two smallest
+//                        fp32 otherwise; stored as all keys (few clusters) or as the three smallest
 //                        tagged keys of every strip of 32 / 64 clusters
 //   select_probes_kernel step 1b: candidates by ranking value with a rigorous error bound, exact
 //                        direct-form distances for them, exact selection of the n_probes nearest
@@ -19,8 +19,9 @@
 //   scan_kernel (mode 2) steps 2-4 for the other probes, in cluster-grouped, XCD-aware order (a
 //                        cluster's codes then come from one XCD's L2); only R values under the bound
 //                        are kept
-//   scan_two_kernel      the same for two neighbouring pairs of one cluster per workgroup (long lists,
-//                        8-bit codes and tables): codebooks and codes are read once for both queries
+//   scan_group_kernel    the same for up to four neighbouring pairs of one cluster per workgroup (8-bit codes):
+//                        their tables are interleaved entry by entry, so one LDS read serves one lookup of
+//                        every query of the group; codebooks and codes are read once for all of them
 //   topk_kernel          step 5: the k smallest R among the survivors of a query, ordered by
 //                        (R, id), and the map from (cluster, position) to the caller's ids
 // Beside the path: dump_lut_kernel (steps 2-3 of one pair, for inspection) and refine_kernel (exact
@@ -1255,232 +1256,7 @@ scan_kernel(ScanArgs a) {
     if (filtered) flush_stage();
 }
 
-// ------------------------------------------------------------------------------------------------
-// The filtered scan for two (query, probe) pairs of the SAME cluster per workgroup (8-bit codes in
-// 16-byte chunks, 8-bit table dtypes with fixed encoding constants).  In the cluster-grouped order
-// neighbouring pairs almost always share their cluster, and then everything that depends on the cluster
-// alone is done once for both queries: every codebook entry is loaded once and turned into two table
-// entries, every code chunk is loaded once and every code byte extracted once for two lookups (5
-// instead of 6 vector instructions per pair of lookups).  The two tables are interleaved row by row
-// (row j of query g at byte (2 j + g) * 256), so both lookups of a code share one address register and
-// differ in the instruction's immediate offset.  Per query the arithmetic and its order are those of
-// scan_kernel: identical results.  A workgroup whose two pairs differ in cluster (the seam between two
-// clusters, or the odd pair at the end) runs them one after the other.
-// LDS: tables (pq_dim * 512) | residuals 2 x d floats | per wave and query kStageCap staged survivors.
-// ------------------------------------------------------------------------------------------------
-template <int LUT, int NCH, int G>
-__device__ __forceinline__ void scan_run(const ScanArgs& a, unsigned char* smem, const int (&q)[2], const uint4 (&pair)[2]) {
-    static_assert(kIsFp8<LUT>, "two-query scan: 8-bit tables only");
-    constexpr int SH = Fp8Format<LUT>::shift;
-    const uint32_t len = pair[0].y;
-    if (len == 0) return;
-    const int l = (int)pair[0].x;
-    unsigned char* lut = smem;
-    float* rq = reinterpret_cast<float*>(smem + (size_t)a.pq_dim * 512);
-    unsigned char* after_rq = reinterpret_cast<unsigned char*>(rq) + (((size_t)2 * a.d * 4 + 15) & ~(size_t)15);
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
-    const int n_waves = blockDim.x >> 6;
-    const Fp8Params fp8 = a.fp8.fixed;
-    uint32_t bound[G], seg0[G], row_pos0[G], staged[G];
-    uint2* stage[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        bound[g] = a.bounds[q[g]];
-        seg0[g] = a.pairs[(size_t)q[g] * a.n_probes + 1].w;
-        row_pos0[g] = pair[g].w;
-        staged[g] = 0;
-        stage[g] = reinterpret_cast<uint2*>(after_rq) + ((size_t)wave * 2 + g) * kStageCap;
-    }
-    const int n_groups = (int)((len + 63u) >> 6);
-    const uint4* cbase = reinterpret_cast<const uint4*>(a.codes + (size_t)pair[0].z * 64 * ((size_t)NCH * 16));
-    auto load_group = [&](uint4 (&buf)[NCH], int grp) {
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) buf[c] = cbase[((size_t)grp * NCH + c) * 64 + lane];
-    };
-    uint4 buf_a[NCH], buf_b[NCH];
-    int grp = wave;
-    if (grp < n_groups) load_group(buf_a, grp);
-
-    // step 2: both residuals against the cluster's centroid
-    for (int t = threadIdx.x; t < a.d; t += blockDim.x) {
-        const float c = a.centroids[(size_t)l * a.d + t];
-#pragma unroll
-        for (int g = 0; g < G; ++g) rq[g * a.d + t] = a.queries[(size_t)q[g] * a.d + t] - c;
-    }
-    __syncthreads();
-    // step 3: both tables from one pass over the codebooks (a wave takes whole rows, 4 entries per lane)
-    {
-        int hi_v = fp8.hi;
-        asm volatile("" : "+v"(hi_v));
-        auto rows = [&](auto m_tag) {
-            constexpr int M = decltype(m_tag)::value;
-            auto load_row = [&](int j, float (&cbv)[4 * M]) {
-                const float4* src = reinterpret_cast<const float4*>(a.codebooks + ((size_t)j * 256 + lane * 4) * M);
-#pragma unroll
-                for (int v = 0; v < M; ++v) {
-                    const float4 x = src[v];
-                    cbv[4 * v] = x.x; cbv[4 * v + 1] = x.y; cbv[4 * v + 2] = x.z; cbv[4 * v + 3] = x.w;
-                }
-            };
-            auto finish_row = [&](int j, const float (&cbv)[4 * M]) {
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    float r[M], f[4];
-#pragma unroll
-                    for (int t = 0; t < M; ++t) r[t] = rq[g * a.d + j * M + t];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) f[u] = lut_entry<M>(cbv + u * M, r);
-                    store4<LUT>(lut, (2 * j + g) * 256 + lane * 4, f, fp8, hi_v);
-                }
-            };
-            // two rows per trip: both rows' loads are in flight before either is used
-            int j = wave;
-            for (; j + n_waves < a.pq_dim; j += 2 * n_waves) {
-                float c0[4 * M], c1[4 * M];
-                load_row(j, c0);
-                load_row(j + n_waves, c1);
-                finish_row(j, c0);
-                finish_row(j + n_waves, c1);
-            }
-            if (j < a.pq_dim) {
-                float c0[4 * M];
-                load_row(j, c0);
-                finish_row(j, c0);
-            }
-        };
-        switch (a.m) {
-            case 1: rows(std::integral_constant<int, 1>{}); break;
-            case 2: rows(std::integral_constant<int, 2>{}); break;
-            default: rows(std::integral_constant<int, 4>{}); break;      // the host admits m = 1, 2, 4 only
-        }
-    }
-    __syncthreads();
-
-    // step 4: Eq. (1) for both queries, sub-spaces in ascending order
-    // A query whose 64 partial sums are all over its bound after a chunk drops out of the rest of the
-    // group's lookups, as in scan_kernel; the other one then goes on alone.
-    auto chunk_all = [&](const uint4& v, int c, float (&acc)[G]) {
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const uint32_t code = (w[u] >> (8 * b)) & 255u;
-                const int row = (c * 4 + u) * 4 + b;
-#pragma unroll
-                for (int g = 0; g < G; ++g) acc[g] += fp8_to_f32<SH>(lut[(uint32_t)(2 * row + g) * 256u + code], fp8);
-            }
-    };
-    auto chunk_one = [&](const uint4& v, int c, int g, float& acc_g) {
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-        const unsigned char* lut_g = lut + g * 256;
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const uint32_t code = (w[u] >> (8 * b)) & 255u;
-                const int row = (c * 4 + u) * 4 + b;
-                acc_g += fp8_to_f32<SH>(lut_g[(uint32_t)(2 * row) * 256u + code], fp8);
-            }
-    };
-    auto accumulate = [&](const uint4 (&buf)[NCH], float (&acc)[G]) {
-        bool alive[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) { acc[g] = 0.f; alive[g] = true; }
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            bool all = true, any = false;
-#pragma unroll
-            for (int g = 0; g < G; ++g) { all = all && alive[g]; any = any || alive[g]; }
-            if (all) {
-                chunk_all(buf[c], c, acc);
-            } else if (any) {
-#pragma unroll
-                for (int g = 0; g < G; ++g)
-                    if (alive[g]) chunk_one(buf[c], c, g, acc[g]);
-            }
-            if (c + 1 < NCH && a.early_exit && any) {
-#pragma unroll
-                for (int g = 0; g < G; ++g)
-                    if (alive[g]) alive[g] = __ballot(__float_as_uint(acc[g]) <= bound[g]) != 0;
-            }
-        }
-    };
-    auto flush = [&](int g) {
-        if (staged[g] == 0) return;
-        uint32_t base = 0;
-        if (lane == 0) base = atomicAdd(&a.counts[q[g]], staged[g]);
-        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
-        uint32_t* dst_key = reinterpret_cast<uint32_t*>(a.R) + (size_t)q[g] * a.stride + seg0[g] + base;
-        uint32_t* dst_pos = a.Rpos + (size_t)q[g] * a.stride + seg0[g] + base;
-        for (uint32_t j = lane; j < staged[g]; j += kWave) {
-            const uint2 e = stage[g][j];
-            dst_key[j] = e.x;
-            dst_pos[j] = e.y;
-        }
-        staged[g] = 0;
-    };
-    auto keep = [&](int grp_i, const float (&acc)[G]) {
-        const uint32_t i = (uint32_t)grp_i * 64u + lane;
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const bool ok = i < len && __float_as_uint(acc[g]) <= bound[g];
-            const unsigned long long m = __ballot(ok);
-            if (m != 0) {
-                if (staged[g] + 64u > (uint32_t)kStageCap) flush(g);
-                if (ok) stage[g][staged[g] + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = make_uint2(__float_as_uint(acc[g]), row_pos0[g] + i);
-                staged[g] += (uint32_t)__popcll(m);
-            }
-        }
-    };
-    float acc[G];
-    while (grp < n_groups) {
-        const int gn = grp + n_waves;
-        if (gn < n_groups) load_group(buf_b, gn);
-        accumulate(buf_a, acc);
-        keep(grp, acc);
-        if (gn >= n_groups) break;
-        grp = gn + n_waves;
-        if (grp < n_groups) load_group(buf_a, grp);
-        accumulate(buf_b, acc);
-        keep(gn, acc);
-    }
-#pragma unroll
-    for (int g = 0; g < G; ++g) flush(g);
-}
-
-template <int LUT, int NCH>
-__global__ void __launch_bounds__(1024)
-scan_two_kernel(ScanArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    // pairs (2 slot, 2 slot + 1) of the cluster-grouped order; the slots are dealt to the XCDs in blocks
-    // of order_block / 2, which is the dealing of scan_kernel's pairs in blocks of order_block
-    const uint32_t n_slots = (a.n_pairs + 1u) / 2u, blk = a.order_block / 2u;
-    const uint32_t xcd = blockIdx.x & 7u, rank = blockIdx.x >> 3;
-    const uint32_t slot = ((rank / blk) * 8u + xcd) * blk + rank % blk;
-    if (slot >= n_slots) return;
-    const bool two = 2u * slot + 1u < a.n_pairs;
-    int q[2];
-    uint4 pair[2];
-#pragma unroll
-    for (int g = 0; g < 2; ++g) {
-        const uint32_t lin = a.order[2u * slot + ((g == 1 && two) ? 1u : 0u)];
-        q[g] = (int)(lin / (uint32_t)(a.n_probes - 1));
-        pair[g] = a.pairs[(size_t)q[g] * a.n_probes + 1 + (lin - (uint32_t)q[g] * (uint32_t)(a.n_probes - 1))];
-    }
-    if (two && pair[0].x == pair[1].x) {
-        scan_run<LUT, NCH, 2>(a, smem, q, pair);
-    } else {
-        scan_run<LUT, NCH, 1>(a, smem, q, pair);
-        if (two) {
-            __syncthreads();                  // the first run's table is still being read by slower waves
-            const int q1[2] = {q[1], q[1]};
-            const uint4 p1[2] = {pair[1], pair[1]};
-            scan_run<LUT, NCH, 1>(a, smem, q1, p1);
-        }
-    }
-}
+#include "ivfpq_scan_group.hpp"
 
 // Steps 2-3 only: the table of one pair, copied out of LDS byte for byte.
 template <int LUT>
@@ -1897,7 +1673,7 @@ int scan_threads(const ivfpq_index* idx, int lut_dtype) {
     // long lists (24 or more 64-vector groups on average) want 2-wave workgroups: the table build of
     // one pair then overlaps the scan of more others
     size_t lds = scan_lds_bytes(idx, lut_dtype);
-    if (idx->n_lists > 0 && idx->n / idx->n_lists >= 24 * 64 && lds <= 40 * 1024) return 128;
+    if (idx->n_lists > 0 && idx->n / idx->n_lists >= 24 * 64 && lds <= 24 * 1024) return 128;
     if (lds <= 20 * 1024) return 256;
     if (lds <= 40 * 1024) return 512;
     if (2 * (lds + (size_t)16 * kStageCap * 8) <= kLdsBytes) return 1024;
@@ -1949,52 +1725,91 @@ int launch_scan_lut(const ScanArgs& a, int bits, int cw, int nch, dim3 grid, int
     }
 }
 
-// The two-pairs-per-workgroup kernel serves the filtered scan of 8-bit codes in 16-byte chunks with an
-// 8-bit table of fixed encoding and sub-vectors of 1, 2 or 4 components, when both tables leave room for
-// enough workgroups per compute unit.  Measured on MI355X (scan stage, 10,000 queries): 6.5 -> 5.7 ms at
-// 10^8 vectors in 50,000 lists (32 sub-spaces: 21 KB of LDS per workgroup), 1.29 -> 1.23 ms at 10^7
-// vectors (48 sub-spaces, 33 KB), but 2.06 -> 2.30 ms with 64 sub-spaces (41 KB: three workgroups per
-// compute unit), so the limit is 36 KB.  ivfpq_set_tuning(IVFPQ_TUNE_SCAN_SHARE) forces it off (1) or on wherever it can run (2).
-size_t scan_two_lds_bytes(const ivfpq_index* idx, int threads) {
-    return (size_t)idx->pq_dim * 512 + (((size_t)2 * idx->d * 4 + 15) & ~(size_t)15) + (size_t)(threads / 64) * 2 * kStageCap * 8;
+// ---- the group kernel: up to G pairs of one cluster per workgroup, tables interleaved entry by entry ----
+// The group kernel addresses its tables by LDS offsets counted from 0: its dynamic LDS must be the first
+// thing in the workgroup's LDS, which holds when the compiled kernel has no static LDS.  Checked once per
+// kernel (hipFuncGetAttributes is not a stream operation; later launches make no call besides the launch).
+int require_no_static_lds(const void* kernel) {
+    static std::mutex mu;
+    static std::vector<const void*> ok;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const void* k : ok)
+        if (k == kernel) return IVFPQ_OK;
+    hipFuncAttributes attr;
+    HIP_TRY(hipFuncGetAttributes(&attr, kernel));
+    if (attr.sharedSizeBytes != 0)
+        return fail(IVFPQ_EUNSUPPORTED, "internal: the group scan kernel was built with %zu bytes of static LDS", (size_t)attr.sharedSizeBytes);
+    ok.push_back(kernel);
+    return IVFPQ_OK;
 }
-bool scan_two_applies(const ivfpq_index* idx, int lut_dtype, const Fp8Mode& fp8, uint32_t order_block) {
-    const int forced = idx->tuning.scan_share == 0 ? -1 : (idx->tuning.scan_share >= 2 ? 1 : 0);
-    if (forced == 0) return false;
-    if (lut_dtype != IVFPQ_LUT_FP8_E5M3 && lut_dtype != IVFPQ_LUT_FP8_E4M4) return false;
-    if (fp8.per_table || idx->pq_bits != 8 || chunk_width(idx) != 16) return false;
+size_t scan_group_lds_bytes(const ivfpq_index* idx, int lut_dtype, int G, int threads) {
+    return kGroupHead + (size_t)idx->pq_dim * 256 * G * lut_elem_bytes(lut_dtype) + (((size_t)G * idx->d * 4 + 15) & ~(size_t)15)
+           + (size_t)(threads / 64) * G * kGroupStage * 8 + (size_t)idx->tuning.lds_pad;
+}
+// Workgroup size of the group kernel.  Measured on MI355X (filtered scan, 10,000 queries): with long lists (24 or
+// more 64-vector groups on average) two-wave workgroups win when six or more of them share a compute unit's LDS
+// (e5m3, two pairs, 10^8 vectors: 4.81 ms against 5.30 with four waves) and lose badly otherwise (half table, two
+// pairs, 35 KB: 8.04 ms against 5.63).
+int scan_group_threads(const ivfpq_index* idx, int lut_dtype, int G) {
+    if (idx->tuning.scan_threads) return std::min(idx->tuning.scan_threads, 512);       // the kernel's launch bound
+    const bool long_lists = idx->n_lists > 0 && idx->n / idx->n_lists >= 24 * 64;
+    return long_lists && scan_group_lds_bytes(idx, lut_dtype, G, 128) <= 24 * 1024 ? 128 : 256;
+}
+// How many pairs of a cluster share a workgroup (0: the group kernel does not apply).  It serves 8-bit codes
+// in 16-byte chunks, sub-vectors of 1, 2 or 4 components and fixed encoding constants.  The widest layout whose
+// workgroup leaves room for four workgroups per compute unit (40 KB of LDS) is taken -- four pairs only for the
+// one-byte table dtypes: with wider entries the LDS read of four entries costs what it saves.  Measured (filtered
+// scan, 10,000 queries; one / two / four pairs): e5m3 at 10^8 vectors, 32 sub-spaces: 6.02 / 4.81 / 4.58 ms; at 10^7,
+// 48 sub-spaces: 1.08 / 0.96 / 1.05; half at 10^8: 6.58 / 5.63 / 7.19; float: 8.30 / 8.75 / -.
+int scan_group_width(const ivfpq_index* idx, int lut_dtype, const Fp8Mode& fp8, uint32_t order_block) {
+    if (idx->pq_bits != 8 || chunk_width(idx) != 16 || fp8.per_table) return 0;
     const int m = idx->d / idx->pq_dim;
-    if (m != 1 && m != 2 && m != 4) return false;
-    if (order_block < 2 || (order_block & 1u)) return false;
-    const size_t lds = scan_two_lds_bytes(idx, scan_threads(idx, lut_dtype));
-    return forced == 1 ? lds <= kLdsBytes / 3 : lds <= 36 * 1024;
+    if (m != 1 && m != 2 && m != 4) return 0;
+    const int want = idx->tuning.scan_share;
+    if (want == 1) return 0;
+    const bool one_byte = lut_dtype == IVFPQ_LUT_FP8_E5M3 || lut_dtype == IVFPQ_LUT_FP8_E4M4;
+    for (int G : {4, 2}) {
+        if (want != 0 && want != G) continue;
+        if (order_block < (uint32_t)G || order_block % (uint32_t)G) continue;
+        const size_t lds = scan_group_lds_bytes(idx, lut_dtype, G, scan_group_threads(idx, lut_dtype, G));
+        if (want == G) { if (lds <= kLdsBytes) return G; continue; }
+        if (G == 4 && !one_byte) continue;
+        if (lut_dtype == IVFPQ_LUT_FP32) continue;
+        if (lds <= 40 * 1024) return G;
+    }
+    return 0;
 }
-int launch_scan_two(const ivfpq_index* idx, const ScanArgs& a, int lut_dtype, hipStream_t st) {
-    const int threads = scan_threads(idx, lut_dtype);
-    const size_t lds = scan_two_lds_bytes(idx, threads) + (size_t)idx->tuning.lds_pad;
+int launch_scan_group(const ivfpq_index* idx, const ScanArgs& a, int lut_dtype, int G, hipStream_t st) {
+    const int threads = scan_group_threads(idx, lut_dtype, G);
+    const size_t lds = scan_group_lds_bytes(idx, lut_dtype, G, threads);
     if (lds > kLdsBytes) return fail(IVFPQ_EUNSUPPORTED, "tables + staging + pad need %zu bytes of LDS (limit %zu)", lds, kLdsBytes);
-    const uint32_t n_slots = (a.n_pairs + 1u) / 2u, per = 8u * (a.order_block / 2u);
+    const uint32_t n_slots = (a.n_pairs + (uint32_t)G - 1u) / (uint32_t)G, per = 8u * (a.order_block / (uint32_t)G);
     const dim3 grid((n_slots + per - 1) / per * per);
     auto go = [&](auto kernel) -> int {
         if (int s = allow_full_lds(kernel)) return s;
+        if (int s = require_no_static_lds(reinterpret_cast<const void*>(kernel))) return s;
         hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, st, a);
         HIP_TRY(hipGetLastError());
         return IVFPQ_OK;
     };
     const int nch = idx->code_bytes() / 16;
-    if (lut_dtype == IVFPQ_LUT_FP8_E5M3) {
+    auto by_nch = [&](auto lut_tag, auto g_tag) -> int {
+        constexpr int LUT = decltype(lut_tag)::value, GG = decltype(g_tag)::value;
         switch (nch) {
-            case 1: return go(scan_two_kernel<IVFPQ_LUT_FP8_E5M3, 1>);
-            case 2: return go(scan_two_kernel<IVFPQ_LUT_FP8_E5M3, 2>);
-            case 3: return go(scan_two_kernel<IVFPQ_LUT_FP8_E5M3, 3>);
-            default: return go(scan_two_kernel<IVFPQ_LUT_FP8_E5M3, 4>);
+            case 1: return go(scan_group_kernel<LUT, 1, GG>);
+            case 2: return go(scan_group_kernel<LUT, 2, GG>);
+            case 3: return go(scan_group_kernel<LUT, 3, GG>);
+            default: return go(scan_group_kernel<LUT, 4, GG>);
         }
-    }
-    switch (nch) {
-        case 1: return go(scan_two_kernel<IVFPQ_LUT_FP8_E4M4, 1>);
-        case 2: return go(scan_two_kernel<IVFPQ_LUT_FP8_E4M4, 2>);
-        case 3: return go(scan_two_kernel<IVFPQ_LUT_FP8_E4M4, 3>);
-        default: return go(scan_two_kernel<IVFPQ_LUT_FP8_E4M4, 4>);
+    };
+    auto by_g = [&](auto lut_tag) -> int {
+        return G == 4 ? by_nch(lut_tag, std::integral_constant<int, 4>{}) : by_nch(lut_tag, std::integral_constant<int, 2>{});
+    };
+    switch (lut_dtype) {
+        case IVFPQ_LUT_FP32: return by_g(std::integral_constant<int, IVFPQ_LUT_FP32>{});
+        case IVFPQ_LUT_FP16: return by_g(std::integral_constant<int, IVFPQ_LUT_FP16>{});
+        case IVFPQ_LUT_FP8_E5M3: return by_g(std::integral_constant<int, IVFPQ_LUT_FP8_E5M3>{});
+        default: return by_g(std::integral_constant<int, IVFPQ_LUT_FP8_E4M4>{});
     }
 }
 
@@ -2183,9 +1998,9 @@ int search_impl(const ivfpq_index* idx, const float* d_queries, int64_t nq, cons
                 const uint32_t blk = idx->tuning.order_block > 0 ? (uint32_t)idx->tuning.order_block : kOrderBlock;
                 a.order_block = blk;
                 if (int s = t6.begin()) return s;
-                if (scan_two_applies(idx, lut_dtype, a.fp8, blk)) {
+                if (const int G = scan_group_width(idx, lut_dtype, a.fp8, blk)) {
                     a.n_chunks = idx->code_bytes() / 16;
-                    if (int s = launch_scan_two(idx, a, lut_dtype, st)) return s;
+                    if (int s = launch_scan_group(idx, a, lut_dtype, G, st)) return s;
                 } else {
                     const size_t grid = (n_pairs + 8 * (size_t)blk - 1) / (8 * (size_t)blk) * (8 * (size_t)blk);
                     if (int s = launch_scan(idx, a, lut_dtype, dim3((unsigned)grid), st)) return s;
@@ -2465,9 +2280,9 @@ int ivfpq_scan_kernel_info(const ivfpq_index_t* idx, int32_t lut_dtype, char* bu
     static const char* const names[4] = {"fp32", "fp16", "e5m3", "e4m4"};
     const int threads = scan_threads(idx, lut_dtype), cw = chunk_width(idx), nch = idx->code_bytes() / cw;
     const uint32_t blk = idx->tuning.order_block > 0 ? (uint32_t)idx->tuning.order_block : kOrderBlock;
-    if (scan_two_applies(idx, lut_dtype, fp8_mode(idx, lut_dtype), blk))
-        snprintf(buf, buf_bytes, "scan_two_kernel<%s, %d chunks> %d threads, %zu bytes of LDS", names[lut_dtype], nch, threads,
-                 scan_two_lds_bytes(idx, threads) + (size_t)idx->tuning.lds_pad);
+    if (const int G = scan_group_width(idx, lut_dtype, fp8_mode(idx, lut_dtype), blk))
+        snprintf(buf, buf_bytes, "scan_group_kernel<%s, %d chunks, %d pairs> %d threads, %zu bytes of LDS", names[lut_dtype], nch, G,
+                 scan_group_threads(idx, lut_dtype, G), scan_group_lds_bytes(idx, lut_dtype, G, scan_group_threads(idx, lut_dtype, G)));
     else
         snprintf(buf, buf_bytes, "scan_kernel<%s, %d-bit codes, %d-byte chunks x %d> %d threads, %zu bytes of LDS", names[lut_dtype],
                  idx->pq_bits, cw, cw == 16 ? nch : 0, threads, scan_lds_bytes_staged(idx, lut_dtype, threads));

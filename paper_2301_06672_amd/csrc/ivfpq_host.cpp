@@ -387,7 +387,8 @@ int ivfpq_set_tuning(ivfpq_index_t* index, int32_t knob, int32_t value) {
             index->tuning.order_block = value;
             return IVFPQ_OK;
         case IVFPQ_TUNE_SCAN_SHARE:
-            if (value < 0 || value > 2) return fail(IVFPQ_EINVAL, "scan share %d (0, 1 or 2)", value);
+            if (value != 0 && value != 1 && value != 2 && value != 4)
+                return fail(IVFPQ_EINVAL, "scan share %d (0, 1, 2 or 4)", value);
             index->tuning.scan_share = value;
             return IVFPQ_OK;
         case IVFPQ_TUNE_EARLY_EXIT:

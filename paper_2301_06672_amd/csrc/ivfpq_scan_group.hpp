@@ -1,0 +1,418 @@
+// The filtered scan for up to G (query, probe) pairs of ONE cluster per workgroup (8-bit codes in 16-byte
+// chunks, every table dtype).  Included by ivfpq_device.hip after the table helpers it uses.
+//
+// In the cluster-grouped order neighbouring pairs share their cluster, and everything that depends on the
+// cluster alone is then done once for all of them: a codebook entry is loaded once and becomes R table
+// entries, a code chunk is loaded once, and -- the point of this kernel -- one LDS read serves R lookups:
+// the R tables are interleaved ENTRY BY ENTRY, entry (sub-space j, code c, query g) at byte
+//     ((j * 256 + c) * R + g) * entry_bytes,
+// so the R entries a code selects are adjacent and come back from a single ds_read of R * entry_bytes
+// (four e5m3 entries in one 32-bit bank word; two halves in one; two floats in a 64-bit read).  What the LDS
+// spends per lookup therefore falls with the entry size (Sec. I-D's argument, carried over from "fewer
+// distinct bank words per table row" to "more lookups per bank word"), and the vector ALU extracts a code
+// byte once per R lookups.
+//
+// Decode and accumulate, per query:
+//   8-bit formats   the FP32 pattern of a code, (b << shift) + lo (Sec. II), has its low 16 bits clear, so its
+//                   upper half is a bf16 number with the same value.  The bytes of two consecutive sub-spaces
+//                   are gathered into the two halves of a register with one byte permute, one shift-add turns
+//                   both into bf16 ((b << (shift - 16)) + (lo >> 16) in each half), and one dot-product
+//                   instruction with (1, 1) adds both to the FP32 sum: 1.5 vector instructions per lookup.
+//   half            fused multiply-add with 1.0 that converts its half operand (either half of a register) in
+//                   the same instruction: 1 per lookup.
+//   float           one add.
+// Per query the sub-spaces are added in ascending order, as scan_kernel does.
+//
+// A run of 1, 2, 3 or 4 pairs of one cluster is processed at once (3 in the 4-wide layout with one byte of
+// every entry unused).  A workgroup takes G consecutive pairs of the grouped order and cuts them into
+// such runs at the seams between clusters.
+// LDS: the slot's pair descriptors | tables | R residuals of d floats | per wave and query kGroupStage staged survivors.
+#pragma once
+
+constexpr int kGroupStage = 32;      // survivors a wave stages per query before it appends them; a group with more goes straight to the list
+constexpr int kGroupHead = 128;      // bytes at the start of the kernel's LDS that hold the slot's pair descriptors
+
+// A W-byte word of the interleaved tables, read from LDS address `a` (counted from the start of the
+// workgroup's LDS) through a pointer to a scalar type of that width.
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+#define IVFPQ_LDS_PTR(T, addr) reinterpret_cast<const __attribute__((address_space(3))) T*>(addr)
+template <int W> struct LdsWord;
+template <> struct LdsWord<1> { using type = uint32_t; static __device__ __forceinline__ type load(uint32_t a) { return *IVFPQ_LDS_PTR(uint8_t, a); } };
+template <> struct LdsWord<2> { using type = uint32_t; static __device__ __forceinline__ type load(uint32_t a) { return *IVFPQ_LDS_PTR(uint16_t, a); } };
+template <> struct LdsWord<4> { using type = uint32_t; static __device__ __forceinline__ type load(uint32_t a) { return *IVFPQ_LDS_PTR(uint32_t, a); } };
+template <> struct LdsWord<8> {
+    using type = u32x2_t;
+    static __device__ __forceinline__ type load(uint32_t a) {
+        const unsigned long long v = *IVFPQ_LDS_PTR(unsigned long long, a);
+        return type{(uint32_t)v, (uint32_t)(v >> 32)};
+    }
+};
+template <> struct LdsWord<16> {
+    using type = u32x4_t;
+    static __device__ __forceinline__ type load(uint32_t a) {
+        const __uint128_t v = *IVFPQ_LDS_PTR(__uint128_t, a);
+        return type{(uint32_t)v, (uint32_t)(v >> 32), (uint32_t)(v >> 64), (uint32_t)(v >> 96)};
+    }
+};
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+// byte BYTE of w, shifted left by SH, in one instruction (sub-dword operand select)
+template <int BYTE, int SH>
+__device__ __forceinline__ uint32_t byte_shl(uint32_t w) {
+    if constexpr (SH == 0) {
+        return (w >> (8 * BYTE)) & 255u;
+    } else {
+        uint32_t r;
+        if constexpr (BYTE == 0) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "n"(SH), "v"(w));
+        if constexpr (BYTE == 1) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "n"(SH), "v"(w));
+        if constexpr (BYTE == 2) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "n"(SH), "v"(w));
+        if constexpr (BYTE == 3) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "n"(SH), "v"(w));
+        return r;
+    }
+}
+
+constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): loops whose index must be a constant in
+// the body (register arrays indexed by it stay in registers)
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+
+// 4 * R table entries -- codes u = 0..3 of one lane, queries g = 0..R-1, f[u * R + g] -- converted to the
+// table dtype and stored at `dst` (their place in the interleaved table: 4 * R * entry_bytes contiguous bytes)
+template <int LUT, int R>
+__device__ __forceinline__ void store_packed(unsigned char* dst, const float (&f)[4 * R], const Fp8Params fp8, int hi_v) {
+    if constexpr (LUT == IVFPQ_LUT_FP32) {
+#pragma unroll
+        for (int i = 0; i < R; ++i)
+            reinterpret_cast<float4*>(dst)[i] = make_float4(f[4 * i], f[4 * i + 1], f[4 * i + 2], f[4 * i + 3]);
+    } else if constexpr (LUT == IVFPQ_LUT_FP16) {
+        uint32_t w[2 * R];
+#pragma unroll
+        for (int i = 0; i < 2 * R; ++i) w[i] = half_bits_from_f32(f[2 * i]) | (half_bits_from_f32(f[2 * i + 1]) << 16);
+        if constexpr (R == 1) *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+        else
+#pragma unroll
+            for (int i = 0; i < R / 2; ++i) reinterpret_cast<uint4*>(dst)[i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
+    } else {
+        constexpr int SH = Fp8Format<LUT>::shift;
+        uint32_t w[R];
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const float g4[4] = {f[4 * i], f[4 * i + 1], f[4 * i + 2], f[4 * i + 3]};
+            w[i] = fp8_pack4<SH>(g4, fp8, hi_v);
+        }
+        if constexpr (R == 1) *reinterpret_cast<uint32_t*>(dst) = w[0];
+        else if constexpr (R == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+        else *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// Q pairs of one cluster, q[g], pair[g], with tables interleaved R >= Q wide (Q < R: the entries of the missing
+// queries are zero bytes that nobody decodes; three pairs run as Q = 3 in the R = 4 layout)
+template <int LUT, int NCH, int R, int Q>
+__device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem, const int (&q)[Q], const uint4 (&pair)[Q]) {
+    static_assert(Q >= 1 && Q <= R, "queries of a run fit its interleave width");
+    constexpr int E = LutTraits<LUT>::bytes, W = E * R, LOGW = ilog2(W);
+    const uint32_t len = pair[0].y;
+    if (len == 0) return;
+    const int l = (int)pair[0].x;
+    unsigned char* lut = smem;
+    float* rq = reinterpret_cast<float*>(smem + (size_t)a.pq_dim * 256 * W);
+    unsigned char* after_rq = reinterpret_cast<unsigned char*>(rq) + (((size_t)Q * a.d * 4 + 15) & ~(size_t)15);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const Fp8Params fp8 = a.fp8.fixed;
+    uint32_t bound[Q], seg0[Q], row_pos0[Q], staged[Q];
+    uint2* stage[Q];
+#pragma unroll
+    for (int g = 0; g < Q; ++g) {
+        bound[g] = a.bounds[q[g]];
+        seg0[g] = a.pairs[(size_t)q[g] * a.n_probes + 1].w;
+        row_pos0[g] = pair[g].w;
+        staged[g] = 0;
+        stage[g] = reinterpret_cast<uint2*>(after_rq) + ((size_t)wave * Q + g) * kGroupStage;
+    }
+    const int n_groups = (int)((len + 63u) >> 6);
+    const uint4* cbase = reinterpret_cast<const uint4*>(a.codes + (size_t)pair[0].z * 64 * ((size_t)NCH * 16));
+    auto load_group = [&](uint4 (&buf)[NCH], int grp) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) buf[c] = cbase[((size_t)grp * NCH + c) * 64 + lane];
+    };
+    uint4 buf_a[NCH], buf_b[NCH];
+    int grp = wave;
+    if (grp < n_groups) load_group(buf_a, grp);       // HBM latency overlaps the table build
+
+    // step 2: the residuals against the cluster's centroid
+    for (int t = threadIdx.x; t < a.d; t += blockDim.x) {
+        const float c = a.centroids[(size_t)l * a.d + t];
+#pragma unroll
+        for (int g = 0; g < Q; ++g) rq[g * a.d + t] = a.queries[(size_t)q[g] * a.d + t] - c;
+    }
+    __syncthreads();
+    // step 3: all R tables from one pass over the codebooks (a wave takes whole rows, 4 codes per lane)
+    {
+        int hi_v = fp8.hi;
+        asm volatile("" : "+v"(hi_v));
+        auto rows = [&](auto m_tag) {
+            constexpr int M = decltype(m_tag)::value;
+            auto load_row = [&](int j, float (&cbv)[4 * M]) {
+                const float4* src = reinterpret_cast<const float4*>(a.codebooks + ((size_t)j * 256 + lane * 4) * M);
+#pragma unroll
+                for (int v = 0; v < M; ++v) {
+                    const float4 x = src[v];
+                    cbv[4 * v] = x.x; cbv[4 * v + 1] = x.y; cbv[4 * v + 2] = x.z; cbv[4 * v + 3] = x.w;
+                }
+            };
+            auto finish_row = [&](int j, const float (&cbv)[4 * M]) {
+                float f[4 * R];
+#pragma unroll
+                for (int i = 0; i < 4 * R; ++i) f[i] = 0.f;
+#pragma unroll
+                for (int g = 0; g < Q; ++g) {
+                    float r[M];
+#pragma unroll
+                    for (int t = 0; t < M; ++t) r[t] = rq[g * a.d + j * M + t];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) f[u * R + g] = lut_entry<M>(cbv + u * M, r);
+                }
+                store_packed<LUT, R>(lut + ((size_t)j * 256 + lane * 4) * W, f, fp8, hi_v);
+            };
+            // two rows per trip: both rows' loads are in flight before either is used (one row per trip in the
+            // 4-wide layout, where two would not fit the register budget of four waves per SIMD)
+            int j = wave;
+            if constexpr (R < 4)
+            for (; j + n_waves < a.pq_dim; j += 2 * n_waves) {
+                float c0[4 * M], c1[4 * M];
+                load_row(j, c0);
+                load_row(j + n_waves, c1);
+                finish_row(j, c0);
+                finish_row(j + n_waves, c1);
+            }
+            for (; j < a.pq_dim; j += n_waves) {
+                float c0[4 * M];
+                load_row(j, c0);
+                finish_row(j, c0);
+            }
+        };
+        switch (a.m) {
+            case 1: rows(std::integral_constant<int, 1>{}); break;
+            case 2: rows(std::integral_constant<int, 2>{}); break;
+            default: rows(std::integral_constant<int, 4>{}); break;      // the host admits m = 1, 2, 4 only
+        }
+    }
+    __syncthreads();
+
+    // step 4: Eq. (1) for all R queries
+    // The tables are read through LDS addresses formed as plain integers: `off` comes out of a sub-dword
+    // shift and the row's constant goes into the read's immediate offset, with no add between them.  This
+    // takes the dynamic LDS of the kernel to start at LDS address 0, i.e. the kernel to have no static LDS;
+    // the host verifies that before the first launch (require_no_static_lds).
+    using word_t = typename LdsWord<W>::type;
+    auto lds_word = [&](int row, uint32_t off) __attribute__((always_inline)) -> word_t {
+        return LdsWord<W>::load(off + ((uint32_t)kGroupHead + (uint32_t)row * (256u * W)));
+    };
+    // both halves of a register hold the bf16 pattern of 1.0; decode constant of the 8-bit formats per half
+    const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
+    const uint32_t k2 = ((uint32_t)fp8.lo >> 16) * 0x10001u;
+    auto chunk = [&](const uint4& v, int c, float (&acc)[Q]) __attribute__((always_inline)) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int row = (c * 4 + u) * 4;
+            const uint32_t off[4] = {byte_shl<0, LOGW>(w[u]), byte_shl<1, LOGW>(w[u]), byte_shl<2, LOGW>(w[u]), byte_shl<3, LOGW>(w[u])};
+            if constexpr (kIsFp8<LUT>) {
+                constexpr int S = Fp8Format<LUT>::shift - 16;
+#pragma unroll
+                for (int b = 0; b < 4; b += 2) {
+                    const uint32_t x0 = (uint32_t)lds_word(row + b, off[b]), x1 = (uint32_t)lds_word(row + b + 1, off[b + 1]);
+#pragma unroll
+                    for (int g = 0; g < Q; ++g) {
+                        // bytes g of x0 and x1 into the low bytes of the two halves
+                        uint32_t p = __builtin_amdgcn_perm(x1, x0, 0x0c000c00u | ((4u + g) << 16) | (uint32_t)g);
+                        p = (p << S) + k2;
+                        acc[g] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, p), ones, acc[g], false);
+                    }
+                }
+            } else if constexpr (LUT == IVFPQ_LUT_FP16) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const word_t x = lds_word(row + b, off[b]);
+                    if constexpr (R == 1) {
+                        acc[0] = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)x), 1.0f, acc[0]);
+                    } else if constexpr (R == 2) {
+                        const half2_t h = __builtin_bit_cast(half2_t, x);
+                        acc[0] = __builtin_fmaf((float)h[0], 1.0f, acc[0]);
+                        acc[1] = __builtin_fmaf((float)h[1], 1.0f, acc[1]);
+                    } else {
+                        // (scalar copies first: a bit cast applied to a vector element directly read element 0 for both)
+                        const uint32_t lo = x.x, hi = x.y;
+                        const half2_t h0 = __builtin_bit_cast(half2_t, lo), h1 = __builtin_bit_cast(half2_t, hi);
+                        acc[0] = __builtin_fmaf((float)h0[0], 1.0f, acc[0]);
+                        acc[1] = __builtin_fmaf((float)h0[1], 1.0f, acc[1]);
+                        acc[2] = __builtin_fmaf((float)h1[0], 1.0f, acc[2]);
+                        if constexpr (Q > 3) acc[3] = __builtin_fmaf((float)h1[1], 1.0f, acc[3]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const word_t x = lds_word(row + b, off[b]);
+                    if constexpr (R == 1) {
+                        acc[0] += __uint_as_float(x);
+                    } else if constexpr (R == 2) {
+                        acc[0] += __uint_as_float(x.x); acc[1] += __uint_as_float(x.y);
+                    } else {
+                        acc[0] += __uint_as_float(x.x); acc[1] += __uint_as_float(x.y);
+                        acc[2] += __uint_as_float(x.z);
+                        if constexpr (Q > 3) acc[3] += __uint_as_float(x.w);
+                    }
+                }
+            }
+        }
+    };
+    // Table entries are never negative, so the partial sums only grow: once all 64 x R of them are over their
+    // queries' bounds no vector of the group can survive for any of the queries, and the remaining chunks are
+    // skipped (the partial sums then fail the filter as the full sums would).
+    auto accumulate = [&](const uint4 (&buf)[NCH], float (&acc)[Q]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int g = 0; g < Q; ++g) acc[g] = 0.f;
+        bool over = false;                  // wave-uniform
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if (over) continue;
+            chunk(buf[c], c, acc);
+            if (c + 1 < NCH && a.early_exit) {
+                bool in_race = false;
+#pragma unroll
+                for (int g = 0; g < Q; ++g) in_race = in_race || __float_as_uint(acc[g]) <= bound[g];
+                over = __ballot(in_race) == 0;
+            }
+        }
+    };
+    auto flush = [&](auto g_tag) __attribute__((always_inline)) {
+        constexpr int g = decltype(g_tag)::value;
+        if (staged[g] == 0) return;
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&a.counts[q[g]], staged[g]);
+        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+        uint32_t* dst_key = reinterpret_cast<uint32_t*>(a.R) + (size_t)q[g] * a.stride + seg0[g] + base;
+        uint32_t* dst_pos = a.Rpos + (size_t)q[g] * a.stride + seg0[g] + base;
+        for (uint32_t j = lane; j < staged[g]; j += kWave) {
+            const uint2 e = stage[g][j];
+            dst_key[j] = e.x;
+            dst_pos[j] = e.y;
+        }
+        staged[g] = 0;
+    };
+    auto keep = [&](int grp_i, const float (&acc)[Q]) __attribute__((always_inline)) {
+        const uint32_t i = (uint32_t)grp_i * 64u + lane;
+        const bool real = i < len;                  // the last group is padded with zero codes
+        static_for<Q>([&](auto g_tag) __attribute__((always_inline)) {
+            constexpr int g = decltype(g_tag)::value;
+            const bool ok = real && __float_as_uint(acc[g]) <= bound[g];
+            const unsigned long long m = __ballot(ok);
+            if (m != 0) {
+                const uint32_t cnt = (uint32_t)__popcll(m), rank = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+                if (staged[g] + cnt > (uint32_t)kGroupStage) flush(g_tag);
+                if (cnt > (uint32_t)kGroupStage) {
+                    // more survivors in one group than the staging area holds: appended directly
+                    uint32_t base = 0;
+                    if (lane == 0) base = atomicAdd(&a.counts[q[g]], cnt);
+                    base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+                    if (ok) {
+                        const size_t at = (size_t)q[g] * a.stride + seg0[g] + base + rank;
+                        reinterpret_cast<uint32_t*>(a.R)[at] = __float_as_uint(acc[g]);
+                        a.Rpos[at] = row_pos0[g] + i;
+                    }
+                } else {
+                    if (ok) stage[g][staged[g] + rank] = make_uint2(__float_as_uint(acc[g]), row_pos0[g] + i);
+                    staged[g] += cnt;
+                }
+            }
+        });
+    };
+    float acc[Q];
+    while (grp < n_groups) {
+        const int gn = grp + n_waves;
+        if (gn < n_groups) load_group(buf_b, gn);
+        accumulate(buf_a, acc);
+        keep(grp, acc);
+        if (gn >= n_groups) break;
+        grp = gn + n_waves;
+        if (grp < n_groups) load_group(buf_a, grp);
+        accumulate(buf_b, acc);
+        keep(gn, acc);
+    }
+    static_for<Q>([&](auto g_tag) __attribute__((always_inline)) { flush(g_tag); });
+}
+
+// Workgroup `slot` takes pairs [G slot, G slot + G) of the cluster-grouped order; the slots are dealt to the
+// XCDs in blocks of order_block / G, which is the dealing of scan_kernel's pairs in blocks of order_block.
+// The first kGroupHead bytes of the LDS hold the slot's pair descriptors (the runs read them by position);
+// group_run's `smem` starts behind them.
+template <int LUT, int NCH, int G>
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8)))
+scan_group_kernel(ScanArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    static_assert(G * 20 <= kGroupHead, "descriptors of a slot must fit the head of the LDS");
+    const uint32_t n_slots = (a.n_pairs + (uint32_t)G - 1u) / (uint32_t)G, blk = a.order_block / (uint32_t)G;
+    const uint32_t xcd = blockIdx.x & 7u, rank = blockIdx.x >> 3;
+    const uint32_t slot = ((rank / blk) * 8u + xcd) * blk + rank % blk;
+    if (slot >= n_slots) return;
+    const uint32_t first = slot * (uint32_t)G;
+    const int n_here = (int)(a.n_pairs - first < (uint32_t)G ? a.n_pairs - first : (uint32_t)G);
+    uint4* s_pair = reinterpret_cast<uint4*>(smem);
+    int* s_q = reinterpret_cast<int*>(smem + G * 16);
+    if ((int)threadIdx.x < n_here) {
+        const uint32_t lin = a.order[first + threadIdx.x];
+        const int qi = (int)(lin / (uint32_t)(a.n_probes - 1));
+        s_q[threadIdx.x] = qi;
+        s_pair[threadIdx.x] = a.pairs[(size_t)qi * a.n_probes + 1 + (lin - (uint32_t)qi * (uint32_t)(a.n_probes - 1))];
+    }
+    __syncthreads();
+    auto uni = [](uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); };
+    auto q_at = [&](int i) { return (int)uni((uint32_t)s_q[i]); };
+    auto pair_at = [&](int i) { const uint4 p = s_pair[i]; return make_uint4(uni(p.x), uni(p.y), uni(p.z), uni(p.w)); };
+    unsigned char* body = smem + kGroupHead;
+    // runs of pairs that name the same cluster, each processed at once
+    int i = 0;
+    while (i < n_here) {
+        int r = 1;
+        const uint32_t cl = uni(s_pair[i].x);
+        while (i + r < n_here && uni(s_pair[i + r].x) == cl) ++r;
+        if (i > 0) __syncthreads();          // the previous run's tables are still being read by slower waves
+        bool done = false;
+        if constexpr (G >= 4) {
+            if (r == 4) {
+                const int qq[4] = {q_at(i), q_at(i + 1), q_at(i + 2), q_at(i + 3)};
+                const uint4 pp[4] = {pair_at(i), pair_at(i + 1), pair_at(i + 2), pair_at(i + 3)};
+                group_run<LUT, NCH, 4, 4>(a, body, qq, pp);
+                done = true;
+            } else if (r == 3) {
+                const int qq[3] = {q_at(i), q_at(i + 1), q_at(i + 2)};
+                const uint4 pp[3] = {pair_at(i), pair_at(i + 1), pair_at(i + 2)};
+                group_run<LUT, NCH, 4, 3>(a, body, qq, pp);
+                done = true;
+            }
+        }
+        if (!done) {
+            if (r == 2) {
+                const int qq[2] = {q_at(i), q_at(i + 1)};
+                const uint4 pp[2] = {pair_at(i), pair_at(i + 1)};
+                group_run<LUT, NCH, 2, 2>(a, body, qq, pp);
+            } else {
+                const int qq[1] = {q_at(i)};
+                const uint4 pp[1] = {pair_at(i)};
+                group_run<LUT, NCH, 1, 1>(a, body, qq, pp);
+            }
+        }
+        i += r;
+    }
+}

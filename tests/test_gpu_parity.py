@@ -603,28 +603,57 @@ def test_stream_read_folds_every_word_once(P, n_words, n_wg):
     np.testing.assert_array_equal(out, want)
 
 
-# ---------------------------------------------------------------- two pairs of one cluster per workgroup
+# ---------------------------------------------------------------- several pairs of one cluster per workgroup
 
-@pytest.mark.parametrize("d,pq_dim,n_lists,n_probes,k,dtype_name", [
-    (32, 16, 7, 5, 10, "e5m3"),        # m = 2, few clusters: most neighbouring pairs share theirs
-    (64, 16, 33, 8, 100, "e4m4"),      # m = 4
-    (48, 48, 200, 40, 10, "e5m3"),     # m = 1, three 16-byte chunks, many seams between clusters
-    (128, 64, 3, 3, 1000, "e5m3"),     # four chunks; two pairs per query: odd and even runs
+@pytest.mark.parametrize("d,pq_dim,n_lists,n_probes,k", [
+    (32, 16, 7, 5, 10),        # m = 2, few clusters: most neighbouring pairs share theirs (runs of 4, 3, 2 and 1)
+    (64, 16, 33, 8, 100),      # m = 4
+    (48, 48, 200, 40, 10),     # m = 1, three 16-byte chunks, many seams between clusters
+    (128, 64, 3, 3, 1000),     # four chunks; two pairs per query: odd and even runs
+    (128, 32, 20, 12, 100),    # two chunks, m = 4: the shape of the 10^8-vector workload
 ])
-def test_search_two_pairs_per_workgroup(P, d, pq_dim, n_lists, n_probes, k, dtype_name):
-    # the kernel that shares a cluster's codes and codebooks between two queries is forced on; results
-    # must be those of the oracle, and identical to the one-pair kernel's
-    dtype = {"e5m3": oracle.LUT_E5M3, "e4m4": oracle.LUT_E4M4}[dtype_name]
+@pytest.mark.parametrize("dtype_name", ["e5m3", "e4m4", "fp16", "fp32"])
+def test_search_group_of_pairs_per_workgroup(P, d, pq_dim, n_lists, n_probes, k, dtype_name):
+    # the kernel that interleaves the tables of two or four queries of one cluster is forced on; results must be
+    # those of the oracle, and identical to the one-pair kernel's (same arithmetic per query, same order)
+    dtype = {"e5m3": oracle.LUT_E5M3, "e4m4": oracle.LUT_E4M4, "fp16": oracle.LUT_FP16, "fp32": oracle.LUT_FP32}[dtype_name]
     oidx, gidx = random_pair(P, 9000, d, n_lists, pq_dim, 8, salt=900 + d, empty_lists=(1,) if n_lists > 3 else ())
     q = np.random.default_rng(900 + d).standard_normal((257, d)).astype(np.float32)
     gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, 1)
+    assert gidx.ivfpq_scan_kernel_info(dtype).startswith("scan_kernel")
     ids_one, d_one = gidx.ivfpq_search(q, n_probes, k, dtype)
-    gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, 2)
-    _step(f"two pairs per workgroup d={d} s={pq_dim} L={n_lists} P={n_probes} k={k} {dtype_name}")
-    ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, n_probes, k, dtype)
-    assert_topk_matches(ids_g, d_g, ids_o, d_o, context="two pairs per workgroup")
-    np.testing.assert_array_equal(d_g, d_one.cpu().numpy())
-    np.testing.assert_array_equal(ids_g, ids_one.cpu().numpy())
+    for share in (2, 4):
+        gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, share)
+        info = gidx.ivfpq_scan_kernel_info(dtype)
+        _step(f"{share} pairs per workgroup d={d} s={pq_dim} L={n_lists} P={n_probes} k={k} {dtype_name}: {info}")
+        if not info.startswith("scan_group_kernel"):
+            continue                      # tables of that many queries do not fit the LDS
+        ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, n_probes, k, dtype)
+        assert_topk_matches(ids_g, d_g, ids_o, d_o, context=f"{share} pairs per workgroup")
+        np.testing.assert_array_equal(d_g, d_one.cpu().numpy())
+        np.testing.assert_array_equal(ids_g, ids_one.cpu().numpy())
+    gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, 0)
+
+
+def test_group_kernel_survivor_overflow_and_small_batches(P):
+    # a bound that admits everything (nearest cluster smaller than k) makes every vector of the big cluster a
+    # survivor: groups with more survivors than a wave stages are appended directly; also 1, 2 and 3 queries
+    # (slots that are not full) and a workspace limit that cuts the batch into tiles
+    n, d = 21000, 64
+    cent, cb, _, codes, ids = si.random_index_arrays(n, d, 3, 32, 8, salt=811)
+    offs = np.array([0, 40, 20040, 21000], dtype=np.int64)
+    oidx = oracle.make_index(d, 3, 32, 8, cent, cb, offs, codes, ids)
+    gidx = to_library(P, oidx)
+    rng = np.random.default_rng(811)
+    for nq in (1, 2, 3, 9):
+        q = (cent[0] + 0.01 * rng.standard_normal((nq, d))).astype(np.float32)       # nearest cluster: the 40-vector one
+        for share in (2, 4):
+            gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, share)
+            for dtype in (oracle.LUT_E5M3, oracle.LUT_FP16):
+                _step(f"overflow nq={nq} share={share} dtype={dtype}")
+                ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, 3, 1000, dtype)
+                assert_topk_matches(ids_g, d_g, ids_o, d_o, context="group kernel, every vector survives")
+    gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, 0)
 
 
 @pytest.mark.parametrize("d,pq_dim,pq_bits,dtype", [
