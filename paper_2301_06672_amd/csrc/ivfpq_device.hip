@@ -37,6 +37,7 @@
 
 #include "ivfpq_internal.hpp"
 #include "ivfpq_rank.hpp"
+#include "ivfpq_lds_util.hpp"
 
 using namespace ivfpq;
 
@@ -963,6 +964,21 @@ template <int BITS> struct CodeGroup {
 template <int LUT, int BITS>
 __device__ inline float add_group(float acc, const unsigned char* lut, const uint32_t* w, int row0, const Fp8Params fp8) {
     constexpr int SPG = CodeGroup<BITS>::SPG, KSUB = 1 << BITS;
+    if constexpr (BITS == 8 && (LUT == IVFPQ_LUT_FP16 || LUT == IVFPQ_LUT_FP32)) {
+        // Whole-byte codes and entries of 2 or 4 bytes: the entry's byte offset in its row comes out of one
+        // sub-dword shift, the row's offset goes into the LDS read's immediate, and a half entry is converted by
+        // the instruction that adds it: 2 vector instructions per lookup.  (The table sits at LDS address 0: the
+        // kernel has no static LDS, which the host verifies before the first launch.)
+        constexpr int E = LutTraits<LUT>::bytes, LG = ilog2(E);
+        const uint32_t off[4] = {byte_shl<0, LG>(w[0]), byte_shl<1, LG>(w[0]), byte_shl<2, LG>(w[0]), byte_shl<3, LG>(w[0])};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t x = LdsWord<E>::load(off[s] + (uint32_t)(row0 + s) * (uint32_t)(KSUB * E));
+            if constexpr (LUT == IVFPQ_LUT_FP16) acc = add_half_lo(acc, x);
+            else acc += __uint_as_float(x);
+        }
+        return acc;
+    }
 #pragma unroll
     for (int s = 0; s < SPG; ++s) {
         constexpr uint32_t mask = (uint32_t)KSUB - 1u;
@@ -1674,7 +1690,7 @@ int scan_threads(const ivfpq_index* idx, int lut_dtype) {
     // one pair then overlaps the scan of more others
     size_t lds = scan_lds_bytes(idx, lut_dtype);
     if (idx->n_lists > 0 && idx->n / idx->n_lists >= 24 * 64 && lds <= 24 * 1024) return 128;
-    if (lds <= 20 * 1024) return 256;
+    if (lds <= 32 * 1024) return 256;       // (half table, 48 sub-spaces, 29 KB: 1.19 ms with 256 threads, 1.26 with 512)
     if (lds <= 40 * 1024) return 512;
     if (2 * (lds + (size_t)16 * kStageCap * 8) <= kLdsBytes) return 1024;
     return 512;
@@ -1687,10 +1703,28 @@ constexpr uint32_t kOrderBlock = 64;     // consecutive pairs of the grouped ord
 
 bool group_pairs_by_cluster(size_t n_pairs) { return n_pairs < ((size_t)1 << 32) - 8 * (size_t)kOrderBlock; }
 
+// The scan kernels address their tables by LDS offsets counted from 0: their dynamic LDS must be the first
+// thing in the workgroup's LDS, which holds when the compiled kernel has no static LDS.  Checked once per
+// kernel (hipFuncGetAttributes is not a stream operation; later launches make no call besides the launch).
+int require_no_static_lds(const void* kernel) {
+    static std::mutex mu;
+    static std::vector<const void*> ok;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const void* k : ok)
+        if (k == kernel) return IVFPQ_OK;
+    hipFuncAttributes attr;
+    HIP_TRY(hipFuncGetAttributes(&attr, kernel));
+    if (attr.sharedSizeBytes != 0)
+        return fail(IVFPQ_EUNSUPPORTED, "internal: a scan kernel was built with %zu bytes of static LDS", (size_t)attr.sharedSizeBytes);
+    ok.push_back(kernel);
+    return IVFPQ_OK;
+}
+
 template <int LUT, int BITS>
 int launch_scan_bits(const ScanArgs& a, int cw, int nch, dim3 grid, int threads, size_t lds, hipStream_t st) {
     auto go = [&](auto kernel) -> int {
         if (int s = allow_full_lds(kernel)) return s;
+        if (int s = require_no_static_lds(reinterpret_cast<const void*>(kernel))) return s;
         hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, st, a);
         HIP_TRY(hipGetLastError());
         return IVFPQ_OK;
@@ -1726,25 +1760,9 @@ int launch_scan_lut(const ScanArgs& a, int bits, int cw, int nch, dim3 grid, int
 }
 
 // ---- the group kernel: up to G pairs of one cluster per workgroup, tables interleaved entry by entry ----
-// The group kernel addresses its tables by LDS offsets counted from 0: its dynamic LDS must be the first
-// thing in the workgroup's LDS, which holds when the compiled kernel has no static LDS.  Checked once per
-// kernel (hipFuncGetAttributes is not a stream operation; later launches make no call besides the launch).
-int require_no_static_lds(const void* kernel) {
-    static std::mutex mu;
-    static std::vector<const void*> ok;
-    std::lock_guard<std::mutex> lock(mu);
-    for (const void* k : ok)
-        if (k == kernel) return IVFPQ_OK;
-    hipFuncAttributes attr;
-    HIP_TRY(hipFuncGetAttributes(&attr, kernel));
-    if (attr.sharedSizeBytes != 0)
-        return fail(IVFPQ_EUNSUPPORTED, "internal: the group scan kernel was built with %zu bytes of static LDS", (size_t)attr.sharedSizeBytes);
-    ok.push_back(kernel);
-    return IVFPQ_OK;
-}
 size_t scan_group_lds_bytes(const ivfpq_index* idx, int lut_dtype, int G, int threads) {
     return kGroupHead + (size_t)idx->pq_dim * 256 * G * lut_elem_bytes(lut_dtype) + (((size_t)G * idx->d * 4 + 15) & ~(size_t)15)
-           + (size_t)(threads / 64) * G * kGroupStage * 8 + (size_t)idx->tuning.lds_pad;
+           + (size_t)(threads / 64) * kGroupStageAll * 8 + (size_t)idx->tuning.lds_pad;
 }
 // Workgroup size of the group kernel.  Measured on MI355X (filtered scan, 10,000 queries): with long lists (24 or
 // more 64-vector groups on average) two-wave workgroups win when six or more of them share a compute unit's LDS
@@ -1775,6 +1793,10 @@ int scan_group_width(const ivfpq_index* idx, int lut_dtype, const Fp8Mode& fp8, 
         if (want == G) { if (lds <= kLdsBytes) return G; continue; }
         if (G == 4 && !one_byte) continue;
         if (lut_dtype == IVFPQ_LUT_FP32) continue;
+        // 64 sub-spaces with the early exit on: scan_kernel builds the second half of a table only if some group
+        // still needs it, which saves more than sharing does (10^6 vectors, e5m3: 1.42-1.49 ms against 1.53-1.54;
+        // without the early exit 3.27 against 2.38, so the rule follows the switch)
+        if (idx->code_bytes() == 64 && idx->tuning.early_exit >= 0) continue;
         if (lds <= 40 * 1024) return G;
     }
     return 0;

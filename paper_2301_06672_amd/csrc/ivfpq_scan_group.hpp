@@ -19,69 +19,19 @@
 //                   both into bf16 ((b << (shift - 16)) + (lo >> 16) in each half), and one dot-product
 //                   instruction with (1, 1) adds both to the FP32 sum: 1.5 vector instructions per lookup.
 //   half            fused multiply-add with 1.0 that converts its half operand (either half of a register) in
-//                   the same instruction: 1 per lookup.
+//                   the same instruction (add_half_lo / add_half_hi): 1 per lookup.
 //   float           one add.
 // Per query the sub-spaces are added in ascending order, as scan_kernel does.
 //
 // A run of 1, 2, 3 or 4 pairs of one cluster is processed at once (3 in the 4-wide layout with one byte of
 // every entry unused).  A workgroup takes G consecutive pairs of the grouped order and cuts them into
 // such runs at the seams between clusters.
-// LDS: the slot's pair descriptors | tables | R residuals of d floats | per wave and query kGroupStage staged survivors.
+// LDS: the slot's pair descriptors | tables | R residuals of d floats | per wave kGroupStageAll staged survivors.
 #pragma once
 
-constexpr int kGroupStage = 32;      // survivors a wave stages per query before it appends them; a group with more goes straight to the list
+constexpr int kGroupStageAll = 128;  // survivors a wave stages before it appends them, over all queries of a run: 128 / R per query
+                                     // (a 64-vector group with more survivors than that goes straight to the list)
 constexpr int kGroupHead = 128;      // bytes at the start of the kernel's LDS that hold the slot's pair descriptors
-
-// A W-byte word of the interleaved tables, read from LDS address `a` (counted from the start of the
-// workgroup's LDS) through a pointer to a scalar type of that width.
-typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-#define IVFPQ_LDS_PTR(T, addr) reinterpret_cast<const __attribute__((address_space(3))) T*>(addr)
-template <int W> struct LdsWord;
-template <> struct LdsWord<1> { using type = uint32_t; static __device__ __forceinline__ type load(uint32_t a) { return *IVFPQ_LDS_PTR(uint8_t, a); } };
-template <> struct LdsWord<2> { using type = uint32_t; static __device__ __forceinline__ type load(uint32_t a) { return *IVFPQ_LDS_PTR(uint16_t, a); } };
-template <> struct LdsWord<4> { using type = uint32_t; static __device__ __forceinline__ type load(uint32_t a) { return *IVFPQ_LDS_PTR(uint32_t, a); } };
-template <> struct LdsWord<8> {
-    using type = u32x2_t;
-    static __device__ __forceinline__ type load(uint32_t a) {
-        const unsigned long long v = *IVFPQ_LDS_PTR(unsigned long long, a);
-        return type{(uint32_t)v, (uint32_t)(v >> 32)};
-    }
-};
-template <> struct LdsWord<16> {
-    using type = u32x4_t;
-    static __device__ __forceinline__ type load(uint32_t a) {
-        const __uint128_t v = *IVFPQ_LDS_PTR(__uint128_t, a);
-        return type{(uint32_t)v, (uint32_t)(v >> 32), (uint32_t)(v >> 64), (uint32_t)(v >> 96)};
-    }
-};
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-
-// byte BYTE of w, shifted left by SH, in one instruction (sub-dword operand select)
-template <int BYTE, int SH>
-__device__ __forceinline__ uint32_t byte_shl(uint32_t w) {
-    if constexpr (SH == 0) {
-        return (w >> (8 * BYTE)) & 255u;
-    } else {
-        uint32_t r;
-        if constexpr (BYTE == 0) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "n"(SH), "v"(w));
-        if constexpr (BYTE == 1) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "n"(SH), "v"(w));
-        if constexpr (BYTE == 2) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "n"(SH), "v"(w));
-        if constexpr (BYTE == 3) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "n"(SH), "v"(w));
-        return r;
-    }
-}
-
-constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
-
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): loops whose index must be a constant in
-// the body (register arrays indexed by it stay in registers)
-template <class F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
 
 // 4 * R table entries -- codes u = 0..3 of one lane, queries g = 0..R-1, f[u * R + g] -- converted to the
 // table dtype and stored at `dst` (their place in the interleaved table: 4 * R * entry_bytes contiguous bytes)
@@ -119,6 +69,7 @@ template <int LUT, int NCH, int R, int Q>
 __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem, const int (&q)[Q], const uint4 (&pair)[Q]) {
     static_assert(Q >= 1 && Q <= R, "queries of a run fit its interleave width");
     constexpr int E = LutTraits<LUT>::bytes, W = E * R, LOGW = ilog2(W);
+    constexpr int kGroupStage = kGroupStageAll / R;
     const uint32_t len = pair[0].y;
     if (len == 0) return;
     const int l = (int)pair[0].x;
@@ -245,19 +196,16 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
                 for (int b = 0; b < 4; ++b) {
                     const word_t x = lds_word(row + b, off[b]);
                     if constexpr (R == 1) {
-                        acc[0] = __builtin_fmaf((float)__builtin_bit_cast(_Float16, (uint16_t)x), 1.0f, acc[0]);
+                        acc[0] = add_half_lo(acc[0], x);
                     } else if constexpr (R == 2) {
-                        const half2_t h = __builtin_bit_cast(half2_t, x);
-                        acc[0] = __builtin_fmaf((float)h[0], 1.0f, acc[0]);
-                        acc[1] = __builtin_fmaf((float)h[1], 1.0f, acc[1]);
+                        acc[0] = add_half_lo(acc[0], x);
+                        acc[1] = add_half_hi(acc[1], x);
                     } else {
-                        // (scalar copies first: a bit cast applied to a vector element directly read element 0 for both)
                         const uint32_t lo = x.x, hi = x.y;
-                        const half2_t h0 = __builtin_bit_cast(half2_t, lo), h1 = __builtin_bit_cast(half2_t, hi);
-                        acc[0] = __builtin_fmaf((float)h0[0], 1.0f, acc[0]);
-                        acc[1] = __builtin_fmaf((float)h0[1], 1.0f, acc[1]);
-                        acc[2] = __builtin_fmaf((float)h1[0], 1.0f, acc[2]);
-                        if constexpr (Q > 3) acc[3] = __builtin_fmaf((float)h1[1], 1.0f, acc[3]);
+                        acc[0] = add_half_lo(acc[0], lo);
+                        acc[1] = add_half_hi(acc[1], lo);
+                        acc[2] = add_half_lo(acc[2], hi);
+                        if constexpr (Q > 3) acc[3] = add_half_hi(acc[3], hi);
                     }
                 }
             } else {
