@@ -32,7 +32,10 @@ LDS_PEAK_LOOKUPS = 256 * 32 * 2.4e9     # conflict-free wave-wide LDS reads: 32 
 # rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a plain
 # copy of known size); the summary file under profiles/ holds the command and the raw figures.
 PROFILED_TRAFFIC = {
-    # (workload, table dtype): (bytes per launch, summary file)
+    # (workload, table dtype): (bytes per launch of the dominant kernel, early exit off; summary file)
+    ("intgrid_100m_p8", "e5m3"): (4993892089, "profiles/scan_kernel_intgrid_100m_p8_e5m3_hbm_traffic.txt"),
+    ("unitnorm_10m", "e5m3"): (745758804, "profiles/scan_kernel_unitnorm_10m_e5m3_hbm_traffic.txt"),
+    ("intgrid_1m", "e5m3"): (300754989, "profiles/scan_kernel_intgrid_1m_e5m3_hbm_traffic.txt"),
 }
 
 
