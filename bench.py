@@ -125,7 +125,7 @@ def main():
                     help="force the filtered scan's early exit off / on for every run (default: the library's, on)")
     ap.add_argument("--lds-pad", type=int, default=0, metavar="BYTES",
                     help="extra LDS requested per scan workgroup (occupancy experiment: a small table at a large table's footprint)")
-    ap.add_argument("--scan-share", type=int, default=0, choices=(0, 1, 2, 4, 102), help="ivfpq_set_tuning(IVFPQ_TUNE_SCAN_SHARE)")
+    ap.add_argument("--scan-share", type=int, default=0, choices=(0, 1, 2, 4), help="ivfpq_set_tuning(IVFPQ_TUNE_SCAN_SHARE)")
     ap.add_argument("--scan-threads", type=int, default=0, help="ivfpq_set_tuning(IVFPQ_TUNE_SCAN_THREADS)")
     ap.add_argument("--no-full-run", action="store_true",
                     help="skip the extra headline run without early exit (profiling runs: keeps the number of search calls fixed)")

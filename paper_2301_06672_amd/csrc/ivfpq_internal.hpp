@@ -24,7 +24,7 @@ struct Fp8Options {
 struct Tuning {
     int32_t scan_threads = 0;   // workgroup size of the scan kernels (64 ... 1024)
     int32_t order_block = 0;    // consecutive pairs of the cluster-grouped order that stay on one XCD
-    int32_t scan_share = 0;     // 0: heuristic; 1: one (query, probe) pair per workgroup; 2: two pairs of a cluster wherever possible
+    int32_t scan_share = 0;     // 0: heuristic; 1: one (query, probe) pair per workgroup; 2 or 4: up to that many pairs of a cluster
     int32_t early_exit = 0;     // 0: on (default); 1: on; -1: off (every lookup of Eq. (1) is made)
     int32_t lds_pad = 0;        // extra bytes of LDS requested per scan workgroup (occupancy experiments)
 };
