@@ -558,7 +558,7 @@ int check_build_plan(const BuildPlan& P) {
         const size_t gy = (P.tile_rows + 63) / 64, gx = ((size_t)k + 63) / 64;
         if (gy > kGridY) return fail(IVFPQ_EUNSUPPORTED, "internal: ranking tile of %zu rows needs %zu grid rows (limit %zu)", P.tile_rows, gy, kGridY);
         if (gx > kGridX) return fail(IVFPQ_EUNSUPPORTED, "%d centres need %zu grid columns", k, gx);
-        if (int s = grid_ok(P.tile_rows * (size_t)(coarse_padded_dim(P.d) / 8), 256, "splitting a tile of rows into bf16 halves")) return s;
+        if (int s = grid_ok(split_rows_padded(P.tile_rows) * (size_t)(coarse_padded_dim(P.d) / 8), 256, "splitting a tile of rows into bf16 halves")) return s;
     }
     const size_t strips = ((size_t)P.n_lists + 31) / 32;
     if (P.use_strips && P.tile_rows * strips >= ((size_t)1 << 32))

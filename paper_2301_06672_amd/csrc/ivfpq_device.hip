@@ -478,7 +478,11 @@ select_probes_kernel(uint32_t* __restrict__ A, const StripSummary* __restrict__ 
     __shared__ RowSelectShared t;
     __shared__ float s_part[SEL_THREADS / kWave];
     SelectShared& s = t.sel;
-    const int q = blockIdx.x;
+    // Workgroup b runs on XCD b % 8.  Inside every block of 64 queries the eight workgroups of one XCD take eight
+    // consecutive queries: their strip summaries (16 bytes per query and strip, strip-major) share 128-byte lines,
+    // so a line is fetched into one XCD's L2 instead of all eight.
+    const int b = blockIdx.x;
+    const int q = b < (int)(gridDim.x & ~63u) ? (b & ~63) + ((b & 7) << 3) + ((b >> 3) & 7) : b;
     const int tid = threadIdx.x, nth = blockDim.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6, n_waves = nth >> 6;
     const float* qv = queries + (size_t)q * d;
@@ -1622,7 +1626,7 @@ int make_plan(const ivfpq_index* idx, int64_t nq, int32_t n_probes, bool given_p
     size_t per_query = (size_t)stride * 8 + (need_D ? ((size_t)idx->n_lists + 4 * strips + coarse_padded_dim(idx->d)) * 4 : 0);
     // what does not grow with the tile: three per-cluster counter arrays, the centroids' bf16 halves, alignment slack
     const size_t fixed = 3 * align_up((size_t)idx->n_lists * 4)
-                         + (need_D ? coarse_split_bytes(0, (size_t)idx->n_lists, idx->d) : 0) + 24 * kAlign;
+                         + (need_D ? coarse_split_bytes(128, (size_t)idx->n_lists, idx->d) : 0) + 24 * kAlign;      // 128: the query rows' padding
     per_query += (size_t)n_probes * 28 + 16;      // probe lists, distances, offsets, descriptors, order, bound, counter
     int64_t tile = limit > fixed ? (int64_t)((limit - fixed) / per_query) : 1;
     tile = std::max<int64_t>(1, std::min<int64_t>(tile, std::max<int64_t>(nq, 1)));

@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <type_traits>
 #include <utility>
 #include <vector>
 
@@ -266,7 +267,6 @@ coarse_rank_kernel(const float* __restrict__ queries, const float* __restrict__ 
 // ------------------------------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int BK = 16;        // components per LDS slice = one matrix instruction deep
-constexpr int BPITCH = 24;    // LDS row pitch in bf16: 48 bytes, so 8 consecutive rows' 16-byte reads cover all banks
 
 __device__ inline uint32_t bf16_round(float f) {          // round to nearest even; Inf stays Inf, NaN stays NaN
     const uint32_t b = __float_as_uint(f);
@@ -274,38 +274,77 @@ __device__ inline uint32_t bf16_round(float f) {          // round to nearest ev
     return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
 }
 
-// X[rows][d] fp32 -> hi, lo [rows][dp] bf16, components d..dp-1 zero; one thread per 8 components
+// X[rows][d] fp32 -> hi, lo in bf16, laid out slice by slice: [dp / 16][rows_pad][16], rows_pad = rows rounded
+// up to the tile edge of 128, so that the 128 rows x 16 components which a workgroup of the GEMM stages per
+// step are 4 KiB of consecutive memory (row-major operands give it 32 bytes out of every row: a quarter of
+// each cache line fetched, four times over).  Components d..dp-1 and rows beyond the matrix are zero.  One
+// thread per 8 components.
+__host__ __device__ inline size_t split_rows_padded(size_t rows) { return (rows + 127) / 128 * 128; }
 __global__ void __launch_bounds__(256)
-split_bf16_kernel(const float* __restrict__ X, size_t rows, int d, int dp, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo) {
+split_bf16_kernel(const float* __restrict__ X, size_t rows, size_t rows_pad, int d, int dp, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo) {
     const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int per_row = dp / 8;
     const size_t row = t / per_row;
     const int k0 = (int)(t % per_row) * 8;
-    if (row >= rows) return;
+    if (row >= rows_pad) return;
     uint32_t h[8], l[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-        const float x = k0 + u < d ? X[row * d + k0 + u] : 0.f;
+        const float x = (row < rows && k0 + u < d) ? X[row * d + k0 + u] : 0.f;
         h[u] = bf16_round(x);
         const float rest = x - __uint_as_float(h[u] << 16);
         l[u] = (rest == rest) ? bf16_round(rest) : 0u;       // Inf - Inf: the hi part already carries it
     }
     uint4 H = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
     uint4 L = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
-    *reinterpret_cast<uint4*>(hi + row * dp + k0) = H;
-    *reinterpret_cast<uint4*>(lo + row * dp + k0) = L;
+    const size_t at = ((size_t)(k0 / BK) * rows_pad + row) * BK + (k0 % BK);
+    *reinterpret_cast<uint4*>(hi + at) = H;
+    *reinterpret_cast<uint4*>(lo + at) = L;
 }
 
-// 128 queries x 128 clusters per workgroup; wave w stages operand array w (Qh, Ql, Ch, Cl) of the slice.
+// Inserts x into the ascending triple (m1, m2, m3) of the smallest values seen: three instructions.
+__device__ inline uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ inline void low3_insert(Low3& m, uint32_t x) {
+    m.m3 = umed3(m.m2, x, m.m3);
+    m.m2 = umed3(m.m1, x, m.m2);
+    m.m1 = umin32(m.m1, x);
+}
+
+// Staging of one operand slice in LDS for the bf16 kernel: 128 rows x 16 components = 32 bytes per row, no
+// padding; the two 16-byte pieces of a row swap places in every second group of four rows, so that the
+// 16-byte reads of eight consecutive rows (one piece each) cover all 32 banks.
+__device__ inline int split_piece_at(int row, int piece) { return row * 16 + ((piece ^ ((row >> 2) & 1)) << 3); }   // in bf16
+
+// 128 x 128 outputs per workgroup, 4 waves 2 x 2, each 2 x 2 blocks of v_mfma_f32_32x32x16_bf16; wave w stages
+// operand array w (Qh, Ql, Ch, Cl) of a slice of 16 components.  Two LDS buffers, one barrier per slice: slice
+// s + 1 is stored while slice s is multiplied, slice s + 2 travels in registers.
+// STRIPS = false: rows of the accumulator blocks are queries, columns clusters; every key is stored
+// (rank_store).  STRIPS = true: the matrix roles are swapped -- rows are clusters, columns queries -- so that a
+// lane holds, for ONE query (its column), 32 of the 64 clusters of a strip in registers: the three smallest
+// tagged keys of the strip come from an in-register insertion (three instructions per key) and a single
+// exchange with the lane 32 further, instead of a fold across 32 lanes.
+template <bool STRIPS>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 coarse_rank_split_kernel(const uint16_t* __restrict__ Qh, const uint16_t* __restrict__ Ql,
                          const uint16_t* __restrict__ Ch, const uint16_t* __restrict__ Cl,
                          const float* __restrict__ centroid_norms, int nq, int n_lists, int dp,
                          uint32_t* __restrict__ A, StripSummary* __restrict__ S) {
-    __shared__ __attribute__((aligned(16))) uint16_t tile[4][128 * BPITCH];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ __attribute__((aligned(16))) uint16_t tile[2][4][128 * BK];
+    __shared__ __attribute__((aligned(16))) float cn_s[128];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave >> 1, wc = wave & 1, half = lane >> 5, l32 = lane & 31;
-    const int q0 = blockIdx.y * 128, l0 = blockIdx.x * 128;
+    // Workgroup b runs on XCD b % 8.  Every XCD owns one eighth of the query tiles, whose operands then stay in
+    // its L2, and walks the cluster tiles in the outer loop, so that a cluster tile is fetched into that L2 once
+    // per pass and used by all of the XCD's query tiles in turn (one query tile row after the other re-reads
+    // every cluster tile from beyond the L2 instead).
+    const int q_tiles = (nq + 127) / 128, per_xcd = (q_tiles + 7) / 8;
+    const int rank = blockIdx.x >> 3, c_tile = rank / per_xcd, q_tile = (blockIdx.x & 7) + 8 * (rank % per_xcd);
+    if (q_tile >= q_tiles) return;                 // the grid is padded to 8 x per_xcd query tiles
+    const int q0 = q_tile * 128, l0 = c_tile * 128;
     floatx16 acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -316,38 +355,50 @@ coarse_rank_split_kernel(const uint16_t* __restrict__ Qh, const uint16_t* __rest
 
     const uint16_t* src = wave == 0 ? Qh : (wave == 1 ? Ql : (wave == 2 ? Ch : Cl));
     const int row0 = wave < 2 ? q0 : l0, n_rows = wave < 2 ? nq : n_lists;
+    if (STRIPS && tid < 128) cn_s[tid] = l0 + tid < n_lists ? centroid_norms[l0 + tid] : 0.f;   // read after the loop's barriers
     uint4 pre[4];
-    // a slice of one operand array is 128 rows x 32 bytes = 256 16-byte pieces, four per lane
-    auto fetch = [&](int k0) {
+    // a slice of one operand array, 128 rows x 32 bytes, is 256 consecutive 16-byte pieces: four per lane
+    const size_t rows_pad = split_rows_padded((size_t)n_rows);
+    const uint16_t* src0 = src + (size_t)row0 * BK + lane * 8;
+    auto fetch = [&](int slice) __attribute__((always_inline)) {
+        const uint16_t* at = src0 + (size_t)slice * rows_pad * BK;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const int piece = c * 64 + lane, r = row0 + (piece >> 1);
-            pre[c] = r < n_rows ? *reinterpret_cast<const uint4*>(src + (size_t)r * dp + k0 + (piece & 1) * 8)
-                                : make_uint4(0u, 0u, 0u, 0u);
+            const uint4* pp = reinterpret_cast<const uint4*>(at + c * 512);
+            pre[c] = make_uint4(pp->x, pp->y, pp->z, pp->w);
         }
     };
-    fetch(0);
-    for (int k0 = 0; k0 < dp; k0 += BK) {
+    auto stash = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int piece = c * 64 + lane;
-            *reinterpret_cast<uint4*>(&tile[wave][(piece >> 1) * BPITCH + (piece & 1) * 8]) = pre[c];
+            *reinterpret_cast<uint4*>(&tile[buf][wave][split_piece_at(piece >> 1, piece & 1)]) = pre[c];
         }
-        __syncthreads();
-        if (k0 + BK < dp) fetch(k0 + BK);      // the next slice travels while this one is multiplied
+    };
+    // the operand arrays of the accumulator's rows and columns
+    constexpr int RH = STRIPS ? 2 : 0, RL = STRIPS ? 3 : 1, CH = STRIPS ? 0 : 2, CL = STRIPS ? 1 : 3;
+    const int n_slices = dp / BK;
+    fetch(0);
+    stash(0);
+    if (n_slices > 1) fetch(1);
+    __syncthreads();
+    for (int sl = 0; sl < n_slices; ++sl) {
+        const int buf = sl & 1;
+        if (sl + 1 < n_slices) stash(buf ^ 1);                 // its last readers passed the barrier that ended slice sl - 1
+        if (sl + 2 < n_slices) fetch(sl + 2);
         // operand of lane L: row L % 32, components 8 * (L / 32) .. + 7
         bf16x8 ah[2], al[2], bh[2], bl[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int at = ((wr * 2 + i) * 32 + l32) * BPITCH + half * 8;
-            ah[i] = *reinterpret_cast<const bf16x8*>(&tile[0][at]);
-            al[i] = *reinterpret_cast<const bf16x8*>(&tile[1][at]);
+            const int at = split_piece_at((wr * 2 + i) * 32 + l32, half);
+            ah[i] = *reinterpret_cast<const bf16x8*>(&tile[buf][RH][at]);
+            al[i] = *reinterpret_cast<const bf16x8*>(&tile[buf][RL][at]);
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int at = ((wc * 2 + j) * 32 + l32) * BPITCH + half * 8;
-            bh[j] = *reinterpret_cast<const bf16x8*>(&tile[2][at]);
-            bl[j] = *reinterpret_cast<const bf16x8*>(&tile[3][at]);
+            const int at = split_piece_at((wc * 2 + j) * 32 + l32, half);
+            bh[j] = *reinterpret_cast<const bf16x8*>(&tile[buf][CH][at]);
+            bl[j] = *reinterpret_cast<const bf16x8*>(&tile[buf][CL][at]);
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -359,7 +410,48 @@ coarse_rank_split_kernel(const uint16_t* __restrict__ Qh, const uint16_t* __rest
             }
         __syncthreads();
     }
-    rank_store<2>(acc, q0, l0, nq, n_lists, centroid_norms, A, S, reinterpret_cast<StripSummary*>(&tile[0][0]));
+    if constexpr (!STRIPS) {
+        rank_store<2>(acc, q0, l0, nq, n_lists, centroid_norms, A, S, reinterpret_cast<StripSummary*>(&tile[0][0][0]));
+    } else {
+        // Register v of lane L of block (i, j): cluster l0 + 64 wr + 32 i + 8 (v / 4) + 4 (L / 32) + v % 4, query
+        // q0 + 64 wc + 32 j + L % 32.  The tag of a key is the cluster's position in the wave's strip of 64.
+        const int strip = c_tile * 2 + wr, n_strips = (n_lists + 63) / 64;
+        const int n_valid = n_lists - (l0 + wr * 64);              // clusters of this strip that exist
+        const float* cn = cn_s + wr * 64 + 4 * half;
+        // the three smallest tagged keys among this lane's 32 clusters of query block j
+        auto lane_low3 = [&](int j, auto partial) __attribute__((always_inline)) {
+            Low3 m{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 c4 = *reinterpret_cast<const float4*>(cn + i * 32 + 8 * g);
+                    const float cv[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int pos = i * 32 + 8 * g + u;        // + 4 * half, added once by the caller
+                        const uint32_t key = ordered_key(__builtin_fmaf(-2.f, acc[i][j][4 * g + u], cv[u]));
+                        uint32_t tagged = (key & ~63u) | (uint32_t)pos;
+                        if (decltype(partial)::value && pos + 4 * half >= n_valid) tagged = 0xFFFFFFFFu;
+                        low3_insert(m, tagged);
+                    }
+                }
+            return m;
+        };
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            // only the last strip of all can be short of clusters
+            Low3 m = n_valid >= 64 ? lane_low3(j, std::false_type{}) : lane_low3(j, std::true_type{});
+            // all-ones stays all-ones; every other key of this lane gets the half-wave's bit of the position
+            m.m1 |= 4u * half; m.m2 |= 4u * half; m.m3 |= 4u * half;
+            const Low3 other{(uint32_t)__shfl_xor((int)m.m1, 32, kWave), (uint32_t)__shfl_xor((int)m.m2, 32, kWave),
+                             (uint32_t)__shfl_xor((int)m.m3, 32, kWave)};
+            m = merge_low3(m, other);
+            const int qi = q0 + wc * 64 + j * 32 + l32;
+            if (half == 0 && qi < nq && strip < n_strips)
+                S[(size_t)strip * nq + qi] = make_uint4(m.m1, m.m2, m.m3, 0xFFFFFFFFu);
+        }
+    }
 }
 
 // |a_computed - a_exact| <= this, for either ranking kernel (qn = |q|^2, cmax = max |c|^2): the split
@@ -386,23 +478,27 @@ inline bool coarse_use_strips(int nq, int n_lists, int k) {
 }
 inline int coarse_padded_dim(int d) { return (d + BK - 1) / BK * BK; }
 inline size_t coarse_split_bytes(size_t nq_max, size_t n_lists, int d) {
-    return 2 * (align_up(nq_max * coarse_padded_dim(d) * 2) + align_up(n_lists * coarse_padded_dim(d) * 2));
+    return 2 * (align_up(split_rows_padded(nq_max) * coarse_padded_dim(d) * 2) + align_up(split_rows_padded(n_lists) * coarse_padded_dim(d) * 2));
 }
 
 int launch_coarse(const float* q, const float* centroids, const float* centroid_norms, int nq, int n_lists, int d,
                   uint32_t* A, StripSummary* S, void* split_ws, hipStream_t st) {
     if (coarse_big_tiles(nq, n_lists)) {
         const int dp = coarse_padded_dim(d);
-        const size_t q_bytes = align_up((size_t)nq * dp * 2), c_bytes = align_up((size_t)n_lists * dp * 2);
+        const size_t q_pad = split_rows_padded((size_t)nq), c_pad = split_rows_padded((size_t)n_lists);
+        const size_t q_bytes = align_up(q_pad * dp * 2), c_bytes = align_up(c_pad * dp * 2);
         uint16_t* qh = (uint16_t*)split_ws;
         uint16_t* ql = (uint16_t*)((unsigned char*)split_ws + q_bytes);
         uint16_t* ch = (uint16_t*)((unsigned char*)split_ws + 2 * q_bytes);
         uint16_t* cl = (uint16_t*)((unsigned char*)split_ws + 2 * q_bytes + c_bytes);
-        const size_t q_threads = (size_t)nq * (dp / 8), c_threads = (size_t)n_lists * (dp / 8);
-        hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((q_threads + 255) / 256)), dim3(256), 0, st, q, (size_t)nq, d, dp, qh, ql);
-        hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((c_threads + 255) / 256)), dim3(256), 0, st, centroids, (size_t)n_lists, d, dp, ch, cl);
-        dim3 grid((n_lists + 127) / 128, (nq + 127) / 128);
-        hipLaunchKernelGGL(coarse_rank_split_kernel, grid, dim3(256), 0, st, qh, ql, ch, cl, centroid_norms, nq, n_lists, dp, A, S);
+        const size_t q_threads = q_pad * (dp / 8), c_threads = c_pad * (dp / 8);
+        hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((q_threads + 255) / 256)), dim3(256), 0, st, q, (size_t)nq, q_pad, d, dp, qh, ql);
+        hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)((c_threads + 255) / 256)), dim3(256), 0, st, centroids, (size_t)n_lists, c_pad, d, dp, ch, cl);
+        const size_t blocks = (size_t)((n_lists + 127) / 128) * 8 * (((nq + 127) / 128 + 7) / 8);
+        if (blocks > 0x7FFFFFFFull) return fail(IVFPQ_EINVAL, "ranking grid of %zu workgroups exceeds the launch limit", blocks);
+        dim3 grid((unsigned)blocks);
+        if (S) hipLaunchKernelGGL(coarse_rank_split_kernel<true>, grid, dim3(256), 0, st, qh, ql, ch, cl, centroid_norms, nq, n_lists, dp, A, S);
+        else hipLaunchKernelGGL(coarse_rank_split_kernel<false>, grid, dim3(256), 0, st, qh, ql, ch, cl, centroid_norms, nq, n_lists, dp, A, S);
     } else {
         dim3 grid((n_lists + 63) / 64, (nq + 63) / 64);
         hipLaunchKernelGGL(coarse_rank_kernel<1>, grid, dim3(256), 0, st, q, centroids, centroid_norms, nq, n_lists, d, A, S);
