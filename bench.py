@@ -443,7 +443,8 @@ def main():
         # a first small pass sizes the sample so that one pass takes about 4 s; then best of 3
         probe_n = min(nq, 4 * cores)
         t = time.perf_counter()
-        oracle.search(oidx, queries_np[:probe_n], n_probes, k, lut_ids[args.lut], e4m4_bias=e4m4_bias)
+        _, _, table_stats = oracle.search(oidx, queries_np[:probe_n], n_probes, k, lut_ids[args.lut], e4m4_bias=e4m4_bias,
+                                          return_stats=True)
         rate0 = probe_n / (time.perf_counter() - t)
         nc = args.cpu_queries or int(min(nq, max(cores, rate0 * 4.0)))
         nc = max(cores, nc // cores * cores)
@@ -461,7 +462,11 @@ def main():
         cpu = {"value": round(nc / min(times), 1), "unit": "queries/s", "cores": cores, "kind": "oracle",
                "sample": f"first {nc} of the {nq} queries, same index, lut={args.lut}, best of 3 passes "
                          f"({', '.join(f'{x:.1f}' for x in times)} s wall)",
-               "one_thread": {"value": round(n1 / dt1, 1), "sample": f"first {n1} queries, one pass, {dt1:.1f}s wall"}}
+               "one_thread": {"value": round(n1 / dt1, 1), "sample": f"first {n1} queries, one pass, {dt1:.1f}s wall"},
+               # entries of the 8-bit tables that fell under the smallest / over the largest code (oracle's count)
+               "table_entries": {"sample": f"tables of the first {probe_n} queries",
+                                 "entries": int(probe_n) * int(n_probes) * int(w.pq_dim) * (1 << int(w.pq_bits)),
+                                 "floored": table_stats["floored"], "saturated": table_stats["saturated"]}}
         log(f"cpu oracle: {cpu}")
 
     def rnd(x, nd=4):
