@@ -39,6 +39,15 @@ PROFILED_TRAFFIC = {
 }
 
 
+# Which unit the dominant kernel keeps busiest.  NOT measured by this process either: busy shares of the vector
+# ALU and of the LDS from a recorded rocprofv3 --pmc run of the same command (early exit off).
+PROFILED_UNITS = {
+    ("intgrid_100m_p8", "e5m3"): ({"valu_busy": 0.93, "lds_busy": 0.51}, "profiles/scan_kernel_intgrid_100m_p8_lds_counters.txt"),
+    ("unitnorm_10m", "e5m3"): ({"valu_busy": 0.94, "lds_busy": 0.66}, "profiles/scan_kernel_unitnorm_10m_lds_counters.txt"),
+    ("intgrid_1m", "e5m3"): ({"valu_busy": 0.98, "lds_busy": 0.90}, "profiles/scan_kernel_intgrid_1m_lds_counters.txt"),
+}
+
+
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -416,6 +425,10 @@ def main():
             "launches_per_step": "one per query tile; one tile at this workload unless the workspace limit is lowered",
             "run": "every lookup of Eq. (1) made (early exit off)" if full_is_exact else
                    "default run: the early exit skips an unknown share of the lookups counted here, so achieved and frac are upper bounds",
+            "recorded_unit_shares": None if (w.name, args.lut) not in PROFILED_UNITS else
+                dict(PROFILED_UNITS[(w.name, args.lut)][0], source=PROFILED_UNITS[(w.name, args.lut)][1] +
+                     ": recorded rocprofv3 --pmc run, not measured by this process; the vector ALU, not the LDS, is what "
+                     "the 8-bit table's kernel keeps busiest"),
             "traffic": None if traffic is None else traffic[0],
             "traffic_source": None if traffic is None else
                 f"{traffic[1]}: recorded rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, not measured by this process",
