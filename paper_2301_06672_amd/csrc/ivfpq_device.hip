@@ -1765,7 +1765,7 @@ int launch_scan_lut(const ScanArgs& a, int bits, int cw, int nch, dim3 grid, int
 
 // ---- the group kernel: up to G pairs of one cluster per workgroup, tables interleaved entry by entry ----
 size_t scan_group_lds_bytes(const ivfpq_index* idx, int lut_dtype, int G, int threads) {
-    return kGroupHead + (size_t)idx->pq_dim * 256 * G * lut_elem_bytes(lut_dtype) + (((size_t)G * idx->d * 4 + 15) & ~(size_t)15)
+    return kGroupHead + (size_t)idx->pq_dim * ((size_t)1 << idx->pq_bits) * G * lut_elem_bytes(lut_dtype) + (((size_t)G * idx->d * 4 + 15) & ~(size_t)15)
            + (size_t)(threads / 64) * kGroupStageAll * 8 + (size_t)idx->tuning.lds_pad;
 }
 // Workgroup size of the group kernel.  Measured on MI355X (filtered scan, 10,000 queries): with long lists (24 or
@@ -1777,14 +1777,17 @@ int scan_group_threads(const ivfpq_index* idx, int lut_dtype, int G) {
     const bool long_lists = idx->n_lists > 0 && idx->n / idx->n_lists >= 24 * 64;
     return long_lists && scan_group_lds_bytes(idx, lut_dtype, G, 128) <= 24 * 1024 ? 128 : 256;
 }
-// How many pairs of a cluster share a workgroup (0: the group kernel does not apply).  It serves 8-bit codes
-// in 16-byte chunks, sub-vectors of 1, 2 or 4 components and fixed encoding constants.  The widest layout whose
-// workgroup leaves room for four workgroups per compute unit (40 KB of LDS) is taken -- four pairs only for the
-// one-byte table dtypes: with wider entries the LDS read of four entries costs what it saves.  Measured (filtered
-// scan, 10,000 queries; one / two / four pairs): e5m3 at 10^8 vectors, 32 sub-spaces: 6.02 / 4.81 / 4.58 ms; at 10^7,
-// 48 sub-spaces: 1.08 / 0.96 / 1.05; half at 10^8: 6.58 / 5.63 / 7.19; float: 8.30 / 8.75 / -.
+// How many pairs of a cluster share a workgroup (0: the group kernel does not apply).  It serves 8-bit and 4-bit
+// codes in 16-byte chunks, sub-vectors of 1, 2 or 4 components and fixed encoding constants.  The widest layout
+// whose workgroup leaves room for four workgroups per compute unit (40 KB of LDS) is taken.  With 8-bit codes,
+// four pairs only for the one-byte table dtypes: with wider entries the LDS read of four entries costs what it
+// saves.  Measured (filtered scan, 10,000 queries; one / two / four pairs): e5m3 at 10^8 vectors, 32 sub-spaces:
+// 6.02 / 4.81 / 4.58 ms; at 10^7, 48 sub-spaces: 1.08 / 0.96 / 1.05; half at 10^8: 6.58 / 5.63 / 7.19; float:
+// 8.30 / 8.75 / -.  With 4-bit codes (16-entry rows, a few KB of tables) four pairs for every dtype: 10^8 vectors,
+// 64 sub-spaces, e5m3 6.67 / 5.95 / 5.21 ms, half 7.56 / 6.48 / 4.62, float 6.31 / 4.71 / 4.02.
 int scan_group_width(const ivfpq_index* idx, int lut_dtype, const Fp8Mode& fp8, uint32_t order_block) {
-    if (idx->pq_bits != 8 || chunk_width(idx) != 16 || fp8.per_table) return 0;
+    if ((idx->pq_bits != 8 && idx->pq_bits != 4) || chunk_width(idx) != 16 || fp8.per_table) return 0;
+    if (idx->pq_bits == 4 && idx->pq_dim % 16 != 0) return 0;      // the table is built in blocks of 256 entries
     const int m = idx->d / idx->pq_dim;
     if (m != 1 && m != 2 && m != 4) return 0;
     const int want = idx->tuning.scan_share;
@@ -1795,12 +1798,14 @@ int scan_group_width(const ivfpq_index* idx, int lut_dtype, const Fp8Mode& fp8, 
         if (order_block < (uint32_t)G || order_block % (uint32_t)G) continue;
         const size_t lds = scan_group_lds_bytes(idx, lut_dtype, G, scan_group_threads(idx, lut_dtype, G));
         if (want == G) { if (lds <= kLdsBytes) return G; continue; }
-        if (G == 4 && !one_byte) continue;
-        if (lut_dtype == IVFPQ_LUT_FP32) continue;
+        if (idx->pq_bits == 8) {
+            if (G == 4 && !one_byte) continue;
+            if (lut_dtype == IVFPQ_LUT_FP32) continue;
+        }
         // 64 sub-spaces with the early exit on: scan_kernel builds the second half of a table only if some group
         // still needs it, which saves more than sharing does (10^6 vectors, e5m3: 1.42-1.49 ms against 1.53-1.54;
         // without the early exit 3.27 against 2.38, so the rule follows the switch)
-        if (idx->code_bytes() == 64 && idx->tuning.early_exit >= 0) continue;
+        if (idx->pq_bits == 8 && idx->code_bytes() == 64 && idx->tuning.early_exit >= 0) continue;
         if (lds <= 40 * 1024) return G;
     }
     return 0;
@@ -1821,11 +1826,18 @@ int launch_scan_group(const ivfpq_index* idx, const ScanArgs& a, int lut_dtype, 
     const int nch = idx->code_bytes() / 16;
     auto by_nch = [&](auto lut_tag, auto g_tag) -> int {
         constexpr int LUT = decltype(lut_tag)::value, GG = decltype(g_tag)::value;
+        if (idx->pq_bits == 4)
+            switch (nch) {
+                case 1: return go(scan_group_kernel<LUT, 1, GG, 4>);
+                case 2: return go(scan_group_kernel<LUT, 2, GG, 4>);
+                case 3: return go(scan_group_kernel<LUT, 3, GG, 4>);
+                default: return go(scan_group_kernel<LUT, 4, GG, 4>);
+            }
         switch (nch) {
-            case 1: return go(scan_group_kernel<LUT, 1, GG>);
-            case 2: return go(scan_group_kernel<LUT, 2, GG>);
-            case 3: return go(scan_group_kernel<LUT, 3, GG>);
-            default: return go(scan_group_kernel<LUT, 4, GG>);
+            case 1: return go(scan_group_kernel<LUT, 1, GG, 8>);
+            case 2: return go(scan_group_kernel<LUT, 2, GG, 8>);
+            case 3: return go(scan_group_kernel<LUT, 3, GG, 8>);
+            default: return go(scan_group_kernel<LUT, 4, GG, 8>);
         }
     };
     auto by_g = [&](auto lut_tag) -> int {
@@ -2307,7 +2319,7 @@ int ivfpq_scan_kernel_info(const ivfpq_index_t* idx, int32_t lut_dtype, char* bu
     const int threads = scan_threads(idx, lut_dtype), cw = chunk_width(idx), nch = idx->code_bytes() / cw;
     const uint32_t blk = idx->tuning.order_block > 0 ? (uint32_t)idx->tuning.order_block : kOrderBlock;
     if (const int G = scan_group_width(idx, lut_dtype, fp8_mode(idx, lut_dtype), blk))
-        snprintf(buf, buf_bytes, "scan_group_kernel<%s, %d chunks, %d pairs> %d threads, %zu bytes of LDS", names[lut_dtype], nch, G,
+        snprintf(buf, buf_bytes, "scan_group_kernel<%s, %d-bit codes, %d chunks, %d pairs> %d threads, %zu bytes of LDS", names[lut_dtype], idx->pq_bits, nch, G,
                  scan_group_threads(idx, lut_dtype, G), scan_group_lds_bytes(idx, lut_dtype, G, scan_group_threads(idx, lut_dtype, G)));
     else
         snprintf(buf, buf_bytes, "scan_kernel<%s, %d-bit codes, %d-byte chunks x %d> %d threads, %zu bytes of LDS", names[lut_dtype],

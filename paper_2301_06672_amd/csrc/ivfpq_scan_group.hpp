@@ -1,11 +1,11 @@
-// The filtered scan for up to G (query, probe) pairs of ONE cluster per workgroup (8-bit codes in 16-byte
-// chunks, every table dtype).  Included by ivfpq_device.hip after the table helpers it uses.
+// The filtered scan for up to G (query, probe) pairs of ONE cluster per workgroup (8-bit or 4-bit codes in
+// 16-byte chunks, every table dtype).  Included by ivfpq_device.hip after the table helpers it uses.
 //
 // In the cluster-grouped order neighbouring pairs share their cluster, and everything that depends on the
 // cluster alone is then done once for all of them: a codebook entry is loaded once and becomes R table
 // entries, a code chunk is loaded once, and -- the point of this kernel -- one LDS read serves R lookups:
 // the R tables are interleaved ENTRY BY ENTRY, entry (sub-space j, code c, query g) at byte
-//     ((j * 256 + c) * R + g) * entry_bytes,
+//     ((j * 2^pq_bits + c) * R + g) * entry_bytes,
 // so the R entries a code selects are adjacent and come back from a single ds_read of R * entry_bytes
 // (four e5m3 entries in one 32-bit bank word; two halves in one; two floats in a 64-bit read).  What the LDS
 // spends per lookup therefore falls with the entry size (Sec. I-D's argument, carried over from "fewer
@@ -22,6 +22,9 @@
 //                   the same instruction (add_half_lo / add_half_hi): 1 per lookup.
 //   float           one add.
 // Per query the sub-spaces are added in ascending order, as scan_kernel does.
+// 4-bit codes: a byte holds the codes of sub-spaces 2b (low nibble) and 2b + 1; the low and the high nibbles of a
+// code word are masked and shifted to entry offsets four at a time (two instructions per four offsets), so that
+// byte b of the one result is the LDS offset for sub-space 2b and byte b of the other that for 2b + 1.
 //
 // A run of 1, 2, 3 or 4 pairs of one cluster is processed at once (3 in the 4-wide layout with one byte of
 // every entry unused).  A workgroup takes G consecutive pairs of the grouped order and cuts them into
@@ -65,16 +68,18 @@ __device__ __forceinline__ void store_packed(unsigned char* dst, const float (&f
 
 // Q pairs of one cluster, q[g], pair[g], with tables interleaved R >= Q wide (Q < R: the entries of the missing
 // queries are zero bytes that nobody decodes; three pairs run as Q = 3 in the R = 4 layout)
-template <int LUT, int NCH, int R, int Q>
+template <int LUT, int NCH, int R, int Q, int BITS>
 __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem, const int (&q)[Q], const uint4 (&pair)[Q]) {
     static_assert(Q >= 1 && Q <= R, "queries of a run fit its interleave width");
-    constexpr int E = LutTraits<LUT>::bytes, W = E * R, LOGW = ilog2(W);
+    static_assert(BITS == 8 || BITS == 4, "codes of 8 or 4 bits");
+    constexpr int E = LutTraits<LUT>::bytes, W = E * R, LOGW = ilog2(W), KSUB = 1 << BITS;
+    static_assert(BITS == 8 || 15 * W < 256, "a 4-bit code's entry offset fits a byte");
     constexpr int kGroupStage = kGroupStageAll / R;
     const uint32_t len = pair[0].y;
     if (len == 0) return;
     const int l = (int)pair[0].x;
     unsigned char* lut = smem;
-    float* rq = reinterpret_cast<float*>(smem + (size_t)a.pq_dim * 256 * W);
+    float* rq = reinterpret_cast<float*>(smem + (size_t)a.pq_dim * KSUB * W);
     unsigned char* after_rq = reinterpret_cast<unsigned char*>(rq) + (((size_t)Q * a.d * 4 + 15) & ~(size_t)15);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
@@ -107,7 +112,9 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
         for (int g = 0; g < Q; ++g) rq[g * a.d + t] = a.queries[(size_t)q[g] * a.d + t] - c;
     }
     __syncthreads();
-    // step 3: all R tables from one pass over the codebooks (a wave takes whole rows, 4 codes per lane)
+    // step 3: all R tables from one pass over the codebooks.  A wave takes blocks of 256 consecutive entries of the
+    // table, 4 codes per lane: one row of an 8-bit sub-space, 16 rows of 4-bit sub-spaces (a lane's four codes
+    // then belong to sub-space 16 block + lane / 4; the host admits only tables that are whole blocks)
     {
         int hi_v = fp8.hi;
         asm volatile("" : "+v"(hi_v));
@@ -128,8 +135,9 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
 #pragma unroll
                 for (int g = 0; g < Q; ++g) {
                     float r[M];
+                    const int sub = BITS == 8 ? j : j * 16 + (lane >> 2);
 #pragma unroll
-                    for (int t = 0; t < M; ++t) r[t] = rq[g * a.d + j * M + t];
+                    for (int t = 0; t < M; ++t) r[t] = rq[g * a.d + sub * M + t];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) f[u * R + g] = lut_entry<M>(cbv + u * M, r);
                 }
@@ -137,16 +145,17 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
             };
             // two rows per trip: both rows' loads are in flight before either is used (one row per trip in the
             // 4-wide layout, where two would not fit the register budget of four waves per SIMD)
+            const int n_blocks = a.pq_dim * KSUB / 256;
             int j = wave;
             if constexpr (R < 4)
-            for (; j + n_waves < a.pq_dim; j += 2 * n_waves) {
+            for (; j + n_waves < n_blocks; j += 2 * n_waves) {
                 float c0[4 * M], c1[4 * M];
                 load_row(j, c0);
                 load_row(j + n_waves, c1);
                 finish_row(j, c0);
                 finish_row(j + n_waves, c1);
             }
-            for (; j < a.pq_dim; j += n_waves) {
+            for (; j < n_blocks; j += n_waves) {
                 float c0[4 * M];
                 load_row(j, c0);
                 finish_row(j, c0);
@@ -167,61 +176,73 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
     // the host verifies that before the first launch (require_no_static_lds).
     using word_t = typename LdsWord<W>::type;
     auto lds_word = [&](int row, uint32_t off) __attribute__((always_inline)) -> word_t {
-        return LdsWord<W>::load(off + ((uint32_t)kGroupHead + (uint32_t)row * (256u * W)));
+        return LdsWord<W>::load(off + ((uint32_t)kGroupHead + (uint32_t)row * ((uint32_t)KSUB * W)));
     };
     // both halves of a register hold the bf16 pattern of 1.0; decode constant of the 8-bit formats per half
     const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
     const uint32_t k2 = ((uint32_t)fp8.lo >> 16) * 0x10001u;
+    // adds the entries of two consecutive sub-spaces, x0 then x1 (the words of all R queries), to every query's sum
+    auto add_two = [&](const word_t& x0, const word_t& x1, float (&acc)[Q]) __attribute__((always_inline)) {
+        if constexpr (kIsFp8<LUT>) {
+            constexpr int S = Fp8Format<LUT>::shift - 16;
+#pragma unroll
+            for (int g = 0; g < Q; ++g) {
+                // bytes g of x0 and x1 into the low bytes of the two halves
+                uint32_t p = __builtin_amdgcn_perm((uint32_t)x1, (uint32_t)x0, 0x0c000c00u | ((4u + g) << 16) | (uint32_t)g);
+                p = (p << S) + k2;
+                acc[g] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, p), ones, acc[g], false);
+            }
+        } else if constexpr (LUT == IVFPQ_LUT_FP16) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const word_t& x = b == 0 ? x0 : x1;
+                if constexpr (R == 1) {
+                    acc[0] = add_half_lo(acc[0], x);
+                } else if constexpr (R == 2) {
+                    acc[0] = add_half_lo(acc[0], x);
+                    acc[1] = add_half_hi(acc[1], x);
+                } else {
+                    const uint32_t lo = x.x, hi = x.y;
+                    acc[0] = add_half_lo(acc[0], lo);
+                    acc[1] = add_half_hi(acc[1], lo);
+                    acc[2] = add_half_lo(acc[2], hi);
+                    if constexpr (Q > 3) acc[3] = add_half_hi(acc[3], hi);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const word_t& x = b == 0 ? x0 : x1;
+                if constexpr (R == 1) {
+                    acc[0] += __uint_as_float(x);
+                } else if constexpr (R == 2) {
+                    acc[0] += __uint_as_float(x.x); acc[1] += __uint_as_float(x.y);
+                } else {
+                    acc[0] += __uint_as_float(x.x); acc[1] += __uint_as_float(x.y);
+                    acc[2] += __uint_as_float(x.z);
+                    if constexpr (Q > 3) acc[3] += __uint_as_float(x.w);
+                }
+            }
+        }
+    };
     auto chunk = [&](const uint4& v, int c, float (&acc)[Q]) __attribute__((always_inline)) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int row = (c * 4 + u) * 4;
-            const uint32_t off[4] = {byte_shl<0, LOGW>(w[u]), byte_shl<1, LOGW>(w[u]), byte_shl<2, LOGW>(w[u]), byte_shl<3, LOGW>(w[u])};
-            if constexpr (kIsFp8<LUT>) {
-                constexpr int S = Fp8Format<LUT>::shift - 16;
+            if constexpr (BITS == 8) {
+                const int row = (c * 4 + u) * 4;
+                const uint32_t off[4] = {byte_shl<0, LOGW>(w[u]), byte_shl<1, LOGW>(w[u]), byte_shl<2, LOGW>(w[u]), byte_shl<3, LOGW>(w[u])};
 #pragma unroll
-                for (int b = 0; b < 4; b += 2) {
-                    const uint32_t x0 = (uint32_t)lds_word(row + b, off[b]), x1 = (uint32_t)lds_word(row + b + 1, off[b + 1]);
-#pragma unroll
-                    for (int g = 0; g < Q; ++g) {
-                        // bytes g of x0 and x1 into the low bytes of the two halves
-                        uint32_t p = __builtin_amdgcn_perm(x1, x0, 0x0c000c00u | ((4u + g) << 16) | (uint32_t)g);
-                        p = (p << S) + k2;
-                        acc[g] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, p), ones, acc[g], false);
-                    }
-                }
-            } else if constexpr (LUT == IVFPQ_LUT_FP16) {
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const word_t x = lds_word(row + b, off[b]);
-                    if constexpr (R == 1) {
-                        acc[0] = add_half_lo(acc[0], x);
-                    } else if constexpr (R == 2) {
-                        acc[0] = add_half_lo(acc[0], x);
-                        acc[1] = add_half_hi(acc[1], x);
-                    } else {
-                        const uint32_t lo = x.x, hi = x.y;
-                        acc[0] = add_half_lo(acc[0], lo);
-                        acc[1] = add_half_hi(acc[1], lo);
-                        acc[2] = add_half_lo(acc[2], hi);
-                        if constexpr (Q > 3) acc[3] = add_half_hi(acc[3], hi);
-                    }
-                }
+                for (int b = 0; b < 4; b += 2) add_two(lds_word(row + b, off[b]), lds_word(row + b + 1, off[b + 1]), acc);
             } else {
+                // byte b of lo4 / hi4: the entry offset of the code in the low / high nibble of byte b
+                constexpr uint32_t kNibbles = 0x0F0F0F0Fu << LOGW;
+                const uint32_t lo4 = (w[u] << LOGW) & kNibbles, hi4 = (w[u] >> (4 - LOGW)) & kNibbles;
+                const int row = (c * 4 + u) * 8;
+                const uint32_t off_lo[4] = {byte_shl<0, 0>(lo4), byte_shl<1, 0>(lo4), byte_shl<2, 0>(lo4), byte_shl<3, 0>(lo4)};
+                const uint32_t off_hi[4] = {byte_shl<0, 0>(hi4), byte_shl<1, 0>(hi4), byte_shl<2, 0>(hi4), byte_shl<3, 0>(hi4)};
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const word_t x = lds_word(row + b, off[b]);
-                    if constexpr (R == 1) {
-                        acc[0] += __uint_as_float(x);
-                    } else if constexpr (R == 2) {
-                        acc[0] += __uint_as_float(x.x); acc[1] += __uint_as_float(x.y);
-                    } else {
-                        acc[0] += __uint_as_float(x.x); acc[1] += __uint_as_float(x.y);
-                        acc[2] += __uint_as_float(x.z);
-                        if constexpr (Q > 3) acc[3] += __uint_as_float(x.w);
-                    }
-                }
+                for (int b = 0; b < 4; ++b) add_two(lds_word(row + 2 * b, off_lo[b]), lds_word(row + 2 * b + 1, off_hi[b]), acc);
             }
         }
     };
@@ -305,7 +326,7 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
 // XCDs in blocks of order_block / G, which is the dealing of scan_kernel's pairs in blocks of order_block.
 // The first kGroupHead bytes of the LDS hold the slot's pair descriptors (the runs read them by position);
 // group_run's `smem` starts behind them.
-template <int LUT, int NCH, int G>
+template <int LUT, int NCH, int G, int BITS>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8)))
 scan_group_kernel(ScanArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -341,12 +362,12 @@ scan_group_kernel(ScanArgs a) {
             if (r == 4) {
                 const int qq[4] = {q_at(i), q_at(i + 1), q_at(i + 2), q_at(i + 3)};
                 const uint4 pp[4] = {pair_at(i), pair_at(i + 1), pair_at(i + 2), pair_at(i + 3)};
-                group_run<LUT, NCH, 4, 4>(a, body, qq, pp);
+                group_run<LUT, NCH, 4, 4, BITS>(a, body, qq, pp);
                 done = true;
             } else if (r == 3) {
                 const int qq[3] = {q_at(i), q_at(i + 1), q_at(i + 2)};
                 const uint4 pp[3] = {pair_at(i), pair_at(i + 1), pair_at(i + 2)};
-                group_run<LUT, NCH, 4, 3>(a, body, qq, pp);
+                group_run<LUT, NCH, 4, 3, BITS>(a, body, qq, pp);
                 done = true;
             }
         }
@@ -354,11 +375,11 @@ scan_group_kernel(ScanArgs a) {
             if (r == 2) {
                 const int qq[2] = {q_at(i), q_at(i + 1)};
                 const uint4 pp[2] = {pair_at(i), pair_at(i + 1)};
-                group_run<LUT, NCH, 2, 2>(a, body, qq, pp);
+                group_run<LUT, NCH, 2, 2, BITS>(a, body, qq, pp);
             } else {
                 const int qq[1] = {q_at(i)};
                 const uint4 pp[1] = {pair_at(i)};
-                group_run<LUT, NCH, 1, 1>(a, body, qq, pp);
+                group_run<LUT, NCH, 1, 1, BITS>(a, body, qq, pp);
             }
         }
         i += r;

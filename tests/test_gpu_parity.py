@@ -605,19 +605,23 @@ def test_stream_read_folds_every_word_once(P, n_words, n_wg):
 
 # ---------------------------------------------------------------- several pairs of one cluster per workgroup
 
-@pytest.mark.parametrize("d,pq_dim,n_lists,n_probes,k", [
-    (32, 16, 7, 5, 10),        # m = 2, few clusters: most neighbouring pairs share theirs (runs of 4, 3, 2 and 1)
-    (64, 16, 33, 8, 100),      # m = 4
-    (48, 48, 200, 40, 10),     # m = 1, three 16-byte chunks, many seams between clusters
-    (128, 64, 3, 3, 1000),     # four chunks; two pairs per query: odd and even runs
-    (128, 32, 20, 12, 100),    # two chunks, m = 4: the shape of the 10^8-vector workload
+@pytest.mark.parametrize("d,pq_dim,pq_bits,n_lists,n_probes,k", [
+    (32, 16, 8, 7, 5, 10),        # m = 2, few clusters: most neighbouring pairs share theirs (runs of 4, 3, 2 and 1)
+    (64, 16, 8, 33, 8, 100),      # m = 4
+    (48, 48, 8, 200, 40, 10),     # m = 1, three 16-byte chunks, many seams between clusters
+    (128, 64, 8, 3, 3, 1000),     # four chunks; two pairs per query: odd and even runs
+    (128, 32, 8, 20, 12, 100),    # two chunks, m = 4: the shape of the 10^8-vector workload with 8-bit codes
+    (128, 64, 4, 20, 12, 100),    # 4-bit codes, two chunks, m = 2: the shape of the 10^8-vector workload with 4-bit codes
+    (32, 32, 4, 7, 5, 10),        # 4-bit codes, one chunk, m = 1
+    (128, 32, 4, 33, 8, 1000),    # 4-bit codes, one chunk, m = 4
+    (96, 96, 4, 50, 20, 10),      # 4-bit codes, three chunks
 ])
 @pytest.mark.parametrize("dtype_name", ["e5m3", "e4m4", "fp16", "fp32"])
-def test_search_group_of_pairs_per_workgroup(P, d, pq_dim, n_lists, n_probes, k, dtype_name):
+def test_search_group_of_pairs_per_workgroup(P, d, pq_dim, pq_bits, n_lists, n_probes, k, dtype_name):
     # the kernel that interleaves the tables of two or four queries of one cluster is forced on; results must be
     # those of the oracle, and identical to the one-pair kernel's (same arithmetic per query, same order)
     dtype = {"e5m3": oracle.LUT_E5M3, "e4m4": oracle.LUT_E4M4, "fp16": oracle.LUT_FP16, "fp32": oracle.LUT_FP32}[dtype_name]
-    oidx, gidx = random_pair(P, 9000, d, n_lists, pq_dim, 8, salt=900 + d, empty_lists=(1,) if n_lists > 3 else ())
+    oidx, gidx = random_pair(P, 9000, d, n_lists, pq_dim, pq_bits, salt=900 + d, empty_lists=(1,) if n_lists > 3 else ())
     q = np.random.default_rng(900 + d).standard_normal((257, d)).astype(np.float32)
     gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, 1)
     assert gidx.ivfpq_scan_kernel_info(dtype).startswith("scan_kernel")
@@ -625,7 +629,7 @@ def test_search_group_of_pairs_per_workgroup(P, d, pq_dim, n_lists, n_probes, k,
     for share in (2, 4):
         gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, share)
         info = gidx.ivfpq_scan_kernel_info(dtype)
-        _step(f"{share} pairs per workgroup d={d} s={pq_dim} L={n_lists} P={n_probes} k={k} {dtype_name}: {info}")
+        _step(f"{share} pairs per workgroup d={d} s={pq_dim} p={pq_bits} L={n_lists} P={n_probes} k={k} {dtype_name}: {info}")
         if not info.startswith("scan_group_kernel"):
             continue                      # tables of that many queries do not fit the LDS
         ids_g, d_g, ids_o, d_o = _search_both(gidx, oidx, q, n_probes, k, dtype)
