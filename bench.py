@@ -36,6 +36,7 @@ PROFILED_TRAFFIC = {
     ("intgrid_100m_p8", "e5m3"): (4993892089, "profiles/scan_kernel_intgrid_100m_p8_e5m3_hbm_traffic.txt"),
     ("unitnorm_10m", "e5m3"): (745758804, "profiles/scan_kernel_unitnorm_10m_e5m3_hbm_traffic.txt"),
     ("intgrid_1m", "e5m3"): (300754989, "profiles/scan_kernel_intgrid_1m_e5m3_hbm_traffic.txt"),
+    ("intgrid_100m_p4", "e5m3"): (6251391079, "profiles/scan_kernel_intgrid_100m_p4_e5m3_hbm_traffic.txt"),
 }
 
 
@@ -45,6 +46,7 @@ PROFILED_UNITS = {
     ("intgrid_100m_p8", "e5m3"): ({"valu_busy": 0.93, "lds_busy": 0.51}, "profiles/scan_kernel_intgrid_100m_p8_lds_counters.txt"),
     ("unitnorm_10m", "e5m3"): ({"valu_busy": 0.94, "lds_busy": 0.66}, "profiles/scan_kernel_unitnorm_10m_lds_counters.txt"),
     ("intgrid_1m", "e5m3"): ({"valu_busy": 0.98, "lds_busy": 0.90}, "profiles/scan_kernel_intgrid_1m_lds_counters.txt"),
+    ("intgrid_100m_p4", "e5m3"): ({"valu_busy": 0.97, "lds_busy": 0.27}, "profiles/scan_kernel_intgrid_100m_p4_lds_counters.txt"),
 }
 
 
