@@ -1766,7 +1766,7 @@ int launch_scan_lut(const ScanArgs& a, int bits, int cw, int nch, dim3 grid, int
 // ---- the group kernel: up to G pairs of one cluster per workgroup, tables interleaved entry by entry ----
 size_t scan_group_lds_bytes(const ivfpq_index* idx, int lut_dtype, int G, int threads) {
     return kGroupHead + (size_t)idx->pq_dim * ((size_t)1 << idx->pq_bits) * G * lut_elem_bytes(lut_dtype) + (((size_t)G * idx->d * 4 + 15) & ~(size_t)15)
-           + (size_t)(threads / 64) * kGroupStageAll * 8 + (size_t)idx->tuning.lds_pad;
+           + (size_t)(threads / 64) * (kGroupStageAll * 8 + kAliveCap * 2) + 16 + (size_t)idx->tuning.lds_pad;
 }
 // Workgroup size of the group kernel.  Measured on MI355X (filtered scan, 10,000 queries): with long lists (24 or
 // more 64-vector groups on average) two-wave workgroups win when six or more of them share a compute unit's LDS
@@ -1802,10 +1802,9 @@ int scan_group_width(const ivfpq_index* idx, int lut_dtype, const Fp8Mode& fp8, 
             if (G == 4 && !one_byte) continue;
             if (lut_dtype == IVFPQ_LUT_FP32) continue;
         }
-        // 64 sub-spaces with the early exit on: scan_kernel builds the second half of a table only if some group
-        // still needs it, which saves more than sharing does (10^6 vectors, e5m3: 1.42-1.49 ms against 1.53-1.54;
-        // without the early exit 3.27 against 2.38, so the rule follows the switch)
-        if (idx->pq_bits == 8 && idx->code_bytes() == 64 && idx->tuning.early_exit >= 0) continue;
+        // (64 sub-spaces with the early exit on: both kernels build the second half of the tables only if some group
+        // still needs it; 10^6 vectors, e5m3, one / two pairs: 1.43-1.51 / 1.32 ms; half and float tables of two queries
+        // exceed the 40 KB and stay with one pair: 1.95 / 2.44 and 2.46 / 3.81 ms)
         if (lds <= 40 * 1024) return G;
     }
     return 0;
@@ -1828,16 +1827,18 @@ int launch_scan_group(const ivfpq_index* idx, const ScanArgs& a, int lut_dtype, 
         constexpr int LUT = decltype(lut_tag)::value, GG = decltype(g_tag)::value;
         if (idx->pq_bits == 4)
             switch (nch) {
-                case 1: return go(scan_group_kernel<LUT, 1, GG, 4>);
-                case 2: return go(scan_group_kernel<LUT, 2, GG, 4>);
-                case 3: return go(scan_group_kernel<LUT, 3, GG, 4>);
-                default: return go(scan_group_kernel<LUT, 4, GG, 4>);
+                case 1: return go(scan_group_kernel<LUT, 1, GG, 4, false>);
+                case 2: return go(scan_group_kernel<LUT, 2, GG, 4, false>);
+                case 3: return go(scan_group_kernel<LUT, 3, GG, 4, false>);
+                default: return go(scan_group_kernel<LUT, 4, GG, 4, false>);
             }
         switch (nch) {
-            case 1: return go(scan_group_kernel<LUT, 1, GG, 8>);
-            case 2: return go(scan_group_kernel<LUT, 2, GG, 8>);
-            case 3: return go(scan_group_kernel<LUT, 3, GG, 8>);
-            default: return go(scan_group_kernel<LUT, 4, GG, 8>);
+            case 1: return go(scan_group_kernel<LUT, 1, GG, 8, false>);
+            case 2: return go(scan_group_kernel<LUT, 2, GG, 8, false>);
+            case 3: return go(scan_group_kernel<LUT, 3, GG, 8, false>);
+            default:
+                // 64 sub-spaces with the early exit on: the second half of the tables is built only if needed
+                return a.early_exit ? go(scan_group_kernel<LUT, 4, GG, 8, true>) : go(scan_group_kernel<LUT, 4, GG, 8, false>);
         }
     };
     auto by_g = [&](auto lut_tag) -> int {

@@ -29,7 +29,8 @@
 // A run of 1, 2, 3 or 4 pairs of one cluster is processed at once (3 in the 4-wide layout with one byte of
 // every entry unused).  A workgroup takes G consecutive pairs of the grouped order and cuts them into
 // such runs at the seams between clusters.
-// LDS: the slot's pair descriptors | tables | R residuals of d floats | per wave kGroupStageAll staged survivors.
+// LDS: the slot's pair descriptors | tables | R residuals of d floats | per wave kGroupStageAll staged survivors |
+// a flag and, per wave, kAliveCap group numbers of the split scan.
 #pragma once
 
 constexpr int kGroupStageAll = 128;  // survivors a wave stages before it appends them, over all queries of a run: 128 / R per query
@@ -68,7 +69,7 @@ __device__ __forceinline__ void store_packed(unsigned char* dst, const float (&f
 
 // Q pairs of one cluster, q[g], pair[g], with tables interleaved R >= Q wide (Q < R: the entries of the missing
 // queries are zero bytes that nobody decodes; three pairs run as Q = 3 in the R = 4 layout)
-template <int LUT, int NCH, int R, int Q, int BITS>
+template <int LUT, int NCH, int R, int Q, int BITS, bool SPLIT>
 __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem, const int (&q)[Q], const uint4 (&pair)[Q]) {
     static_assert(Q >= 1 && Q <= R, "queries of a run fit its interleave width");
     static_assert(BITS == 8 || BITS == 4, "codes of 8 or 4 bits");
@@ -115,7 +116,15 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
     // step 3: all R tables from one pass over the codebooks.  A wave takes blocks of 256 consecutive entries of the
     // table, 4 codes per lane: one row of an 8-bit sub-space, 16 rows of 4-bit sub-spaces (a lane's four codes
     // then belong to sub-space 16 block + lane / 4; the host admits only tables that are whole blocks)
-    {
+    // 64 sub-spaces of 8-bit codes with the early exit on: most groups are over every bound after half of the
+    // sub-spaces, so only the first 32 rows are built now; the rest follows if some group is still in the race
+    // (scan_kernel's split scan, for a run of queries)
+    static_assert(!SPLIT || (BITS == 8 && NCH == 4), "the split scan is for 64 sub-spaces of 8-bit codes");
+    constexpr bool lazy = SPLIT;
+    uint32_t* any_alive = reinterpret_cast<uint32_t*>(after_rq + (size_t)n_waves * kGroupStageAll * 8);
+    uint16_t* alive = reinterpret_cast<uint16_t*>(any_alive + 4) + (size_t)wave * kAliveCap;
+    if (threadIdx.x == 0) *any_alive = 0u;
+    auto build = [&](int block0, int block1) __attribute__((always_inline)) {
         int hi_v = fp8.hi;
         asm volatile("" : "+v"(hi_v));
         auto rows = [&](auto m_tag) {
@@ -145,8 +154,8 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
             };
             // two rows per trip: both rows' loads are in flight before either is used (one row per trip in the
             // 4-wide layout, where two would not fit the register budget of four waves per SIMD)
-            const int n_blocks = a.pq_dim * KSUB / 256;
-            int j = wave;
+            const int n_blocks = block1;
+            int j = block0 + wave;
             if constexpr (R < 4)
             for (; j + n_waves < n_blocks; j += 2 * n_waves) {
                 float c0[4 * M], c1[4 * M];
@@ -166,7 +175,8 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
             case 2: rows(std::integral_constant<int, 2>{}); break;
             default: rows(std::integral_constant<int, 4>{}); break;      // the host admits m = 1, 2, 4 only
         }
-    }
+    };
+    build(0, lazy ? 32 : a.pq_dim * KSUB / 256);
     __syncthreads();
 
     // step 4: Eq. (1) for all R queries
@@ -249,15 +259,16 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
     // Table entries are never negative, so the partial sums only grow: once all 64 x R of them are over their
     // queries' bounds no vector of the group can survive for any of the queries, and the remaining chunks are
     // skipped (the partial sums then fail the filter as the full sums would).
-    auto accumulate = [&](const uint4 (&buf)[NCH], float (&acc)[Q]) __attribute__((always_inline)) {
+    auto accumulate = [&](const uint4 (&buf)[NCH], float (&acc)[Q], auto chunks_tag) __attribute__((always_inline)) {
+        constexpr int CHUNKS = decltype(chunks_tag)::value;      // the leading chunks to add; NCH = all
 #pragma unroll
         for (int g = 0; g < Q; ++g) acc[g] = 0.f;
         bool over = false;                  // wave-uniform
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
+        for (int c = 0; c < CHUNKS; ++c) {
             if (over) continue;
             chunk(buf[c], c, acc);
-            if (c + 1 < NCH && a.early_exit) {
+            if (c + 1 < CHUNKS && a.early_exit) {
                 bool in_race = false;
 #pragma unroll
                 for (int g = 0; g < Q; ++g) in_race = in_race || __float_as_uint(acc[g]) <= bound[g];
@@ -308,15 +319,69 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
         });
     };
     float acc[Q];
+    constexpr std::integral_constant<int, NCH> kAllChunks{};
+    if constexpr (SPLIT) {
+        {
+            constexpr int HCH = NCH / 2;            // chunks of the first pass: the codes of the 32 leading sub-spaces
+            uint32_t n_alive = 0;                   // wave-uniform
+            bool redo_all = false;                  // more groups in the race than the list holds: take them all again
+            auto load_head = [&](uint4 (&buf)[NCH], int g) __attribute__((always_inline)) {
+#pragma unroll
+                for (int c = 0; c < HCH; ++c) buf[c] = cbase[((size_t)g * NCH + c) * 64 + lane];
+            };
+            auto first_pass = [&](int g, const uint4 (&buf)[NCH]) __attribute__((always_inline)) {
+                accumulate(buf, acc, std::integral_constant<int, HCH>{});
+                bool in_race = false;
+#pragma unroll
+                for (int gq = 0; gq < Q; ++gq) in_race = in_race || __float_as_uint(acc[gq]) <= bound[gq];
+                in_race = in_race && (uint32_t)g * 64u + lane < len;
+                if (__ballot(in_race) != 0) {
+                    if (n_alive < (uint32_t)kAliveCap && g / n_waves < 65536) { if (lane == 0) alive[n_alive] = (uint16_t)(g / n_waves); ++n_alive; }
+                    else redo_all = true;
+                }
+            };
+            // (the loads of the wave's first group were issued in full before the build; later groups load the head only)
+            while (grp < n_groups) {
+                const int gn = grp + n_waves;
+                if (gn < n_groups) load_head(buf_b, gn);
+                first_pass(grp, buf_a);
+                if (gn >= n_groups) break;
+                grp = gn + n_waves;
+                if (grp < n_groups) load_head(buf_a, grp);
+                first_pass(gn, buf_b);
+            }
+            if (lane == 0 && (n_alive != 0 || redo_all)) atomicOr(any_alive, 1u);
+            __syncthreads();
+            if (*any_alive == 0u) return;           // the same for every wave
+            build(32, a.pq_dim * KSUB / 256);
+            __syncthreads();
+            if (redo_all) {
+                for (grp = wave; grp < n_groups; grp += n_waves) {
+                    load_group(buf_a, grp);
+                    accumulate(buf_a, acc, kAllChunks);
+                    keep(grp, acc);
+                }
+            } else {
+                for (uint32_t t = 0; t < n_alive; ++t) {
+                    grp = (int)alive[t] * n_waves + wave;
+                    load_group(buf_a, grp);
+                    accumulate(buf_a, acc, kAllChunks);
+                    keep(grp, acc);
+                }
+            }
+            static_for<Q>([&](auto g_tag) __attribute__((always_inline)) { flush(g_tag); });
+            return;
+        }
+    }
     while (grp < n_groups) {
         const int gn = grp + n_waves;
         if (gn < n_groups) load_group(buf_b, gn);
-        accumulate(buf_a, acc);
+        accumulate(buf_a, acc, kAllChunks);
         keep(grp, acc);
         if (gn >= n_groups) break;
         grp = gn + n_waves;
         if (grp < n_groups) load_group(buf_a, grp);
-        accumulate(buf_b, acc);
+        accumulate(buf_b, acc, kAllChunks);
         keep(gn, acc);
     }
     static_for<Q>([&](auto g_tag) __attribute__((always_inline)) { flush(g_tag); });
@@ -326,7 +391,7 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
 // XCDs in blocks of order_block / G, which is the dealing of scan_kernel's pairs in blocks of order_block.
 // The first kGroupHead bytes of the LDS hold the slot's pair descriptors (the runs read them by position);
 // group_run's `smem` starts behind them.
-template <int LUT, int NCH, int G, int BITS>
+template <int LUT, int NCH, int G, int BITS, bool SPLIT>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8)))
 scan_group_kernel(ScanArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -362,12 +427,12 @@ scan_group_kernel(ScanArgs a) {
             if (r == 4) {
                 const int qq[4] = {q_at(i), q_at(i + 1), q_at(i + 2), q_at(i + 3)};
                 const uint4 pp[4] = {pair_at(i), pair_at(i + 1), pair_at(i + 2), pair_at(i + 3)};
-                group_run<LUT, NCH, 4, 4, BITS>(a, body, qq, pp);
+                group_run<LUT, NCH, 4, 4, BITS, SPLIT>(a, body, qq, pp);
                 done = true;
             } else if (r == 3) {
                 const int qq[3] = {q_at(i), q_at(i + 1), q_at(i + 2)};
                 const uint4 pp[3] = {pair_at(i), pair_at(i + 1), pair_at(i + 2)};
-                group_run<LUT, NCH, 4, 3, BITS>(a, body, qq, pp);
+                group_run<LUT, NCH, 4, 3, BITS, SPLIT>(a, body, qq, pp);
                 done = true;
             }
         }
@@ -375,11 +440,11 @@ scan_group_kernel(ScanArgs a) {
             if (r == 2) {
                 const int qq[2] = {q_at(i), q_at(i + 1)};
                 const uint4 pp[2] = {pair_at(i), pair_at(i + 1)};
-                group_run<LUT, NCH, 2, 2, BITS>(a, body, qq, pp);
+                group_run<LUT, NCH, 2, 2, BITS, SPLIT>(a, body, qq, pp);
             } else {
                 const int qq[1] = {q_at(i)};
                 const uint4 pp[1] = {pair_at(i)};
-                group_run<LUT, NCH, 1, 1, BITS>(a, body, qq, pp);
+                group_run<LUT, NCH, 1, 1, BITS, SPLIT>(a, body, qq, pp);
             }
         }
         i += r;

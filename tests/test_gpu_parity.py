@@ -695,13 +695,18 @@ def test_split_scan_when_every_group_stays_in_the_race(P):
     oidx = oracle.make_index(d, 3, 64, 8, cent, cb, offs, codes, ids)
     gidx = to_library(P, oidx)
     q = np.random.default_rng(810).standard_normal((6, d)).astype(np.float32)
-    for probes_row, k in (([0, 1], 100), ([0, 1, 2], 1000), ([2, 1], 10), ([1, 2, 0], 10)):
-        probes = np.tile(np.array([probes_row], dtype=np.uint32), (6, 1))
-        for dtype in (oracle.LUT_FP32, oracle.LUT_E5M3):
-            _step(f"split scan, everything in the race: probes={probes_row} k={k} dtype={dtype}")
-            ids_g, d_g = gidx.ivfpq_search_with_probes(q, probes, k, dtype)
-            ids_o, d_o = oracle.search(oidx, q, len(probes_row), k, dtype, probes=probes)
-            assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"probes={probes_row} k={k}")
+    # (share: the one-pair kernel, the library's choice, and the group kernel with two and four pairs per workgroup)
+    for share in (1, 0, 2, 4):
+        gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, share)
+        for probes_row, k in (([0, 1], 100), ([0, 1, 2], 1000), ([2, 1], 10), ([1, 2, 0], 10)):
+            probes = np.tile(np.array([probes_row], dtype=np.uint32), (6, 1))
+            for dtype in (oracle.LUT_FP32, oracle.LUT_E5M3):
+                _step(f"split scan, everything in the race: share={share} probes={probes_row} k={k} dtype={dtype}: "
+                      f"{gidx.ivfpq_scan_kernel_info(dtype)}")
+                ids_g, d_g = gidx.ivfpq_search_with_probes(q, probes, k, dtype)
+                ids_o, d_o = oracle.search(oidx, q, len(probes_row), k, dtype, probes=probes)
+                assert_topk_matches(ids_g.cpu().numpy(), d_g.cpu().numpy(), ids_o, d_o, context=f"share={share} probes={probes_row} k={k}")
+    gidx.ivfpq_set_tuning(P.TUNE_SCAN_SHARE, 0)
 
 
 def test_search_nearest_cluster_smaller_than_k(P):
