@@ -172,7 +172,7 @@ typedef enum {
     IVFPQ_TUNE_ORDER_BLOCK = 1,  /* consecutive (query, probe) pairs of the cluster-grouped order that stay on one
                                     XCD (>= 1; the scan that shares a workgroup between pairs needs an even value) */
     IVFPQ_TUNE_SCAN_SHARE = 2,   /* 1: one (query, probe) pair per scan workgroup; 2 or 4: up to that many pairs of
-                                    one cluster per workgroup wherever the kernel for it applies (8-bit codes) */
+                                    one cluster per workgroup wherever the kernel for it applies (8- and 4-bit codes) */
     IVFPQ_TUNE_EARLY_EXIT = 3,   /* 1: on (the default: a 64-vector group stops adding once all its partial sums are
                                     over the query's bound); -1: off, every lookup of Eq. (1) is made */
     IVFPQ_TUNE_LDS_PAD = 4       /* extra bytes of LDS requested per scan workgroup (lowers occupancy without

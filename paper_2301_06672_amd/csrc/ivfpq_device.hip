@@ -92,14 +92,21 @@ struct KthShared {
     uint32_t n_rec;
 };
 
-struct SelectShared {
+// CAP: how many records the selection can return (>= k); kernels whose k is small take a small CAP, so that more of
+// their workgroups share a compute unit (they wait on barriers and memory most of the time: the top-k kernel with
+// k = 100 took 0.25 ms at six workgroups per compute unit and 0.21 ms at eight)
+template <int CAP>
+struct SelectSharedT {
+    static constexpr int kCap = CAP;
     uint32_t hist[256];
-    uint32_t rec_key[SEL_CAP];
-    uint32_t rec_pos[SEL_CAP];
-    long long rec_tie[SEL_CAP];
+    uint32_t rec_key[CAP];
+    uint32_t rec_pos[CAP];
+    long long rec_tie[CAP];
     uint32_t digit, need, count;   // broadcast slots of the digit search
     uint32_t n_rec, n_eq;
 };
+using SelectShared = SelectSharedT<SEL_CAP>;
+constexpr int SEL_CAP_SMALL = 256;  // >= 2 * kFewMax: block_select_few parks tie keys in the upper half of the records
 
 __device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
     const int lane = threadIdx.x & (kWave - 1);
@@ -142,8 +149,9 @@ __device__ inline bool rec_less(uint32_t ka, long long ta, uint32_t pa, uint32_t
     return pa < pb;
 }
 
-// sorts records [0, np2) ascending by (key, tie, pos); np2 is a power of two <= SEL_CAP
-__device__ __forceinline__ void sort_records(SelectShared& s, int np2) {
+// sorts records [0, np2) ascending by (key, tie, pos); np2 is a power of two <= the record capacity
+template <class S>
+__device__ __forceinline__ void sort_records(S& s, int np2) {
     for (int size = 2; size <= np2; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
             __syncthreads();
@@ -215,8 +223,8 @@ __device__ __forceinline__ uint32_t block_kth_key(Shared& s, uint32_t n, uint32_
 // KeyFn(i) -> uint32 key of element i; TieFn(i) -> long long tie key of element i.
 // On return records [0, min(k, n)) hold the selected elements in ascending (key, tie, pos) order.
 // Returns min(k, n).  Must be called by every thread of the workgroup.
-template <class KeyFn, class TieFn>
-__device__ __forceinline__ int block_select_smallest(SelectShared& s, uint32_t n, uint32_t k, KeyFn key_of, TieFn tie_of) {
+template <class S, class KeyFn, class TieFn>
+__device__ __forceinline__ int block_select_smallest(S& s, uint32_t n, uint32_t k, KeyFn key_of, TieFn tie_of) {
     const uint32_t kk = k < n ? k : n;
     if (kk == 0) return 0;
     const int tid = threadIdx.x, nth = blockDim.x;
@@ -229,7 +237,7 @@ __device__ __forceinline__ int block_select_smallest(SelectShared& s, uint32_t n
     __syncthreads();
     if (tid == 0) { s.n_rec = 0; s.n_eq = 0; }
     __syncthreads();
-    const bool all_fit = (n_less + n_eq) <= (uint32_t)SEL_CAP;
+    const bool all_fit = (n_less + n_eq) <= (uint32_t)S::kCap;
     if (all_fit) {
         // everything <= T goes into the records; the sort decides which ties stay
         for (uint32_t i = tid; i < n; i += nth) {
@@ -298,12 +306,13 @@ __device__ __forceinline__ int block_select_smallest(SelectShared& s, uint32_t n
 // and the sort cost several hundred whatever n is.  Tie keys are fetched only for elements with fewer than
 // k smaller keys, and wait in the upper half of the record array while the ranks are settled.
 constexpr uint32_t kFewMax = 128;
-template <class KeyFn, class TieFn>
-__device__ __forceinline__ int block_select_few(SelectShared& s, uint32_t n, uint32_t k, KeyFn key_of, TieFn tie_of) {
+template <class S, class KeyFn, class TieFn>
+__device__ __forceinline__ int block_select_few(S& s, uint32_t n, uint32_t k, KeyFn key_of, TieFn tie_of) {
+    static_assert(S::kCap >= 2 * (int)kFewMax, "tie keys wait in the upper half of the records");
     const uint32_t kk = k < n ? k : n;
     if (kk == 0) return 0;
     const uint32_t e = threadIdx.x;
-    constexpr uint32_t SCR = SEL_CAP / 2;
+    constexpr uint32_t SCR = S::kCap / 2;
     __syncthreads();
     const uint32_t key = e < n ? key_of(e) : 0xFFFFFFFFu;
     uint32_t less = 0, same = 0;
@@ -343,12 +352,14 @@ __device__ __forceinline__ int block_select_few(SelectShared& s, uint32_t n, uin
 // ------------------------------------------------------------------------------------------------
 constexpr int CAND_CAP = 1024;   // >= IVFPQ_MAX_K
 
-struct RowSelectShared {
-    SelectShared sel;
+template <int CAP>
+struct RowSelectSharedT {
+    SelectSharedT<CAP> sel;
     uint32_t cand_key[CAND_CAP];
     uint32_t cand_pos[CAND_CAP];
     uint32_t n_cand;
 };
+using RowSelectShared = RowSelectSharedT<SEL_CAP>;
 
 // pos_of(i): logical position of row element i (what the records report and what tie_of_pos
 // takes); have_bound/bound: an upper bound of the k-th smallest key that the caller already knows
@@ -361,11 +372,11 @@ struct RowSelectShared {
 struct NoWiden { __device__ uint32_t operator()(uint32_t b) const { return b; } };
 struct NoRefine { __device__ uint32_t operator()(uint32_t n) const { return n; } };
 
-template <class PosFn, class TieFn, class WidenFn, class RefineFn, class WholeRowFn>
-__device__ __forceinline__ int block_select_row_ex(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
+template <class T, class PosFn, class TieFn, class WidenFn, class RefineFn, class WholeRowFn>
+__device__ __forceinline__ int block_select_row_ex(T& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
                                    bool have_bound, uint32_t bound, PosFn pos_of, TieFn tie_of_pos,
                                    WidenFn widen, RefineFn refine, WholeRowFn whole_row) {
-    SelectShared& s = t.sel;
+    auto& s = t.sel;
     const int tid = threadIdx.x, nth = blockDim.x;
     const uint32_t kk = k < (uint32_t)CAND_CAP ? k : (uint32_t)CAND_CAP;
     bool compact = true;
@@ -438,10 +449,10 @@ __device__ __forceinline__ int block_select_row_ex(RowSelectShared& t, const uin
     return got;
 }
 
-template <class PosFn, class TieFn>
-__device__ __forceinline__ int block_select_row(RowSelectShared& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
+template <class T, class PosFn, class TieFn>
+__device__ __forceinline__ int block_select_row(T& t, const uint32_t* __restrict__ row, uint32_t n, uint32_t k,
                                 bool have_bound, uint32_t bound, PosFn pos_of, TieFn tie_of_pos) {
-    SelectShared& s = t.sel;
+    auto& s = t.sel;
     return block_select_row_ex(t, row, n, k, have_bound, bound, pos_of, tie_of_pos, NoWiden{}, NoRefine{},
         [&]() -> int {
             const int got = block_select_smallest(s, n, k,
@@ -1483,14 +1494,15 @@ bound_kernel(float* __restrict__ R, uint32_t* __restrict__ Rpos, size_t stride, 
 // (the nearest cluster's values under the bound, then what the filtered scan kept); with one probe, the
 // cluster's segment itself.
 // ================================================================================================
+template <int CAP>          // record capacity, >= k
 __global__ void __launch_bounds__(SEL_THREADS)
 topk_kernel(const float* __restrict__ R, const uint32_t* __restrict__ Rpos, size_t stride,
             const uint32_t* __restrict__ roff, const uint32_t* __restrict__ probes,
             const uint32_t* __restrict__ bounds, const uint32_t* __restrict__ counts, int n_probes, int k,
             const int64_t* __restrict__ list_offsets, const int64_t* __restrict__ ids,
             int64_t* __restrict__ out_ids, float* __restrict__ out_dists) {
-    __shared__ RowSelectShared t;
-    SelectShared& s = t.sel;
+    __shared__ RowSelectSharedT<CAP> t;
+    auto& s = t.sel;
     const int q = blockIdx.x;
     const int tid = threadIdx.x, nth = blockDim.x;
     const uint32_t* s_roff = roff + (size_t)q * (n_probes + 1);     // read through the vector cache:
@@ -2054,9 +2066,14 @@ int search_impl(const ivfpq_index* idx, const float* d_queries, int64_t nq, cons
         // step 5
         StageTimer t2(idx, st, 2);
         if (int s = t2.begin()) return s;
-        hipLaunchKernelGGL(topk_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, w_R, w_Rpos, plan.stride, w_roff, w_probes,
-                           w_bounds, w_counts, n_probes, k, idx->dev.list_offsets, idx->dev.ids, d_ids + (size_t)q0 * k,
-                           d_dists + (size_t)q0 * k);
+        if (k <= SEL_CAP_SMALL)
+            hipLaunchKernelGGL(topk_kernel<SEL_CAP_SMALL>, dim3(tq), dim3(SEL_THREADS), 0, st, w_R, w_Rpos, plan.stride, w_roff, w_probes,
+                               w_bounds, w_counts, n_probes, k, idx->dev.list_offsets, idx->dev.ids, d_ids + (size_t)q0 * k,
+                               d_dists + (size_t)q0 * k);
+        else
+            hipLaunchKernelGGL(topk_kernel<SEL_CAP>, dim3(tq), dim3(SEL_THREADS), 0, st, w_R, w_Rpos, plan.stride, w_roff, w_probes,
+                               w_bounds, w_counts, n_probes, k, idx->dev.list_offsets, idx->dev.ids, d_ids + (size_t)q0 * k,
+                               d_dists + (size_t)q0 * k);
         HIP_TRY(hipGetLastError());
         if (int s = t2.end()) return s;
     }
