@@ -615,6 +615,7 @@ def test_stream_read_folds_every_word_once(P, n_words, n_wg):
     (32, 32, 4, 7, 5, 10),        # 4-bit codes, one chunk, m = 1
     (128, 32, 4, 33, 8, 1000),    # 4-bit codes, one chunk, m = 4
     (96, 96, 4, 50, 20, 10),      # 4-bit codes, three chunks
+    (128, 128, 4, 9, 6, 100),     # 4-bit codes, four chunks
 ])
 @pytest.mark.parametrize("dtype_name", ["e5m3", "e4m4", "fp16", "fp32"])
 def test_search_group_of_pairs_per_workgroup(P, d, pq_dim, pq_bits, n_lists, n_probes, k, dtype_name):
