@@ -478,6 +478,9 @@ __device__ __forceinline__ int block_select_row(T& t, const uint32_t* __restrict
 // the third does as well, and all of
 // these get their exact distance.  A is then only scratch for the whole-row fallback.
 // ================================================================================================
+// CAP: record capacity, >= n_probes.  The small one serves selections from strip summaries only (S given): the path
+// that streams all keys short-lists up to CAND_CAP indices in the record arrays.
+template <int CAP>
 __global__ void __launch_bounds__(SEL_THREADS)
 select_probes_kernel(uint32_t* __restrict__ A, const StripSummary* __restrict__ S, int strip_w,
                      const float* __restrict__ queries,
@@ -486,9 +489,9 @@ select_probes_kernel(uint32_t* __restrict__ A, const StripSummary* __restrict__ 
                      const uint32_t* __restrict__ list_sizes, const int64_t* __restrict__ group_offsets,
                      uint32_t* __restrict__ probes, float* __restrict__ probe_dists,
                      uint32_t* __restrict__ roff, uint4* __restrict__ pairs, int k_hint) {
-    __shared__ RowSelectShared t;
+    __shared__ RowSelectSharedT<CAP> t;
     __shared__ float s_part[SEL_THREADS / kWave];
-    SelectShared& s = t.sel;
+    auto& s = t.sel;
     // Workgroup b runs on XCD b % 8.  Inside every block of 64 queries the eight workgroups of one XCD take eight
     // consecutive queries: their strip summaries (16 bytes per query and strip, strip-major) share 128-byte lines,
     // so a line is fetched into one XCD's L2 instead of all eight.
@@ -588,17 +591,15 @@ select_probes_kernel(uint32_t* __restrict__ A, const StripSummary* __restrict__ 
         const uint32_t n_strips = ((uint32_t)n_lists + strip_w - 1) / strip_w, sw = (uint32_t)strip_w;
         const size_t stride = gridDim.x;
         const StripSummary* mine = S + q;
-        // the summaries are read several times: from the (still unused) record and candidate-key arrays if they fit
-        const bool in_lds = n_strips <= (uint32_t)SEL_CAP;
+        // the strip minima are read several times: from the (still unused) candidate-key array if they fit; the
+        // second and third keys are needed only for the few strips whose minimum passes the bound
+        const bool in_lds = n_strips <= (uint32_t)CAND_CAP;
         if (in_lds)
-            for (uint32_t i = tid; i < n_strips; i += nth) {
-                const StripSummary v = mine[i * stride];
-                s.rec_key[i] = v.x; s.rec_pos[i] = v.y; t.cand_key[i] = v.z;
-            }
+            for (uint32_t i = tid; i < n_strips; i += nth) t.cand_key[i] = mine[i * stride].x;
         __syncthreads();
-        auto low1 = [&](uint32_t i) { return in_lds ? s.rec_key[i] : mine[i * stride].x; };
-        auto low2 = [&](uint32_t i) { return in_lds ? s.rec_pos[i] : mine[i * stride].y; };
-        auto low3 = [&](uint32_t i) { return in_lds ? t.cand_key[i] : mine[i * stride].z; };
+        auto low1 = [&](uint32_t i) { return in_lds ? t.cand_key[i] : mine[i * stride].x; };
+        auto low2 = [&](uint32_t i) { return mine[i * stride].y; };
+        auto low3 = [&](uint32_t i) { return mine[i * stride].z; };
         uint32_t r0, r1;
         const uint32_t kk = (uint32_t)n_probes < n_strips ? (uint32_t)n_probes : n_strips;
         // kk strips hold a key not above this, so it bounds the kk-th smallest key of the row
@@ -646,11 +647,13 @@ select_probes_kernel(uint32_t* __restrict__ A, const StripSummary* __restrict__ 
             got = whole_row();       // a plateau of equal ranking values (or not-a-number keys)
         }
         __syncthreads();
-    } else {
+    } else if constexpr (CAP == SEL_CAP) {
         got = block_select_row_ex(t, row, (uint32_t)n_lists, (uint32_t)n_probes, false, 0u,
                                   [](uint32_t i) { return i; },
                                   [](uint32_t pos, uint32_t) { return (long long)pos; },
                                   widen, refine, whole_row);
+    } else {
+        return;              // not launched: the host gives the small capacity strip summaries
     }
     if (!roff) {             // the caller's probe lists: nearest first
         for (int p = tid; p < got; p += nth) {
@@ -668,8 +671,8 @@ select_probes_kernel(uint32_t* __restrict__ A, const StripSummary* __restrict__ 
         t.cand_key[p] = list_sizes[l];
         t.cand_pos[p] = (uint32_t)group_offsets[l];
     }
-    uint32_t* slot_of = reinterpret_cast<uint32_t*>(s.rec_tie);          // 2048 words: slot of probe p, then offsets
-    uint32_t* offs = slot_of + SEL_CAP;
+    uint32_t* slot_of = reinterpret_cast<uint32_t*>(s.rec_tie);          // 2 CAP words: slot of probe p, then offsets
+    uint32_t* offs = slot_of + CAP;
     __syncthreads();
     if (tid == 0) {
         int pivot = 0;
@@ -693,6 +696,19 @@ select_probes_kernel(uint32_t* __restrict__ A, const StripSummary* __restrict__ 
         roff[(size_t)q * (n_probes + 1) + i] = at;
         pairs[(size_t)q * n_probes + i] = make_uint4(l, t.cand_key[p], t.cand_pos[p], at);
     }
+}
+
+// One workgroup per query; the small record capacity (more workgroups per compute unit) when the selection works
+// from strip summaries and n_probes allows.
+template <class... Args>
+void launch_select_probes(int nq, hipStream_t st, uint32_t* A, const StripSummary* S, int strip_w, const float* queries,
+                          const float* centroids, float centroid_norm_max, int d, int n_lists, int n_probes, Args... rest) {
+    if (S && n_probes <= SEL_CAP_SMALL)
+        hipLaunchKernelGGL(select_probes_kernel<SEL_CAP_SMALL>, dim3(nq), dim3(SEL_THREADS), 0, st, A, S, strip_w, queries, centroids,
+                           centroid_norm_max, d, n_lists, n_probes, rest...);
+    else
+        hipLaunchKernelGGL(select_probes_kernel<SEL_CAP>, dim3(nq), dim3(SEL_THREADS), 0, st, A, S, strip_w, queries, centroids,
+                           centroid_norm_max, d, n_lists, n_probes, rest...);
 }
 
 // Same layout step for caller-given probes.
@@ -1989,10 +2005,10 @@ int search_impl(const ivfpq_index* idx, const float* d_queries, int64_t nq, cons
             if (int s = t4.begin()) return s;
             if (int s = launch_coarse(qt, idx->dev.centroids, idx->dev.centroid_norms, tq, idx->n_lists, idx->d, (uint32_t*)w_D, strips, ws + plan.split, st)) return s;
             if (int s = t4.end()) return s;
-            hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, (const StripSummary*)strips,
-                               coarse_strip_width(tq, idx->n_lists), qt,
-                               idx->dev.centroids, idx->centroid_norm_max, idx->d, idx->n_lists,
-                               n_probes, idx->dev.list_sizes, idx->dev.group_offsets, w_probes, w_probe_d, w_roff, w_pairs, k);
+            launch_select_probes((int)tq, st, (uint32_t*)w_D, (const StripSummary*)strips,
+                                 coarse_strip_width(tq, idx->n_lists), qt,
+                                 idx->dev.centroids, idx->centroid_norm_max, idx->d, idx->n_lists,
+                                 n_probes, idx->dev.list_sizes, idx->dev.group_offsets, w_probes, w_probe_d, w_roff, w_pairs, k);
             HIP_TRY(hipGetLastError());
         } else {
             hipLaunchKernelGGL(layout_probes_kernel, dim3((tq + 255) / 256), dim3(256), 0, st,
@@ -2256,11 +2272,11 @@ int ivfpq_select_probes(const ivfpq_index_t* idx, const float* d_queries, int64_
         if (int s = launch_coarse(d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->dev.centroid_norms, tq,
                                   idx->n_lists, idx->d, (uint32_t*)w_D, strips, (unsigned char*)d_workspace + plan.split, st))
             return s;
-        hipLaunchKernelGGL(select_probes_kernel, dim3(tq), dim3(SEL_THREADS), 0, st, (uint32_t*)w_D, (const StripSummary*)strips,
-                           coarse_strip_width(tq, idx->n_lists), d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->centroid_norm_max, idx->d,
-                           idx->n_lists, n_probes, idx->dev.list_sizes, idx->dev.group_offsets, d_probes + (size_t)q0 * n_probes,
-                           d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr,
-                           (uint4*)nullptr, 0);
+        launch_select_probes((int)tq, st, (uint32_t*)w_D, (const StripSummary*)strips,
+                             coarse_strip_width(tq, idx->n_lists), d_queries + (size_t)q0 * idx->d, idx->dev.centroids, idx->centroid_norm_max, idx->d,
+                             idx->n_lists, n_probes, idx->dev.list_sizes, idx->dev.group_offsets, d_probes + (size_t)q0 * n_probes,
+                             d_probe_dists ? d_probe_dists + (size_t)q0 * n_probes : nullptr, (uint32_t*)nullptr,
+                             (uint4*)nullptr, 0);
         HIP_TRY(hipGetLastError());
     }
     return IVFPQ_OK;
