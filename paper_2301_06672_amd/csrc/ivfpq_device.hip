@@ -178,11 +178,11 @@ __device__ __forceinline__ void sort_records(S& s, int np2) {
 // LDS atomic when all its active lanes hit the same bin (the usual case for the leading digit of
 // distances of similar magnitude, where per-lane atomics on one address would serialise).
 __device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t digit, bool active) {
-    const unsigned long long act = __ballot(active);
+    const unsigned long long act = ballot64(active);
     if (act == 0) return;
     const int first = __ffsll((long long)act) - 1;
     const uint32_t d0 = (uint32_t)__shfl((int)digit, first, kWave);
-    const unsigned long long same = __ballot(active && digit == d0);
+    const unsigned long long same = ballot64(active && digit == d0);
     if (same == act) {
         if ((int)(threadIdx.x & (kWave - 1)) == first) atomicAdd(&hist[d0], (uint32_t)__popcll(act));
     } else if (active) {
@@ -1156,7 +1156,7 @@ scan_kernel(ScanArgs a) {
                     const int cg = blk * EVERY + e;
                     if (cg < NG) acc = add_group<LUT, BITS>(acc, lut, w + cg * WPG, cg * SPG, fp8);
                 }
-                if (blk + 1 < BLOCKS && prune) over = __ballot(__float_as_uint(acc) <= bound) == 0;
+                if (blk + 1 < BLOCKS && prune) over = ballot64(__float_as_uint(acc) <= bound) == 0;
             }
         }
         return acc;      // 4-byte chunks take the loop over code groups below instead
@@ -1182,8 +1182,9 @@ scan_kernel(ScanArgs a) {
             else if (a.single_list < 0) Rout[i] = __uint_as_float(kPadKey);   // padding slot of the R scratch
         } else {
             // keep only what can still be among the k best
+            // (the mask is the AND of two compares' results; a ballot of their conjunction goes through a 0/1 value)
             const bool keep = i < len && __float_as_uint(acc) <= bound;
-            const unsigned long long m = __ballot(keep);
+            const unsigned long long m = ballot64(i < len) & ballot64(__float_as_uint(acc) <= bound);
             if (m != 0) {
                 if (staged + 64u > (uint32_t)kStageCap) flush_stage();
                 if (keep) stage[staged + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = make_uint2(__float_as_uint(acc), row_pos0 + i);
@@ -1233,8 +1234,7 @@ scan_kernel(ScanArgs a) {
             };
             auto first_pass = [&](int grp, const chunk_t (&buf)[NBUF]) {
                 const float acc = accumulate(buf, std::integral_constant<int, HBLK>{});
-                const bool in_race = (uint32_t)grp * 64u + lane < len && __float_as_uint(acc) <= bound;
-                if (__ballot(in_race) != 0) {
+                if ((ballot64((uint32_t)grp * 64u + lane < len) & ballot64(__float_as_uint(acc) <= bound)) != 0) {
                     if (n_alive < (uint32_t)kAliveCap && grp / n_waves < 65536) { if (lane == 0) alive[n_alive] = (uint16_t)(grp / n_waves); ++n_alive; }
                     else redo_all = true;
                 }
@@ -1295,7 +1295,7 @@ scan_kernel(ScanArgs a) {
                 for (int u = 0; u < WPG; ++u)
                     w[u] = reinterpret_cast<const uint32_t*>(codes_l)[((size_t)g * nch + cg * WPG + u) * 64 + lane];
                 acc = add_group<LUT, BITS>(acc, lut, w, cg * SPG, fp8);
-                if (prune && ((cg + 1) * SPG) % 16 == 0 && cg + 1 < ncg && __ballot(__float_as_uint(acc) <= bound) == 0) break;
+                if (prune && ((cg + 1) * SPG) % 16 == 0 && cg + 1 < ncg && ballot64(__float_as_uint(acc) <= bound) == 0) break;
             }
             store_R(g, acc);
         }

@@ -49,6 +49,9 @@ __device__ __forceinline__ uint32_t byte_shl(uint32_t w) {
     }
 }
 
+// the lanes of the wave for which `p` holds, as a mask: the compare's own result, with no 0/1 value in between
+__device__ __forceinline__ unsigned long long ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
 constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): loops whose index must be a constant in

@@ -269,10 +269,10 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
             if (over) continue;
             chunk(buf[c], c, acc);
             if (c + 1 < CHUNKS && a.early_exit) {
-                bool in_race = false;
+                unsigned long long in_race = 0;
 #pragma unroll
-                for (int g = 0; g < Q; ++g) in_race = in_race || __float_as_uint(acc[g]) <= bound[g];
-                over = __ballot(in_race) == 0;
+                for (int g = 0; g < Q; ++g) in_race |= ballot64(__float_as_uint(acc[g]) <= bound[g]);
+                over = in_race == 0;
             }
         }
     };
@@ -294,10 +294,13 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
     auto keep = [&](int grp_i, const float (&acc)[Q]) __attribute__((always_inline)) {
         const uint32_t i = (uint32_t)grp_i * 64u + lane;
         const bool real = i < len;                  // the last group is padded with zero codes
+        const unsigned long long m_real = ballot64(real);
         static_for<Q>([&](auto g_tag) __attribute__((always_inline)) {
             constexpr int g = decltype(g_tag)::value;
-            const bool ok = real && __float_as_uint(acc[g]) <= bound[g];
-            const unsigned long long m = __ballot(ok);
+            // (the mask is the AND of two compares' results; a ballot of their conjunction goes through a 0/1 value)
+            const bool under = __float_as_uint(acc[g]) <= bound[g];
+            const unsigned long long m = ballot64(under) & m_real;
+            const bool ok = real && under;
             if (m != 0) {
                 const uint32_t cnt = (uint32_t)__popcll(m), rank = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
                 if (staged[g] + cnt > (uint32_t)kGroupStage) flush(g_tag);
@@ -331,11 +334,11 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
             };
             auto first_pass = [&](int g, const uint4 (&buf)[NCH]) __attribute__((always_inline)) {
                 accumulate(buf, acc, std::integral_constant<int, HCH>{});
-                bool in_race = false;
+                unsigned long long in_race = 0;
 #pragma unroll
-                for (int gq = 0; gq < Q; ++gq) in_race = in_race || __float_as_uint(acc[gq]) <= bound[gq];
-                in_race = in_race && (uint32_t)g * 64u + lane < len;
-                if (__ballot(in_race) != 0) {
+                for (int gq = 0; gq < Q; ++gq) in_race |= ballot64(__float_as_uint(acc[gq]) <= bound[gq]);
+                in_race &= ballot64((uint32_t)g * 64u + lane < len);
+                if (in_race != 0) {
                     if (n_alive < (uint32_t)kAliveCap && g / n_waves < 65536) { if (lane == 0) alive[n_alive] = (uint16_t)(g / n_waves); ++n_alive; }
                     else redo_all = true;
                 }
