@@ -1112,11 +1112,11 @@ scan_kernel(ScanArgs a) {
     // filtered mode: every wave stages its survivors in a private LDS buffer and appends them to the
     // query's row with one global atomic per flush (the counter of a query is shared by all the
     // workgroups of that query: one atomic per 64-vector group would serialise on it)
-    uint2* stage = reinterpret_cast<uint2*>(after_rq + 16) + (size_t)(threadIdx.x >> 6) * kStageCap;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));    // the same for the whole wave: loop counters and group addresses stay scalar
+    uint2* stage = reinterpret_cast<uint2*>(after_rq + 16) + (size_t)wave * kStageCap;
     uint32_t staged = 0;       // wave-uniform
     const int n_groups = (int)((len + 63u) >> 6);
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
     const int n_waves = blockDim.x >> 6;
     const int nch = NCH > 0 ? NCH : a.n_chunks;
     const uint8_t* codes_l = a.codes + (size_t)first_group * 64 * ((size_t)nch * CW);

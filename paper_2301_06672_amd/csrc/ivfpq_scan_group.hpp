@@ -83,7 +83,7 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
     float* rq = reinterpret_cast<float*>(smem + (size_t)a.pq_dim * KSUB * W);
     unsigned char* after_rq = reinterpret_cast<unsigned char*>(rq) + (((size_t)Q * a.d * 4 + 15) & ~(size_t)15);
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));      // the same for the whole wave: loop counters and group addresses stay scalar
     const int n_waves = blockDim.x >> 6;
     const Fp8Params fp8 = a.fp8.fixed;
     uint32_t bound[Q], seg0[Q], row_pos0[Q], staged[Q];
