@@ -152,11 +152,9 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
                 }
                 store_packed<LUT, R>(lut + ((size_t)j * 256 + lane * 4) * W, f, fp8, hi_v);
             };
-            // two rows per trip: both rows' loads are in flight before either is used (one row per trip in the
-            // 4-wide layout, where two would not fit the register budget of four waves per SIMD)
+            // two rows per trip: both rows' loads are in flight before either is used
             const int n_blocks = block1;
             int j = block0 + wave;
-            if constexpr (R < 4)
             for (; j + n_waves < n_blocks; j += 2 * n_waves) {
                 float c0[4 * M], c1[4 * M];
                 load_row(j, c0);
