@@ -19,7 +19,7 @@
 //   scan_kernel (mode 2) steps 2-4 for the other probes, in cluster-grouped, XCD-aware order (a
 //                        cluster's codes then come from one XCD's L2); only R values under the bound
 //                        are kept
-//   scan_group_kernel    the same for up to four neighbouring pairs of one cluster per workgroup (8-bit codes):
+//   scan_group_kernel    the same for up to four neighbouring pairs of one cluster per workgroup (8- and 4-bit codes):
 //                        their tables are interleaved entry by entry, so one LDS read serves one lookup of
 //                        every query of the group; codebooks and codes are read once for all of them
 //   topk_kernel          step 5: the k smallest R among the survivors of a query, ordered by
