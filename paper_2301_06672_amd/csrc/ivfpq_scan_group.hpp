@@ -238,10 +238,19 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             if constexpr (BITS == 8) {
-                const int row = (c * 4 + u) * 4;
-                const uint32_t off[4] = {byte_shl<0, LOGW>(w[u]), byte_shl<1, LOGW>(w[u]), byte_shl<2, LOGW>(w[u]), byte_shl<3, LOGW>(w[u])};
+                // the table words of two code words (eight sub-spaces) are read before the first is used
+                if (u & 1) continue;
+                word_t x[8];
 #pragma unroll
-                for (int b = 0; b < 4; b += 2) add_two(lds_word(row + b, off[b]), lds_word(row + b + 1, off[b + 1]), acc);
+                for (int v2 = 0; v2 < 2; ++v2) {
+                    const uint32_t cw = w[u + v2];
+                    const int row = (c * 4 + u + v2) * 4;
+                    const uint32_t off[4] = {byte_shl<0, LOGW>(cw), byte_shl<1, LOGW>(cw), byte_shl<2, LOGW>(cw), byte_shl<3, LOGW>(cw)};
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) x[4 * v2 + b] = lds_word(row + b, off[b]);
+                }
+#pragma unroll
+                for (int pr = 0; pr < 4; ++pr) add_two(x[2 * pr], x[2 * pr + 1], acc);
             } else {
                 // byte b of lo4 / hi4: the entry offset of the code in the low / high nibble of byte b
                 constexpr uint32_t kNibbles = 0x0F0F0F0Fu << LOGW;
@@ -249,8 +258,11 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
                 const int row = (c * 4 + u) * 8;
                 const uint32_t off_lo[4] = {byte_shl<0, 0>(lo4), byte_shl<1, 0>(lo4), byte_shl<2, 0>(lo4), byte_shl<3, 0>(lo4)};
                 const uint32_t off_hi[4] = {byte_shl<0, 0>(hi4), byte_shl<1, 0>(hi4), byte_shl<2, 0>(hi4), byte_shl<3, 0>(hi4)};
+                word_t x[8];             // read before the first is used, like the eight words of 8-bit codes above
 #pragma unroll
-                for (int b = 0; b < 4; ++b) add_two(lds_word(row + 2 * b, off_lo[b]), lds_word(row + 2 * b + 1, off_hi[b]), acc);
+                for (int b = 0; b < 4; ++b) { x[2 * b] = lds_word(row + 2 * b, off_lo[b]); x[2 * b + 1] = lds_word(row + 2 * b + 1, off_hi[b]); }
+#pragma unroll
+                for (int pr = 0; pr < 4; ++pr) add_two(x[2 * pr], x[2 * pr + 1], acc);
             }
         }
     };
