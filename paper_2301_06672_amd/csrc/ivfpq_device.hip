@@ -1541,11 +1541,10 @@ topk_kernel(const float* __restrict__ R, const uint32_t* __restrict__ Rpos, size
         }
         return (long long)ids[list_offsets[s_probe[lo]] + (int64_t)(pos - s_roff[lo])];
     };
-    // a bound that admits everything (fewer than k vectors in the nearest cluster) filters nothing: let the
-    // selection take its own from a sample, or a long survivor list goes through several passes
-    const uint32_t known = listed ? bounds[q] : kAdmitAll;
-    const bool have_bound = known != kAdmitAll;
-    const int got = block_select_row(t, row, n, (uint32_t)k, have_bound, have_bound ? known : 0u, pos_of, id_of);
+    // The survivor list was filtered by the query's bound already, so that bound weeds out nothing here: the
+    // selection takes its own from a sample of the list (the k-th smallest of its first entries), and one pass over
+    // the list with that bound leaves a few hundred candidates.
+    const int got = block_select_row(t, row, n, (uint32_t)k, false, 0u, pos_of, id_of);
     for (int j = tid; j < k; j += nth) {
         int64_t id = -1;
         float dist = __uint_as_float(0x7F800000u);
