@@ -108,13 +108,18 @@ struct SelectSharedT {
 using SelectShared = SelectSharedT<SEL_CAP>;
 constexpr int SEL_CAP_SMALL = 256;  // >= 2 * kFewMax: block_select_few parks tie keys in the upper half of the records
 
+// Sum over this lane and the lanes below it, by data-parallel permutes (no trip through the LDS): a scan inside
+// every row of 16 lanes, then the last lane of a row added to the rows above.  (A lane a permute has no source
+// for, or whose row is masked out, receives 0.)
+template <int CTRL, int ROWS>
+__device__ inline uint32_t dpp_or_zero(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROWS, 0xF, true); }
 __device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        uint32_t o = __shfl_up(v, off, kWave);
-        if (lane >= off) v += o;
-    }
+    v += dpp_or_zero<0x111, 0xF>(v);       // row_shr:1
+    v += dpp_or_zero<0x112, 0xF>(v);       // row_shr:2
+    v += dpp_or_zero<0x114, 0xF>(v);       // row_shr:4
+    v += dpp_or_zero<0x118, 0xF>(v);       // row_shr:8
+    v += dpp_or_zero<0x142, 0xA>(v);       // row_bcast:15 into rows 1 and 3
+    v += dpp_or_zero<0x143, 0xC>(v);       // row_bcast:31 into rows 2 and 3
     return v;
 }
 
