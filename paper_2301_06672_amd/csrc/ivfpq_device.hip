@@ -108,6 +108,16 @@ struct SelectSharedT {
 using SelectShared = SelectSharedT<SEL_CAP>;
 constexpr int SEL_CAP_SMALL = 256;  // >= 2 * kFewMax: block_select_few parks tie keys in the upper half of the records
 
+// The sum of a value over every aligned group of 8 lanes, left in all 8: neighbours, then pairs inside a quad, then
+// the other quad of the group (whose four lanes hold the same value by then, so the mirrored order does not matter).
+// Each step adds the same two numbers in both partners: all 8 lanes end with the same bits.
+__device__ inline float sum_over_8_lanes(float v) {
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));     // quad_perm [1,0,3,2]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));     // quad_perm [2,3,0,1]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));    // row_half_mirror
+    return v;
+}
+
 // Sum over this lane and the lanes below it, by data-parallel permutes (no trip through the LDS): a scan inside
 // every row of 16 lanes, then the last lane of a row added to the rows above.  (A lane a permute has no source
 // for, or whose row is masked out, receives 0.)
@@ -186,7 +196,7 @@ __device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t digit, bool ac
     const unsigned long long act = ballot64(active);
     if (act == 0) return;
     const int first = __ffsll((long long)act) - 1;
-    const uint32_t d0 = (uint32_t)__shfl((int)digit, first, kWave);
+    const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)digit, first);      // `first` is the same for the whole wave
     const unsigned long long same = ballot64(active && digit == d0);
     if (same == act) {
         if ((int)(threadIdx.x & (kWave - 1)) == first) atomicAdd(&hist[d0], (uint32_t)__popcll(act));
@@ -538,9 +548,7 @@ select_probes_kernel(uint32_t* __restrict__ A, const StripSummary* __restrict__ 
             const float* c = centroids + (size_t)l * d;
             for (int u = tid & 7; u < d; u += 8) { const float diff = qv[u] - c[u]; acc = __builtin_fmaf(diff, diff, acc); }
         }
-        acc += __shfl_xor(acc, 1, kWave);
-        acc += __shfl_xor(acc, 2, kWave);
-        acc += __shfl_xor(acc, 4, kWave);
+        acc = sum_over_8_lanes(acc);
         return acc;
     };
     // candidates in LDS: keep those whose a() is within 2 delta of the n_probes-th smallest a() among
@@ -1585,9 +1593,7 @@ refine_kernel(const float* __restrict__ data, long long n_data, int d, const flo
             const float* x = data + (size_t)id * d;
             for (int u = tid & 7; u < d; u += 8) { const float diff = qv[u] - x[u]; acc = __builtin_fmaf(diff, diff, acc); }
         }
-        acc += __shfl_xor(acc, 1, kWave);
-        acc += __shfl_xor(acc, 2, kWave);
-        acc += __shfl_xor(acc, 4, kWave);
+        acc = sum_over_8_lanes(acc);
         if (valid && (tid & 7) == 0) keys[c] = ok ? __float_as_uint(acc) : kPadKey;
     }
     __syncthreads();
