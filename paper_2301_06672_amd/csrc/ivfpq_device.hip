@@ -1200,7 +1200,7 @@ scan_kernel(ScanArgs a) {
             const unsigned long long m = ballot64(i < len) & ballot64(__float_as_uint(acc) <= bound);
             if (m != 0) {
                 if (staged + 64u > (uint32_t)kStageCap) flush_stage();
-                if (keep) stage[staged + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = make_uint2(__float_as_uint(acc), row_pos0 + i);
+                if (keep) stage[staged + lanes_below(m)] = make_uint2(__float_as_uint(acc), row_pos0 + i);
                 staged += (uint32_t)__popcll(m);
             }
         }

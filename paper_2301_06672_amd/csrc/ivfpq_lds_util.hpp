@@ -52,6 +52,11 @@ __device__ __forceinline__ uint32_t byte_shl(uint32_t w) {
 // the lanes of the wave for which `p` holds, as a mask: the compare's own result, with no 0/1 value in between
 __device__ __forceinline__ unsigned long long ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 
+// how many lanes below this one are set in `mask` (two count instructions on the mask's halves)
+__device__ __forceinline__ uint32_t lanes_below(unsigned long long mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
 constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): loops whose index must be a constant in

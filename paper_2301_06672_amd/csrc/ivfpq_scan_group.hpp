@@ -312,7 +312,7 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
             const unsigned long long m = ballot64(under) & m_real;
             const bool ok = real && under;
             if (m != 0) {
-                const uint32_t cnt = (uint32_t)__popcll(m), rank = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+                const uint32_t cnt = (uint32_t)__popcll(m), rank = lanes_below(m);
                 if (staged[g] + cnt > (uint32_t)kGroupStage) flush(g_tag);
                 if (cnt > (uint32_t)kGroupStage) {
                     // more survivors in one group than the staging area holds: appended directly
