@@ -301,6 +301,29 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
         }
         staged[g] = 0;
     };
+    // end of the run: what every query still has staged.  The slots of all queries are requested first (one atomic
+    // each, all in flight together), then the copies follow: one wait for the counters instead of one per query.
+    auto flush_all = [&]() __attribute__((always_inline)) {
+        uint32_t base[Q];
+#pragma unroll
+        for (int g = 0; g < Q; ++g) {
+            base[g] = 0;
+            if (staged[g] != 0 && lane == 0) base[g] = atomicAdd(&a.counts[q[g]], staged[g]);
+        }
+        static_for<Q>([&](auto g_tag) __attribute__((always_inline)) {
+            constexpr int g = decltype(g_tag)::value;
+            if (staged[g] == 0) return;
+            const uint32_t at = (uint32_t)__builtin_amdgcn_readfirstlane((int)base[g]);
+            uint32_t* dst_key = reinterpret_cast<uint32_t*>(a.R) + (size_t)q[g] * a.stride + seg0[g] + at;
+            uint32_t* dst_pos = a.Rpos + (size_t)q[g] * a.stride + seg0[g] + at;
+            for (uint32_t j = lane; j < staged[g]; j += kWave) {
+                const uint2 e = stage[g][j];
+                dst_key[j] = e.x;
+                dst_pos[j] = e.y;
+            }
+            staged[g] = 0;
+        });
+    };
     auto keep = [&](int grp_i, const float (&acc)[Q]) __attribute__((always_inline)) {
         const uint32_t i = (uint32_t)grp_i * 64u + lane;
         const bool real = i < len;                  // the last group is padded with zero codes
@@ -382,7 +405,7 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
                     keep(grp, acc);
                 }
             }
-            static_for<Q>([&](auto g_tag) __attribute__((always_inline)) { flush(g_tag); });
+            flush_all();
             return;
         }
     }
@@ -397,7 +420,7 @@ __device__ __forceinline__ void group_run(const ScanArgs& a, unsigned char* smem
         accumulate(buf_b, acc, kAllChunks);
         keep(gn, acc);
     }
-    static_for<Q>([&](auto g_tag) __attribute__((always_inline)) { flush(g_tag); });
+    flush_all();
 }
 
 // Workgroup `slot` takes pairs [G slot, G slot + G) of the cluster-grouped order; the slots are dealt to the
